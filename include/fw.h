@@ -1,0 +1,194 @@
+/*
+ * fw.h -- C ABI of the MI355X (gfx950) feature-whitening hot path.
+ *
+ * Method: "Feature Whitening via Gradient Transformation for Improved Convergence"
+ * (arXiv 2010.01546).  Per whitened layer the library
+ *   (1) accumulates the block sums behind the input moments  mu_x, Phi_x, phi_x   (Sec. 2, Sec. 4.1),
+ *   (2) transforms the weight gradient  G -> G Q,  Q = T^T T                      (Sec. 3.1),
+ *   (3) runs the recursive condition-number-reduction update of T, Q, Q_s         (Sec. 4),
+ *   (4) builds the EVD / ZCA whitening matrix as the reference construction       (Sec. 2, Sec. 3.2).
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless the comment says "host".
+ *     Parameter structs (fw_conv_desc, fw_cond_params, fw_evd_params, fw_cond_state) are HOST structs
+ *     read during the call; the pointers inside fw_cond_state are device pointers.
+ *   - Matrices are dense, row-major, leading dimension = number of columns, float32 unless stated.
+ *     Device pointers must be 16-byte aligned (FW_ERR_ALIGNMENT otherwise).
+ *   - A convolution layer is taken in unfolded form: the sample rows x are the B*P patches of the input
+ *     (P = Ho*Wo output positions), M = Cin*kh*kw features in the order m = (c*kh + ky)*kw + kx, zero
+ *     padding counts as data.  N_rows = B*P.
+ *   - The library allocates no device memory, keeps no state between calls and never frees.  Scratch comes
+ *     from the caller through (ws, ws_bytes); fw_workspace_bytes gives the size an entry point needs.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on it and the
+ *     call returns without waiting, except fw_whiten_evd, which waits on its own convergence flag.
+ *   - Errors are return codes.  Arguments are validated before anything is enqueued; on a non-OK return
+ *     from validation no output has been touched.  Data-dependent events of the recursive step (empty
+ *     coherence set, estimate below the target power) are not errors: they are reported in fw_cond_info.
+ */
+#ifndef FW_H
+#define FW_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FW_OK = 0,
+    FW_ERR_INVALID_ARG = 1,   /* NULL pointer, non-positive size, parameter out of its range */
+    FW_ERR_UNSUPPORTED = 2,   /* valid in principle but not built (e.g. a shape beyond a stated limit) */
+    FW_ERR_ALIGNMENT = 3,     /* a device pointer is not 16-byte aligned */
+    FW_ERR_WORKSPACE = 4,     /* ws is NULL or ws_bytes is below fw_workspace_bytes(...) */
+    FW_ERR_HIP = 5,           /* a HIP runtime call failed (launch error, no device) */
+    FW_ERR_NOT_CONVERGED = 6  /* fw_whiten_evd hit max_sweeps; outputs hold the last iterate's result */
+} fw_status;
+
+typedef enum { FW_F32 = 0, FW_BF16 = 1 } fw_dtype;
+
+typedef enum {
+    FW_LAYOUT_ROWS = 0,  /* X is the row matrix [N_rows, M] itself (fully connected layer, or pre-unfolded) */
+    FW_LAYOUT_NCHW = 1,  /* activation tensor [B, Cin, H, W] */
+    FW_LAYOUT_NHWC = 2   /* activation tensor [B, H, W, Cin] */
+} fw_layout;
+
+/* Geometry of a layer input.  FW_LAYOUT_ROWS: B = N_rows, Cin = M, H = W = kh = kw = stride = 1, pad = 0. */
+typedef struct { int B, Cin, H, W, kh, kw, stride, pad; } fw_conv_desc;
+
+/* Operations for fw_workspace_bytes. */
+typedef enum { FW_OP_COV_ACCUMULATE = 0, FW_OP_GRAD_TRANSFORM = 1, FW_OP_COND_REDUCE_STEP = 2, FW_OP_WHITEN_EVD = 3 } fw_op;
+
+/* ------------------------------------------------------------------------------------------------------------
+ * (1) Moment accumulation -- the sums inside eqs. (vmuxi), (vPhixi) of Sec. 2 and eq. (phixmi) of Sec. 4.1.
+ *
+ *   A[i][j] += sum_rows x_i x_j   for i >= j (lower triangle incl. diagonal; entries above it are not touched)
+ *   s[i]    += sum_rows x_i
+ * over the N_rows = B*P patch rows of X, formed on the fly from the activation tensor (never materialised).
+ *   X      in   activation in layout `lay`, element type `dt` (float32, or bfloat16 as raw 16-bit patterns)
+ *   d      host geometry
+ *   A      i/o  [M, M] float32, accumulated in place (zero it before the first batch of a block)
+ *   s      i/o  [M] float32, accumulated in place
+ *   ws     scratch, fw_workspace_bytes(FW_OP_COV_ACCUMULATE, M, 0, d, dt) bytes
+ * Products are accumulated in float32 on the matrix cores (bf16 inputs: bf16 x bf16 -> float32); partial sums of
+ * row ranges are combined in float64 before they are added to A.  The result is deterministic run to run.
+ * Limits: M <= 16384; activation below 2^31 elements.
+ */
+fw_status fw_cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d,
+                            float* A, float* s, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------------------
+ * (1') Block moments from the accumulated sums -- eqs. (vmuxi), (vPhixi), (vmuxnz), (vPhixnz), (phixmi), (blambday).
+ *
+ *   mhat = s/n;   mu(i) = alpha*mu(i-1) + (1-alpha)*mhat
+ *   C    = A/n - mhat mu(i)^T - mu(i) mhat^T + mu(i) mu(i)^T        (the covariance centred on mu(i), expanded)
+ *   Phi_x(i) = alpha*Phi_x(i-1) + (1-alpha)*C;   phi_x(i) = alpha*phi_x(i-1) + (1-alpha)*diag(A)/n
+ *   lambda_bar = mean(phi_x(i));   first_block != 0 drops the recursive average (alpha is ignored).
+ *   A, s     in   sums from fw_cov_accumulate (lower triangle of A is read)
+ *   n        total number of rows accumulated into A and s
+ *   mu       i/o  [M]     in: mu(i-1), out: mu(i)
+ *   Phi_x    i/o  [M, M]  in: Phi_x(i-1), out: Phi_x(i), written as a full symmetric matrix
+ *   phi_x    i/o  [M]
+ *   lambda_bar out one float on the device
+ * Evaluated in float64 per element, stored as float32.
+ */
+fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, float alpha, int first_block,
+                          float* mu, float* Phi_x, float* phi_x, float* lambda_bar, void* stream);
+
+/* ------------------------------------------------------------------------------------------------------------
+ * (2) Gradient transformation -- eqs. (mod_weight_grad), (vQ) of Sec. 3.1:  G_out = G Q,  Q = T^T T.
+ *
+ *   G      in   [S, M] element type `dt`
+ *   Q      in   [M, M] float32, symmetric (Q or its smoothed version Q_s, eq. (vQs)); may be NULL if T is given
+ *   T      in   [M, M] float32 or NULL.  Used only when Q is NULL: Q = T^T T is then built in the workspace first.
+ *   G_out  out  [S, M] element type `dt`; must not overlap G
+ *   ws     scratch, fw_workspace_bytes(FW_OP_GRAD_TRANSFORM, M, S, NULL, dt) bytes (only needed when Q is NULL)
+ * dt = FW_F32: float32 matrix-core products.  dt = FW_BF16: Q is rounded to bfloat16 on the fly, products are
+ * bf16 x bf16 accumulated in float32, G_out is rounded to bfloat16 (nearest even).
+ */
+fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const float* T, const float* Q,
+                            void* G_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------------------
+ * (3) Recursive condition-number reduction -- Sec. 4 (eqs. (lambda)-(vQ_rec), (xim)-(tve)).
+ */
+typedef struct {
+    float gamma;        /* leakage factor, 0 < gamma <= 1                      eq. (vT_rec) */
+    float delta;        /* power-reduction target factor, > 0                  eq. (ge)     */
+    float eps;          /* lower bound of the denominator, > 0                 eq. (ge)     */
+    float c_rel;        /* relative coherence threshold                        Sec. 4.2     */
+    float c_abs;        /* absolute coherence threshold                        Sec. 4.2     */
+    float beta;         /* smoothing factor of Q_s, 0 <= beta < 1              eq. (vQs)    */
+    int n_power_iters;  /* extra refinements v <- Phi_y v/|Phi_y v| of the estimate (0 = the paper's estimator) */
+    int guard;          /* != 0: skip the shrink when it would amplify (g_e >= 1); the leak is still applied */
+} fw_cond_params;
+
+/* State of one layer; all pointers are device pointers to caller-owned [M, M] float32 matrices unless noted. */
+typedef struct {
+    int M;
+    const float* Phi_x;     /* in:  covariance of the block, symmetric (from fw_cov_finalize)          */
+    const float* lambda_bar;/* in:  one float on the device, average input power, eq. (blambday)       */
+    float* T;               /* i/o: whitening matrix (non-symmetric in general)                         */
+    float* Q;               /* i/o: T^T T, maintained by eq. (vQ_rec)                                   */
+    float* Qs;              /* i/o: smoothed Q, eq. (vQs)                                               */
+    float* Phi_y;           /* i/o: T Phi_x T^T, maintained by O(M^2) updates                           */
+    float* Psi;             /* i/o: T Phi_x, needed for the update of Phi_y when gamma < 1; may be NULL if gamma == 1 */
+    float* xi2;             /* i/o: [M] squared column norms of Phi_y, carried from step to step        */
+} fw_cond_state;
+
+/* Diagnostics of one step, written to device memory. */
+typedef struct {
+    float lambda_e, g_e, a_e, v_norm;  /* eq. (lambda), eq. (ge), eq. (xi) as applied (0 if skipped), |v~| */
+    int m_prime, set_size;            /* eq. (mt), |set| of Sec. 4.2 */
+    int applied;                      /* 1 if the shrink was applied, 0 if only the leak */
+    int flags;                        /* bit 0: coherence set empty; bit 1: skipped by the guard; bit 2: non-finite value seen */
+} fw_cond_info;
+
+/* T = Q = Qs = I, Phi_y = Psi = Phi_x, xi2 = squared column norms of Phi_x  (eqs. (vT_init), Qs(-1) = I). */
+fw_status fw_cond_state_init(const fw_cond_state* st, void* stream);
+
+/* One step: estimate the high-power direction v of Phi_y (Sec. 4.2), lambda_e, g_e, a_e (eqs. (lambda), (ge), (xi)),
+ * t = T^T v, then in one pass T <- gamma (T + a v t^T) + (1-gamma) I (eq. (vT_rec)), Q by eq. (vQ_rec),
+ * Qs <- beta Qs + (1-beta) Q (eq. (vQs)), and Phi_y, Psi, xi2 brought up to date for the new T.
+ *   info_dev  out  one fw_cond_info on the device (may be NULL)
+ *   ws        scratch, fw_workspace_bytes(FW_OP_COND_REDUCE_STEP, M, 0, NULL, FW_F32) bytes
+ * Phi_y is taken as symmetric (its rows are read where the paper names columns).  Ties of the arg-max go to the
+ * lowest index.
+ */
+fw_status fw_cond_reduce_step(const fw_cond_state* st, const fw_cond_params* p, fw_cond_info* info_dev,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------------------
+ * (4) EVD / ZCA reference -- eqs. (vPhix_evd), (vT_EVD), (vg) of Sec. 2; gain variant eqs. (hMs), (g_mod) of Sec. 3.2.
+ */
+typedef struct {
+    float eps;        /* eq. (vg) */
+    float g_max;      /* eq. (g_mod), gain_mode 1 only */
+    float beta;       /* smoothing of Qs when Qs != NULL, eq. (vQs) */
+    float tol;        /* rotation threshold of the Jacobi sweeps (relative); <= 0 selects the default 1e-12 */
+    int gain_mode;    /* 0: g = 1/max(lambda, eps); 1: g = min(1/(M lambda_bar_m), g_max) on the signal subspace, 1 elsewhere */
+    int max_sweeps;   /* <= 0 selects the default 30 */
+} fw_evd_params;
+
+/*   Phi_x   in   [M, M] symmetric
+ *   T, Q    out  [M, M]: T = V diag(sqrt g) V^T, Q = V diag(g) V^T
+ *   Qs      i/o  [M, M] or NULL: Qs <- beta Qs + (1-beta) Q
+ *   lambda  out  [M] eigenvalues, decreasing
+ *   ws      scratch, fw_workspace_bytes(FW_OP_WHITEN_EVD, M, 0, NULL, FW_F32) bytes
+ * The decomposition is a one-sided Jacobi iteration carried out in float64 inside the workspace; the call blocks
+ * once per sweep to read the rotation count.
+ */
+fw_status fw_whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float* T, float* Q, float* Qs,
+                        float* lambda, void* ws, size_t ws_bytes, void* stream);
+
+/* Scratch bytes an entry point needs for the given sizes (0 if none).  `d` is needed for FW_OP_COV_ACCUMULATE only. */
+size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtype dt);
+
+const char* fw_status_string(fw_status st);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int fw_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FW_H */

@@ -1,0 +1,146 @@
+// C ABI of the feature-whitening library: argument validation, workspace carving, dispatch to the kernels.
+#include "fw_internal.h"
+
+using namespace fw;
+
+namespace {
+
+bool desc_ok(const fw_conv_desc* d, fw_layout lay) {
+    if (!d) return false;
+    if (d->B <= 0 || d->Cin <= 0 || d->H <= 0 || d->W <= 0 || d->kh <= 0 || d->kw <= 0 || d->stride <= 0 || d->pad < 0) return false;
+    if (d->H + 2 * d->pad < d->kh || d->W + 2 * d->pad < d->kw) return false;
+    if (d->pad > 0 && (d->pad >= d->kh || d->pad >= d->kw)) return false;  // a window lying wholly in the padding
+    if (lay == FW_LAYOUT_ROWS && (d->H != 1 || d->W != 1 || d->kh != 1 || d->kw != 1 || d->stride != 1 || d->pad != 0)) return false;
+    return true;
+}
+
+bool dtype_ok(fw_dtype dt) { return dt == FW_F32 || dt == FW_BF16; }
+bool layout_ok(fw_layout l) { return l == FW_LAYOUT_ROWS || l == FW_LAYOUT_NCHW || l == FW_LAYOUT_NHWC; }
+
+size_t grad_ws_bytes(int M) {
+    fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0};
+    return align_up((size_t)M * M * sizeof(float), 256) + align_up((size_t)M * sizeof(float), 256) +
+           cov_workspace_bytes(M, &d, FW_F32, FW_LAYOUT_ROWS);
+}
+
+}  // namespace
+
+extern "C" {
+
+fw_status fw_cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,
+                            size_t ws_bytes, void* stream) {
+    if (!X || !A || !s || !d || !dtype_ok(dt) || !layout_ok(lay) || !desc_ok(d, lay)) return FW_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(A) || !aligned16(s) || (ws && !aligned16(ws))) return FW_ERR_ALIGNMENT;
+    const size_t need = cov_workspace_bytes(0, d, dt, lay);
+    if (need == 0) return FW_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < need) return FW_ERR_WORKSPACE;
+    return cov_accumulate(X, dt, lay, d, A, s, ws, ws_bytes, reinterpret_cast<hipStream_t>(stream));
+}
+
+fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, float alpha, int first_block, float* mu, float* Phi_x,
+                          float* phi_x, float* lambda_bar, void* stream) {
+    if (!A || !s || !mu || !Phi_x || !phi_x || !lambda_bar || n <= 0 || M <= 0) return FW_ERR_INVALID_ARG;
+    if (!first_block && !(alpha >= 0.f && alpha < 1.f)) return FW_ERR_INVALID_ARG;
+    if (!aligned16(A) || !aligned16(s) || !aligned16(mu) || !aligned16(Phi_x) || !aligned16(phi_x)) return FW_ERR_ALIGNMENT;
+    return cov_finalize(A, s, n, M, alpha, first_block ? 1 : 0, mu, Phi_x, phi_x, lambda_bar, reinterpret_cast<hipStream_t>(stream));
+}
+
+fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const float* T, const float* Q, void* G_out, void* ws,
+                            size_t ws_bytes, void* stream) {
+    if (!G || !G_out || S <= 0 || M <= 0 || !dtype_ok(dt) || (!Q && !T) || G == G_out) return FW_ERR_INVALID_ARG;
+    if (M > 16384) return FW_ERR_UNSUPPORTED;
+    if (!aligned16(G) || !aligned16(G_out) || (Q && !aligned16(Q)) || (T && !aligned16(T)) || (ws && !aligned16(ws)))
+        return FW_ERR_ALIGNMENT;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!Q) {
+        if (!ws || ws_bytes < grad_ws_bytes(M)) return FW_ERR_WORKSPACE;
+        char* base = reinterpret_cast<char*>(ws);
+        float* Qb = reinterpret_cast<float*>(base);
+        const size_t qbytes = align_up((size_t)M * M * sizeof(float), 256);
+        float* sdummy = reinterpret_cast<float*>(base + qbytes);
+        const size_t sbytes = align_up((size_t)M * sizeof(float), 256);
+        const fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0};
+        fw_status rc = fill_f32(Qb, (size_t)M * M, 0.f, st);
+        if (rc != FW_OK) return rc;
+        rc = fill_f32(sdummy, (size_t)M, 0.f, st);
+        if (rc != FW_OK) return rc;
+        // Q = T^T T: the rows of T are the "samples" of a symmetric rank-M update (eq. (vQ))
+        rc = cov_accumulate(T, FW_F32, FW_LAYOUT_ROWS, &d, Qb, sdummy, base + qbytes + sbytes, ws_bytes - qbytes - sbytes, st);
+        if (rc != FW_OK) return rc;
+        rc = symmetrize_from_lower(Qb, M, st);
+        if (rc != FW_OK) return rc;
+        Q = Qb;
+    }
+    return grad_gemm(G, dt, S, M, Q, G_out, st);
+}
+
+fw_status fw_cond_state_init(const fw_cond_state* st, void* stream) {
+    if (!st || st->M <= 0 || !st->Phi_x || !st->T || !st->Q || !st->Qs || !st->Phi_y || !st->xi2) return FW_ERR_INVALID_ARG;
+    if (!aligned16(st->Phi_x) || !aligned16(st->T) || !aligned16(st->Q) || !aligned16(st->Qs) || !aligned16(st->Phi_y) ||
+        !aligned16(st->xi2) || (st->Psi && !aligned16(st->Psi)))
+        return FW_ERR_ALIGNMENT;
+    return cond_state_init(st, reinterpret_cast<hipStream_t>(stream));
+}
+
+fw_status fw_cond_reduce_step(const fw_cond_state* st, const fw_cond_params* p, fw_cond_info* info_dev, void* ws, size_t ws_bytes,
+                              void* stream) {
+    if (!st || !p || st->M <= 0 || !st->Phi_x || !st->lambda_bar || !st->T || !st->Q || !st->Qs || !st->Phi_y || !st->xi2)
+        return FW_ERR_INVALID_ARG;
+    if (!(p->gamma > 0.f && p->gamma <= 1.f) || !(p->delta > 0.f) || !(p->eps > 0.f) || !(p->beta >= 0.f && p->beta < 1.f) ||
+        !(p->c_rel >= 0.f) || !(p->c_abs >= 0.f) || p->n_power_iters < 0 || p->n_power_iters > 1024)
+        return FW_ERR_INVALID_ARG;
+    if (p->gamma < 1.f && !st->Psi) return FW_ERR_INVALID_ARG;
+    if (st->M > 16384) return FW_ERR_UNSUPPORTED;
+    if (!aligned16(st->Phi_x) || !aligned16(st->T) || !aligned16(st->Q) || !aligned16(st->Qs) || !aligned16(st->Phi_y) ||
+        !aligned16(st->xi2) || (st->Psi && !aligned16(st->Psi)) || (ws && !aligned16(ws)))
+        return FW_ERR_ALIGNMENT;
+    if (!ws || ws_bytes < cond_workspace_bytes(st->M)) return FW_ERR_WORKSPACE;
+    return cond_reduce_step(st, p, info_dev, ws, reinterpret_cast<hipStream_t>(stream));
+}
+
+fw_status fw_whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float* T, float* Q, float* Qs, float* lambda, void* ws,
+                        size_t ws_bytes, void* stream) {
+    if (!Phi_x || !p || !T || !Q || !lambda || M <= 0) return FW_ERR_INVALID_ARG;
+    if (!(p->eps > 0.f) || (p->gain_mode != 0 && p->gain_mode != 1) || (p->gain_mode == 1 && !(p->g_max > 0.f)) ||
+        (Qs && !(p->beta >= 0.f && p->beta < 1.f)))
+        return FW_ERR_INVALID_ARG;
+    if (M > 16384) return FW_ERR_UNSUPPORTED;
+    if (!aligned16(Phi_x) || !aligned16(T) || !aligned16(Q) || !aligned16(lambda) || (Qs && !aligned16(Qs)) || (ws && !aligned16(ws)))
+        return FW_ERR_ALIGNMENT;
+    if (!ws || ws_bytes < evd_workspace_bytes(M)) return FW_ERR_WORKSPACE;
+    return whiten_evd(Phi_x, M, p, T, Q, Qs, lambda, ws, ws_bytes, reinterpret_cast<hipStream_t>(stream));
+}
+
+size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtype dt) {
+    (void)S;
+    switch (op) {
+        case FW_OP_COV_ACCUMULATE: {
+            if (!d || !dtype_ok(dt)) return 0;
+            // the layout does not change the size: rows and tensors of one geometry split alike
+            const bool rows = d->H == 1 && d->W == 1 && d->kh == 1 && d->kw == 1;
+            if (!desc_ok(d, rows ? FW_LAYOUT_ROWS : FW_LAYOUT_NHWC)) return 0;
+            return cov_workspace_bytes(M, d, dt, FW_LAYOUT_NHWC);
+        }
+        case FW_OP_GRAD_TRANSFORM: return M > 0 && M <= 16384 ? grad_ws_bytes(M) : 0;
+        case FW_OP_COND_REDUCE_STEP: return M > 0 && M <= 16384 ? cond_workspace_bytes(M) : 0;
+        case FW_OP_WHITEN_EVD: return M > 0 && M <= 16384 ? evd_workspace_bytes(M) : 0;
+    }
+    return 0;
+}
+
+const char* fw_status_string(fw_status st) {
+    switch (st) {
+        case FW_OK: return "ok";
+        case FW_ERR_INVALID_ARG: return "invalid argument";
+        case FW_ERR_UNSUPPORTED: return "unsupported size or mode";
+        case FW_ERR_ALIGNMENT: return "device pointer not 16-byte aligned";
+        case FW_ERR_WORKSPACE: return "workspace missing or too small";
+        case FW_ERR_HIP: return "HIP runtime error";
+        case FW_ERR_NOT_CONVERGED: return "eigen-decomposition did not converge";
+    }
+    return "unknown status";
+}
+
+int fw_version(void) { return 100; }
+
+}  // extern "C"

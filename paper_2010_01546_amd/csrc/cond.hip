@@ -1,0 +1,354 @@
+// Recursive condition-number reduction (Sec. 4) for gfx950: one step is a chain of bandwidth-bound passes over
+// M x M float32 matrices.
+//
+//   estimate (Sec. 4.2):  m' = argmax xi   ->  c = Phi_y Phi_y e_m'  ->  coherence set, weights w  ->
+//                         v~ = Phi_y w  ->  v = v~/|v~|   [optional refinements v <- Phi_y v / |Phi_y v|]
+//   step (Sec. 4.1):      u = Phi_y v, lambda_e = v^T u, g_e, a_e;  t = T^T v;  p = Phi_x t (only if gamma < 1)
+//   update, one fused pass over pairs of mirrored 32x32 tiles:
+//       T'     = gamma (T + a v t^T) + (1-gamma) I                                               eq. (vT_rec)
+//       Q'     = gamma^2 (Q + a(a+2) t t^T) + (1-gamma)^2 I
+//                + gamma(1-gamma) (a (v t^T + t v^T) + T + T^T)                                  eq. (vQ_rec)
+//       Qs'    = beta Qs + (1-beta) Q'                                                           eq. (vQs)
+//       Phi_y' = gamma^2 (Phi_y + a (v u^T + u v^T) + a^2 lambda_e v v^T)
+//                + gamma(1-gamma) (Psi + Psi^T + a (v p^T + p v^T)) + (1-gamma)^2 Phi_x          (= T' Phi_x T'^T)
+//       Psi'   = gamma (Psi + a v p^T) + (1-gamma) Phi_x                                         (= T' Phi_x)
+//     and the squared row norms of Phi_y' for the next step's arg-max.
+// t = T^T v (the transposed reading of eq. (vtve)) is what makes T' equal gamma T~ T + (1-gamma) I.
+// Matrix-vector products use one wavefront per row with a 64-lane shuffle reduction.
+#include "fw_internal.h"
+
+namespace fw {
+namespace {
+
+struct Scal {
+    int m_prime, set_size, applied, flags;
+    float xi_mp, lambda_e, g_e, a_e, vnorm;
+};
+
+constexpr int TILE = 32;
+constexpr int VM_ROWS = 256;  // rows per workgroup in the T^T v partial products
+
+struct WsLayout {
+    size_t c, w, vt, v, u, t, p, tpart, xpart, scal, total;
+    int Mp, nrb, nt;
+};
+inline WsLayout ws_layout(int M) {
+    WsLayout L;
+    L.Mp = (M + 63) / 64 * 64;
+    L.nrb = (M + VM_ROWS - 1) / VM_ROWS;
+    L.nt = (M + TILE - 1) / TILE;
+    size_t o = 0;
+    auto take = [&](size_t floats) { size_t at = o; o += align_up(floats * sizeof(float), 256); return at; };
+    L.c = take(L.Mp); L.w = take(L.Mp); L.vt = take(L.Mp); L.v = take(L.Mp); L.u = take(L.Mp); L.t = take(L.Mp); L.p = take(L.Mp);
+    L.tpart = take((size_t)L.nrb * L.Mp);
+    L.xpart = take((size_t)L.nt * L.Mp);
+    L.scal = take(64);
+    L.total = o;
+    return L;
+}
+
+// block-wide helpers for single-workgroup kernels of 1024 threads
+__device__ __forceinline__ float block_sum(float v, float* red) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += red[i];
+    return t;
+}
+
+// m' = argmax_m xi2[m], lowest index on ties (eq. (mt))
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ xi2, int M, Scal* __restrict__ sc) {
+    __shared__ float bv[16];
+    __shared__ int bi[16];
+    float best = -1.f;
+    int idx = 0x7fffffff;
+    for (int m = threadIdx.x; m < M; m += blockDim.x) {
+        const float v = xi2[m];
+        if (v > best) { best = v; idx = m; }   // strided ascending scan keeps the lowest index per thread
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o, 64);
+        const int oi = __shfl_xor(idx, o, 64);
+        if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = idx; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < (int)(blockDim.x >> 6); ++i)
+            if (bv[i] > best || (bv[i] == best && bi[i] < idx)) { best = bv[i]; idx = bi[i]; }
+        sc->m_prime = idx;
+        sc->xi_mp = sqrtf(fmaxf(best, 0.f));
+        sc->flags = 0;
+    }
+}
+
+// y[r] = P[r,:] . x, one wavefront per row.  x_row_from_scal: x is row sc->m_prime of P (c of eq. (vc)).
+__global__ __launch_bounds__(256) void matvec_kernel(const float* __restrict__ P, const float* __restrict__ x, const Scal* __restrict__ sc,
+                                                     int x_row_from_scal, int M, float* __restrict__ y) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;
+    const float* xv = x_row_from_scal ? P + (size_t)sc->m_prime * M : x;
+    const float* row = P + (size_t)r * M;
+    float acc = 0.f;
+    if ((M & 3) == 0) {
+        const float4* r4 = reinterpret_cast<const float4*>(row);
+        const float4* x4 = reinterpret_cast<const float4*>(xv);
+        for (int k = lane; k < (M >> 2); k += 64) {
+            const float4 a = r4[k], b = x4[k];
+            acc += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+        }
+    } else {
+        for (int k = lane; k < M; k += 64) acc += row[k] * xv[k];
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) y[r] = acc;
+}
+
+// coherence set and alignment weights: w_m = 1/(|set| c_m) on the set, 0 elsewhere (rule after eq. (vc), eq. (tve))
+__global__ __launch_bounds__(1024) void build_w_kernel(const float* __restrict__ c, const float* __restrict__ xi2, int M, float c_rel,
+                                                       float c_abs, Scal* __restrict__ sc, float* __restrict__ w) {
+    __shared__ float red[16];
+    const float xi_mp = sc->xi_mp;
+    float cnt = 0.f;
+    for (int m = threadIdx.x; m < M; m += blockDim.x) {
+        const float thr = fmaxf(c_rel * xi_mp * sqrtf(fmaxf(xi2[m], 0.f)), c_abs);
+        cnt += (fabsf(c[m]) >= thr) ? 1.f : 0.f;
+    }
+    const float total = block_sum(cnt, red);
+    for (int m = threadIdx.x; m < M; m += blockDim.x) {
+        const float thr = fmaxf(c_rel * xi_mp * sqrtf(fmaxf(xi2[m], 0.f)), c_abs);
+        const float cm = c[m];
+        w[m] = (fabsf(cm) >= thr) ? 1.f / (total * cm) : 0.f;
+    }
+    if (threadIdx.x == 0) {
+        sc->set_size = (int)total;
+        if (total == 0.f) sc->flags |= 1;
+    }
+}
+
+// v = vt / |vt| (second line of eq. (tve)); an empty set gives v = 0
+__global__ __launch_bounds__(1024) void normalize_kernel(const float* __restrict__ vt, int M, Scal* __restrict__ sc, float* __restrict__ v) {
+    __shared__ float red[16];
+    float ss = 0.f;
+    for (int m = threadIdx.x; m < M; m += blockDim.x) ss += vt[m] * vt[m];
+    const float nrm = sqrtf(block_sum(ss, red));
+    const float inv = (nrm > 0.f && (sc->flags & 1) == 0) ? 1.f / nrm : 0.f;
+    for (int m = threadIdx.x; m < M; m += blockDim.x) v[m] = vt[m] * inv;
+    if (threadIdx.x == 0) {
+        sc->vnorm = nrm;
+        if (!(nrm == nrm) || nrm > 3.0e38f) sc->flags |= 4;
+    }
+}
+
+// partial products of t = T^T v over blocks of VM_ROWS rows: tpart[rb][j] = sum_{i in rb} T[i][j] v[i]
+__global__ __launch_bounds__(256) void vecmat_partial_kernel(const float* __restrict__ T, const float* __restrict__ v, int M, int Mp,
+                                                             float* __restrict__ tpart) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int i0 = blockIdx.y * VM_ROWS;
+    const int i1 = min(M, i0 + VM_ROWS);
+    if (j >= M) return;
+    float acc = 0.f;
+    for (int i = i0; i < i1; ++i) acc += T[(size_t)i * M + j] * v[i];
+    tpart[(size_t)blockIdx.y * Mp + j] = acc;
+}
+
+// t = sum of partials; lambda_e = v^T u (eq. (lambda)); g_e, a_e (eqs. (ge), (xi)); guard; diagnostics
+__global__ __launch_bounds__(1024) void scalars_kernel(const float* __restrict__ v, const float* __restrict__ u,
+                                                       const float* __restrict__ tpart, int nrb, int M, int Mp,
+                                                       const float* __restrict__ lambda_bar, fw_cond_params prm, Scal* __restrict__ sc,
+                                                       float* __restrict__ t, fw_cond_info* __restrict__ info) {
+    __shared__ float red[16];
+    float dot = 0.f;
+    for (int m = threadIdx.x; m < M; m += blockDim.x) {
+        float acc = 0.f;
+        for (int b = 0; b < nrb; ++b) acc += tpart[(size_t)b * Mp + m];
+        t[m] = acc;
+        dot += v[m] * u[m];
+    }
+    const float lam_e = block_sum(dot, red);
+    if (threadIdx.x == 0) {
+        int flags = sc->flags;
+        float g_e = 1.f, a_e = 0.f;
+        int applied = 0;
+        if ((flags & 1) == 0) {
+            g_e = prm.delta * (*lambda_bar) / fmaxf(lam_e, prm.eps);
+            if (prm.guard && g_e >= 1.f) flags |= 2;
+            else if (!(g_e == g_e) || g_e > 3.0e38f) flags |= 4;
+            else { a_e = sqrtf(g_e) - 1.f; applied = 1; }
+        }
+        sc->lambda_e = (flags & 1) ? 0.f : lam_e;
+        sc->g_e = g_e; sc->a_e = a_e; sc->applied = applied; sc->flags = flags;
+        if (info) {
+            info->lambda_e = sc->lambda_e; info->g_e = g_e; info->a_e = a_e; info->v_norm = sc->vnorm;
+            info->m_prime = sc->m_prime; info->set_size = sc->set_size; info->applied = applied; info->flags = flags;
+        }
+    }
+}
+
+// Fused update over the pair of mirrored tiles (I,J) and (J,I), I >= J.
+__global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const float* __restrict__ v, const float* __restrict__ u,
+                                                     const float* __restrict__ t, const float* __restrict__ p, const Scal* __restrict__ sc,
+                                                     float gamma, float beta, int Mp, float* __restrict__ xpart) {
+    const int I = blockIdx.y, J = blockIdx.x;
+    if (J > I) return;
+    const int M = s.M;
+    const bool leak = gamma < 1.f;
+    __shared__ float Ta[TILE][TILE + 1], Tb[TILE][TILE + 1], Pa[TILE][TILE + 1], Pb[TILE][TILE + 1];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const float a = sc->a_e, lam = sc->lambda_e;
+    const float g1 = 1.f - gamma, g2 = gamma * gamma, gg1 = gamma * g1, g1sq = g1 * g1, b1 = 1.f - beta;
+    const float aa2 = a * (a + 2.f), a2lam = a * a * lam;
+
+    // stage the old T and Psi tiles of both positions (only needed for the transposed terms)
+    if (leak) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int yy = ty + 8 * r;
+            const int ia = I * TILE + yy, ja = J * TILE + tx;   // position a
+            const int ib = J * TILE + yy, jb = I * TILE + tx;   // position b (mirrored tile)
+            const bool oka = ia < M && ja < M, okb = ib < M && jb < M;
+            Ta[yy][tx] = oka ? s.T[(size_t)ia * M + ja] : 0.f;
+            Pa[yy][tx] = oka ? s.Psi[(size_t)ia * M + ja] : 0.f;
+            Tb[yy][tx] = okb ? s.T[(size_t)ib * M + jb] : 0.f;
+            Pb[yy][tx] = okb ? s.Psi[(size_t)ib * M + jb] : 0.f;
+        }
+        __syncthreads();
+    }
+
+    const int npos = (I == J) ? 1 : 2;
+    for (int pos = 0; pos < npos; ++pos) {
+        const int rowblk = pos == 0 ? I : J, colblk = pos == 0 ? J : I;
+        const int j = colblk * TILE + tx;
+        const float vj = j < M ? v[j] : 0.f, uj = j < M ? u[j] : 0.f, tj = j < M ? t[j] : 0.f;
+        const float pj = (leak && j < M) ? p[j] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int yy = ty + 8 * r;
+            const int i = rowblk * TILE + yy;
+            float sq = 0.f;
+            if (i < M && j < M) {
+                const size_t e = (size_t)i * M + j;
+                const float vi = v[i], ui = u[i], ti = t[i];
+                const float dij = (i == j) ? 1.f : 0.f;
+                float Told, Tt = 0.f, Psiold = 0.f, Psit = 0.f, phix = 0.f, pi = 0.f;
+                if (leak) {
+                    // own element from the staged tile, transposed element from the mirrored tile
+                    Told = pos == 0 ? Ta[yy][tx] : Tb[yy][tx];
+                    Psiold = pos == 0 ? Pa[yy][tx] : Pb[yy][tx];
+                    if (I == J) { Tt = Ta[tx][yy]; Psit = Pa[tx][yy]; }
+                    else { Tt = pos == 0 ? Tb[tx][yy] : Ta[tx][yy]; Psit = pos == 0 ? Pb[tx][yy] : Pa[tx][yy]; }
+                    phix = s.Phi_x[e];
+                    pi = p[i];
+                } else {
+                    Told = s.T[e];
+                }
+                const float Tn = gamma * (Told + a * vi * tj) + g1 * dij;
+                float Qn = g2 * (s.Q[e] + aa2 * (ti * tj)) + g1sq * dij;
+                float Yn = g2 * (s.Phi_y[e] + a * (vi * uj + ui * vj) + a2lam * (vi * vj));
+                if (leak) {
+                    Qn += gg1 * (a * (vi * tj + ti * vj) + Told + Tt);
+                    Yn += gg1 * (Psiold + Psit + a * (vi * pj + pi * vj)) + g1sq * phix;
+                    s.Psi[e] = gamma * (Psiold + a * vi * pj) + g1 * phix;
+                }
+                s.T[e] = Tn;
+                s.Q[e] = Qn;
+                s.Qs[e] = beta * s.Qs[e] + b1 * Qn;
+                s.Phi_y[e] = Yn;
+                sq = Yn * Yn;
+            }
+            // sum over the 32 lanes that share row i
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+            if (tx == 0 && i < M) xpart[(size_t)colblk * Mp + i] = sq;
+        }
+    }
+}
+
+// xi2[m] = sum over tile columns of the partial squared row norms
+__global__ __launch_bounds__(256) void xi2_reduce_kernel(const float* __restrict__ xpart, int nt, int M, int Mp, float* __restrict__ xi2) {
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= M) return;
+    float acc = 0.f;
+    for (int b = 0; b < nt; ++b) acc += xpart[(size_t)b * Mp + m];
+    xi2[m] = acc;
+}
+
+__global__ __launch_bounds__(256) void state_init_kernel(fw_cond_state s) {
+    const int M = s.M;
+    const size_t n = (size_t)M * M;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256) {
+        const int i = (int)(e / M), j = (int)(e - (size_t)i * M);
+        const float d = i == j ? 1.f : 0.f;
+        const float ph = s.Phi_x[e];
+        s.T[e] = d; s.Q[e] = d; s.Qs[e] = d;
+        s.Phi_y[e] = ph;
+        if (s.Psi) s.Psi[e] = ph;
+    }
+}
+
+__global__ __launch_bounds__(256) void rownorm2_kernel(const float* __restrict__ P, int M, float* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;
+    float acc = 0.f;
+    for (int k = lane; k < M; k += 64) { const float x = P[(size_t)r * M + k]; acc += x * x; }
+    acc = wave_sum(acc);
+    if (lane == 0) out[r] = acc;
+}
+
+}  // namespace
+
+size_t cond_workspace_bytes(int M) { return ws_layout(M).total; }
+
+fw_status cond_state_init(const fw_cond_state* s, hipStream_t st) {
+    const size_t n = (size_t)s->M * s->M;
+    int blocks = (int)((n + 255) / 256);
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(state_init_kernel, dim3(blocks), dim3(256), 0, st, *s);
+    FW_LAUNCH_CHECK();
+    hipLaunchKernelGGL(rownorm2_kernel, dim3((s->M + 3) / 4), dim3(256), 0, st, s->Phi_x, s->M, s->xi2);
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
+fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_cond_info* info, void* ws, hipStream_t st) {
+    const int M = s->M;
+    const WsLayout L = ws_layout(M);
+    char* base = reinterpret_cast<char*>(ws);
+    float* c = reinterpret_cast<float*>(base + L.c);
+    float* w = reinterpret_cast<float*>(base + L.w);
+    float* vt = reinterpret_cast<float*>(base + L.vt);
+    float* v = reinterpret_cast<float*>(base + L.v);
+    float* u = reinterpret_cast<float*>(base + L.u);
+    float* t = reinterpret_cast<float*>(base + L.t);
+    float* pv = reinterpret_cast<float*>(base + L.p);
+    float* tpart = reinterpret_cast<float*>(base + L.tpart);
+    float* xpart = reinterpret_cast<float*>(base + L.xpart);
+    Scal* sc = reinterpret_cast<Scal*>(base + L.scal);
+    const dim3 mv_grid((M + 3) / 4), mv_blk(256);
+
+    hipLaunchKernelGGL(argmax_kernel, dim3(1), dim3(1024), 0, st, s->xi2, M, sc);
+    hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, (const float*)nullptr, sc, 1, M, c);
+    hipLaunchKernelGGL(build_w_kernel, dim3(1), dim3(1024), 0, st, c, s->xi2, M, p->c_rel, p->c_abs, sc, w);
+    hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, w, sc, 0, M, vt);
+    hipLaunchKernelGGL(normalize_kernel, dim3(1), dim3(1024), 0, st, vt, M, sc, v);
+    for (int it = 0; it < p->n_power_iters; ++it) {
+        hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, v, sc, 0, M, vt);
+        hipLaunchKernelGGL(normalize_kernel, dim3(1), dim3(1024), 0, st, vt, M, sc, v);
+    }
+    hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, v, sc, 0, M, u);
+    hipLaunchKernelGGL(vecmat_partial_kernel, dim3((M + 255) / 256, L.nrb), dim3(256), 0, st, s->T, v, M, L.Mp, tpart);
+    hipLaunchKernelGGL(scalars_kernel, dim3(1), dim3(1024), 0, st, v, u, tpart, L.nrb, M, L.Mp, s->lambda_bar, *p, sc, t, info);
+    if (p->gamma < 1.f)
+        hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_x, t, sc, 0, M, pv);
+    hipLaunchKernelGGL(update_kernel, dim3(L.nt, L.nt), dim3(256), 0, st, *s, v, u, t, pv, sc, p->gamma, p->beta, L.Mp, xpart);
+    hipLaunchKernelGGL(xi2_reduce_kernel, dim3((M + 255) / 256), dim3(256), 0, st, xpart, L.nt, M, L.Mp, s->xi2);
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
+}  // namespace fw

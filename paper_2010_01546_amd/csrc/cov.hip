@@ -1,0 +1,452 @@
+// Moment accumulation (the block sums of Sec. 2, eqs. (vmuxi)/(vPhixi), and Sec. 4.1, eq. (phixmi)) and the
+// block-moment epilogue, for gfx950.
+//
+// A += X^T X over the patch rows of a layer input is a symmetric rank-N_rows update.  The output is cut into
+// 64x64 blocks of the lower triangle; one wavefront owns one block (2x2 MFMA 32x32 tiles) and four wavefronts
+// that share operand panels form a workgroup.  The reduction axis (patch rows) is split across workgroups;
+// partial blocks go to the workspace and a second kernel sums them in float64 and adds them into A.
+// Patch rows are never materialised: every staged element is gathered from the activation tensor through a
+// per-row table (image, top-left corner) and a per-feature offset (tap, channel), zero outside the image.
+//
+// Internally features are ordered tap-major / channel-minor for NHWC and ROWS inputs so that consecutive lanes
+// read consecutive channels; the reduce kernel maps back to the external order m = (c*kh + ky)*kw + kx.
+#include "fw_internal.h"
+
+namespace fw {
+namespace {
+
+constexpr int BLK = 64;        // features per operand panel = edge of a wavefront's output block
+constexpr int MAX_SLOTS = 5;   // operand panels a workgroup may stage
+constexpr int KT_F32 = 16;     // patch rows per staged chunk, float32 path
+constexpr int KT_BF16 = 32;    // patch rows per staged chunk, bfloat16 path
+constexpr int BF16_ROW_BYTES = KT_BF16 * 2 + 16;  // K-major LDS row of one feature, padded, 16-byte aligned
+
+struct CovGeom {
+    int n_rows, M, nb;
+    int B, Cin, H, W, kh, kw, stride, pad, Ho, Wo;
+    int layout;
+    int rows_per_split, nsplit;
+    int n0, n1, n2, nitems;
+};
+
+struct Item {
+    int slot_blk[MAX_SLOTS];  // 64-feature block staged in each LDS slot, -1 = unused
+    int ja[4], jb[4];         // per wavefront: slots of the row panel and the column panel of its block, -1 = idle
+    int summask;              // slots whose column sums this workgroup accumulates
+};
+
+// Closed-form enumeration of workgroup items covering every 64x64 block (bi >= bj) of the lower triangle once.
+//  type 0: 2x2 squares of blocks strictly below the diagonal of the 128-block grid
+//  type 1: diagonal 128-blocks (three 64-blocks)
+//  type 2: when the number of 64-blocks is odd, the last block row including its diagonal block, four per item
+__device__ __host__ inline Item get_item(int idx, int nb) {
+    Item it;
+    for (int i = 0; i < MAX_SLOTS; ++i) it.slot_blk[i] = -1;
+    for (int w = 0; w < 4; ++w) it.ja[w] = it.jb[w] = -1;
+    it.summask = 0;
+    const int h = nb >> 1;
+    const int n0 = h * (h - 1) / 2, n1 = h;
+    if (idx < n0) {
+        int I = 1;
+        while ((I + 1) * I / 2 <= idx) ++I;  // I*(I-1)/2 <= idx < (I+1)*I/2
+        const int J = idx - I * (I - 1) / 2;
+        it.slot_blk[0] = 2 * I; it.slot_blk[1] = 2 * I + 1; it.slot_blk[2] = 2 * J; it.slot_blk[3] = 2 * J + 1;
+        it.ja[0] = 0; it.jb[0] = 2;
+        it.ja[1] = 0; it.jb[1] = 3;
+        it.ja[2] = 1; it.jb[2] = 2;
+        it.ja[3] = 1; it.jb[3] = 3;
+    } else if (idx < n0 + n1) {
+        const int I = idx - n0;
+        it.slot_blk[0] = 2 * I; it.slot_blk[1] = 2 * I + 1;
+        it.ja[0] = 0; it.jb[0] = 0;
+        it.ja[1] = 1; it.jb[1] = 0;
+        it.ja[2] = 1; it.jb[2] = 1;
+        it.summask = 3;
+    } else {
+        const int K = idx - n0 - n1;
+        const int r = nb - 1;
+        it.slot_blk[0] = r;
+        for (int w = 0; w < 4; ++w) {
+            const int li = 4 * K + w;  // position in the list (r,r), (r,0), (r,1), ..., (r,r-1)
+            if (li > r) break;
+            if (li == 0) { it.ja[w] = 0; it.jb[w] = 0; }
+            else { it.slot_blk[1 + w] = li - 1; it.ja[w] = 0; it.jb[w] = 1 + w; }
+        }
+        if (K == 0) it.summask = 1;
+    }
+    return it;
+}
+
+inline void item_counts(int nb, int* n0, int* n1, int* n2) {
+    const int h = nb >> 1;
+    *n0 = h * (h - 1) / 2;
+    *n1 = h;
+    *n2 = (nb & 1) ? ((nb - 1) + 4) / 4 : 0;
+}
+
+// internal feature index -> (offset inside a patch, ky, kx, external feature index)
+struct Feat { int off, ky, kx, ext; };
+__device__ __forceinline__ Feat feat_of(int fi, const CovGeom& g) {
+    Feat f;
+    if (g.layout == FW_LAYOUT_NCHW) {
+        const int kk = g.kh * g.kw;
+        const int c = fi / kk, t = fi - c * kk;
+        f.ky = t / g.kw; f.kx = t - f.ky * g.kw;
+        f.off = (c * g.H + f.ky) * g.W + f.kx;
+        f.ext = fi;
+    } else {  // NHWC and ROWS: tap-major, channel-minor
+        const int t = fi / g.Cin, c = fi - t * g.Cin;
+        f.ky = t / g.kw; f.kx = t - f.ky * g.kw;
+        f.off = (f.ky * g.W + f.kx) * g.Cin + c;
+        f.ext = c * (g.kh * g.kw) + t;
+    }
+    return f;
+}
+
+struct RowInfo { long long base; int iy0, ix0; };
+
+__device__ __forceinline__ RowInfo row_of(int r, bool valid, const CovGeom& g) {
+    RowInfo ri;
+    if (!valid) { ri.base = 0; ri.iy0 = -(1 << 28); ri.ix0 = -(1 << 28); return ri; }
+    const int P = g.Ho * g.Wo;
+    const int b = r / P, p = r - b * P;
+    const int oy = p / g.Wo, ox = p - oy * g.Wo;
+    ri.iy0 = oy * g.stride - g.pad;
+    ri.ix0 = ox * g.stride - g.pad;
+    if (g.layout == FW_LAYOUT_NCHW)
+        ri.base = ((long long)b * g.Cin * g.H + ri.iy0) * g.W + ri.ix0;
+    else
+        ri.base = (((long long)b * g.H + ri.iy0) * g.W + ri.ix0) * g.Cin;
+    return ri;
+}
+
+template <bool BF16>
+struct Smem;
+template <>
+struct Smem<false> {
+    float tile[MAX_SLOTS][KT_F32][BLK];  // [slot][row][feature], feature position rotated by 32 on odd rows
+    RowInfo rows[KT_F32];
+};
+template <>
+struct Smem<true> {
+    unsigned char tile[MAX_SLOTS][BLK][BF16_ROW_BYTES];  // [slot][feature][row] bf16, K-major
+    RowInfo rows[KT_BF16];
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void cov_partial_kernel(const void* __restrict__ Xv, CovGeom g, float* __restrict__ part,
+                                                          float* __restrict__ spart) {
+    constexpr int KT = BF16 ? KT_BF16 : KT_F32;
+    __shared__ Smem<BF16> sm;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int item_idx = blockIdx.x, split = blockIdx.y;
+    const Item it = get_item(item_idx, g.nb);
+
+    // this thread stages feature `lane` of every slot, rows wave, wave+4, ...
+    int f_off[MAX_SLOTS], f_ky[MAX_SLOTS], f_kx[MAX_SLOTS];
+    bool f_ok[MAX_SLOTS];
+#pragma unroll
+    for (int s = 0; s < MAX_SLOTS; ++s) {
+        const int fi = it.slot_blk[s] * BLK + lane;
+        f_ok[s] = it.slot_blk[s] >= 0 && fi < g.M;
+        Feat f = feat_of(f_ok[s] ? fi : 0, g);
+        f_off[s] = f.off; f_ky[s] = f.ky; f_kx[s] = f.kx;
+    }
+    float ssum[MAX_SLOTS];
+#pragma unroll
+    for (int s = 0; s < MAX_SLOTS; ++s) ssum[s] = 0.f;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    const int sa = it.ja[wave], sb = it.jb[wave];
+    const int r_begin = split * g.rows_per_split;
+    const int r_end = min(g.n_rows, r_begin + g.rows_per_split);
+    const int half = lane >> 5, l32 = lane & 31;
+
+    for (int r0 = r_begin; r0 < r_end; r0 += KT) {
+        if (tid < KT) sm.rows[tid] = row_of(r0 + tid, r0 + tid < r_end, g);
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < MAX_SLOTS; ++s) {
+            if (it.slot_blk[s] < 0) continue;
+#pragma unroll
+            for (int j = 0; j < KT / 4; ++j) {
+                const int k = wave + 4 * j;
+                const RowInfo ri = sm.rows[k];
+                const bool ok = f_ok[s] && (unsigned)(ri.iy0 + f_ky[s]) < (unsigned)g.H &&
+                                (unsigned)(ri.ix0 + f_kx[s]) < (unsigned)g.W;
+                if constexpr (BF16) {
+                    unsigned short v = 0;
+                    if (ok) v = reinterpret_cast<const unsigned short*>(Xv)[ri.base + f_off[s]];
+                    *reinterpret_cast<unsigned short*>(&sm.tile[s][lane][2 * k]) = v;
+                    ssum[s] += bf16_to_f32(v);
+                } else {
+                    float v = 0.f;
+                    if (ok) v = reinterpret_cast<const float*>(Xv)[ri.base + f_off[s]];
+                    sm.tile[s][k][(lane + ((k & 1) << 5)) & 63] = v;
+                    ssum[s] += v;
+                }
+            }
+        }
+        __syncthreads();
+        if (sa >= 0) {
+            if constexpr (BF16) {
+#pragma unroll
+                for (int k0 = 0; k0 < KT; k0 += 16) {
+                    bf16x8 a[2], b[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        a[t] = *reinterpret_cast<const bf16x8*>(&sm.tile[sa][32 * t + l32][2 * (k0 + 8 * half)]);
+                        b[t] = *reinterpret_cast<const bf16x8*>(&sm.tile[sb][32 * t + l32][2 * (k0 + 8 * half)]);
+                    }
+#pragma unroll
+                    for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+                        for (int tb = 0; tb < 2; ++tb)
+                            acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int k0 = 0; k0 < KT; k0 += 2) {
+                    const int k = k0 + half;
+                    const int rot = (k & 1) << 5;
+                    float a[2], b[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        a[t] = sm.tile[sa][k][(32 * t + l32 + rot) & 63];
+                        b[t] = sm.tile[sb][k][(32 * t + l32 + rot) & 63];
+                    }
+#pragma unroll
+                    for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+                        for (int tb = 0; tb < 2; ++tb)
+                            acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // partial 64x64 block of this wavefront: element (i, j) = sum over this split's rows of x_i x_j
+    if (sa >= 0) {
+        float* dst = part + (((size_t)split * g.nitems + item_idx) * 4 + wave) * (BLK * BLK);
+#pragma unroll
+        for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int row = 32 * ta + 8 * (i >> 2) + 4 * half + (i & 3);
+                    const int col = 32 * tb + l32;
+                    dst[row * BLK + col] = acc[ta][tb][i];
+                }
+    }
+    // column sums: combine the four row groups through LDS
+    if (it.summask) {
+        __syncthreads();
+        float* red = reinterpret_cast<float*>(&sm.tile[0][0][0]);  // [slot][wave][lane]
+#pragma unroll
+        for (int s = 0; s < MAX_SLOTS; ++s)
+            if ((it.summask >> s) & 1) red[(s * 4 + wave) * 64 + lane] = ssum[s];
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int s = 0; s < MAX_SLOTS; ++s)
+                if ((it.summask >> s) & 1) {
+                    const float v = red[(s * 4 + 0) * 64 + lane] + red[(s * 4 + 1) * 64 + lane] +
+                                    red[(s * 4 + 2) * 64 + lane] + red[(s * 4 + 3) * 64 + lane];
+                    spart[(size_t)split * g.nb * BLK + it.slot_blk[s] * BLK + lane] = v;
+                }
+        }
+    }
+}
+
+// Sum the partial blocks over the row splits in float64 and add them into A (lower triangle, external order);
+// the last grid blocks do the same for the column sums.
+__global__ __launch_bounds__(256) void cov_reduce_kernel(CovGeom g, const float* __restrict__ part,
+                                                         const float* __restrict__ spart, float* __restrict__ A,
+                                                         float* __restrict__ s) {
+    const int nblk = g.nitems * 4;
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x < nblk) {
+        const int item_idx = blockIdx.x >> 2, wave = blockIdx.x & 3;
+        const Item it = get_item(item_idx, g.nb);
+        if (it.ja[wave] < 0) return;
+        const int bi = it.slot_blk[it.ja[wave]], bj = it.slot_blk[it.jb[wave]];
+        const int col = tid & 63;
+        const int fj = bj * BLK + col;
+        if (fj >= g.M) return;
+        const int ej = feat_of(fj, g).ext;
+        const size_t stride = (size_t)g.nitems * 4 * BLK * BLK;
+        const float* src = part + (size_t)blockIdx.x * (BLK * BLK);
+        for (int row = tid >> 6; row < BLK; row += 4) {
+            const int fi = bi * BLK + row;
+            if (fi >= g.M) break;
+            if (bi == bj && row < col) continue;  // diagonal block: its upper half duplicates the lower
+            double v = 0.0;
+            for (int sp = 0; sp < g.nsplit; ++sp) v += (double)src[sp * stride + row * BLK + col];
+            const int ei = feat_of(fi, g).ext;
+            const int hi = max(ei, ej), lo = min(ei, ej);
+            float* dst = A + (size_t)hi * g.M + lo;
+            *dst = (float)((double)*dst + v);
+        }
+    } else {
+        const int f = ((int)blockIdx.x - nblk) * 256 + tid;
+        if (f >= g.M) return;
+        double v = 0.0;
+        for (int sp = 0; sp < g.nsplit; ++sp) v += (double)spart[(size_t)sp * g.nb * BLK + f];
+        const int e = feat_of(f, g).ext;
+        s[e] = (float)((double)s[e] + v);
+    }
+}
+
+bool make_geom(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, CovGeom* g) {
+    g->B = d->B; g->Cin = d->Cin; g->H = d->H; g->W = d->W;
+    g->kh = d->kh; g->kw = d->kw; g->stride = d->stride; g->pad = d->pad;
+    g->layout = (int)lay;
+    g->Ho = (d->H + 2 * d->pad - d->kh) / d->stride + 1;
+    g->Wo = (d->W + 2 * d->pad - d->kw) / d->stride + 1;
+    const long long n_rows = (long long)d->B * g->Ho * g->Wo;
+    const long long M = (long long)d->Cin * d->kh * d->kw;
+    if (n_rows <= 0 || n_rows >= (1ll << 31) || M <= 0 || M > 16384) return false;
+    if ((long long)d->B * d->Cin * d->H * d->W >= (1ll << 31)) return false;
+    g->n_rows = (int)n_rows; g->M = (int)M; g->nb = (int)((M + BLK - 1) / BLK);
+    item_counts(g->nb, &g->n0, &g->n1, &g->n2);
+    g->nitems = g->n0 + g->n1 + g->n2;
+    const int KT = dt == FW_BF16 ? KT_BF16 : KT_F32;
+    long long want = (1024 + g->nitems - 1) / g->nitems;            // aim at about 1024 workgroups
+    const long long max_split = (n_rows + 4 * KT - 1) / (4 * KT);   // at least four chunks per split
+    if (want > max_split) want = max_split;
+    if (want < 1) want = 1;
+    long long rps = (n_rows + want - 1) / want;
+    rps = (rps + KT - 1) / KT * KT;
+    g->rows_per_split = (int)rps;
+    g->nsplit = (int)((n_rows + rps - 1) / rps);
+    return true;
+}
+
+// mu and phi_x are updated in place AFTER finalize_phi_kernel has consumed the old mean.
+__global__ void finalize_mu_kernel(const float* __restrict__ A, const float* __restrict__ s, double inv_n, int M, float alpha,
+                                   int first, float* __restrict__ mu, float* __restrict__ phi) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    const double mh = (double)s[i] * inv_n;
+    const double raw = (double)A[(size_t)i * M + i] * inv_n;
+    double m, p;
+    if (first) { m = mh; p = raw; }
+    else {
+        m = (double)alpha * (double)mu[i] + (1.0 - (double)alpha) * mh;
+        p = (double)alpha * (double)phi[i] + (1.0 - (double)alpha) * raw;
+    }
+    mu[i] = (float)m;
+    phi[i] = (float)p;
+}
+
+// one workgroup: lambda_bar = mean(phi)
+__global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ phi, int M, float* __restrict__ out) {
+    __shared__ double red[4];
+    double v = 0.0;
+    for (int i = threadIdx.x; i < M; i += 256) v += (double)phi[i];
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) *out = (float)((red[0] + red[1] + red[2] + red[3]) / (double)M);
+}
+
+// Covariance centred on the updated mean, expanded into the raw sums (float64 per element):
+//   C_ij = A_ij/n - mhat_i mu_j - mu_i mhat_j + mu_i mu_j,  mhat = s/n,  mu = alpha*mu_old + (1-alpha)*mhat.
+// 16x16 threads cover a tile with i >= j; each thread writes (i,j) and its mirror.
+__global__ __launch_bounds__(256) void finalize_phi_kernel(const float* __restrict__ A, const float* __restrict__ s,
+                                                           const float* __restrict__ mu_old, double inv_n, int M, float alpha,
+                                                           int first, float* __restrict__ Phi) {
+    const int i = blockIdx.y * 16 + threadIdx.y, j = blockIdx.x * 16 + threadIdx.x;
+    if (blockIdx.x > blockIdx.y || i >= M || j >= M || j > i) return;
+    const double mhi = (double)s[i] * inv_n, mhj = (double)s[j] * inv_n;
+    double mi = mhi, mj = mhj;
+    if (!first) {
+        mi = (double)alpha * (double)mu_old[i] + (1.0 - (double)alpha) * mhi;
+        mj = (double)alpha * (double)mu_old[j] + (1.0 - (double)alpha) * mhj;
+    }
+    double c = (double)A[(size_t)i * M + j] * inv_n - mhi * mj - mi * mhj + mi * mj;
+    if (!first) c = (double)alpha * (double)Phi[(size_t)i * M + j] + (1.0 - (double)alpha) * c;
+    const float o = (float)c;
+    Phi[(size_t)i * M + j] = o;
+    Phi[(size_t)j * M + i] = o;
+}
+
+__global__ __launch_bounds__(256) void mirror_lower_kernel(float* __restrict__ A, int M) {
+    const int i = blockIdx.y * 16 + threadIdx.y, j = blockIdx.x * 16 + threadIdx.x;
+    if (i >= M || j >= M || j >= i) return;
+    A[(size_t)j * M + i] = A[(size_t)i * M + j];
+}
+
+__global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ p, size_t n, float v) {
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256) p[e] = v;
+}
+
+}  // namespace
+
+fw_status fill_f32(float* p, size_t n, float v, hipStream_t st) {
+    size_t b = (n + 255) / 256;
+    if (b > 8192) b = 8192;
+    if (b == 0) return FW_OK;
+    hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)b), dim3(256), 0, st, p, n, v);
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
+size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_layout lay) {
+    CovGeom g;
+    if (!d || !make_geom(d, dt, lay, &g)) return 0;
+    const size_t part = (size_t)g.nsplit * g.nitems * 4 * BLK * BLK * sizeof(float);
+    const size_t sp = (size_t)g.nsplit * g.nb * BLK * sizeof(float);
+    return align_up(part, 256) + align_up(sp, 256);
+}
+
+fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,
+                         size_t ws_bytes, hipStream_t st) {
+    CovGeom g;
+    if (!make_geom(d, dt, lay, &g)) return FW_ERR_UNSUPPORTED;
+    const size_t part_bytes = align_up((size_t)g.nsplit * g.nitems * 4 * BLK * BLK * sizeof(float), 256);
+    const size_t need = part_bytes + align_up((size_t)g.nsplit * g.nb * BLK * sizeof(float), 256);
+    if (!ws || ws_bytes < need) return FW_ERR_WORKSPACE;
+    float* part = reinterpret_cast<float*>(ws);
+    float* spart = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + part_bytes);
+    const dim3 grid(g.nitems, g.nsplit);
+    if (dt == FW_BF16)
+        hipLaunchKernelGGL(cov_partial_kernel<true>, grid, dim3(256), 0, st, X, g, part, spart);
+    else
+        hipLaunchKernelGGL(cov_partial_kernel<false>, grid, dim3(256), 0, st, X, g, part, spart);
+    FW_LAUNCH_CHECK();
+    const int rblocks = g.nitems * 4 + (g.M + 255) / 256;
+    hipLaunchKernelGGL(cov_reduce_kernel, dim3(rblocks), dim3(256), 0, st, g, part, spart, A, s);
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
+fw_status cov_finalize(const float* A, const float* s, long long n, int M, float alpha, int first_block, float* mu, float* Phi_x,
+                       float* phi_x, float* lambda_bar, hipStream_t st) {
+    const double inv_n = 1.0 / (double)n;
+    const int tb = (M + 15) / 16;
+    hipLaunchKernelGGL(finalize_phi_kernel, dim3(tb, tb), dim3(16, 16), 0, st, A, s, mu, inv_n, M, alpha, first_block, Phi_x);
+    FW_LAUNCH_CHECK();
+    hipLaunchKernelGGL(finalize_mu_kernel, dim3((M + 255) / 256), dim3(256), 0, st, A, s, inv_n, M, alpha, first_block, mu, phi_x);
+    FW_LAUNCH_CHECK();
+    hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st, phi_x, M, lambda_bar);
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
+fw_status symmetrize_from_lower(float* A, int M, hipStream_t st) {
+    const int tb = (M + 15) / 16;
+    hipLaunchKernelGGL(mirror_lower_kernel, dim3(tb, tb), dim3(16, 16), 0, st, A, M);
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
+}  // namespace fw

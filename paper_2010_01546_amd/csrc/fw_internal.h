@@ -1,0 +1,73 @@
+// Internal declarations shared by the gfx950 kernels of the feature-whitening library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "fw.h"
+
+#define FW_HIP_TRY(expr)                            \
+    do {                                            \
+        hipError_t e__ = (expr);                    \
+        if (e__ != hipSuccess) return FW_ERR_HIP;   \
+    } while (0)
+
+#define FW_LAUNCH_CHECK()                                        \
+    do {                                                         \
+        if (hipGetLastError() != hipSuccess) return FW_ERR_HIP;  \
+    } while (0)
+
+namespace fw {
+
+constexpr int kWave = 64;
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short shortx8 __attribute__((ext_vector_type(8)));
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// bfloat16 bit pattern <-> float
+__device__ __forceinline__ float bf16_to_f32(unsigned short h) { return __uint_as_float(((unsigned)h) << 16); }
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+// 64-lane butterfly reductions.
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ---- cov.hip
+size_t cov_workspace_bytes(int M, const fw_conv_desc* d, fw_dtype dt, fw_layout lay);
+fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d, float* A, float* s,
+                         void* ws, size_t ws_bytes, hipStream_t st);
+fw_status cov_finalize(const float* A, const float* s, long long n, int M, float alpha, int first_block, float* mu,
+                       float* Phi_x, float* phi_x, float* lambda_bar, hipStream_t st);
+fw_status symmetrize_from_lower(float* A, int M, hipStream_t st);
+fw_status fill_f32(float* p, size_t n, float v, hipStream_t st);
+
+// ---- gemm.hip
+fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st);
+
+// ---- cond.hip
+size_t cond_workspace_bytes(int M);
+fw_status cond_state_init(const fw_cond_state* s, hipStream_t st);
+fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_cond_info* info, void* ws, hipStream_t st);
+
+// ---- evd.hip
+size_t evd_workspace_bytes(int M);
+fw_status whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float* T, float* Q, float* Qs, float* lambda,
+                     void* ws, size_t ws_bytes, hipStream_t st);
+
+}  // namespace fw
