@@ -79,6 +79,7 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
     if (threadIdx.x == 0) {
         for (int i = 1; i < (int)(blockDim.x >> 6); ++i)
             if (bv[i] > best || (bv[i] == best && bi[i] < idx)) { best = bv[i]; idx = bi[i]; }
+        if (idx < 0 || idx >= M) idx = 0;  // every norm was NaN: keep the index in range
         sc->m_prime = idx;
         sc->xi_mp = sqrtf(fmaxf(best, 0.f));
         sc->flags = 0;

@@ -124,12 +124,12 @@ template <bool BF16>
 struct Smem;
 template <>
 struct Smem<false> {
-    float tile[MAX_SLOTS][KT_F32][BLK];  // [slot][row][feature], feature position rotated by 32 on odd rows
+    alignas(16) float tile[MAX_SLOTS][KT_F32][BLK];  // [slot][row][feature], feature position rotated by 32 on odd rows
     RowInfo rows[KT_F32];
 };
 template <>
 struct Smem<true> {
-    unsigned char tile[MAX_SLOTS][BLK][BF16_ROW_BYTES];  // [slot][feature][row] bf16, K-major
+    alignas(16) unsigned char tile[MAX_SLOTS][BLK][BF16_ROW_BYTES];  // [slot][feature][row] bf16, K-major
     RowInfo rows[KT_BF16];
 };
 

@@ -1,0 +1,100 @@
+"""GPU parity of the moment accumulation and block-moment epilogue against the CPU oracle (Sec. 2, Sec. 4.1)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_common import (b, dev, lower, oracle_rows, ora, relF, run_cov, run_finalize, upload_act, desc_of, dt_of, workspace, DEV)
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}     # relative Frobenius error on the centred covariance
+RAW_TOL = {"f32": 1e-5, "bf16": 1e-5}  # raw sums: products of bf16 values are exact in float32, only summation rounds
+
+
+def check_layer(layer, layout):
+    X = oracle_rows(layer)
+    A_o, s_o, n = ora.raw_sums(X)
+    A, s = run_cov(layer, layout)
+    A_h, s_h = A.cpu().numpy(), s.cpu().numpy()
+    assert np.array_equal(np.triu(A_h, 1), np.zeros_like(A_h)), "entries above the diagonal must stay untouched"
+    assert relF(lower(A_h), lower(A_o)) < RAW_TOL[layer.dtype]
+    assert relF(s_h, s_o) < RAW_TOL[layer.dtype]
+    M = layer.desc.M
+    mu, Phi, phi, lbar = run_finalize(A, s, n, M, 0.0, 1)
+    mu_o, Phi_o, phi_o, lbar_o = ora.block_moments(X, 0.0, True)
+    assert relF(Phi.cpu().numpy(), Phi_o) < TOL[layer.dtype]
+    assert relF(mu.cpu().numpy(), mu_o) < 1e-6 and relF(phi.cpu().numpy(), phi_o) < 1e-5
+    assert abs(float(lbar[0]) - lbar_o) <= 1e-5 * abs(lbar_o)
+    Ph = Phi.cpu().numpy()
+    assert np.array_equal(Ph, Ph.T)
+
+
+ROWS_CASES = [  # (n_rows, M, dtype): ragged tails in both dimensions, single block, odd/even block counts
+    (128, 64, "f32"), (37, 5, "f32"), (1000, 147, "f32"), (513, 200, "f32"), (300, 321, "f32"), (64, 1, "f32"),
+    (129, 64, "bf16"), (1000, 147, "bf16"), (777, 330, "bf16"),
+]
+
+
+@pytest.mark.parametrize("n_rows,M,dtype", ROWS_CASES)
+def test_rows_layout(n_rows, M, dtype):
+    check_layer(wl.small_rows(10 + M, n_rows, M, 4, dtype=dtype), b.FW_LAYOUT_ROWS)
+
+
+CONV_CASES = [  # (B, Cin, H, W, k, stride, pad, dtype)
+    (3, 8, 9, 7, 3, 1, 1, "f32"), (2, 16, 8, 8, 3, 2, 1, "f32"), (2, 3, 20, 20, 7, 2, 3, "f32"), (4, 24, 6, 6, 1, 2, 0, "f32"),
+    (2, 70, 5, 5, 3, 1, 1, "f32"), (1, 4, 3, 3, 3, 1, 0, "f32"),
+    (3, 8, 9, 7, 3, 1, 1, "bf16"), (2, 32, 7, 7, 3, 1, 1, "bf16"), (2, 3, 20, 20, 7, 2, 3, "bf16"), (2, 40, 8, 8, 1, 2, 0, "bf16"),
+]
+
+
+@pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NCHW])
+@pytest.mark.parametrize("B,Cin,H,W,k,stride,pad,dtype", CONV_CASES)
+def test_conv_layouts(B, Cin, H, W, k, stride, pad, dtype, layout):
+    check_layer(wl.small_conv(B * 100 + Cin, B, Cin, H, W, k, stride, pad, 8, dtype=dtype), layout)
+
+
+def test_accumulates_over_batches_and_two_block_recursion():
+    """Two batches added into one block equal the block of their union; the second block follows eqs. (vmuxi), (vPhixi)."""
+    L0 = wl.small_conv(1, 3, 8, 6, 6, 3, 1, 1, 8)
+    L1 = wl.small_conv(2, 3, 8, 6, 6, 3, 1, 1, 8)
+    L2 = wl.small_conv(3, 3, 8, 6, 6, 3, 1, 1, 8, relu=True)
+    X0, X1, X2 = (oracle_rows(L) for L in (L0, L1, L2))
+    M = L0.desc.M
+    A, s = run_cov(L0, b.FW_LAYOUT_NHWC)
+    A, s = run_cov(L1, b.FW_LAYOUT_NHWC, A, s)
+    X01 = np.vstack([X0, X1])
+    mu, Phi, phi, lbar = run_finalize(A, s, X01.shape[0], M, 0.3, 1)
+    mu_o, Phi_o, phi_o, lb_o = ora.block_moments(X01, 0.3, True)
+    assert relF(Phi.cpu().numpy(), Phi_o) < 1e-4
+    A2, s2 = run_cov(L2, b.FW_LAYOUT_NHWC)
+    mu, Phi, phi, lbar = run_finalize(A2, s2, X2.shape[0], M, 0.3, 0, mu, Phi, phi)
+    mu_o2, Phi_o2, phi_o2, lb_o2 = ora.block_moments(X2, 0.3, False, mu_o, Phi_o, phi_o)
+    assert relF(Phi.cpu().numpy(), Phi_o2) < 1e-4 and relF(mu.cpu().numpy(), mu_o2) < 1e-6
+    assert relF(phi.cpu().numpy(), phi_o2) < 1e-5 and abs(float(lbar[0]) - lb_o2) < 1e-5 * lb_o2
+
+
+def test_config1_covariance():
+    check_layer(wl.config1(), b.FW_LAYOUT_ROWS)
+
+
+def test_empty_and_bad_arguments_on_device():
+    M = 8
+    A = torch.zeros(M, M, device=DEV); s = torch.zeros(M, device=DEV)
+    X = torch.zeros(4, M, device=DEV)
+    ws = workspace(1 << 20)
+    d = b.conv_desc(0, M)
+    with pytest.raises(b.FwError) as e:
+        b.fw_cov_accumulate(X, b.FW_F32, b.FW_LAYOUT_ROWS, d, A, s, ws)
+    assert e.value.status == b.FW_ERR_INVALID_ARG
+    with pytest.raises(b.FwError) as e:
+        b.fw_cov_accumulate(X, b.FW_F32, b.FW_LAYOUT_ROWS, b.conv_desc(4, M), A, s, workspace(256))
+    assert e.value.status == b.FW_ERR_WORKSPACE
+    assert float(A.abs().sum()) == 0.0
+
+
+def test_run_to_run_determinism():
+    L = wl.small_conv(5, 4, 32, 10, 10, 3, 1, 1, 8)
+    A1, s1 = run_cov(L, b.FW_LAYOUT_NHWC)
+    A2, s2 = run_cov(L, b.FW_LAYOUT_NHWC)
+    assert torch.equal(A1, A2) and torch.equal(s1, s2)

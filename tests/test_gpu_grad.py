@@ -1,0 +1,68 @@
+"""GPU parity of the gradient transformation G Q, Q = T^T T (Sec. 3.1) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_common import b, dev, ora, relF, workspace, DEV
+
+pytestmark = pytest.mark.gpu
+rng = np.random.default_rng(77)
+
+
+def sym_Q(M, seed):
+    r = np.random.default_rng(seed)
+    T = np.eye(M) + 0.2 * r.standard_normal((M, M)) / np.sqrt(M)
+    return T.astype(np.float32), (T.astype(np.float32).astype(np.float64).T @ T.astype(np.float32).astype(np.float64))
+
+
+@pytest.mark.parametrize("S,M", [(32, 64), (5, 7), (64, 576), (70, 200), (1, 129), (130, 147), (256, 300)])
+def test_f32_with_Q(S, M):
+    T32, Q64 = sym_Q(M, M)
+    Q32 = Q64.astype(np.float32)
+    G = (rng.standard_normal((S, M)) * 0.1).astype(np.float32)
+    out = torch.full((S, M), float("nan"), device=DEV)
+    b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, dev(Q32), out)
+    torch.cuda.synchronize()
+    want = ora.grad_transform(G, Q32)
+    assert relF(out.cpu().numpy(), want) < 1e-5
+
+
+@pytest.mark.parametrize("S,M", [(32, 64), (5, 7), (64, 576), (70, 200), (130, 147)])
+def test_bf16_with_Q(S, M):
+    T32, Q64 = sym_Q(M, M + 1)
+    Q32 = Q64.astype(np.float32)
+    G = wl.round_to_bf16((rng.standard_normal((S, M)) * 0.1).astype(np.float32))
+    out = torch.zeros(S, M, device=DEV, dtype=torch.bfloat16)
+    b.fw_grad_transform(dev(G, torch.bfloat16), b.FW_BF16, S, M, None, dev(Q32), out)
+    torch.cuda.synchronize()
+    want = ora.grad_transform(G, Q32)
+    assert relF(out.float().cpu().numpy(), want) < 2e-2
+    # against the same computation with Q rounded to bf16 the only error left is accumulation order and output rounding
+    want_r = ora.grad_transform(G, wl.round_to_bf16(Q32))
+    assert relF(out.float().cpu().numpy(), want_r) < 4e-3
+
+
+@pytest.mark.parametrize("S,M", [(8, 64), (33, 150), (64, 576)])
+def test_f32_from_nonsymmetric_T(S, M):
+    """Q is built as T^T T (eq. (vQ)); a transposed product would fail for this non-symmetric T."""
+    T32, Q64 = sym_Q(M, 3 * M)
+    assert not np.allclose(T32, T32.T)
+    G = (rng.standard_normal((S, M)) * 0.1).astype(np.float32)
+    out = torch.zeros(S, M, device=DEV)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S))
+    b.fw_grad_transform(dev(G), b.FW_F32, S, M, dev(T32), None, out, ws)
+    torch.cuda.synchronize()
+    want = ora.grad_transform(G, ora.Q_from_T(T32))
+    assert relF(out.cpu().numpy(), want) < 1e-5
+    wrong = ora.grad_transform(G, T32.astype(np.float64) @ T32.astype(np.float64).T)
+    assert relF(out.cpu().numpy(), wrong) > 1e-3
+
+
+def test_config1_gradient_with_identity_is_copy():
+    L = wl.config1()
+    S, M = L.G.shape
+    out = torch.zeros(S, M, device=DEV)
+    b.fw_grad_transform(dev(L.G), b.FW_F32, S, M, None, torch.eye(M, device=DEV), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), L.G)
