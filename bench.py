@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the feature-whitening hot path on one MI355X.
+
+One "step" is one whitened gradient update of one layer: fw_cov_accumulate (+ fw_cov_finalize) on a batch, one
+fw_cond_reduce_step, and fw_grad_transform of the layer's weight gradient -- block length L = 1, the worst case
+(the paper amortises the recursive step over L batches).  Inputs are seeded synthetic activations and gradients,
+resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel pair (the split-K covariance kernel and its reduce,
+i.e. one fw_cov_accumulate call) timed with events on the launch stream inside the timed region; `cpu_baseline`
+times the float64 numpy oracle on the host cores for one update of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"f32": 157.3e12, "bf16": 2.5e15}   # dense MFMA peaks of MI355X, flop/s
+HBM_PEAK = 8.0e12
+
+# HBM bytes per fw_cov_accumulate call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), scaled by
+# the reading of the same counters on a plain copy of known size; None until measured for that workload.
+MEASURED_TRAFFIC = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--layout", default="nhwc", choices=["nhwc", "nchw"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import workloads as wl
+    from paper_2010_01546_amd import binding as b
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    layer = {"c1": wl.config1, "c2": wl.config2, "c3": wl.config3, "c4": wl.config4}[args.config]()
+    d = layer.desc
+    M, S, n_rows = d.M, layer.S, d.n_rows
+    bf16 = layer.dtype == "bf16"
+    dt = b.FW_BF16 if bf16 else b.FW_F32
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    if layer.is_rows:
+        lay = b.FW_LAYOUT_ROWS
+        X = torch.as_tensor(layer.act).to(dev).to(tdt).contiguous()
+    else:
+        lay = b.FW_LAYOUT_NHWC if args.layout == "nhwc" else b.FW_LAYOUT_NCHW
+        X = torch.as_tensor(wl.to_layout(layer.act, lay)).to(dev).to(tdt).contiguous()
+    desc = b.conv_desc(*d.astuple())
+    G = torch.as_tensor(layer.G).to(dev)          # float32 gradient (configs 3-5 cast inside a bf16 variant; fp32 here)
+    Gout = torch.empty_like(G)
+
+    A = torch.zeros(M, M, device=dev); s = torch.zeros(M, device=dev)
+    mu = torch.zeros(M, device=dev); Phi = torch.zeros(M, M, device=dev); phi = torch.zeros(M, device=dev)
+    lbar = torch.zeros(4, device=dev)
+    T, Q, Qs, Py, Psi = (torch.empty(M, M, device=dev) for _ in range(5))
+    xi2 = torch.empty(M, device=dev)
+    info = torch.zeros(8, dtype=torch.int32, device=dev)
+    ws_cov = torch.empty(b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, M, 0, desc, dt), dtype=torch.uint8, device=dev)
+    ws_cond = torch.empty(b.fw_workspace_bytes(b.FW_OP_COND_REDUCE_STEP, M), dtype=torch.uint8, device=dev)
+    prm = b.cond_params()                          # the paper's hyper-parameters (Sec. 6)
+    alpha = 0.1
+    st = b.cond_state(M, Phi, lbar, T, Q, Qs, Py, Psi, xi2)
+
+    # first block: moments and initial state
+    b.fw_cov_accumulate(X, dt, lay, desc, A, s, ws_cov)
+    b.fw_cov_finalize(A, s, n_rows, M, alpha, 1, mu, Phi, phi, lbar)
+    b.fw_cond_state_init(st)
+    torch.cuda.synchronize()
+
+    def step(ev=None):
+        A.zero_(); s.zero_()
+        if ev is not None:
+            ev[0].record()
+        b.fw_cov_accumulate(X, dt, lay, desc, A, s, ws_cov)
+        if ev is not None:
+            ev[1].record()
+        b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar)
+        b.fw_cond_reduce_step(st, prm, info, ws_cond)
+        b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    cov_ms = sum(e0.elapsed_time(e1) for e0, e1 in events) / args.steps
+    assert torch.isfinite(Gout).all() and torch.isfinite(T).all()
+
+    # separate, untimed-for-the-headline breakdown of the other exports
+    def time_call(fn, reps=20):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn(); torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    cond_ms = time_call(lambda: b.fw_cond_reduce_step(st, prm, info, ws_cond))
+    grad_ms = time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout))
+    fin_ms = time_call(lambda: b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar))
+
+    cov_flops = float(n_rows) * M * (M + 1)                 # lower triangle incl. diagonal, 2 flops per product
+    achieved = cov_flops / (cov_ms * 1e-3)
+    peak = PEAK[layer.dtype]
+    cond_words = 16 if prm.gamma < 1.0 else 10
+    cond_bytes = cond_words * M * M * 4.0
+    out = {
+        "metric": "whitened grad-updates/s per layer",
+        "value": 1e3 / ms_per_step,
+        "unit": "updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if not bf16 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{layer.name}: M={M} S={S} N_rows={n_rows} layout={args.layout if not layer.is_rows else 'rows'}",
+                   "batch": d.B, "block_length": 1, "cond_params": "gamma=0.99 beta=0.1 delta=0.25 (paper defaults)"},
+        "roofline": {"bound": "mfma", "kernel": "cov_partial_kernel+cov_reduce_kernel (one fw_cov_accumulate)",
+                     "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": MEASURED_TRAFFIC.get(args.config)},
+        "breakdown_ms": {"cov_accumulate": cov_ms, "cov_finalize": fin_ms, "cond_reduce_step": cond_ms, "grad_transform": grad_ms},
+        "cond_step_GBps": cond_bytes / (cond_ms * 1e-3) / 1e9,
+        "grad_transform_TFLOPs": 2.0 * S * M * M / (grad_ms * 1e-3) / 1e12,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import fw_oracle as ora
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        # bounded sample: whole updates of the same workload by the oracle, repeated until about 10 s have passed
+        # (at most 3 updates); images beyond a memory bound are dropped and the moment terms scaled, which are linear
+        # in the rows
+        Bs = d.B if layer.is_rows else max(1, min(d.B, int(4e9 // max(1, 8 * d.P * M))))
+        scale = d.B / Bs
+        reps, spent, secs = 0, 0.0, {"unfold": 0.0, "moments": 0.0, "cond_step": 0.0, "grad_transform": 0.0}
+        while reps < 3 and spent < 10.0:
+            tc0 = time.perf_counter()
+            if layer.is_rows:
+                Xr = np.asarray(layer.act[:Bs], dtype=np.float64)
+            else:
+                Xr = ora.patch_rows(layer.act[:Bs], Bs, d.Cin, d.H, d.W, d.kh, d.kw, d.stride, d.pad)
+            tc1 = time.perf_counter()
+            mu_o, Phi_o, phi_o, lb_o = ora.block_moments(Xr, alpha, True)
+            del Xr
+            tc2 = time.perf_counter()
+            st_o, _ = ora.cond_reduce_step(ora.CondState.initial(Phi_o), lb_o, ora.CondParams())
+            tc3 = time.perf_counter()
+            ora.grad_transform(layer.G, st_o.Qs)
+            tc4 = time.perf_counter()
+            for k, v in zip(secs, (tc1 - tc0, tc2 - tc1, tc3 - tc2, tc4 - tc3)):
+                secs[k] += v
+            reps += 1
+            spent += tc4 - tc0
+        secs = {k: v / reps for k, v in secs.items()}
+        t_update = (secs["unfold"] + secs["moments"]) * scale + secs["cond_step"] + secs["grad_transform"]
+        out["cpu_baseline"] = {"value": 1.0 / t_update, "unit": "updates/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"{reps} update(s) on {Bs} of {d.B} images (moment terms scaled by {scale:g}), "
+                                         f"float64 numpy, {spent:.1f} s of CPU work",
+                               "seconds_per_update": secs}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
