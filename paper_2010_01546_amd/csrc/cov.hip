@@ -11,6 +11,8 @@
 // Internally features are ordered tap-major / channel-minor for NHWC and ROWS inputs so that consecutive lanes
 // read consecutive channels; the reduce kernel maps back to the external order m = (c*kh + ky)*kw + kx.
 #include "fw_internal.h"
+#include <stdlib.h>
+#include <type_traits>
 
 namespace fw {
 namespace {
@@ -27,6 +29,7 @@ struct CovGeom {
     int layout;
     int rows_per_split, nsplit;
     int n0, n1, n2, nitems;
+    int adv_b, adv_y, adv_x;  // a chunk of KT_F32 rows ahead = adv_b images + adv_y output rows + adv_x output columns
 };
 
 struct Item {
@@ -36,15 +39,18 @@ struct Item {
 };
 
 // Closed-form enumeration of workgroup items covering every 64x64 block (bi >= bj) of the lower triangle once.
-//  type 0: 2x2 squares of blocks strictly below the diagonal of the 128-block grid
-//  type 1: diagonal 128-blocks (three 64-blocks)
-//  type 2: when the number of 64-blocks is odd, the last block row including its diagonal block, four per item
+// h = nb/2 is the number of 128-blocks; with an odd number of 64-blocks the last block row r = nb-1 is left over.
+//  type 0: 2x2 squares of blocks strictly below the diagonal of the 128-block grid (4 blocks, 4 panels)
+//  type 1: diagonal 128-block I: (2I,2I), (2I+1,2I), (2I+1,2I+1) and, if nb is odd, (r,2I) for the fourth wavefront
+//  type 2: (nb odd) what is left of row r: (r,r), (r,1), (r,3), ..., (r,2h-1), four per item
 __device__ __host__ inline Item get_item(int idx, int nb) {
     Item it;
     for (int i = 0; i < MAX_SLOTS; ++i) it.slot_blk[i] = -1;
     for (int w = 0; w < 4; ++w) it.ja[w] = it.jb[w] = -1;
     it.summask = 0;
     const int h = nb >> 1;
+    const bool odd = nb & 1;
+    const int r = nb - 1;
     const int n0 = h * (h - 1) / 2, n1 = h;
     if (idx < n0) {
         int I = 1;
@@ -61,27 +67,33 @@ __device__ __host__ inline Item get_item(int idx, int nb) {
         it.ja[0] = 0; it.jb[0] = 0;
         it.ja[1] = 1; it.jb[1] = 0;
         it.ja[2] = 1; it.jb[2] = 1;
+        if (odd) { it.slot_blk[2] = r; it.ja[3] = 2; it.jb[3] = 0; }
         it.summask = 3;
     } else {
         const int K = idx - n0 - n1;
-        const int r = nb - 1;
         it.slot_blk[0] = r;
         for (int w = 0; w < 4; ++w) {
-            const int li = 4 * K + w;  // position in the list (r,r), (r,0), (r,1), ..., (r,r-1)
-            if (li > r) break;
+            const int li = 4 * K + w;  // position in the list (r,r), (r,1), (r,3), ..., (r,2h-1)
+            if (li > h) break;
             if (li == 0) { it.ja[w] = 0; it.jb[w] = 0; }
-            else { it.slot_blk[1 + w] = li - 1; it.ja[w] = 0; it.jb[w] = 1 + w; }
+            else { it.slot_blk[1 + w] = 2 * (li - 1) + 1; it.ja[w] = 0; it.jb[w] = 1 + w; }
         }
         if (K == 0) it.summask = 1;
     }
     return it;
 }
 
+// selection by compare chain: keeps the item in scalar registers (a dynamically indexed array would go to scratch)
+__device__ __forceinline__ int pick4(const int* a, int w) { return w == 0 ? a[0] : w == 1 ? a[1] : w == 2 ? a[2] : a[3]; }
+__device__ __forceinline__ int pick_slot(const Item& it, int s) {
+    return s == 0 ? it.slot_blk[0] : s == 1 ? it.slot_blk[1] : s == 2 ? it.slot_blk[2] : s == 3 ? it.slot_blk[3] : it.slot_blk[4];
+}
+
 inline void item_counts(int nb, int* n0, int* n1, int* n2) {
     const int h = nb >> 1;
     *n0 = h * (h - 1) / 2;
     *n1 = h;
-    *n2 = (nb & 1) ? ((nb - 1) + 4) / 4 : 0;
+    *n2 = (nb & 1) ? (h + 1 + 3) / 4 : 0;
 }
 
 // internal feature index -> (offset inside a patch, ky, kx, external feature index)
@@ -138,7 +150,8 @@ __global__ __launch_bounds__(256) void cov_partial_kernel(const void* __restrict
                                                           float* __restrict__ spart) {
     constexpr int KT = BF16 ? KT_BF16 : KT_F32;
     __shared__ Smem<BF16> sm;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int item_idx = blockIdx.x, split = blockIdx.y;
     const Item it = get_item(item_idx, g.nb);
 
@@ -164,7 +177,7 @@ __global__ __launch_bounds__(256) void cov_partial_kernel(const void* __restrict
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    const int sa = it.ja[wave], sb = it.jb[wave];
+    const int sa = pick4(it.ja, wave), sb = pick4(it.jb, wave);
     const int r_begin = split * g.rows_per_split;
     const int r_end = min(g.n_rows, r_begin + g.rows_per_split);
     const int half = lane >> 5, l32 = lane & 31;
@@ -266,43 +279,196 @@ __global__ __launch_bounds__(256) void cov_partial_kernel(const void* __restrict
     }
 }
 
-// Sum the partial blocks over the row splits in float64 and add them into A (lower triangle, external order);
-// the last grid blocks do the same for the column sums.
-__global__ __launch_bounds__(256) void cov_reduce_kernel(CovGeom g, const float* __restrict__ part,
-                                                         const float* __restrict__ spart, float* __restrict__ A,
-                                                         float* __restrict__ s) {
-    const int nblk = g.nitems * 4;
-    const int tid = threadIdx.x;
-    if ((int)blockIdx.x < nblk) {
-        const int item_idx = blockIdx.x >> 2, wave = blockIdx.x & 3;
-        const Item it = get_item(item_idx, g.nb);
-        if (it.ja[wave] < 0) return;
-        const int bi = it.slot_blk[it.ja[wave]], bj = it.slot_blk[it.jb[wave]];
-        const int col = tid & 63;
-        const int fj = bj * BLK + col;
-        if (fj >= g.M) return;
-        const int ej = feat_of(fj, g).ext;
-        const size_t stride = (size_t)g.nitems * 4 * BLK * BLK;
-        const float* src = part + (size_t)blockIdx.x * (BLK * BLK);
-        for (int row = tid >> 6; row < BLK; row += 4) {
-            const int fi = bi * BLK + row;
-            if (fi >= g.M) break;
-            if (bi == bj && row < col) continue;  // diagonal block: its upper half duplicates the lower
-            double v = 0.0;
-            for (int sp = 0; sp < g.nsplit; ++sp) v += (double)src[sp * stride + row * BLK + col];
-            const int ei = feat_of(fi, g).ext;
-            const int hi = max(ei, ej), lo = min(ei, ej);
-            float* dst = A + (size_t)hi * g.M + lo;
-            *dst = (float)((double)*dst + v);
-        }
-    } else {
-        const int f = ((int)blockIdx.x - nblk) * 256 + tid;
-        if (f >= g.M) return;
-        double v = 0.0;
-        for (int sp = 0; sp < g.nsplit; ++sp) v += (double)spart[(size_t)sp * g.nb * BLK + f];
-        const int e = feat_of(f, g).ext;
-        s[e] = (float)((double)s[e] + v);
+// ------------------------------------------------------------------------------------------------------------
+// float32 fast path: NHWC / ROWS inputs with Cin % 4 == 0.  In the internal (tap-major, channel-minor) feature order
+// four consecutive features are four consecutive channels of one tap, i.e. 16 contiguous bytes of the activation.
+// Thread (k = tid / 16, q = tid % 16) stages features 4q..4q+3 of row k of every panel with one 16-byte load; its
+// row position (image, oy, ox) is advanced incrementally from chunk to chunk.  Loads for chunk c+1 are issued before
+// the MFMAs of chunk c and written to the other LDS buffer afterwards, so a chunk costs one barrier.
+struct SmemVec {
+    alignas(16) float tile[2][MAX_SLOTS][KT_F32][BLK];
+};
+
+__global__ __launch_bounds__(256) void cov_partial_f32v4_kernel(const float* __restrict__ X, CovGeom g, float* __restrict__ part,
+                                                                float* __restrict__ spart) {
+    constexpr int KT = KT_F32;
+    __shared__ SmemVec sm;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int item_idx = blockIdx.x, split = blockIdx.y;
+    const Item it = get_item(item_idx, g.nb);
+    const int k = tid >> 4, q = tid & 15;
+
+    int f_off[MAX_SLOTS], f_tap[MAX_SLOTS];  // tap packed as ky << 16 | kx; -1 = nothing to stage
+#pragma unroll
+    for (int s = 0; s < MAX_SLOTS; ++s) {
+        const int fi = it.slot_blk[s] * BLK + 4 * q;
+        const bool ok = it.slot_blk[s] >= 0 && fi < g.M;
+        Feat f = feat_of(ok ? fi : 0, g);
+        f_off[s] = f.off;
+        f_tap[s] = ok ? ((f.ky << 16) | f.kx) : -1;
     }
+    float4 ssum[2];  // column sums are only ever asked for panels 0 and 1
+    ssum[0] = ssum[1] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    const int sa = pick4(it.ja, wave), sb = pick4(it.jb, wave);
+    const int r_begin = split * g.rows_per_split;
+    const int r_end = min(g.n_rows, r_begin + g.rows_per_split);
+    const int half = lane >> 5, l32 = lane & 31;
+
+    // position of this thread's row in the first chunk
+    int r = r_begin + k;
+    int rb, oy, ox;
+    {
+        const int P = g.Ho * g.Wo;
+        rb = r / P;
+        const int p = r - rb * P;
+        oy = p / g.Wo;
+        ox = p - oy * g.Wo;
+    }
+    float4 pre[MAX_SLOTS];
+    auto load_chunk = [&]() {
+        const int iy0 = oy * g.stride - g.pad, ix0 = ox * g.stride - g.pad;
+        const long long base = (((long long)rb * g.H + iy0) * g.W + ix0) * g.Cin;
+        const bool row_ok = r < r_end;
+#pragma unroll
+        for (int s = 0; s < MAX_SLOTS; ++s) {
+            pre[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (it.slot_blk[s] < 0) continue;
+            const bool ok = row_ok && f_tap[s] >= 0 && (unsigned)(iy0 + (f_tap[s] >> 16)) < (unsigned)g.H &&
+                            (unsigned)(ix0 + (f_tap[s] & 0xffff)) < (unsigned)g.W;
+            if (ok) pre[s] = *reinterpret_cast<const float4*>(X + base + f_off[s]);
+        }
+    };
+    auto advance = [&]() {
+        r += KT;
+        rb += g.adv_b; oy += g.adv_y; ox += g.adv_x;
+        if (ox >= g.Wo) { ox -= g.Wo; ++oy; }
+        if (oy >= g.Ho) { oy -= g.Ho; ++rb; }
+    };
+    auto store_chunk = [&](int buf) {
+        const int pos = (4 * q + ((k & 1) << 5)) & 63;
+#pragma unroll
+        for (int s = 0; s < MAX_SLOTS; ++s) {
+            if (it.slot_blk[s] < 0) continue;
+            *reinterpret_cast<float4*>(&sm.tile[buf][s][k][pos]) = pre[s];
+            if (s < 2 && ((it.summask >> s) & 1)) {
+                ssum[s].x += pre[s].x; ssum[s].y += pre[s].y; ssum[s].z += pre[s].z; ssum[s].w += pre[s].w;
+            }
+        }
+    };
+
+    const int nchunks = (r_end - r_begin + KT - 1) / KT;
+    if (nchunks > 0) {
+        load_chunk();
+        store_chunk(0);
+    }
+    __syncthreads();
+    // The loop exists twice, with and without the matrix instructions, so that a wavefront without a block keeps
+    // staging and meeting the barriers while the accumulators of the others never sit behind a branch.
+    auto run = [&](auto active) {
+        for (int c = 0; c < nchunks; ++c) {
+            const int buf = c & 1;
+            const bool more = c + 1 < nchunks;
+            if (more) { advance(); load_chunk(); }
+            if constexpr (decltype(active)::value) {
+                const float* ta_base = &sm.tile[buf][sa][0][0];
+                const float* tb_base = &sm.tile[buf][sb][0][0];
+#pragma unroll
+                for (int k0 = 0; k0 < KT; k0 += 2) {
+                    const int kk = k0 + half;
+                    const int rot = half << 5;  // k0 is even, so the parity of the row is `half`
+                    float a[2], b[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        a[t] = ta_base[kk * BLK + ((32 * t + l32 + rot) & 63)];
+                        b[t] = tb_base[kk * BLK + ((32 * t + l32 + rot) & 63)];
+                    }
+#pragma unroll
+                    for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+                        for (int tb = 0; tb < 2; ++tb)
+                            acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
+                }
+            }
+            if (more) store_chunk(buf ^ 1);
+            __syncthreads();
+        }
+    };
+    if (sa >= 0) run(std::true_type{}); else run(std::false_type{});
+
+    if (sa >= 0) {
+        float* dst = part + (((size_t)split * g.nitems + item_idx) * 4 + wave) * (BLK * BLK);
+#pragma unroll
+        for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int row = 32 * ta + 8 * (i >> 2) + 4 * half + (i & 3);
+                    const int col = 32 * tb + l32;
+                    dst[row * BLK + col] = acc[ta][tb][i];
+                }
+    }
+    if (it.summask) {
+        // column sums: 16 row-threads share a feature quad; combine them through LDS (the tiles are dead by now)
+        float* red = &sm.tile[0][0][0][0];  // [slot][k][64 features]
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+            if ((it.summask >> s) & 1) *reinterpret_cast<float4*>(&red[(s * 16 + k) * 64 + 4 * q]) = ssum[s];
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                if ((it.summask >> s) & 1) {
+                    float v = 0.f;
+#pragma unroll
+                    for (int kk = 0; kk < 16; ++kk) v += red[(s * 16 + kk) * 64 + lane];
+                    spart[(size_t)split * g.nb * BLK + it.slot_blk[s] * BLK + lane] = v;
+                }
+        }
+    }
+}
+
+// Sum the partial blocks over the row splits in float64 and add them into A (lower triangle, external order).
+// One thread per element of a partial block; consecutive threads read consecutive addresses of every split.
+__global__ __launch_bounds__(256) void cov_reduce_kernel(CovGeom g, const float* __restrict__ part, float* __restrict__ A) {
+    const int blk = blockIdx.x >> 4;                       // (item, wavefront)
+    const int e = ((blockIdx.x & 15) << 8) + threadIdx.x;  // element of the 64x64 block
+    const int item_idx = blk >> 2, wave = blk & 3;
+    const Item it = get_item(item_idx, g.nb);
+    const int ja = pick4(it.ja, wave), jb = pick4(it.jb, wave);
+    if (ja < 0) return;
+    const int bi = pick_slot(it, ja), bj = pick_slot(it, jb);
+    const int row = e >> 6, col = e & 63;
+    const int fi = bi * BLK + row, fj = bj * BLK + col;
+    if (fi >= g.M || fj >= g.M) return;
+    if (bi == bj && row < col) return;  // diagonal block: its upper half duplicates the lower
+    const size_t stride = (size_t)g.nitems * 4 * BLK * BLK;
+    const float* src = part + (size_t)blk * (BLK * BLK) + e;
+    double v = 0.0;
+    for (int sp = 0; sp < g.nsplit; ++sp) v += (double)src[sp * stride];
+    const int ei = feat_of(fi, g).ext, ej = feat_of(fj, g).ext;
+    const int hi = max(ei, ej), lo = min(ei, ej);
+    float* dst = A + (size_t)hi * g.M + lo;
+    *dst = (float)((double)*dst + v);
+}
+
+__global__ __launch_bounds__(256) void cov_reduce_sums_kernel(CovGeom g, const float* __restrict__ spart, float* __restrict__ s) {
+    const int f = blockIdx.x * 256 + threadIdx.x;
+    if (f >= g.M) return;
+    double v = 0.0;
+    for (int sp = 0; sp < g.nsplit; ++sp) v += (double)spart[(size_t)sp * g.nb * BLK + f];
+    const int e = feat_of(f, g).ext;
+    s[e] = (float)((double)s[e] + v);
 }
 
 bool make_geom(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, CovGeom* g) {
@@ -319,14 +485,22 @@ bool make_geom(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, CovGeom* g) {
     item_counts(g->nb, &g->n0, &g->n1, &g->n2);
     g->nitems = g->n0 + g->n1 + g->n2;
     const int KT = dt == FW_BF16 ? KT_BF16 : KT_F32;
-    long long want = (1024 + g->nitems - 1) / g->nitems;            // aim at about 1024 workgroups
-    const long long max_split = (n_rows + 4 * KT - 1) / (4 * KT);   // at least four chunks per split
+    // Split the rows so that the grid is close to a whole number of resident rounds: 256 compute units times the
+    // workgroups one of them holds (LDS-limited), with at least four chunks of rows per split.
+    long long capacity = 256 * (dt == FW_BF16 ? 4 : 3);
+    if (const char* e = getenv("FW_COV_CAPACITY")) capacity = atoll(e);
+    long long want = capacity / g->nitems;
+    const long long max_split = (n_rows + 4 * KT - 1) / (4 * KT);
     if (want > max_split) want = max_split;
     if (want < 1) want = 1;
     long long rps = (n_rows + want - 1) / want;
     rps = (rps + KT - 1) / KT * KT;
     g->rows_per_split = (int)rps;
     g->nsplit = (int)((n_rows + rps - 1) / rps);
+    const int P = g->Ho * g->Wo;
+    g->adv_b = KT_F32 / P;
+    g->adv_y = (KT_F32 % P) / g->Wo;
+    g->adv_x = (KT_F32 % P) % g->Wo;
     return true;
 }
 
@@ -418,13 +592,16 @@ fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_con
     float* part = reinterpret_cast<float*>(ws);
     float* spart = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + part_bytes);
     const dim3 grid(g.nitems, g.nsplit);
-    if (dt == FW_BF16)
+    const bool vec4 = dt == FW_F32 && lay != FW_LAYOUT_NCHW && (g.Cin % 4) == 0;
+    if (vec4)
+        hipLaunchKernelGGL(cov_partial_f32v4_kernel, grid, dim3(256), 0, st, reinterpret_cast<const float*>(X), g, part, spart);
+    else if (dt == FW_BF16)
         hipLaunchKernelGGL(cov_partial_kernel<true>, grid, dim3(256), 0, st, X, g, part, spart);
     else
         hipLaunchKernelGGL(cov_partial_kernel<false>, grid, dim3(256), 0, st, X, g, part, spart);
     FW_LAUNCH_CHECK();
-    const int rblocks = g.nitems * 4 + (g.M + 255) / 256;
-    hipLaunchKernelGGL(cov_reduce_kernel, dim3(rblocks), dim3(256), 0, st, g, part, spart, A, s);
+    hipLaunchKernelGGL(cov_reduce_kernel, dim3(g.nitems * 4 * 16), dim3(256), 0, st, g, part, A);
+    hipLaunchKernelGGL(cov_reduce_sums_kernel, dim3((g.M + 255) / 256), dim3(256), 0, st, g, spart, s);
     FW_LAUNCH_CHECK();
     return FW_OK;
 }
