@@ -26,16 +26,23 @@ struct Scal {
 };
 
 constexpr int TILE = 32;
-constexpr int VM_ROWS = 256;  // rows per workgroup in the T^T v partial products
+constexpr int VM_ROWS_MIN = 16;  // fewest rows a workgroup takes in the T^T v partial products
 
 struct WsLayout {
     size_t c, w, vt, v, u, t, p, tpart, xpart, scal, total;
-    int Mp, nrb, nt;
+    int Mp, nrb, vm_rows, nt;
 };
 inline WsLayout ws_layout(int M) {
     WsLayout L;
     L.Mp = (M + 63) / 64 * 64;
-    L.nrb = (M + VM_ROWS - 1) / VM_ROWS;
+    // rows per workgroup of the T^T v pass: about 1024 workgroups in all, a multiple of 16 rows, at least 16
+    {
+        const long long colblocks = (M + 255) / 256;
+        long long rows = ((long long)M * colblocks + 1023) / 1024;
+        rows = (rows + VM_ROWS_MIN - 1) / VM_ROWS_MIN * VM_ROWS_MIN;
+        L.vm_rows = (int)rows;
+    }
+    L.nrb = (M + L.vm_rows - 1) / L.vm_rows;
     L.nt = (M + TILE - 1) / TILE;
     size_t o = 0;
     auto take = [&](size_t floats) { size_t at = o; o += align_up(floats * sizeof(float), 256); return at; };
@@ -147,29 +154,40 @@ __global__ __launch_bounds__(1024) void normalize_kernel(const float* __restrict
 
 // partial products of t = T^T v over blocks of VM_ROWS rows: tpart[rb][j] = sum_{i in rb} T[i][j] v[i]
 __global__ __launch_bounds__(256) void vecmat_partial_kernel(const float* __restrict__ T, const float* __restrict__ v, int M, int Mp,
-                                                             float* __restrict__ tpart) {
+                                                             int vm_rows, float* __restrict__ tpart) {
     const int j = blockIdx.x * 256 + threadIdx.x;
-    const int i0 = blockIdx.y * VM_ROWS;
-    const int i1 = min(M, i0 + VM_ROWS);
+    const int i0 = blockIdx.y * vm_rows;
+    const int i1 = min(M, i0 + vm_rows);
     if (j >= M) return;
     float acc = 0.f;
-    for (int i = i0; i < i1; ++i) acc += T[(size_t)i * M + j] * v[i];
+    int i = i0;
+    for (; i + 8 <= i1; i += 8) {
+        float x[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) x[q] = T[(size_t)(i + q) * M + j];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc += x[q] * v[i + q];
+    }
+    for (; i < i1; ++i) acc += T[(size_t)i * M + j] * v[i];
     tpart[(size_t)blockIdx.y * Mp + j] = acc;
 }
 
-// t = sum of partials; lambda_e = v^T u (eq. (lambda)); g_e, a_e (eqs. (ge), (xi)); guard; diagnostics
-__global__ __launch_bounds__(1024) void scalars_kernel(const float* __restrict__ v, const float* __restrict__ u,
-                                                       const float* __restrict__ tpart, int nrb, int M, int Mp,
+// t[j] = sum over row blocks of the partial products
+__global__ __launch_bounds__(256) void t_reduce_kernel(const float* __restrict__ tpart, int nrb, int M, int Mp, float* __restrict__ t) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= M) return;
+    float acc = 0.f;
+    for (int b = 0; b < nrb; ++b) acc += tpart[(size_t)b * Mp + j];
+    t[j] = acc;
+}
+
+// lambda_e = v^T u (eq. (lambda)); g_e, a_e (eqs. (ge), (xi)); guard; diagnostics
+__global__ __launch_bounds__(1024) void scalars_kernel(const float* __restrict__ v, const float* __restrict__ u, int M,
                                                        const float* __restrict__ lambda_bar, fw_cond_params prm, Scal* __restrict__ sc,
-                                                       float* __restrict__ t, fw_cond_info* __restrict__ info) {
+                                                       fw_cond_info* __restrict__ info) {
     __shared__ float red[16];
     float dot = 0.f;
-    for (int m = threadIdx.x; m < M; m += blockDim.x) {
-        float acc = 0.f;
-        for (int b = 0; b < nrb; ++b) acc += tpart[(size_t)b * Mp + m];
-        t[m] = acc;
-        dot += v[m] * u[m];
-    }
+    for (int m = threadIdx.x; m < M; m += blockDim.x) dot += v[m] * u[m];
     const float lam_e = block_sum(dot, red);
     if (threadIdx.x == 0) {
         int flags = sc->flags;
@@ -342,8 +360,9 @@ fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_c
         hipLaunchKernelGGL(normalize_kernel, dim3(1), dim3(1024), 0, st, vt, M, sc, v);
     }
     hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, v, sc, 0, M, u);
-    hipLaunchKernelGGL(vecmat_partial_kernel, dim3((M + 255) / 256, L.nrb), dim3(256), 0, st, s->T, v, M, L.Mp, tpart);
-    hipLaunchKernelGGL(scalars_kernel, dim3(1), dim3(1024), 0, st, v, u, tpart, L.nrb, M, L.Mp, s->lambda_bar, *p, sc, t, info);
+    hipLaunchKernelGGL(vecmat_partial_kernel, dim3((M + 255) / 256, L.nrb), dim3(256), 0, st, s->T, v, M, L.Mp, L.vm_rows, tpart);
+    hipLaunchKernelGGL(t_reduce_kernel, dim3((M + 255) / 256), dim3(256), 0, st, tpart, L.nrb, M, L.Mp, t);
+    hipLaunchKernelGGL(scalars_kernel, dim3(1), dim3(1024), 0, st, v, u, M, s->lambda_bar, *p, sc, info);
     if (p->gamma < 1.f)
         hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_x, t, sc, 0, M, pv);
     hipLaunchKernelGGL(update_kernel, dim3(L.nt, L.nt), dim3(256), 0, st, *s, v, u, t, pv, sc, p->gamma, p->beta, L.Mp, xpart);

@@ -462,13 +462,20 @@ __global__ __launch_bounds__(256) void cov_reduce_kernel(CovGeom g, const float*
     *dst = (float)((double)*dst + v);
 }
 
+// column sums: 64 features per workgroup, the splits dealt to four groups of threads and combined through LDS
 __global__ __launch_bounds__(256) void cov_reduce_sums_kernel(CovGeom g, const float* __restrict__ spart, float* __restrict__ s) {
-    const int f = blockIdx.x * 256 + threadIdx.x;
-    if (f >= g.M) return;
+    __shared__ double red[4][64];
+    const int f = blockIdx.x * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
     double v = 0.0;
-    for (int sp = 0; sp < g.nsplit; ++sp) v += (double)spart[(size_t)sp * g.nb * BLK + f];
-    const int e = feat_of(f, g).ext;
-    s[e] = (float)((double)s[e] + v);
+    if (f < g.M)
+        for (int sp = grp; sp < g.nsplit; sp += 4) v += (double)spart[(size_t)sp * g.nb * BLK + f];
+    red[grp][threadIdx.x & 63] = v;
+    __syncthreads();
+    if (grp == 0 && f < g.M) {
+        v = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+        const int e = feat_of(f, g).ext;
+        s[e] = (float)((double)s[e] + v);
+    }
 }
 
 bool make_geom(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, CovGeom* g) {
@@ -601,7 +608,7 @@ fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_con
         hipLaunchKernelGGL(cov_partial_kernel<false>, grid, dim3(256), 0, st, X, g, part, spart);
     FW_LAUNCH_CHECK();
     hipLaunchKernelGGL(cov_reduce_kernel, dim3(g.nitems * 4 * 16), dim3(256), 0, st, g, part, A);
-    hipLaunchKernelGGL(cov_reduce_sums_kernel, dim3((g.M + 255) / 256), dim3(256), 0, st, g, spart, s);
+    hipLaunchKernelGGL(cov_reduce_sums_kernel, dim3((g.M + 63) / 64), dim3(256), 0, st, g, spart, s);
     FW_LAUNCH_CHECK();
     return FW_OK;
 }

@@ -72,6 +72,59 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_kernel(const float* __restr
         }
 }
 
+// Small problems (too few 64x128 tiles to fill the chip): a workgroup owns a 32x32 tile of G_out and its four
+// wavefronts split the contraction index four ways; operands come straight from global memory / L2 (G is small and
+// Q rows are read coalesced), partial tiles are combined through LDS.  Latency-bound by design.
+__global__ __launch_bounds__(256) void grad_gemm_f32_small_kernel(const float* __restrict__ G, const float* __restrict__ Q,
+                                                                  float* __restrict__ Out, int S, int M) {
+    __shared__ float red[3][32 * 32];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    const int row0 = blockIdx.y * 32, col0 = blockIdx.x * 32;
+    int kq = ((M + 3) / 4 + 1) & ~1;             // even slice length per wavefront
+    const int kb = wave * kq, ke = min(M, kb + kq);
+    const int r = row0 + l32, c = col0 + l32;
+    const bool r_ok = r < S, c_ok = c < M;
+    const float* gp = G + (size_t)(r_ok ? r : 0) * M;
+    const float* qp = Q + (c_ok ? c : 0);
+    floatx16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    int k = kb;
+    for (; k + 16 <= ke; k += 16) {
+        float a[8], b[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int kk = k + 2 * j + half;
+            a[j] = r_ok ? gp[kk] : 0.f;
+            b[j] = c_ok ? qp[(size_t)kk * M] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b[j], acc, 0, 0, 0);
+    }
+    for (; k < ke; k += 2) {
+        const int kk = k + half;
+        const bool k_ok = kk < ke;
+        const float a = (r_ok && k_ok) ? gp[kk] : 0.f;
+        const float b = (c_ok && k_ok) ? qp[(size_t)kk * M] : 0.f;
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) red[wave - 1][(8 * (i >> 2) + 4 * half + (i & 3)) * 32 + l32] = acc[i];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int rr = 8 * (i >> 2) + 4 * half + (i & 3);
+            const float v = acc[i] + red[0][rr * 32 + l32] + red[1][rr * 32 + l32] + red[2][rr * 32 + l32];
+            if (row0 + rr < S && c_ok) Out[(size_t)(row0 + rr) * M + c] = v;
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void grad_gemm_bf16_kernel(const unsigned short* __restrict__ G, const float* __restrict__ Q,
                                                              unsigned short* __restrict__ Out, int S, int M) {
     __shared__ __attribute__((aligned(16))) unsigned char Gt[TM][ROWB];   // [row][k] bf16
@@ -130,6 +183,9 @@ fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, vo
     if (dt == FW_BF16)
         hipLaunchKernelGGL(grad_gemm_bf16_kernel, grid, dim3(256), 0, st, reinterpret_cast<const unsigned short*>(G), Q,
                            reinterpret_cast<unsigned short*>(G_out), S, M);
+    else if ((long long)grid.x * grid.y < 200)
+        hipLaunchKernelGGL(grad_gemm_f32_small_kernel, dim3((M + 31) / 32, (S + 31) / 32), dim3(256), 0, st,
+                           reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M);
     else
         hipLaunchKernelGGL(grad_gemm_f32_kernel, grid, dim3(256), 0, st, reinterpret_cast<const float*>(G), Q,
                            reinterpret_cast<float*>(G_out), S, M);
