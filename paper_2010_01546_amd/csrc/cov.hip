@@ -582,6 +582,7 @@ fw_status fill_f32(float* p, size_t n, float v, hipStream_t st) {
 }
 
 size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_layout lay) {
+    if (dt == FW_BF16) return cov_bf16_workspace_bytes(d, lay);
     CovGeom g;
     if (!d || !make_geom(d, dt, lay, &g)) return 0;
     const size_t part = (size_t)g.nsplit * g.nitems * 4 * BLK * BLK * sizeof(float);
@@ -591,6 +592,7 @@ size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_lay
 
 fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,
                          size_t ws_bytes, hipStream_t st) {
+    if (dt == FW_BF16) return cov_bf16_accumulate(X, lay, d, A, s, ws, ws_bytes, st);
     CovGeom g;
     if (!make_geom(d, dt, lay, &g)) return FW_ERR_UNSUPPORTED;
     const size_t part_bytes = align_up((size_t)g.nsplit * g.nitems * 4 * BLK * BLK * sizeof(float), 256);
