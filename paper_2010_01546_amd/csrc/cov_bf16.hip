@@ -160,6 +160,24 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
         }
     };
 
+    // L2 warm-up: every chunk ahead of the register prefetch is touched with one 4-byte load per 128-byte line, so that
+    // the 16-byte panel loads find their lines in L2 instead of waiting, all lanes at a barrier, for the slowest miss.
+    // Thread -> (panel, unit, line): 2 x 8 x 32 lines of 8 features.  The value is never used; the empty asm at the top
+    // of the next iteration is only there to retire the load one iteration after it was issued.
+    constexpr int PD = 3;   // chunks between the touch and the MFMAs that consume the chunk
+    const int t_unit = (tid >> 5) & 7, t_panel = tid >> 8;
+    int t_off, t_ext;
+    const int t_feat = (t_panel ? J : I) * TB + 8 * (tid & 31);
+    const bool t_ok = t_feat < g.M && !(diag && t_panel);
+    feat_map(t_ok ? t_feat : 0, g, &t_off, &t_ext);
+    unsigned pending = 0;
+    int t_base = -1;
+    auto touch_base = [&](int c) {
+        const int u = u_begin + c * KU + t_unit;
+        return (c < nchunks && u < u_end) ? utab[u] : -1;
+    };
+    t_base = touch_base(PD);
+
     load_bases(0);
     if (nchunks > 0) {
         load_chunk();
@@ -171,20 +189,30 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
         const bool more = c + 1 < nchunks;
+        asm volatile("" ::"v"(pending));
         if (more) { load_chunk(); load_bases(c + 2); }
+        if (t_ok && t_base >= 0) pending = *reinterpret_cast<const unsigned*>(P + t_base + t_off);
+        t_base = touch_base(c + PD + 1);
+        // operand fragments are read one k-step ahead of the MFMAs that use them (two register sets)
+        bf16x8 fa[2][4], fb[2][2];
+        auto read_frags = [&](int ks, int set) {
+            const int unit = 2 * ks + half;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) fa[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[buf][0][unit][128 * wi + 32 * t + l32]);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) fb[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[buf][pj][unit][64 * wj + 32 * t + l32]);
+        };
+        read_frags(0, 0);
 #pragma unroll
         for (int ks = 0; ks < KU / 2; ++ks) {
-            const int unit = 2 * ks + half;
-            bf16x8 fa[4], fb[2];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) fa[t] = *reinterpret_cast<const bf16x8*>(&sm.pan[buf][0][unit][128 * wi + 32 * t + l32]);
-#pragma unroll
-            for (int t = 0; t < 2; ++t) fb[t] = *reinterpret_cast<const bf16x8*>(&sm.pan[buf][pj][unit][64 * wj + 32 * t + l32]);
+            if (ks + 1 < KU / 2) read_frags(ks + 1, (ks + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);   // keep the reads of the next step ahead of this step's MFMAs
 #pragma unroll
             for (int ta = 0; ta < 4; ++ta)
 #pragma unroll
                 for (int tb = 0; tb < 2; ++tb)
-                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ta], fb[tb], acc[ta][tb], 0, 0, 0);
+                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][ta], fb[ks & 1][tb], acc[ta][tb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (more) store_chunk(buf ^ 1);
         __syncthreads();
