@@ -36,7 +36,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4"])
-    ap.add_argument("--layout", default="nhwc", choices=["nhwc", "nchw"])
+    ap.add_argument("--layout", default="kkc", choices=["kkc", "nhwc", "nchw"],
+                    help="kkc: NHWC tensor with channels-last feature order (ky,kx,c); nhwc/nchw: feature order (c,ky,kx)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -64,7 +65,7 @@ def main():
         lay = b.FW_LAYOUT_ROWS
         X = torch.as_tensor(layer.act).to(dev).to(tdt).contiguous()
     else:
-        lay = b.FW_LAYOUT_NHWC if args.layout == "nhwc" else b.FW_LAYOUT_NCHW
+        lay = {"kkc": b.FW_LAYOUT_NHWC_KKC, "nhwc": b.FW_LAYOUT_NHWC, "nchw": b.FW_LAYOUT_NCHW}[args.layout]
         X = torch.as_tensor(wl.to_layout(layer.act, lay)).to(dev).to(tdt).contiguous()
     desc = b.conv_desc(*d.astuple())
     G = torch.as_tensor(layer.G).to(dev)          # float32 gradient (configs 3-5 cast inside a bf16 variant; fp32 here)

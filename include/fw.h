@@ -15,8 +15,9 @@
  *   - Matrices are dense, row-major, leading dimension = number of columns, float32 unless stated.
  *     Device pointers must be 16-byte aligned (FW_ERR_ALIGNMENT otherwise).
  *   - A convolution layer is taken in unfolded form: the sample rows x are the B*P patches of the input
- *     (P = Ho*Wo output positions), M = Cin*kh*kw features in the order m = (c*kh + ky)*kw + kx, zero
- *     padding counts as data.  N_rows = B*P.
+ *     (P = Ho*Wo output positions), M = Cin*kh*kw features in the order m = (c*kh + ky)*kw + kx (the order of a
+ *     contiguous weight tensor [S, Cin, kh, kw] viewed as [S, M]) unless the layout says otherwise, zero padding
+ *     counts as data.  N_rows = B*P.  Whatever order is chosen, G, T, Q and Phi_x of a layer must all use it.
  *   - The library allocates no device memory, keeps no state between calls and never frees.  Scratch comes
  *     from the caller through (ws, ws_bytes); fw_workspace_bytes gives the size an entry point needs.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on it and the
@@ -49,7 +50,10 @@ typedef enum { FW_F32 = 0, FW_BF16 = 1 } fw_dtype;
 typedef enum {
     FW_LAYOUT_ROWS = 0,  /* X is the row matrix [N_rows, M] itself (fully connected layer, or pre-unfolded) */
     FW_LAYOUT_NCHW = 1,  /* activation tensor [B, Cin, H, W] */
-    FW_LAYOUT_NHWC = 2   /* activation tensor [B, H, W, Cin] */
+    FW_LAYOUT_NHWC = 2,  /* activation tensor [B, H, W, Cin] */
+    FW_LAYOUT_NHWC_KKC = 3 /* activation tensor [B, H, W, Cin], features ordered m = (ky*kw + kx)*Cin + c: the order of a
+                              channels-last weight tensor [S, kh, kw, Cin] viewed as [S, M].  This is the order the kernels
+                              work in; the other tensor layouts pay a permutation of A when the sums are written out. */
 } fw_layout;
 
 /* Geometry of a layer input.  FW_LAYOUT_ROWS: B = N_rows, Cin = M, H = W = kh = kw = stride = 1, pad = 0. */

@@ -30,11 +30,12 @@ F64 = np.float64
 # Patch rows (explicit unfolding) -- Sec. 2, eq. (vXp): the matrix whose columns are
 # the spatial elements x_n; here stored row-wise.
 # =============================================================================
-def patch_rows(act_nhwc: np.ndarray, B, Cin, H, W, kh, kw, stride, pad) -> np.ndarray:
+def patch_rows(act_nhwc: np.ndarray, B, Cin, H, W, kh, kw, stride, pad, order: str = "ckk") -> np.ndarray:
     """Explicit unfolding of an activation tensor [B,H,W,Cin] into patch rows [B*Ho*Wo, Cin*kh*kw].
 
     X[(b*Ho+oy)*Wo+ox, (c*kh+ky)*kw+kx] = act[b, oy*stride+ky-pad, ox*stride+kx-pad, c], zero outside the image.
     Padding zeros are data of the patch vectors like any other value.
+    order "kkc" puts the same values in the feature order m = (ky*kw+kx)*Cin + c (channels-last weights).
     """
     a = np.asarray(act_nhwc, dtype=F64).reshape(B, H, W, Cin)
     Ho = (H + 2 * pad - kh) // stride + 1
@@ -45,13 +46,20 @@ def patch_rows(act_nhwc: np.ndarray, B, Cin, H, W, kh, kw, stride, pad) -> np.nd
     for ky in range(kh):
         for kx in range(kw):
             X[:, :, :, :, ky, kx] = ap[:, ky:ky + stride * (Ho - 1) + 1:stride, kx:kx + stride * (Wo - 1) + 1:stride, :]
+    if order == "kkc":
+        X = np.ascontiguousarray(np.transpose(X, (0, 1, 2, 4, 5, 3)))
+    elif order != "ckk":
+        raise ValueError(order)
     return X.reshape(B * Ho * Wo, Cin * kh * kw)
 
 
-def patch_feature_column(act_nhwc: np.ndarray, B, Cin, H, W, kh, kw, stride, pad, m: int) -> np.ndarray:
+def patch_feature_column(act_nhwc: np.ndarray, B, Cin, H, W, kh, kw, stride, pad, m: int, order: str = "ckk") -> np.ndarray:
     """One column of the patch-row matrix (feature m over all B*P rows), without forming the matrix."""
     a = np.asarray(act_nhwc).reshape(B, H, W, Cin)
-    c, r = divmod(m, kh * kw)
+    if order == "ckk":
+        c, r = divmod(m, kh * kw)
+    else:
+        r, c = divmod(m, Cin)
     ky, kx = divmod(r, kw)
     Ho = (H + 2 * pad - kh) // stride + 1
     Wo = (W + 2 * pad - kw) // stride + 1

@@ -20,7 +20,7 @@ lib = C.CDLL(LIB_PATH)
 
 FW_OK, FW_ERR_INVALID_ARG, FW_ERR_UNSUPPORTED, FW_ERR_ALIGNMENT, FW_ERR_WORKSPACE, FW_ERR_HIP, FW_ERR_NOT_CONVERGED = range(7)
 FW_F32, FW_BF16 = 0, 1
-FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC = 0, 1, 2
+FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
 FW_OP_COV_ACCUMULATE, FW_OP_GRAD_TRANSFORM, FW_OP_COND_REDUCE_STEP, FW_OP_WHITEN_EVD = range(4)
 
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",

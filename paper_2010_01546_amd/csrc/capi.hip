@@ -15,7 +15,7 @@ bool desc_ok(const fw_conv_desc* d, fw_layout lay) {
 }
 
 bool dtype_ok(fw_dtype dt) { return dt == FW_F32 || dt == FW_BF16; }
-bool layout_ok(fw_layout l) { return l == FW_LAYOUT_ROWS || l == FW_LAYOUT_NCHW || l == FW_LAYOUT_NHWC; }
+bool layout_ok(fw_layout l) { return l == FW_LAYOUT_ROWS || l == FW_LAYOUT_NCHW || l == FW_LAYOUT_NHWC || l == FW_LAYOUT_NHWC_KKC; }
 
 size_t grad_ws_bytes(int M) {
     fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0};

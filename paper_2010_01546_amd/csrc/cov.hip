@@ -9,7 +9,8 @@
 // per-row table (image, top-left corner) and a per-feature offset (tap, channel), zero outside the image.
 //
 // Internally features are ordered tap-major / channel-minor for NHWC and ROWS inputs so that consecutive lanes
-// read consecutive channels; the reduce kernel maps back to the external order m = (c*kh + ky)*kw + kx.
+// read consecutive channels; the reduce kernel maps back to the external order m = (c*kh + ky)*kw + kx, or keeps the
+// internal order when the caller asked for it (FW_LAYOUT_NHWC_KKC).
 #include "fw_internal.h"
 #include <stdlib.h>
 #include <type_traits>
@@ -110,7 +111,7 @@ __device__ __forceinline__ Feat feat_of(int fi, const CovGeom& g) {
         const int t = fi / g.Cin, c = fi - t * g.Cin;
         f.ky = t / g.kw; f.kx = t - f.ky * g.kw;
         f.off = (f.ky * g.W + f.kx) * g.Cin + c;
-        f.ext = c * (g.kh * g.kw) + t;
+        f.ext = g.layout == FW_LAYOUT_NHWC_KKC ? fi : c * (g.kh * g.kw) + t;
     }
     return f;
 }

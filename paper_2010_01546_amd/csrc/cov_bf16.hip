@@ -29,6 +29,7 @@ struct TileGeom {
     int B, Bg, Cin, H, W, Hp, Wp, kh, kw, stride, pad, Ho, Wo;
     int layout;
     int n_units, units_per_split, nsplit;
+    int direct;   // one range per tile and external order == internal order: tiles are added straight into A
 };
 
 typedef unsigned short u16;
@@ -78,11 +79,12 @@ __global__ __launch_bounds__(256) void unit_table_kernel(TileGeom g, int* __rest
 }
 
 // internal feature (tap-major, channel-minor) -> offset inside a unit, external index m = (c*kh + ky)*kw + kx
+// (or the internal index itself when the caller works in channels-last feature order)
 __device__ __forceinline__ void feat_map(int fi, const TileGeom& g, int* off, int* ext) {
     const int t = fi / g.Cin, c = fi - t * g.Cin;
     const int ky = t / g.kw, kx = t - ky * g.kw;
     *off = (ky * g.Wp + kx) * g.Cin + c;
-    *ext = c * (g.kh * g.kw) + t;
+    *ext = g.layout == FW_LAYOUT_NHWC_KKC ? fi : c * (g.kh * g.kw) + t;
 }
 
 __device__ __forceinline__ float sum8_bf16(const uint4& v) {
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
     }
 
     // ---- epilogue
-    if (g.nsplit > 1) {
+    if (!g.direct) {
         float* dst = part + ((size_t)split * g.ntiles + tile) * (TB * TB);
 #pragma unroll
         for (int ta = 0; ta < 4; ++ta)
@@ -232,31 +234,25 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
                     dst[row * TB + col] = acc[ta][tb][i];
                 }
     } else {
-        // one range per tile: add into A directly; the external indices of the tile's features go through LDS
-        int* ext = reinterpret_cast<int*>(&sm.pan[0][0][0][0]);   // [2][256]; the panels are dead after the last barrier
-        if (tid < 256) { ext[f] = okA ? extA : -1; ext[256 + f] = okB ? extB : -1; }
-        __syncthreads();
+        // one range per tile, feature order kept: add into the lower triangle of A, 32 lanes along a row
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
             const int col = 64 * wj + 32 * tb + l32;
-            const int ej = ext[256 + col];
+            const int gj = J * TB + col;
 #pragma unroll
             for (int ta = 0; ta < 4; ++ta)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int row = 128 * wi + 32 * ta + 8 * (i >> 2) + 4 * half + (i & 3);
-                    const int ei = ext[row];
-                    if (ei < 0 || ej < 0 || (diag && row < col)) continue;
-                    float* dst = A + (size_t)max(ei, ej) * g.M + min(ei, ej);
-                    *dst += acc[ta][tb][i];
+                    const int gi = I * TB + row;
+                    if (gi >= g.M || gj >= g.M || gj > gi) continue;
+                    A[(size_t)gi * g.M + gj] += acc[ta][tb][i];
                 }
         }
-        __syncthreads();
     }
     if (diag) {
         // column sums of this block: the two unit groups of a feature meet in LDS
         float* red = reinterpret_cast<float*>(&sm.pan[1][0][0][0]);
-        if (g.nsplit > 1) __syncthreads();
         red[tid] = ssum;
         __syncthreads();
         if (tid < 256 && okA) spart[(size_t)split * g.nb * TB + I * TB + f] = red[f] + red[256 + f];
@@ -335,6 +331,8 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     const long long cps = (nchunks + best_ns - 1) / best_ns;
     g->units_per_split = (int)(cps * KU);
     g->nsplit = (int)((n_units + g->units_per_split - 1) / g->units_per_split);
+    const bool ident = lay == FW_LAYOUT_NHWC_KKC || lay == FW_LAYOUT_ROWS || d->kh * d->kw == 1;
+    g->direct = (g->nsplit == 1 && ident) ? 1 : 0;
     return true;
 }
 
@@ -345,7 +343,7 @@ Bf16Ws ws_layout(const TileGeom& g) {
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
     L.packed = take((size_t)g.Bg * g.Hp * g.Wp * g.Cin * 16);
     L.utab = take((size_t)g.n_units * 4);
-    L.part = take(g.nsplit > 1 ? (size_t)g.nsplit * g.ntiles * TB * TB * 4 : 0);
+    L.part = take(g.direct ? 0 : (size_t)g.nsplit * g.ntiles * TB * TB * 4);
     L.spart = take((size_t)g.nsplit * g.nb * TB * 4);
     L.total = o;
     return L;
@@ -378,7 +376,7 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     FW_LAUNCH_CHECK();
     hipLaunchKernelGGL(cov_bf16_tile_kernel, dim3(g.ntiles, g.nsplit), dim3(512), 0, st, P, utab, g, part, spart, A);
     FW_LAUNCH_CHECK();
-    if (g.nsplit > 1) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * 256), dim3(256), 0, st, g, part, A);
+    if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * 256), dim3(256), 0, st, g, part, A);
     hipLaunchKernelGGL(tile_reduce_sums_kernel, dim3((g.M + 63) / 64), dim3(256), 0, st, g, spart, s);
     FW_LAUNCH_CHECK();
     return FW_OK;

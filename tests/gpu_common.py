@@ -65,10 +65,11 @@ def run_finalize(A, s, n, M, alpha, first, mu=None, Phi=None, phi=None):
     return mu, Phi, phi, lbar
 
 
-def oracle_rows(layer: wl.Layer):
+def oracle_rows(layer: wl.Layer, layout: int = 0):
+    """Patch rows of the layer in the feature order the given layout implies."""
     if layer.is_rows:
         return np.asarray(layer.act, dtype=np.float64)
-    return ora.patch_rows(layer.act, *layer.desc.astuple())
+    return ora.patch_rows(layer.act, *layer.desc.astuple(), order="kkc" if layout == b.FW_LAYOUT_NHWC_KKC else "ckk")
 
 
 def lower(Am):

@@ -15,12 +15,12 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 def full_config_check(layer, layouts, n_forced, n_free, evd, prm_kw=None):
     M, S = layer.desc.M, layer.S
-    X = oracle_rows(layer)
-    mu_o, Phi_o, phi_o, lbar_o = ora.block_moments(X, 0.0, True)
-    n = X.shape[0]
-    del X
     Phi_dev = None
     for layout in layouts:
+        X = oracle_rows(layer, layout)
+        mu_o, Phi_o, phi_o, lbar_o = ora.block_moments(X, 0.0, True)
+        n = X.shape[0]
+        del X
         A, s = run_cov(layer, layout)
         mu, Phi, phi, lbar = run_finalize(A, s, n, M, 0.0, 1)
         e = relF(Phi.cpu().numpy(), Phi_o)
@@ -91,15 +91,15 @@ def test_config1_pipeline():
 
 
 def test_config2_cifar_layer():
-    full_config_check(wl.config2(), [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NCHW], n_forced=6, n_free=26, evd=False)
+    full_config_check(wl.config2(), [b.FW_LAYOUT_NCHW, b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NHWC_KKC], n_forced=6, n_free=26, evd=False)
 
 
 def test_config3_resnet50_14x14():
-    full_config_check(wl.config3(), [b.FW_LAYOUT_NHWC], n_forced=3, n_free=61, evd=True)
+    full_config_check(wl.config3(), [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NHWC_KKC], n_forced=3, n_free=61, evd=True)
 
 
 def test_config4_resnet50_7x7():
-    full_config_check(wl.config4(), [b.FW_LAYOUT_NHWC], n_forced=2, n_free=62, evd=True)
+    full_config_check(wl.config4(), [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NHWC_KKC], n_forced=2, n_free=62, evd=True)
 
 
 @pytest.mark.parametrize("index", list(range(len(wl.RESNET18_LAYERS))))

@@ -13,7 +13,7 @@ RAW_TOL = {"f32": 1e-5, "bf16": 1e-5}  # raw sums: products of bf16 values are e
 
 
 def check_layer(layer, layout):
-    X = oracle_rows(layer)
+    X = oracle_rows(layer, layout)
     A_o, s_o, n = ora.raw_sums(X)
     A, s = run_cov(layer, layout)
     A_h, s_h = A.cpu().numpy(), s.cpu().numpy()
@@ -48,7 +48,7 @@ CONV_CASES = [  # (B, Cin, H, W, k, stride, pad, dtype)
 ]
 
 
-@pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NCHW])
+@pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NCHW, b.FW_LAYOUT_NHWC_KKC])
 @pytest.mark.parametrize("B,Cin,H,W,k,stride,pad,dtype", CONV_CASES)
 def test_conv_layouts(B, Cin, H, W, k, stride, pad, dtype, layout):
     check_layer(wl.small_conv(B * 100 + Cin, B, Cin, H, W, k, stride, pad, 8, dtype=dtype), layout)
@@ -72,6 +72,13 @@ def test_accumulates_over_batches_and_two_block_recursion():
     mu_o2, Phi_o2, phi_o2, lb_o2 = ora.block_moments(X2, 0.3, False, mu_o, Phi_o, phi_o)
     assert relF(Phi.cpu().numpy(), Phi_o2) < 1e-4 and relF(mu.cpu().numpy(), mu_o2) < 1e-6
     assert relF(phi.cpu().numpy(), phi_o2) < 1e-5 and abs(float(lbar[0]) - lb_o2) < 1e-5 * lb_o2
+
+
+@pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NHWC_KKC])
+@pytest.mark.parametrize("B,Cin,HW,dtype", [(16, 96, 6, "bf16"), (9, 160, 5, "bf16"), (16, 64, 8, "f32")])
+def test_several_tiles_and_single_range(B, Cin, HW, dtype, layout):
+    """M = 9*Cin spans several 256-feature tiles with a ragged last one; few rows, so a tile gets a single row range."""
+    check_layer(wl.small_conv(B + Cin, B, Cin, HW, HW, 3, 1, 1, 8, dtype=dtype), layout)
 
 
 def test_config1_covariance():

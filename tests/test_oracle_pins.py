@@ -43,6 +43,21 @@ def test_unfold_matches_six_nested_loops(B, Cin, H, W, k, stride, pad):
         assert np.array_equal(col, want[:, m])
 
 
+def test_unfold_channels_last_feature_order():
+    """order="kkc": feature (ky*kw+kx)*Cin + c, i.e. X @ weight.permute(0,2,3,1).reshape(S,-1).T is the convolution."""
+    B, Cin, H, W, k, S = 2, 3, 5, 4, 3, 2
+    act = rng0.standard_normal((B, H, W, Cin))
+    Xc = ora.patch_rows(act, B, Cin, H, W, k, k, 1, 1)
+    Xk = ora.patch_rows(act, B, Cin, H, W, k, k, 1, 1, order="kkc")
+    for c in range(Cin):
+        for t in range(k * k):
+            assert np.array_equal(Xk[:, t * Cin + c], Xc[:, c * k * k + t])
+    wgt = rng0.standard_normal((S, Cin, k, k))
+    assert np.allclose(Xk @ wgt.transpose(0, 2, 3, 1).reshape(S, -1).T, Xc @ wgt.reshape(S, -1).T, atol=1e-12)
+    m = 7
+    assert np.array_equal(ora.patch_feature_column(act, B, Cin, H, W, k, k, 1, 1, m, order="kkc"), Xk[:, m])
+
+
 def test_unfold_feature_order_is_torch_weight_view_order():
     """With patch rows in this feature order, X @ weight.view(S,-1).T is the convolution output."""
     torch = pytest.importorskip("torch")

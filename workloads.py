@@ -27,6 +27,7 @@ import numpy as np
 LAYOUT_ROWS = 0
 LAYOUT_NCHW = 1
 LAYOUT_NHWC = 2
+LAYOUT_NHWC_KKC = 3   # NHWC tensor, features ordered (ky, kx, c)
 
 
 @dataclass
@@ -96,7 +97,7 @@ def bf16_bits(x: np.ndarray) -> np.ndarray:
 
 
 def to_layout(act_nhwc: np.ndarray, layout: int) -> np.ndarray:
-    if layout == LAYOUT_NHWC:
+    if layout in (LAYOUT_NHWC, LAYOUT_NHWC_KKC):
         return np.ascontiguousarray(act_nhwc)
     if layout == LAYOUT_NCHW:
         return np.ascontiguousarray(np.transpose(act_nhwc, (0, 3, 1, 2)))
