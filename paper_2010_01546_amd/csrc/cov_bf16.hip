@@ -1,4 +1,5 @@
-// bfloat16 moment accumulation A += X^T X (sums inside eqs. (vmuxi), (vPhixi), (phixmi)) on the gfx950 matrix cores.
+// bfloat16 moment accumulation A += X^T X, s += X^T 1 (sums inside eqs. (vmuxi), (vPhixi), (phixmi)) on the gfx950
+// matrix cores.
 //
 // v_mfma_f32_32x32x16_bf16 wants, per lane, eight consecutive entries of the reduction index for one feature.
 // The reduction index of X^T X is the patch row (image, oy, ox); any order of it gives the same sums, so the
@@ -7,13 +8,15 @@
 //     P[image group][y + pad][x + pad][channel] -> 8 x bf16 (16 bytes: the same pixel and channel of 8 images)
 // with a zero border of `pad` pixels, so that every tap of every output position is one aligned 16-byte load with
 // no bounds test, for any window, stride and input layout.  A "unit" is (image group, oy, ox); an MFMA consumes two.
+// The same pass adds up, per padded pixel and channel, the values it packs; the column sums s are sums of those
+// per-pixel sums over the output positions of a tap, so the contraction kernel does not touch them.
 //
 // The contraction kernel cuts the lower triangle of A into 256x256 tiles.  A workgroup of 8 wavefronts (2 x 4, each
-// 128x64 = 4x2 MFMA tiles) owns one tile over a range of units; panels of 8 units are prefetched into registers one
-// chunk ahead and double-buffered in LDS as [unit][feature][16 B], which both the staging writes and the
-// ds_read_b128 operand reads traverse contiguously.  Diagonal tiles stage one panel and accumulate the column sums.
-// With one range per tile the result is added straight into A; otherwise partial tiles go to the workspace and are
-// summed in float64.
+// 128x64 = 4x2 MFMA tiles) owns one tile over a range of units.  Panels of 4 units travel from global memory
+// straight into LDS (global_load_lds_dwordx4, no register staging) into a ring of four stages laid out as
+// [unit][feature][16 B], three chunks ahead of the MFMAs; a chunk costs one s_waitcnt and one barrier.
+// With one range per tile and the feature order kept, the result is added straight into A; otherwise partial
+// tiles go to the workspace and are summed in float64 (and permuted to the caller's feature order).
 #include "fw_internal.h"
 #include <math.h>
 #include <stdlib.h>
@@ -22,7 +25,8 @@ namespace fw {
 namespace {
 
 constexpr int TB = 256;  // tile edge (features)
-constexpr int KU = 8;    // units per staged chunk (64 reduction entries)
+constexpr int KU = 4;    // units per staged chunk (32 reduction entries)
+constexpr int NST = 4;   // stages of the LDS ring
 
 struct TileGeom {
     int M, nb, ntiles;
@@ -30,43 +34,55 @@ struct TileGeom {
     int layout;
     int n_units, units_per_split, nsplit;
     int direct;   // one range per tile and external order == internal order: tiles are added straight into A
+    int bg_chunks, bg_per_chunk;   // the pre-pass deals the image groups to this many thread groups
+    int zero_off;                  // 16-byte element of P that is always zero (target of masked-off loads)
 };
 
 typedef unsigned short u16;
 
-// ---- pre-pass: pack 8 images per 16 bytes, zero border ---------------------------------------------------------
-__global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict__ X, TileGeom g, uint4* __restrict__ P) {
-    const long long total = (long long)g.Bg * g.Hp * g.Wp * g.Cin;
-    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
-        int c, xp, yp, bg;
-        long long t = e;
-        if (g.layout == FW_LAYOUT_NCHW) {  // walk the source along x for coalescing; the packed order stays [bg][yp][xp][c]
-            xp = (int)(t % g.Wp); t /= g.Wp;
-            yp = (int)(t % g.Hp); t /= g.Hp;
-            c = (int)(t % g.Cin); bg = (int)(t / g.Cin);
-        } else {
-            c = (int)(t % g.Cin); t /= g.Cin;
-            xp = (int)(t % g.Wp); t /= g.Wp;
-            yp = (int)(t % g.Hp); bg = (int)(t / g.Hp);
-        }
-        const int y = yp - g.pad, x = xp - g.pad;
+// ---- pre-pass: pack 8 images per 16 bytes, zero border; per-pixel sums for the column sums ----------------------
+// One thread per (chunk of image groups, padded pixel, channel); it walks its image groups, so the sum it leaves in
+// S8[chunk][yp][xp][c] has a fixed order of additions.
+__global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict__ X, TileGeom g, uint4* __restrict__ P,
+                                                          float* __restrict__ S8) {
+    const int per_img = g.Hp * g.Wp * g.Cin;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    const int chunk = blockIdx.y;
+    if (blockIdx.x == 0 && chunk == 0 && threadIdx.x < 16) P[g.zero_off + threadIdx.x] = make_uint4(0, 0, 0, 0);
+    if (e >= per_img) return;
+    int c, xp, yp;
+    if (g.layout == FW_LAYOUT_NCHW) {  // walk the source along x for coalescing; the packed order stays [yp][xp][c]
+        xp = e % g.Wp; const int t = e / g.Wp;
+        yp = t % g.Hp; c = t / g.Hp;
+    } else {
+        c = e % g.Cin; const int t = e / g.Cin;
+        xp = t % g.Wp; yp = t / g.Wp;
+    }
+    const int y = yp - g.pad, x = xp - g.pad;
+    const bool inside = (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
+    const long long img_stride = (long long)g.Cin * g.H * g.W;
+    const long long src0 = g.layout == FW_LAYOUT_NCHW ? ((long long)c * g.H + y) * g.W + x : ((long long)y * g.W + x) * g.Cin + c;
+    const int dst0 = (yp * g.Wp + xp) * g.Cin + c;
+    const int bg0 = chunk * g.bg_per_chunk, bg1 = min(g.Bg, bg0 + g.bg_per_chunk);
+    float acc = 0.f;
+    for (int bg = bg0; bg < bg1; ++bg) {
         unsigned v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int b = bg * 8 + i;
-            unsigned val = 0;
-            if (b < g.B && (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W) {
-                const long long src = g.layout == FW_LAYOUT_NCHW ? (((long long)b * g.Cin + c) * g.H + y) * g.W + x
-                                                                 : (((long long)b * g.H + y) * g.W + x) * g.Cin + c;
-                val = X[src];
-            }
-            v[i] = val;
+            v[i] = (inside && b < g.B) ? X[(long long)b * img_stride + src0] : 0u;
         }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc += __uint_as_float(v[i] << 16);
         uint4 o;
         o.x = v[0] | (v[1] << 16); o.y = v[2] | (v[3] << 16); o.z = v[4] | (v[5] << 16); o.w = v[6] | (v[7] << 16);
-        P[(((long long)bg * g.Hp + yp) * g.Wp + xp) * g.Cin + c] = o;
+        P[(long long)bg * per_img + dst0] = o;
     }
+    S8[(size_t)chunk * per_img + dst0] = acc;
 }
+
+// s[m] += sum over the output positions of the per-pixel sums under tap (ky,kx): one workgroup per feature
+__global__ __launch_bounds__(256) void column_sums_kernel(TileGeom g, const float* __restrict__ S8, float* __restrict__ s);
 
 // offset (in 16-byte elements) of the top-left tap of every unit
 __global__ __launch_bounds__(256) void unit_table_kernel(TileGeom g, int* __restrict__ utab) {
@@ -87,21 +103,15 @@ __device__ __forceinline__ void feat_map(int fi, const TileGeom& g, int* off, in
     *ext = g.layout == FW_LAYOUT_NHWC_KKC ? fi : c * (g.kh * g.kw) + t;
 }
 
-__device__ __forceinline__ float sum8_bf16(const uint4& v) {
-    float s = 0.f;
-    s += __uint_as_float(v.x << 16) + __uint_as_float(v.x & 0xffff0000u);
-    s += __uint_as_float(v.y << 16) + __uint_as_float(v.y & 0xffff0000u);
-    s += __uint_as_float(v.z << 16) + __uint_as_float(v.z & 0xffff0000u);
-    s += __uint_as_float(v.w << 16) + __uint_as_float(v.w & 0xffff0000u);
-    return s;
-}
-
 struct SmemTile {
-    alignas(16) uint4 pan[2][2][KU][TB];  // [buffer][row panel / column panel][unit][feature], 128 KB
+    alignas(16) uint4 pan[NST][2][KU][TB];  // [stage][row panel / column panel][unit][feature], 128 KB
 };
 
+// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+#define FW_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+
 __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restrict__ P, const int* __restrict__ utab, TileGeom g,
-                                                            float* __restrict__ part, float* __restrict__ spart, float* __restrict__ A) {
+                                                            float* __restrict__ part, float* __restrict__ A) {
     __shared__ SmemTile sm;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -114,11 +124,19 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
     const int J = tile - I * (I + 1) / 2;
     const bool diag = I == J;
 
-    const int f = tid & 255, ul = tid >> 8;
-    int offA, offB, extA, extB;
-    const bool okA = I * TB + f < g.M, okB = J * TB + f < g.M;
-    feat_map(okA ? I * TB + f : 0, g, &offA, &extA);
-    feat_map(okB ? J * TB + f : 0, g, &offB, &extB);
+    // Staging: a wavefront-wide 16-byte load fills 64 consecutive features of one unit of one panel (1 KB of LDS).
+    // Wavefront w always takes feature quarter w & 3; its loads of a chunk are (panel, unit) = (0, g2), (0, g2 + 2),
+    // (1, g2), (1, g2 + 2) with g2 = w >> 2.  Lanes whose feature lies beyond M, and units beyond the range, read
+    // the zero element instead, so every stage is completely rewritten by every chunk.
+    const int q = wave & 3, g2 = wave >> 2;
+    int off[2], ext_unused;
+    bool ok[2];
+    {
+        const int fA = I * TB + 64 * q + lane, fB = J * TB + 64 * q + lane;
+        ok[0] = fA < g.M; ok[1] = fB < g.M;
+        feat_map(ok[0] ? fA : 0, g, &off[0], &ext_unused);
+        feat_map(ok[1] ? fB : 0, g, &off[1], &ext_unused);
+    }
 
     floatx16 acc[4][2];
 #pragma unroll
@@ -131,78 +149,43 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
     const int u_begin = split * g.units_per_split;
     const int u_end = min(g.n_units, u_begin + g.units_per_split);
     const int nchunks = (u_end - u_begin + KU - 1) / KU;
+    const int npanels = diag ? 1 : 2;
 
-    uint4 pa[KU / 2], pb[KU / 2];
-    int base[KU / 2];      // unit offsets of the chunk whose loads come next; -1 past the end of the range
-    float ssum = 0.f;
-    auto load_bases = [&](int c) {
+    // unit offsets of the chunk whose loads are issued next (wavefront-uniform, fetched one iteration early)
+    int nbase[2];
+    auto fetch_bases = [&](int c) {
 #pragma unroll
-        for (int j = 0; j < KU / 2; ++j) {
-            const int u = u_begin + c * KU + ul + 2 * j;
-            base[j] = (c < nchunks && u < u_end) ? utab[u] : -1;
+        for (int k = 0; k < 2; ++k) {
+            const int uu = u_begin + c * KU + g2 + 2 * k;
+            nbase[k] = (c < nchunks && uu < u_end) ? utab[uu] : -1;
         }
     };
-    auto load_chunk = [&]() {
+    auto issue = [&](int c) {
+        const int stage = c & (NST - 1);
 #pragma unroll
-        for (int j = 0; j < KU / 2; ++j) {
-            pa[j] = make_uint4(0, 0, 0, 0);
-            pb[j] = make_uint4(0, 0, 0, 0);
-            if (base[j] >= 0) {
-                if (okA) pa[j] = P[base[j] + offA];
-                if (!diag && okB) pb[j] = P[base[j] + offB];
+        for (int pnl = 0; pnl < 2; ++pnl) {
+            if (pnl >= npanels) break;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int u = g2 + 2 * k;
+                const int idx = (nbase[k] >= 0 && ok[pnl]) ? nbase[k] + off[pnl] : g.zero_off;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(P + idx),
+                                                 (__attribute__((address_space(3))) void*)(&sm.pan[stage][pnl][u][64 * q]), 16, 0, 0);
             }
         }
-    };
-    auto store_chunk = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < KU / 2; ++j) {
-            sm.pan[buf][0][ul + 2 * j][f] = pa[j];
-            if (!diag) sm.pan[buf][1][ul + 2 * j][f] = pb[j];
-            else ssum += sum8_bf16(pa[j]);
-        }
+        fetch_bases(c + 1);
     };
 
-    // L2 warm-up: every chunk ahead of the register prefetch is touched with one 4-byte load per 128-byte line, so that
-    // the 16-byte panel loads find their lines in L2 instead of waiting, all lanes at a barrier, for the slowest miss.
-    // Thread -> (panel, unit, line): 2 x 8 x 32 lines of 8 features.  The value is never used; the empty asm at the top
-    // of the next iteration is only there to retire the load one iteration after it was issued.
-    constexpr int PD = 3;   // chunks between the touch and the MFMAs that consume the chunk
-    const int t_unit = (tid >> 5) & 7, t_panel = tid >> 8;
-    int t_off, t_ext;
-    const int t_feat = (t_panel ? J : I) * TB + 8 * (tid & 31);
-    const bool t_ok = t_feat < g.M && !(diag && t_panel);
-    feat_map(t_ok ? t_feat : 0, g, &t_off, &t_ext);
-    unsigned pending = 0;
-    int t_base = -1;
-    auto touch_base = [&](int c) {
-        const int u = u_begin + c * KU + t_unit;
-        return (c < nchunks && u < u_end) ? utab[u] : -1;
-    };
-    t_base = touch_base(PD);
-
-    load_bases(0);
-    if (nchunks > 0) {
-        load_chunk();
-        load_bases(1);
-        store_chunk(0);
-    }
-    __syncthreads();
     const int pj = diag ? 0 : 1;
-    for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
-        const bool more = c + 1 < nchunks;
-        asm volatile("" ::"v"(pending));
-        if (more) { load_chunk(); load_bases(c + 2); }
-        if (t_ok && t_base >= 0) pending = *reinterpret_cast<const unsigned*>(P + t_base + t_off);
-        t_base = touch_base(c + PD + 1);
-        // operand fragments are read one k-step ahead of the MFMAs that use them (two register sets)
+    auto compute = [&](int c) {
+        const int stage = c & (NST - 1);
         bf16x8 fa[2][4], fb[2][2];
         auto read_frags = [&](int ks, int set) {
             const int unit = 2 * ks + half;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) fa[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[buf][0][unit][128 * wi + 32 * t + l32]);
+            for (int t = 0; t < 4; ++t) fa[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[stage][0][unit][128 * wi + 32 * t + l32]);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) fb[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[buf][pj][unit][64 * wj + 32 * t + l32]);
+            for (int t = 0; t < 2; ++t) fb[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[stage][pj][unit][64 * wj + 32 * t + l32]);
         };
         read_frags(0, 0);
 #pragma unroll
@@ -216,9 +199,27 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
                     acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][ta], fb[ks & 1][tb], acc[ta][tb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) store_chunk(buf ^ 1);
-        __syncthreads();
+    };
+
+    // Ring protocol.  Chunks c, c+1, c+2 are in flight when iteration c starts.  Loads of one wavefront complete in
+    // order, so "at most the loads of two chunks outstanding" means chunk c has landed for this wavefront; the barrier
+    // extends that to all wavefronts and also tells that everyone has finished reading chunk c-1, whose stage the
+    // loads of chunk c+3 then overwrite.  Every iteration issues the same number of loads (past the end they fetch
+    // the zero element), which keeps the outstanding-load arithmetic valid in the tail.
+    // The barrier is the bare instruction: __syncthreads() would first drain every outstanding load, which is exactly
+    // what the ring is there to avoid.  What a wavefront reads after the barrier was written by loads that their
+    // issuers waited for before it.
+    fetch_bases(0);
+    issue(0); issue(1); issue(2);
+    for (int c = 0; c < nchunks; ++c) {
+        if (diag) FW_WAIT_VMCNT(4); else FW_WAIT_VMCNT(8);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue(c + 3);
+        compute(c);
     }
+    FW_WAIT_VMCNT(0);
+    __syncthreads();
 
     // ---- epilogue
     if (!g.direct) {
@@ -250,13 +251,25 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
                 }
         }
     }
-    if (diag) {
-        // column sums of this block: the two unit groups of a feature meet in LDS
-        float* red = reinterpret_cast<float*>(&sm.pan[1][0][0][0]);
-        red[tid] = ssum;
-        __syncthreads();
-        if (tid < 256 && okA) spart[(size_t)split * g.nb * TB + I * TB + f] = red[f] + red[256 + f];
-    }
+}
+
+__global__ __launch_bounds__(256) void column_sums_kernel(TileGeom g, const float* __restrict__ S8, float* __restrict__ s) {
+    __shared__ double red[4];
+    const int fi = blockIdx.x;
+    int off, ext;
+    feat_map(fi, g, &off, &ext);
+    const int per_img = g.Hp * g.Wp * g.Cin;
+    const int npos = g.Ho * g.Wo;
+    double v = 0.0;
+    for (int k = 0; k < g.bg_chunks; ++k)
+        for (int p = threadIdx.x; p < npos; p += 256) {
+            const int oy = p / g.Wo, ox = p - oy * g.Wo;
+            v += (double)S8[(size_t)k * per_img + ((oy * g.stride) * g.Wp + ox * g.stride) * g.Cin + off];
+        }
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) s[ext] = (float)((double)s[ext] + red[0] + red[1] + red[2] + red[3]);
 }
 
 // partial tiles -> A (float64 sum over the ranges), one thread per tile element
@@ -281,22 +294,6 @@ __global__ __launch_bounds__(256) void tile_reduce_kernel(TileGeom g, const floa
     *dst = (float)((double)*dst + v);
 }
 
-__global__ __launch_bounds__(256) void tile_reduce_sums_kernel(TileGeom g, const float* __restrict__ spart, float* __restrict__ s) {
-    __shared__ double red[4][64];
-    const int fi = blockIdx.x * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
-    double v = 0.0;
-    if (fi < g.M)
-        for (int sp = grp; sp < g.nsplit; sp += 4) v += (double)spart[(size_t)sp * g.nb * TB + fi];
-    red[grp][threadIdx.x & 63] = v;
-    __syncthreads();
-    if (grp == 0 && fi < g.M) {
-        v = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
-        int o, e;
-        feat_map(fi, g, &o, &e);
-        s[e] = (float)((double)s[e] + v);
-    }
-}
-
 bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     g->B = d->B; g->Cin = d->Cin; g->H = d->H; g->W = d->W;
     g->kh = d->kh; g->kw = d->kw; g->stride = d->stride; g->pad = d->pad;
@@ -308,7 +305,7 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     const long long M = (long long)d->Cin * d->kh * d->kw;
     const long long n_units = (long long)g->Bg * g->Ho * g->Wo;
     const long long packed = (long long)g->Bg * g->Hp * g->Wp * d->Cin;
-    if (M <= 0 || M > 16384 || n_units <= 0 || n_units >= (1ll << 31) || packed >= (1ll << 31)) return false;
+    if (M <= 0 || M > 16384 || n_units <= 0 || n_units >= (1ll << 31) || packed + 16 >= (1ll << 31)) return false;
     if ((long long)d->B * d->Cin * d->H * d->W >= (1ll << 31)) return false;
     g->M = (int)M; g->nb = (int)((M + TB - 1) / TB); g->ntiles = g->nb * (g->nb + 1) / 2;
     g->n_units = (int)n_units;
@@ -331,20 +328,30 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     const long long cps = (nchunks + best_ns - 1) / best_ns;
     g->units_per_split = (int)(cps * KU);
     g->nsplit = (int)((n_units + g->units_per_split - 1) / g->units_per_split);
+    // the pre-pass wants about 32k threads: split the image groups when one image gives fewer
+    {
+        const long long per_img = (long long)g->Hp * g->Wp * d->Cin;
+        long long ch = (32768 + per_img - 1) / per_img;
+        if (ch > g->Bg) ch = g->Bg;
+        if (ch < 1) ch = 1;
+        g->bg_per_chunk = (int)((g->Bg + ch - 1) / ch);
+        g->bg_chunks = (g->Bg + g->bg_per_chunk - 1) / g->bg_per_chunk;
+        g->zero_off = (int)packed;
+    }
     const bool ident = lay == FW_LAYOUT_NHWC_KKC || lay == FW_LAYOUT_ROWS || d->kh * d->kw == 1;
     g->direct = (g->nsplit == 1 && ident) ? 1 : 0;
     return true;
 }
 
-struct Bf16Ws { size_t packed, utab, part, spart, total; };
+struct Bf16Ws { size_t packed, utab, part, s8, total; };
 Bf16Ws ws_layout(const TileGeom& g) {
     Bf16Ws L;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
-    L.packed = take((size_t)g.Bg * g.Hp * g.Wp * g.Cin * 16);
+    L.packed = take(((size_t)g.Bg * g.Hp * g.Wp * g.Cin + 16) * 16);
     L.utab = take((size_t)g.n_units * 4);
     L.part = take(g.direct ? 0 : (size_t)g.nsplit * g.ntiles * TB * TB * 4);
-    L.spart = take((size_t)g.nsplit * g.nb * TB * 4);
+    L.s8 = take((size_t)g.bg_chunks * g.Hp * g.Wp * g.Cin * 4);
     L.total = o;
     return L;
 }
@@ -367,17 +374,16 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     uint4* P = reinterpret_cast<uint4*>(base + L.packed);
     int* utab = reinterpret_cast<int*>(base + L.utab);
     float* part = reinterpret_cast<float*>(base + L.part);
-    float* spart = reinterpret_cast<float*>(base + L.spart);
-    const long long total = (long long)g.Bg * g.Hp * g.Wp * g.Cin;
-    long long pb = (total + 255) / 256;
-    if (pb > 65536) pb = 65536;
-    hipLaunchKernelGGL(pack_images_kernel, dim3((unsigned)pb), dim3(256), 0, st, reinterpret_cast<const u16*>(X), g, P);
+    float* S8 = reinterpret_cast<float*>(base + L.s8);
+    const int per_img = g.Hp * g.Wp * g.Cin;
+    hipLaunchKernelGGL(pack_images_kernel, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st, reinterpret_cast<const u16*>(X),
+                       g, P, S8);
     hipLaunchKernelGGL(unit_table_kernel, dim3((g.n_units + 255) / 256), dim3(256), 0, st, g, utab);
     FW_LAUNCH_CHECK();
-    hipLaunchKernelGGL(cov_bf16_tile_kernel, dim3(g.ntiles, g.nsplit), dim3(512), 0, st, P, utab, g, part, spart, A);
+    hipLaunchKernelGGL(cov_bf16_tile_kernel, dim3(g.ntiles, g.nsplit), dim3(512), 0, st, P, utab, g, part, A);
     FW_LAUNCH_CHECK();
     if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * 256), dim3(256), 0, st, g, part, A);
-    hipLaunchKernelGGL(tile_reduce_sums_kernel, dim3((g.M + 63) / 64), dim3(256), 0, st, g, spart, s);
+    hipLaunchKernelGGL(column_sums_kernel, dim3(g.M), dim3(256), 0, st, g, S8, s);
     FW_LAUNCH_CHECK();
     return FW_OK;
 }
