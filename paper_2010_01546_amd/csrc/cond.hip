@@ -172,13 +172,17 @@ __global__ __launch_bounds__(256) void vecmat_partial_kernel(const float* __rest
     tpart[(size_t)blockIdx.y * Mp + j] = acc;
 }
 
-// t[j] = sum over row blocks of the partial products
-__global__ __launch_bounds__(256) void t_reduce_kernel(const float* __restrict__ tpart, int nrb, int M, int Mp, float* __restrict__ t) {
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= M) return;
+// out[m] = sum over b < nparts of part[b][m]: 64 entries per workgroup, the parts dealt to four groups of threads in
+// a fixed order and combined through LDS (used for t = T^T v and for the squared row norms of Phi_y)
+__global__ __launch_bounds__(256) void partial_sum_kernel(const float* __restrict__ part, int nparts, int M, int Mp, float* __restrict__ out) {
+    __shared__ float red[4][64];
+    const int m = blockIdx.x * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
     float acc = 0.f;
-    for (int b = 0; b < nrb; ++b) acc += tpart[(size_t)b * Mp + j];
-    t[j] = acc;
+    if (m < M)
+        for (int b = grp; b < nparts; b += 4) acc += part[(size_t)b * Mp + m];
+    red[grp][threadIdx.x & 63] = acc;
+    __syncthreads();
+    if (grp == 0 && m < M) out[m] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
 
 // lambda_e = v^T u (eq. (lambda)); g_e, a_e (eqs. (ge), (xi)); guard; diagnostics
@@ -287,15 +291,6 @@ __global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const floa
     }
 }
 
-// xi2[m] = sum over tile columns of the partial squared row norms
-__global__ __launch_bounds__(256) void xi2_reduce_kernel(const float* __restrict__ xpart, int nt, int M, int Mp, float* __restrict__ xi2) {
-    const int m = blockIdx.x * 256 + threadIdx.x;
-    if (m >= M) return;
-    float acc = 0.f;
-    for (int b = 0; b < nt; ++b) acc += xpart[(size_t)b * Mp + m];
-    xi2[m] = acc;
-}
-
 __global__ __launch_bounds__(256) void state_init_kernel(fw_cond_state s) {
     const int M = s.M;
     const size_t n = (size_t)M * M;
@@ -361,12 +356,12 @@ fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_c
     }
     hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, v, sc, 0, M, u);
     hipLaunchKernelGGL(vecmat_partial_kernel, dim3((M + 255) / 256, L.nrb), dim3(256), 0, st, s->T, v, M, L.Mp, L.vm_rows, tpart);
-    hipLaunchKernelGGL(t_reduce_kernel, dim3((M + 255) / 256), dim3(256), 0, st, tpart, L.nrb, M, L.Mp, t);
+    hipLaunchKernelGGL(partial_sum_kernel, dim3((M + 63) / 64), dim3(256), 0, st, tpart, L.nrb, M, L.Mp, t);
     hipLaunchKernelGGL(scalars_kernel, dim3(1), dim3(1024), 0, st, v, u, M, s->lambda_bar, *p, sc, info);
     if (p->gamma < 1.f)
         hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_x, t, sc, 0, M, pv);
     hipLaunchKernelGGL(update_kernel, dim3(L.nt, L.nt), dim3(256), 0, st, *s, v, u, t, pv, sc, p->gamma, p->beta, L.Mp, xpart);
-    hipLaunchKernelGGL(xi2_reduce_kernel, dim3((M + 255) / 256), dim3(256), 0, st, xpart, L.nt, M, L.Mp, s->xi2);
+    hipLaunchKernelGGL(partial_sum_kernel, dim3((M + 63) / 64), dim3(256), 0, st, xpart, L.nt, M, L.Mp, s->xi2);
     FW_LAUNCH_CHECK();
     return FW_OK;
 }

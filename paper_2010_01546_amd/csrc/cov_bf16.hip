@@ -328,10 +328,10 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     const long long cps = (nchunks + best_ns - 1) / best_ns;
     g->units_per_split = (int)(cps * KU);
     g->nsplit = (int)((n_units + g->units_per_split - 1) / g->units_per_split);
-    // the pre-pass wants about 32k threads: split the image groups when one image gives fewer
+    // the pre-pass wants about half a million threads: split the image groups when one image gives fewer
     {
         const long long per_img = (long long)g->Hp * g->Wp * d->Cin;
-        long long ch = (32768 + per_img - 1) / per_img;
+        long long ch = (524288 + per_img - 1) / per_img;
         if (ch > g->Bg) ch = g->Bg;
         if (ch < 1) ch = 1;
         g->bg_per_chunk = (int)((g->Bg + ch - 1) / ch);
