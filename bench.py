@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--layout", default="kkc", choices=["kkc", "nhwc", "nchw"],
                     help="kkc: NHWC tensor with channels-last feature order (ky,kx,c); nhwc/nchw: feature order (c,ky,kx)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed region, copy a 256 MiB tensor five times: the known-size kernel against which the\n"
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command are scaled")
     return ap.parse_args()
 
 
@@ -141,13 +144,22 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{layer.name}: M={M} S={S} N_rows={n_rows} layout={args.layout if not layer.is_rows else 'rows'}",
                    "batch": d.B, "block_length": 1, "cond_params": "gamma=0.99 beta=0.1 delta=0.25 (paper defaults)"},
-        "roofline": {"bound": "mfma", "kernel": "cov_partial_kernel+cov_reduce_kernel (one fw_cov_accumulate)",
+        "roofline": {"bound": "mfma",
+                     "kernel": ("pack_images + cov_bf16_tile (+ tile_reduce) + column_sums" if bf16 else
+                                "cov_partial_f32v4 + cov_reduce + cov_reduce_sums") + " = one fw_cov_accumulate",
                      "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": MEASURED_TRAFFIC.get(args.config)},
         "breakdown_ms": {"cov_accumulate": cov_ms, "cov_finalize": fin_ms, "cond_reduce_step": cond_ms, "grad_transform": grad_ms},
         "cond_step_GBps": cond_bytes / (cond_ms * 1e-3) / 1e9,
         "grad_transform_TFLOPs": 2.0 * S * M * M / (grad_ms * 1e-3) / 1e12,
     }
+
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, device=dev)      # 256 MiB read + 256 MiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
         from oracle import fw_oracle as ora

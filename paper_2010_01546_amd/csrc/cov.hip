@@ -12,7 +12,6 @@
 // read consecutive channels; the reduce kernel maps back to the external order m = (c*kh + ky)*kw + kx, or keeps the
 // internal order when the caller asked for it (FW_LAYOUT_NHWC_KKC).
 #include "fw_internal.h"
-#include <stdlib.h>
 #include <type_traits>
 
 namespace fw {
@@ -21,8 +20,6 @@ namespace {
 constexpr int BLK = 64;        // features per operand panel = edge of a wavefront's output block
 constexpr int MAX_SLOTS = 5;   // operand panels a workgroup may stage
 constexpr int KT_F32 = 16;     // patch rows per staged chunk, float32 path
-constexpr int KT_BF16 = 32;    // patch rows per staged chunk, bfloat16 path
-constexpr int BF16_ROW_BYTES = KT_BF16 * 2 + 16;  // K-major LDS row of one feature, padded, 16-byte aligned
 
 struct CovGeom {
     int n_rows, M, nb;
@@ -133,24 +130,17 @@ __device__ __forceinline__ RowInfo row_of(int r, bool valid, const CovGeom& g) {
     return ri;
 }
 
-template <bool BF16>
-struct Smem;
-template <>
-struct Smem<false> {
+struct Smem {
     alignas(16) float tile[MAX_SLOTS][KT_F32][BLK];  // [slot][row][feature], feature position rotated by 32 on odd rows
     RowInfo rows[KT_F32];
 };
-template <>
-struct Smem<true> {
-    alignas(16) unsigned char tile[MAX_SLOTS][BLK][BF16_ROW_BYTES];  // [slot][feature][row] bf16, K-major
-    RowInfo rows[KT_BF16];
-};
 
-template <bool BF16>
-__global__ __launch_bounds__(256) void cov_partial_kernel(const void* __restrict__ Xv, CovGeom g, float* __restrict__ part,
+// Generic float32 path (any layout, any Cin): one element per load through a per-row table.  bfloat16 inputs take
+// the packed-tile path of cov_bf16.hip.
+__global__ __launch_bounds__(256) void cov_partial_kernel(const float* __restrict__ X, CovGeom g, float* __restrict__ part,
                                                           float* __restrict__ spart) {
-    constexpr int KT = BF16 ? KT_BF16 : KT_F32;
-    __shared__ Smem<BF16> sm;
+    constexpr int KT = KT_F32;
+    __shared__ Smem sm;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int item_idx = blockIdx.x, split = blockIdx.y;
@@ -195,37 +185,15 @@ __global__ __launch_bounds__(256) void cov_partial_kernel(const void* __restrict
                 const RowInfo ri = sm.rows[k];
                 const bool ok = f_ok[s] && (unsigned)(ri.iy0 + f_ky[s]) < (unsigned)g.H &&
                                 (unsigned)(ri.ix0 + f_kx[s]) < (unsigned)g.W;
-                if constexpr (BF16) {
-                    unsigned short v = 0;
-                    if (ok) v = reinterpret_cast<const unsigned short*>(Xv)[ri.base + f_off[s]];
-                    *reinterpret_cast<unsigned short*>(&sm.tile[s][lane][2 * k]) = v;
-                    ssum[s] += bf16_to_f32(v);
-                } else {
-                    float v = 0.f;
-                    if (ok) v = reinterpret_cast<const float*>(Xv)[ri.base + f_off[s]];
-                    sm.tile[s][k][(lane + ((k & 1) << 5)) & 63] = v;
-                    ssum[s] += v;
-                }
+                float v = 0.f;
+                if (ok) v = X[ri.base + f_off[s]];
+                sm.tile[s][k][(lane + ((k & 1) << 5)) & 63] = v;
+                ssum[s] += v;
             }
         }
         __syncthreads();
         if (sa >= 0) {
-            if constexpr (BF16) {
-#pragma unroll
-                for (int k0 = 0; k0 < KT; k0 += 16) {
-                    bf16x8 a[2], b[2];
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        a[t] = *reinterpret_cast<const bf16x8*>(&sm.tile[sa][32 * t + l32][2 * (k0 + 8 * half)]);
-                        b[t] = *reinterpret_cast<const bf16x8*>(&sm.tile[sb][32 * t + l32][2 * (k0 + 8 * half)]);
-                    }
-#pragma unroll
-                    for (int ta = 0; ta < 2; ++ta)
-#pragma unroll
-                        for (int tb = 0; tb < 2; ++tb)
-                            acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
-                }
-            } else {
+            {
 #pragma unroll
                 for (int k0 = 0; k0 < KT; k0 += 2) {
                     const int k = k0 + half;
@@ -296,7 +264,11 @@ __global__ __launch_bounds__(256) void cov_partial_f32v4_kernel(const float* __r
     __shared__ SmemVec sm;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int item_idx = blockIdx.x, split = blockIdx.y;
+    // Workgroups go to the 8 XCDs round-robin by linear index; give every XCD whole row ranges (all items of a
+    // split), so that a range of the activation is pulled into one L2 only.
+    const int item_idx = (blockIdx.x >> 3) % g.nitems;
+    const int split = (blockIdx.x & 7) + 8 * ((blockIdx.x >> 3) / g.nitems);
+    if (split >= g.nsplit) return;
     const Item it = get_item(item_idx, g.nb);
     const int k = tid >> 4, q = tid & 15;
 
@@ -492,11 +464,10 @@ bool make_geom(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, CovGeom* g) {
     g->n_rows = (int)n_rows; g->M = (int)M; g->nb = (int)((M + BLK - 1) / BLK);
     item_counts(g->nb, &g->n0, &g->n1, &g->n2);
     g->nitems = g->n0 + g->n1 + g->n2;
-    const int KT = dt == FW_BF16 ? KT_BF16 : KT_F32;
+    const int KT = KT_F32;
     // Split the rows so that the grid is close to a whole number of resident rounds: 256 compute units times the
     // workgroups one of them holds (LDS-limited), with at least four chunks of rows per split.
-    long long capacity = 256 * (dt == FW_BF16 ? 4 : 3);
-    if (const char* e = getenv("FW_COV_CAPACITY")) capacity = atoll(e);
+    const long long capacity = 256 * 3;
     long long want = capacity / g->nitems;
     const long long max_split = (n_rows + 4 * KT - 1) / (4 * KT);
     if (want > max_split) want = max_split;
@@ -604,11 +575,10 @@ fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_con
     const dim3 grid(g.nitems, g.nsplit);
     const bool vec4 = dt == FW_F32 && lay != FW_LAYOUT_NCHW && (g.Cin % 4) == 0;
     if (vec4)
-        hipLaunchKernelGGL(cov_partial_f32v4_kernel, grid, dim3(256), 0, st, reinterpret_cast<const float*>(X), g, part, spart);
-    else if (dt == FW_BF16)
-        hipLaunchKernelGGL(cov_partial_kernel<true>, grid, dim3(256), 0, st, X, g, part, spart);
+        hipLaunchKernelGGL(cov_partial_f32v4_kernel, dim3(8 * g.nitems * ((g.nsplit + 7) / 8)), dim3(256), 0, st,
+                           reinterpret_cast<const float*>(X), g, part, spart);
     else
-        hipLaunchKernelGGL(cov_partial_kernel<false>, grid, dim3(256), 0, st, X, g, part, spart);
+        hipLaunchKernelGGL(cov_partial_kernel, grid, dim3(256), 0, st, reinterpret_cast<const float*>(X), g, part, spart);
     FW_LAUNCH_CHECK();
     hipLaunchKernelGGL(cov_reduce_kernel, dim3(g.nitems * 4 * 16), dim3(256), 0, st, g, part, A);
     hipLaunchKernelGGL(cov_reduce_sums_kernel, dim3((g.M + 63) / 64), dim3(256), 0, st, g, spart, s);

@@ -14,12 +14,12 @@
 // The contraction kernel cuts the lower triangle of A into 256x256 tiles.  A workgroup of 8 wavefronts (2 x 4, each
 // 128x64 = 4x2 MFMA tiles) owns one tile over a range of units.  Panels of 4 units travel from global memory
 // straight into LDS (global_load_lds_dwordx4, no register staging) into a ring of four stages laid out as
-// [unit][feature][16 B], three chunks ahead of the MFMAs; a chunk costs one s_waitcnt and one barrier.
+// [unit][feature][16 B], three chunks ahead of the MFMAs; a chunk costs one s_waitcnt and one barrier, and the
+// operand fragments of every group of eight MFMAs are read from LDS while the previous group executes.
 // With one range per tile and the feature order kept, the result is added straight into A; otherwise partial
 // tiles go to the workspace and are summed in float64 (and permuted to the caller's feature order).
 #include "fw_internal.h"
 #include <math.h>
-#include <stdlib.h>
 
 namespace fw {
 namespace {
@@ -109,6 +109,8 @@ struct SmemTile {
 
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 #define FW_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+// the same, and lgkmcnt(0): LDS reads of this wavefront have returned as well
+#define FW_WAIT_VM_LGKM0(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0070)
 
 __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restrict__ P, const int* __restrict__ utab, TileGeom g,
                                                             float* __restrict__ part, float* __restrict__ A) {
@@ -117,7 +119,19 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wi = wave >> 2, wj = wave & 3;
     const int half = lane >> 5, l32 = lane & 31;
-    const int tile = blockIdx.x, split = blockIdx.y;
+    // Workgroups are handed to the 8 XCDs round-robin by their linear index.  Re-index so that each XCD works on a
+    // contiguous run of (range, tile) pairs: neighbours in that run share the unit range and mostly the row panel, which
+    // keeps what one XCD pulls into its own L2 small.
+    const int total = g.ntiles * g.nsplit;
+    const int per_xcd = (total + 7) / 8;
+    int tile, split;
+    {
+        const int w = blockIdx.x;
+        const int n = (w & 7) * per_xcd + (w >> 3);
+        if (n >= total || (w >> 3) >= per_xcd) return;   // padding of the last run
+        split = n / g.ntiles;
+        tile = n - split * g.ntiles;
+    }
     int I = (int)((sqrtf(8.f * tile + 1.f) - 1.f) * 0.5f);
     while ((I + 1) * (I + 2) / 2 <= tile) ++I;
     while (I * (I + 1) / 2 > tile) --I;
@@ -177,46 +191,54 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
     };
 
     const int pj = diag ? 0 : 1;
-    auto compute = [&](int c) {
+    // Operand fragments of k-step ks (units 2ks, 2ks+1) of chunk c; two register sets alternate so that the reads
+    // for the next group of MFMAs are always issued before the current group.
+    bf16x8 fa[2][4], fb[2][2];
+    auto read_frags = [&](int c, int ks, int set) {
         const int stage = c & (NST - 1);
-        bf16x8 fa[2][4], fb[2][2];
-        auto read_frags = [&](int ks, int set) {
-            const int unit = 2 * ks + half;
+        const int unit = 2 * ks + half;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) fa[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[stage][0][unit][128 * wi + 32 * t + l32]);
+        for (int t = 0; t < 4; ++t) fa[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[stage][0][unit][128 * wi + 32 * t + l32]);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) fb[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[stage][pj][unit][64 * wj + 32 * t + l32]);
-        };
-        read_frags(0, 0);
-#pragma unroll
-        for (int ks = 0; ks < KU / 2; ++ks) {
-            if (ks + 1 < KU / 2) read_frags(ks + 1, (ks + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);   // keep the reads of the next step ahead of this step's MFMAs
-#pragma unroll
-            for (int ta = 0; ta < 4; ++ta)
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
-                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][ta], fb[ks & 1][tb], acc[ta][tb], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        for (int t = 0; t < 2; ++t) fb[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[stage][pj][unit][64 * wj + 32 * t + l32]);
     };
+    auto mfma_group = [&](int set) {
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][ta], fb[set][tb], acc[ta][tb], 0, 0, 0);
+    };
+    static_assert(KU == 4 && NST == 4, "the loop below is written for two k-steps per chunk and a ring of four");
 
-    // Ring protocol.  Chunks c, c+1, c+2 are in flight when iteration c starts.  Loads of one wavefront complete in
-    // order, so "at most the loads of two chunks outstanding" means chunk c has landed for this wavefront; the barrier
-    // extends that to all wavefronts and also tells that everyone has finished reading chunk c-1, whose stage the
-    // loads of chunk c+3 then overwrite.  Every iteration issues the same number of loads (past the end they fetch
-    // the zero element), which keeps the outstanding-load arithmetic valid in the tail.
+    // Ring protocol.  Loads of one wavefront complete in order, so "at most the loads of two chunks outstanding" means
+    // the chunk before those two has landed for this wavefront; the barrier extends that to all wavefronts.  The
+    // barrier sits in the middle of a chunk: by then every wavefront has its last fragments of chunk c in registers
+    // (lgkmcnt 0), so the stage of chunk c is free for the loads of chunk c+4, and chunk c+1 is ready to be read while
+    // the second half of chunk c is still being multiplied.  Every iteration issues the same number of loads (past the
+    // end they fetch the zero element), which keeps the outstanding-load arithmetic valid in the tail.
     // The barrier is the bare instruction: __syncthreads() would first drain every outstanding load, which is exactly
-    // what the ring is there to avoid.  What a wavefront reads after the barrier was written by loads that their
-    // issuers waited for before it.
+    // what the ring is there to avoid.
     fetch_bases(0);
     issue(0); issue(1); issue(2);
+    if (diag) FW_WAIT_VMCNT(4); else FW_WAIT_VMCNT(8);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(3);
+    read_frags(0, 0, 0);
     for (int c = 0; c < nchunks; ++c) {
-        if (diag) FW_WAIT_VMCNT(4); else FW_WAIT_VMCNT(8);
+        read_frags(c, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_group(0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (diag) FW_WAIT_VM_LGKM0(4); else FW_WAIT_VM_LGKM0(8);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        issue(c + 3);
-        compute(c);
+        issue(c + 4);
+        read_frags(c + 1, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_group(1);
+        __builtin_amdgcn_sched_barrier(0);
     }
     FW_WAIT_VMCNT(0);
     __syncthreads();
@@ -323,7 +345,6 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
         if (ns > 1) cost += (double)wgs * TB * TB * 4.0 * 2.0 / bw;
         if (cost < best * 0.999) { best = cost; best_ns = ns; }
     }
-    if (const char* e = getenv("FW_COV_BF16_SPLITS")) best_ns = atoi(e) > 0 ? atoi(e) : best_ns;
     if (best_ns > nchunks) best_ns = (int)nchunks;
     const long long cps = (nchunks + best_ns - 1) / best_ns;
     g->units_per_split = (int)(cps * KU);
@@ -380,7 +401,8 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
                        g, P, S8);
     hipLaunchKernelGGL(unit_table_kernel, dim3((g.n_units + 255) / 256), dim3(256), 0, st, g, utab);
     FW_LAUNCH_CHECK();
-    hipLaunchKernelGGL(cov_bf16_tile_kernel, dim3(g.ntiles, g.nsplit), dim3(512), 0, st, P, utab, g, part, A);
+    const int per_xcd = (g.ntiles * g.nsplit + 7) / 8;
+    hipLaunchKernelGGL(cov_bf16_tile_kernel, dim3(per_xcd * 8), dim3(512), 0, st, P, utab, g, part, A);
     FW_LAUNCH_CHECK();
     if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * 256), dim3(256), 0, st, g, part, A);
     hipLaunchKernelGGL(column_sums_kernel, dim3(g.M), dim3(256), 0, st, g, S8, s);
