@@ -73,8 +73,9 @@ typedef enum { FW_OP_COV_ACCUMULATE = 0, FW_OP_GRAD_TRANSFORM = 1, FW_OP_COND_RE
  *   A      i/o  [M, M] float32, accumulated in place (zero it before the first batch of a block)
  *   s      i/o  [M] float32, accumulated in place
  *   ws     scratch, fw_workspace_bytes(FW_OP_COV_ACCUMULATE, M, 0, d, dt) bytes
- * Products are accumulated in float32 on the matrix cores (bf16 inputs: bf16 x bf16 -> float32); partial sums of
- * row ranges are combined in float64 before they are added to A.  The result is deterministic run to run.
+ * Products are accumulated in float32 on the matrix cores (bf16 inputs: bf16 x bf16 -> float32).  When the rows are
+ * split into ranges, the partial sums of the ranges are combined in float64 before they are added to A; a tile
+ * covered by a single range is added to A directly in float32.  The result is deterministic run to run.
  * Limits: M <= 16384; activation below 2^31 elements.
  */
 fw_status fw_cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d,
