@@ -25,9 +25,13 @@ if ROOT not in sys.path:
 PEAK = {"f32": 157.3e12, "bf16": 2.5e15}   # dense MFMA peaks of MI355X, flop/s
 HBM_PEAK = 8.0e12
 
-# HBM bytes per fw_cov_accumulate call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), scaled by
-# the reading of the same counters on a plain copy of known size; None until measured for that workload.
-MEASURED_TRAFFIC = {}
+# HBM bytes (read + written) per fw_cov_accumulate call, all its kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this script with --copy-calibration (summary: profiles/fw_cov_accumulate_hbm_traffic_counters.txt), each
+# counter scaled by what it reads on a 256 MiB device copy (2 KiB per FETCH_SIZE count, 1 KiB per WRITE_SIZE count).
+# Measured with the default layout (kkc); other layouts report null.
+MEASURED_TRAFFIC = {"c2": {"read": 79.5e6, "written": 48.0e6},
+                    "c3": {"read": 186.9e6, "written": 105.4e6},
+                    "c4": {"read": 229.6e6, "written": 65.8e6}}
 
 
 def parse():
@@ -132,6 +136,9 @@ def main():
     cov_flops = float(n_rows) * M * (M + 1)                 # lower triangle incl. diagonal, 2 flops per product
     achieved = cov_flops / (cov_ms * 1e-3)
     peak = PEAK[layer.dtype]
+    tr = MEASURED_TRAFFIC.get(args.config) if (layer.is_rows or args.layout == "kkc") else None
+    traffic = tr["read"] + tr["written"] if tr else None
+    alg_bytes = float(X.numel() * X.element_size() + 4 * M * M)   # activation once + A once
     cond_words = 16 if prm.gamma < 1.0 else 10
     cond_bytes = cond_words * M * M * 4.0
     out = {
@@ -148,7 +155,8 @@ def main():
                      "kernel": ("pack_images + cov_bf16_tile (+ tile_reduce) + column_sums" if bf16 else
                                 "cov_partial_f32v4 + cov_reduce + cov_reduce_sums") + " = one fw_cov_accumulate",
                      "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": MEASURED_TRAFFIC.get(args.config)},
+                     "traffic": traffic, "traffic_unit": "bytes per fw_cov_accumulate call (HBM read + written, counters)",
+                     "traffic_read_written": tr, "algorithmic_bytes": alg_bytes},
         "breakdown_ms": {"cov_accumulate": cov_ms, "cov_finalize": fin_ms, "cond_reduce_step": cond_ms, "grad_transform": grad_ms},
         "cond_step_GBps": cond_bytes / (cond_ms * 1e-3) / 1e9,
         "grad_transform_TFLOPs": 2.0 * S * M * M / (grad_ms * 1e-3) / 1e12,
@@ -169,12 +177,12 @@ def main():
         except Exception:
             cores = os.cpu_count() or 1
         # bounded sample: whole updates of the same workload by the oracle, repeated until about 10 s have passed
-        # (at most 3 updates); images beyond a memory bound are dropped and the moment terms scaled, which are linear
-        # in the rows
+        # (at least one, at most 64 updates); images beyond a memory bound are dropped and the moment terms scaled,
+        # which are linear in the rows
         Bs = d.B if layer.is_rows else max(1, min(d.B, int(4e9 // max(1, 8 * d.P * M))))
         scale = d.B / Bs
         reps, spent, secs = 0, 0.0, {"unfold": 0.0, "moments": 0.0, "cond_step": 0.0, "grad_transform": 0.0}
-        while reps < 3 and spent < 10.0:
+        while reps < 64 and spent < 10.0:
             tc0 = time.perf_counter()
             if layer.is_rows:
                 Xr = np.asarray(layer.act[:Bs], dtype=np.float64)
