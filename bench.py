@@ -153,7 +153,7 @@ def main():
                    "batch": d.B, "block_length": 1, "cond_params": "gamma=0.99 beta=0.1 delta=0.25 (paper defaults)"},
         "roofline": {"bound": "mfma",
                      "kernel": ("pack_images + cov_bf16_tile (+ tile_reduce) + column_sums" if bf16 else
-                                "cov_partial_f32v4 + cov_reduce + cov_reduce_sums") + " = one fw_cov_accumulate",
+                                "cov_partial_f32v4 + cov_reduce") + " = one fw_cov_accumulate",
                      "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": traffic, "traffic_unit": "bytes per fw_cov_accumulate call (HBM read + written, counters)",
                      "traffic_read_written": tr, "algorithmic_bytes": alg_bytes},

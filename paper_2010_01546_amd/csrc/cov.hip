@@ -411,9 +411,27 @@ __global__ __launch_bounds__(256) void cov_partial_f32v4_kernel(const float* __r
     }
 }
 
-// Sum the partial blocks over the row splits in float64 and add them into A (lower triangle, external order).
-// One thread per element of a partial block; consecutive threads read consecutive addresses of every split.
-__global__ __launch_bounds__(256) void cov_reduce_kernel(CovGeom g, const float* __restrict__ part, float* __restrict__ A) {
+// Sum of the partial blocks over the row ranges in float64, added into A in the caller's feature order: one thread per
+// element, the loads of eight ranges in flight at a time.  The last (M+63)/64 workgroups do the same for the column
+// sums: 64 features each, the ranges dealt to four groups of threads and combined through LDS.
+__global__ __launch_bounds__(256) void cov_reduce_kernel(CovGeom g, const float* __restrict__ part, const float* __restrict__ spart,
+                                                         float* __restrict__ A, float* __restrict__ s) {
+    __shared__ double red[4][64];
+    const int nblk = g.nitems * 4 * 16;
+    if ((int)blockIdx.x >= nblk) {
+        const int f = ((int)blockIdx.x - nblk) * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
+        double v = 0.0;
+        if (f < g.M)
+            for (int sp = grp; sp < g.nsplit; sp += 4) v += (double)spart[(size_t)sp * g.nb * BLK + f];
+        red[grp][threadIdx.x & 63] = v;
+        __syncthreads();
+        if (grp == 0 && f < g.M) {
+            v = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+            const int e = feat_of(f, g).ext;
+            s[e] = (float)((double)s[e] + v);
+        }
+        return;
+    }
     const int blk = blockIdx.x >> 4;                       // (item, wavefront)
     const int e = ((blockIdx.x & 15) << 8) + threadIdx.x;  // element of the 64x64 block
     const int item_idx = blk >> 2, wave = blk & 3;
@@ -428,27 +446,19 @@ __global__ __launch_bounds__(256) void cov_reduce_kernel(CovGeom g, const float*
     const size_t stride = (size_t)g.nitems * 4 * BLK * BLK;
     const float* src = part + (size_t)blk * (BLK * BLK) + e;
     double v = 0.0;
-    for (int sp = 0; sp < g.nsplit; ++sp) v += (double)src[sp * stride];
+    int sp = 0;
+    for (; sp + 8 <= g.nsplit; sp += 8) {
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = src[(size_t)(sp + j) * stride];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v += (double)x[j];
+    }
+    for (; sp < g.nsplit; ++sp) v += (double)src[(size_t)sp * stride];
     const int ei = feat_of(fi, g).ext, ej = feat_of(fj, g).ext;
     const int hi = max(ei, ej), lo = min(ei, ej);
     float* dst = A + (size_t)hi * g.M + lo;
     *dst = (float)((double)*dst + v);
-}
-
-// column sums: 64 features per workgroup, the splits dealt to four groups of threads and combined through LDS
-__global__ __launch_bounds__(256) void cov_reduce_sums_kernel(CovGeom g, const float* __restrict__ spart, float* __restrict__ s) {
-    __shared__ double red[4][64];
-    const int f = blockIdx.x * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
-    double v = 0.0;
-    if (f < g.M)
-        for (int sp = grp; sp < g.nsplit; sp += 4) v += (double)spart[(size_t)sp * g.nb * BLK + f];
-    red[grp][threadIdx.x & 63] = v;
-    __syncthreads();
-    if (grp == 0 && f < g.M) {
-        v = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
-        const int e = feat_of(f, g).ext;
-        s[e] = (float)((double)s[e] + v);
-    }
 }
 
 bool make_geom(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, CovGeom* g) {
@@ -580,8 +590,7 @@ fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_con
     else
         hipLaunchKernelGGL(cov_partial_kernel, grid, dim3(256), 0, st, reinterpret_cast<const float*>(X), g, part, spart);
     FW_LAUNCH_CHECK();
-    hipLaunchKernelGGL(cov_reduce_kernel, dim3(g.nitems * 4 * 16), dim3(256), 0, st, g, part, A);
-    hipLaunchKernelGGL(cov_reduce_sums_kernel, dim3((g.M + 63) / 64), dim3(256), 0, st, g, spart, s);
+    hipLaunchKernelGGL(cov_reduce_kernel, dim3(g.nitems * 4 * 16 + (g.M + 63) / 64), dim3(256), 0, st, g, part, spart, A, s);
     FW_LAUNCH_CHECK();
     return FW_OK;
 }

@@ -1,11 +1,10 @@
 // Gradient transformation G_out = G Q (Sec. 3.1, eqs. (mod_weight_grad), (vQ)) on the gfx950 matrix cores.
 //
-// A workgroup of four wavefronts owns a tile of G_out (64 x 64 in float32, 64 x 128 in bfloat16); the contraction
-// index runs over the M features in chunks staged through LDS.
-//   float32: v_mfma_f32_32x32x2_f32, G panel [row][k], Q panel [k][col].
-//   bfloat16: v_mfma_f32_32x32x16_bf16, both panels K-major; Q is symmetric, so the K-major panel of Q is read
-//   along its rows (contiguous) and rounded to bfloat16 while it is staged.
+// Q = T^T T is symmetric, so column c of Q is read as row c: both operands are contiguous along the contraction index.
+//   float32: v_mfma_f32_32x32x2_f32 or v_mfma_f32_16x16x4_f32, strips of output tiles per workgroup (see below).
+//   bfloat16: v_mfma_f32_32x32x16_bf16, 64 x 128 tile per workgroup, Q rounded to bfloat16 while it is staged.
 #include "fw_internal.h"
+#include <type_traits>
 
 namespace fw {
 namespace {
@@ -15,78 +14,266 @@ constexpr int TN = 128;   // columns per workgroup
 constexpr int KC16 = 32;  // contraction chunk, bfloat16
 constexpr int ROWB = KC16 * 2 + 16;  // bytes of one K-major bf16 LDS row
 
-// float32, large problems: 64x64 tile per workgroup, one 32x32 MFMA tile per wavefront.  Chunks of 32 contraction
-// entries are fetched with 16-byte loads one chunk ahead of the MFMAs and double-buffered in LDS, both panels
-// K-major ([k][row] for G, [k][col] for Q), so that a chunk costs one barrier.  Needs M % 4 == 0.
-struct GemmSmem {
-    float Gt[2][32][65];   // [buffer][k][row], row stride 65 words: the transposing stores spread over the banks
-    alignas(16) float Qt[2][32][64];   // [buffer][k][col]
+// float32: a workgroup of four wavefronts owns a strip of C output tiles (MF x MF each, MF = 32 or 16) that share one
+// row tile of G.  The contraction index is cut into chunks; a chunk of the G rows and of the Q rows that belong to
+// the strip's columns (Q is symmetric: column c of Q is row c, contiguous along the contraction index) travels from
+// global memory straight into LDS (global_load_lds_dwordx4) into a ring of three stages, up to three chunks ahead of
+// the MFMAs, laid out [panel][row][16-byte group] with the group index XOR-ed by a function of the row so that the
+// fragment reads of 16 consecutive rows hit distinct banks.  Inside a chunk the four wavefronts take disjoint quarters
+// of the contraction index and each of them updates ALL tiles of the strip, so every SIMD gets the same number of
+// MFMAs whatever the tile count; the fragments of the next chunk are read into registers while the MFMAs of the
+// current one run, and the four partial strips are summed through LDS at the end, in wavefront order.  A ragged last
+// chunk is staged through registers with zero fill.  The host picks (MF, C) so that the workgroup count comes close
+// to a multiple of the 256 compute units.  Needs M % 4 == 0.
+template <int MF>
+struct Mfma;
+template <>
+struct Mfma<32> {
+    typedef floatx16 acc_t;
+    static __device__ __forceinline__ acc_t run(float a, float b, acc_t c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+    // register i of lane (lr, lk) holds row 8*(i/4) + 4*lk + i%4, column lr
+    static __device__ __forceinline__ int row(int i, int lk) { return 8 * (i >> 2) + 4 * lk + (i & 3); }
+};
+template <>
+struct Mfma<16> {
+    typedef floatx4 acc_t;
+    static __device__ __forceinline__ acc_t run(float a, float b, acc_t c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+    // register i of lane (lr, lk) holds row 4*lk + i, column lr
+    static __device__ __forceinline__ int row(int i, int lk) { return 4 * lk + i; }
 };
 
-__global__ __launch_bounds__(256) void grad_gemm_f32_kernel(const float* __restrict__ G, const float* __restrict__ Q,
-                                                            float* __restrict__ Out, int S, int M) {
-    constexpr int KC = 32;
-    __shared__ GemmSmem sm;
+template <int MF, int C>
+struct StripCfg {
+    static constexpr int KL = 64 / MF;                       // lanes of one row along the contraction index
+    static constexpr int KW = 4 * KL;                        // contraction entries one float4 per lane covers
+    static constexpr int U = C >= 3 ? 1 : (C == 2 ? 2 : 4);  // float4 per lane, panel and chunk
+    static constexpr int KC = 4 * KW * U;                    // contraction entries per chunk (four wavefronts)
+    static constexpr int QR = KC / 4;                        // 16-byte groups per staged row: 8, 16, 32 or 64
+    static constexpr int NP = 1 + C;                         // staged panels: G rows, then C tiles of Q rows
+    static constexpr int IPW = NP * U;                       // direct-to-LDS loads per wavefront and chunk
+    static constexpr int NACC = MF * MF / 64;
+    static constexpr int PANEL = MF * KC;                    // floats of one staged panel = 256 U groups
+    static constexpr int STAGE = NP * PANEL;
+    static constexpr int NST = 3;
+    static constexpr int RED = 16 * MF * MF;                 // epilogue: 4 tiles x 4 wavefronts
+    static constexpr int SMEM = NST * STAGE > RED ? NST * STAGE : RED;
+    // group g of row r is stored at group g ^ swz(r): 16 consecutive rows reading one g then cover 16 distinct
+    // 16-byte bank groups
+    static __device__ __forceinline__ int swz(int r) { return QR == 8 ? (r >> 1) & 7 : r & 15; }
+};
+
+// s_waitcnt vmcnt(n), the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+#define FW_GEMM_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+// s_waitcnt lgkmcnt(0): the LDS reads of this wavefront have returned
+#define FW_GEMM_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+// keeps the compiler from moving memory accesses across this point (no instruction)
+#define FW_COMPILER_FENCE() asm volatile("" ::: "memory")
+
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds_base + 16 l (lds_base is
+// wavefront-uniform and travels in M0).  Written as assembly so that the compiler does not track it as a pending LDS
+// store (it would wait for ALL outstanding loads before every LDS read): completion is awaited by hand with
+// FW_GEMM_WAIT_VM, counting these loads in issue order, followed by a workgroup barrier.
+__device__ __forceinline__ void dma16(const float* src, float* lds_dst) {
+    const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds_dst;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
+}
+
+template <int MF, int C>
+__global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* __restrict__ G, const float* __restrict__ Q,
+                                                                  float* __restrict__ Out, int S, int M) {
+    typedef StripCfg<MF, C> K;
+    typedef typename Mfma<MF>::acc_t acc_t;
+    __shared__ __attribute__((aligned(16))) float sm[K::SMEM];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int half = lane >> 5, l32 = lane & 31;
-    const int row0 = blockIdx.y * 64, col0 = blockIdx.x * 64;
-    const int wr = wave & 1, wc = wave >> 1;
-    floatx16 acc;
+    const int lr = lane % MF, lk = lane / MF;
+    const int row0 = blockIdx.y * MF, col0 = blockIdx.x * (C * MF);
+    acc_t acc[C];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int j = 0; j < C; ++j)
+#pragma unroll
+        for (int i = 0; i < K::NACC; ++i) acc[j][i] = 0.f;
 
-    // staging roles: G panel 64 rows x 32 k = 512 float4 (row = e / 8, k quad = e % 8), Q panel 32 k x 64 cols = 512 float4
-    float4 pg[2], pq[2];
-    const int nchunks = (M + KC - 1) / KC;
-    auto load_chunk = [&](int c) {
-        const int k0 = c * KC;
+    // Load i of this wavefront fills groups ((i % U)*4 + wave)*64 .. +63 of panel i / U; lane l brings group +l.
+    // Rows past the end of G or Q are clamped: they only feed outputs that are never stored.
+    int doff[K::IPW];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int e = tid + 256 * j;
-            const int gr = row0 + (e >> 3), gk = k0 + 4 * (e & 7);
-            pg[j] = (gr < S && gk < M) ? *reinterpret_cast<const float4*>(G + (size_t)gr * M + gk) : make_float4(0.f, 0.f, 0.f, 0.f);
-            const int qk = k0 + (e >> 4), qc = col0 + 4 * (e & 15);
-            pq[j] = (qk < M && qc < M) ? *reinterpret_cast<const float4*>(Q + (size_t)qk * M + qc) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    };
-    auto store_chunk = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int e = tid + 256 * j;
-            const int r = e >> 3, kq = 4 * (e & 7);
-            sm.Gt[buf][kq + 0][r] = pg[j].x; sm.Gt[buf][kq + 1][r] = pg[j].y;
-            sm.Gt[buf][kq + 2][r] = pg[j].z; sm.Gt[buf][kq + 3][r] = pg[j].w;
-            *reinterpret_cast<float4*>(&sm.Qt[buf][e >> 4][4 * (e & 15)]) = pq[j];
-        }
-    };
-    load_chunk(0);
-    store_chunk(0);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
-        const bool more = c + 1 < nchunks;
-        if (more) load_chunk(c + 1);
-#pragma unroll
-        for (int kk = 0; kk < KC; kk += 2) {
-            const float a = sm.Gt[buf][kk + half][32 * wr + l32];
-            const float b = sm.Qt[buf][kk + half][32 * wc + l32];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
-        }
-        if (more) store_chunk(buf ^ 1);
-        __syncthreads();
+    for (int i = 0; i < K::IPW; ++i) {
+        const int p = i / K::U;
+        const int sgrp = ((i % K::U) * 4 + wave) * 64 + lane;
+        const int r = sgrp / K::QR, q = (sgrp % K::QR) ^ K::swz(r);
+        const int grow = p == 0 ? min(row0 + r, S - 1) : min(col0 + (p - 1) * MF + r, M - 1);
+        doff[i] = grow * M + 4 * q;
     }
+    auto dma_one = [&](int k0, int stage, int i) {   // i is a compile-time constant after unrolling
+        const int p = i / K::U;
+        dma16((p == 0 ? G : Q) + doff[i] + k0, &sm[stage * K::STAGE + p * K::PANEL + ((i % K::U) * 4 + wave) * 256]);
+    };
+    auto issue = [&](int c, int stage) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = row0 + 32 * wr + 8 * (i >> 2) + 4 * half + (i & 3);
-        const int c = col0 + 32 * wc + l32;
-        if (r < S && c < M) Out[(size_t)r * M + c] = acc[i];
+        for (int i = 0; i < K::IPW; ++i) dma_one(c * K::KC, stage, i);
+    };
+    // operand fragments of a chunk for this wavefront's quarter of it
+    int foff[K::U];
+#pragma unroll
+    for (int u = 0; u < K::U; ++u) foff[u] = 4 * (lr * K::QR + (((wave * K::U + u) * K::KL + lk) ^ K::swz(lr)));
+    float4 fr[2][K::IPW];
+    auto read_one = [&](int stage, float4* f, int i) {   // fragment i = u * NP + p
+        f[i] = *reinterpret_cast<const float4*>(&sm[stage * K::STAGE + (i % K::NP) * K::PANEL + foff[i / K::NP]]);
+    };
+    auto read_frags = [&](int stage, float4* f) {
+#pragma unroll
+        for (int i = 0; i < K::IPW; ++i) read_one(stage, f, i);
+    };
+    // MFMA t of a chunk, 0 <= t < NT: t = (u*4 + s)*C + j updates tile j with entry s of the float4 pair u
+    constexpr int NT = 4 * K::U * C;
+    auto mfma_one = [&](const float4* f, int t) {
+        const int j = t % C, s4 = (t / C) % 4, u = t / (4 * C);
+        const float4 a = f[u * K::NP], b = f[u * K::NP + 1 + j];
+        const float av = s4 == 0 ? a.x : s4 == 1 ? a.y : s4 == 2 ? a.z : a.w;
+        const float bv = s4 == 0 ? b.x : s4 == 1 ? b.y : s4 == 2 ? b.z : b.w;
+        acc[j] = Mfma<MF>::run(av, bv, acc[j]);
+    };
+    auto mfmas = [&](const float4* f) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) mfma_one(f, t);
+    };
+
+    const int nfull = M / K::KC;
+    if (nfull > 0) {
+        issue(0, 0);
+        if (nfull > 1) issue(1, 1);
+        if (nfull > 2) issue(2, 2);
+        if (nfull > 2) FW_GEMM_WAIT_VM(2 * K::IPW);
+        else if (nfull > 1) FW_GEMM_WAIT_VM(K::IPW);
+        else FW_GEMM_WAIT_VM(0);
+        __builtin_amdgcn_s_barrier();
+        FW_COMPILER_FENCE();
+        read_frags(0, fr[0]);
+        int sc = 0;   // stage of chunk c
+        // Iteration c.  On entry every wavefront has asked for its fragments of chunk c (registers `cur`).  After the
+        // first half of the MFMAs: chunk c+1 must have landed (chunk c+2 may still be on its way) and, past the
+        // barrier, nobody reads the stage of chunk c any more, so it takes chunk c+3.  The loads of chunk c+3 and the
+        // fragment reads of chunk c+1 are then issued one by one between the remaining MFMAs, which keeps the matrix
+        // pipe fed while a single wavefront per SIMD does the issuing.
+        constexpr int H = NT / 2, REST = NT - H;
+        auto iteration = [&](int c, const float4* cur, float4* nxt, auto STEADY) {
+            constexpr bool steady = decltype(STEADY)::value;   // c + 3 < nfull known: no branches around the MFMAs
+            const int sn = sc == 2 ? 0 : sc + 1;
+            FW_GEMM_WAIT_LGKM0();
+#pragma unroll
+            for (int t = 0; t < H; ++t) mfma_one(cur, t);
+            __builtin_amdgcn_sched_barrier(0);
+            if (steady || c + 2 < nfull) FW_GEMM_WAIT_VM(K::IPW);
+            else FW_GEMM_WAIT_VM(0);
+            __builtin_amdgcn_s_barrier();
+            FW_COMPILER_FENCE();
+#pragma unroll
+            for (int i = 0; i < K::IPW; ++i) {
+                if (steady || c + 3 < nfull) dma_one((c + 3) * K::KC, sc, i);
+                if (steady || c + 1 < nfull) read_one(sn, nxt, i);
+#pragma unroll
+                for (int t = H + i * REST / K::IPW; t < H + (i + 1) * REST / K::IPW; ++t) mfma_one(cur, t);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            sc = sn;
+        };
+        int c = 0;
+        for (; c + 4 < nfull; c += 2) {
+            iteration(c, fr[0], fr[1], std::true_type());
+            iteration(c + 1, fr[1], fr[0], std::true_type());
+        }
+        for (; c < nfull; c += 2) {   // the last one to four chunks
+            iteration(c, fr[0], fr[1], std::false_type());
+            if (c + 1 < nfull) iteration(c + 1, fr[1], fr[0], std::false_type());
+        }
+    }
+    if (nfull * K::KC < M) {   // ragged last chunk through registers, zero beyond M
+        const int k0 = nfull * K::KC;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < K::IPW; ++i) {
+            const int p = i / K::U;
+            const int sgrp = ((i % K::U) * 4 + wave) * 64 + lane;
+            const int r = sgrp / K::QR, q = (sgrp % K::QR) ^ K::swz(r);
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k0 + 4 * q < M) v = *reinterpret_cast<const float4*>((p == 0 ? G : Q) + doff[i] + k0);
+            *reinterpret_cast<float4*>(&sm[p * K::PANEL + 4 * sgrp]) = v;
+        }
+        __syncthreads();
+        read_frags(0, fr[0]);
+        mfmas(fr[0]);
+    }
+    __syncthreads();
+
+    // sum of the four partial strips: rounds of four tiles, wavefront q owns tile q of the round
+    float* red = sm;   // [tile of the round][wavefront][register][lane]
+#pragma unroll
+    for (int g = 0; g < (C + 3) / 4; ++g) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (4 * g + q < C && wave != q) {
+#pragma unroll
+                for (int i = 0; i < K::NACC; ++i) red[((q * 4 + wave) * K::NACC + i) * 64 + lane] = acc[(4 * g + q) % C][i];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (4 * g + q < C && wave == q) {
+                const int col = col0 + (4 * g + q) * MF + lr;
+#pragma unroll
+                for (int i = 0; i < K::NACC; ++i) {
+                    float v = 0.f;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) v += (w == q) ? acc[(4 * g + q) % C][i] : red[((q * 4 + w) * K::NACC + i) * 64 + lane];
+                    const int row = row0 + Mfma<MF>::row(i, lk);
+                    if (row < S && col < M) Out[(size_t)row * M + col] = v;
+                }
+            }
+        }
+        __syncthreads();
     }
 }
 
-// Small problems (too few 64x128 tiles to fill the chip): a workgroup owns a 32x32 tile of G_out and its four
-// wavefronts split the contraction index four ways; operands come straight from global memory / L2 (G is small and
-// Q rows are read coalesced), partial tiles are combined through LDS.  Latency-bound by design.
+// (MF, C) with the lowest cost: rounds of 256 workgroups x MFMA time of a workgroup, contraction padded to whole chunks
+struct StripChoice { int mf, c; };
+inline StripChoice pick_strip(int S, int M) {
+    static const int cs[6] = {9, 6, 4, 3, 2, 1};
+    StripChoice best = {32, 1};
+    double best_cost = 1e300;
+    for (int mf = 32; mf >= 16; mf -= 16)
+        for (int ci = 0; ci < 6; ++ci) {
+            const int c = cs[ci];
+            const int kw = mf == 32 ? 8 : 16, u = c >= 3 ? 1 : (c == 2 ? 2 : 4), kc = 4 * kw * u;
+            const long long tr = (S + mf - 1) / mf, tc = (M + mf - 1) / mf;
+            const long long wgs = tr * ((tc + c - 1) / c);
+            const double rounds = (double)((wgs + 255) / 256);
+            const double kpad = (double)((M + kc - 1) / kc * kc) / M;
+            // a 16x16 tile is a quarter of the MFMA work of a 32x32 tile and reads twice the operands per flop;
+            // a wider strip reads fewer operands per MFMA
+            const double cost = rounds * c * (mf == 32 ? 1.0 : 0.25 * 1.06) * kpad * (1.0 + 0.02 / c);
+            if (cost < best_cost) { best_cost = cost; best = {mf, c}; }
+        }
+    return best;
+}
+
+template <int MF>
+void launch_strip(int c, const float* G, const float* Q, float* Out, int S, int M, hipStream_t st) {
+    const dim3 grid(((M + MF - 1) / MF + c - 1) / c, (S + MF - 1) / MF);
+    switch (c) {
+        case 9: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 9>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
+        case 6: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 6>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
+        case 4: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 4>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
+        case 3: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 3>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
+        case 2: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 2>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
+        default: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 1>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
+    }
+}
+
+// M not a multiple of 4 (rows of G and Q not 16-byte aligned): a workgroup owns a 32x32 tile of G_out and its four
+// wavefronts split the contraction index four ways; operands come straight from global memory / L2 with scalar
+// loads, partial tiles are combined through LDS.
 __global__ __launch_bounds__(256) void grad_gemm_f32_small_kernel(const float* __restrict__ G, const float* __restrict__ Q,
                                                                   float* __restrict__ Out, int S, int M) {
     __shared__ float red[3][32 * 32];
@@ -195,12 +382,14 @@ fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, vo
     if (dt == FW_BF16)
         hipLaunchKernelGGL(grad_gemm_bf16_kernel, grid, dim3(256), 0, st, reinterpret_cast<const unsigned short*>(G), Q,
                            reinterpret_cast<unsigned short*>(G_out), S, M);
-    else if ((long long)((M + 63) / 64) * ((S + 63) / 64) < 400 || (M & 3) != 0)
+    else if ((M & 3) != 0)
         hipLaunchKernelGGL(grad_gemm_f32_small_kernel, dim3((M + 31) / 32, (S + 31) / 32), dim3(256), 0, st,
                            reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M);
-    else
-        hipLaunchKernelGGL(grad_gemm_f32_kernel, dim3((M + 63) / 64, (S + 63) / 64), dim3(256), 0, st,
-                           reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M);
+    else {
+        const StripChoice ch = pick_strip(S, M);
+        if (ch.mf == 32) launch_strip<32>(ch.c, reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M, st);
+        else launch_strip<16>(ch.c, reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M, st);
+    }
     FW_LAUNCH_CHECK();
     return FW_OK;
 }

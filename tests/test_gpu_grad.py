@@ -16,7 +16,8 @@ def sym_Q(M, seed):
     return T.astype(np.float32), (T.astype(np.float32).astype(np.float64).T @ T.astype(np.float32).astype(np.float64))
 
 
-@pytest.mark.parametrize("S,M", [(32, 64), (5, 7), (64, 576), (70, 200), (1, 129), (130, 147), (256, 300)])
+@pytest.mark.parametrize("S,M", [(32, 64), (5, 7), (64, 576), (70, 200), (1, 129), (130, 147), (256, 300), (40, 260), (200, 1156),
+                                 (256, 2304), (96, 1024), (17, 4608)])
 def test_f32_with_Q(S, M):
     T32, Q64 = sym_Q(M, M)
     Q32 = Q64.astype(np.float32)
