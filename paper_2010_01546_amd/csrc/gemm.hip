@@ -17,7 +17,7 @@ constexpr int ROWB = KC16 * 2 + 16;  // bytes of one K-major bf16 LDS row
 // float32: a workgroup of four wavefronts owns a strip of C output tiles (MF x MF each, MF = 32 or 16) that share one
 // row tile of G.  The contraction index is cut into chunks; a chunk of the G rows and of the Q rows that belong to
 // the strip's columns (Q is symmetric: column c of Q is row c, contiguous along the contraction index) travels from
-// global memory straight into LDS (global_load_lds_dwordx4) into a ring of three stages, up to three chunks ahead of
+// global memory straight into LDS (global_load_lds_dwordx4) into a ring of two or three stages, that many chunks ahead of
 // the MFMAs, laid out [panel][row][16-byte group] with the group index XOR-ed by a function of the row so that the
 // fragment reads of 16 consecutive rows hit distinct banks.  Inside a chunk the four wavefronts take disjoint quarters
 // of the contraction index and each of them updates ALL tiles of the strip, so every SIMD gets the same number of
@@ -42,11 +42,17 @@ struct Mfma<16> {
     static __device__ __forceinline__ int row(int i, int lk) { return 4 * lk + i; }
 };
 
+// float4 per lane, panel and chunk: enough for about 2000 cycles of MFMAs per chunk and wavefront, within an LDS stage
+// of at most 80 KB
+__host__ __device__ constexpr int strip_u(int mf, int c) {
+    return mf == 32 ? (c >= 9 ? 1 : c >= 4 ? 2 : c >= 2 ? 4 : 8) : (c >= 5 ? 2 : c >= 2 ? 4 : 8);
+}
+
 template <int MF, int C>
 struct StripCfg {
     static constexpr int KL = 64 / MF;                       // lanes of one row along the contraction index
     static constexpr int KW = 4 * KL;                        // contraction entries one float4 per lane covers
-    static constexpr int U = C >= 3 ? 1 : (C == 2 ? 2 : 4);  // float4 per lane, panel and chunk
+    static constexpr int U = strip_u(MF, C);
     static constexpr int KC = 4 * KW * U;                    // contraction entries per chunk (four wavefronts)
     static constexpr int QR = KC / 4;                        // 16-byte groups per staged row: 8, 16, 32 or 64
     static constexpr int NP = 1 + C;                         // staged panels: G rows, then C tiles of Q rows
@@ -54,7 +60,7 @@ struct StripCfg {
     static constexpr int NACC = MF * MF / 64;
     static constexpr int PANEL = MF * KC;                    // floats of one staged panel = 256 U groups
     static constexpr int STAGE = NP * PANEL;
-    static constexpr int NST = 3;
+    static constexpr int NST = 3 * STAGE * 4 <= 160 * 1024 ? 3 : 2;   // stages of the LDS ring
     static constexpr int RED = 16 * MF * MF;                 // epilogue: 4 tiles x 4 wavefronts
     static constexpr int SMEM = NST * STAGE > RED ? NST * STAGE : RED;
     // group g of row r is stored at group g ^ swz(r): 16 consecutive rows reading one g then cover 16 distinct
@@ -143,8 +149,8 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
     if (nfull > 0) {
         issue(0, 0);
         if (nfull > 1) issue(1, 1);
-        if (nfull > 2) issue(2, 2);
-        if (nfull > 2) FW_GEMM_WAIT_VM(2 * K::IPW);
+        if (K::NST > 2 && nfull > 2) issue(2, 2);
+        if (K::NST > 2 && nfull > 2) FW_GEMM_WAIT_VM(2 * K::IPW);
         else if (nfull > 1) FW_GEMM_WAIT_VM(K::IPW);
         else FW_GEMM_WAIT_VM(0);
         __builtin_amdgcn_s_barrier();
@@ -152,25 +158,25 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
         read_frags(0, fr[0]);
         int sc = 0;   // stage of chunk c
         // Iteration c.  On entry every wavefront has asked for its fragments of chunk c (registers `cur`).  After the
-        // first half of the MFMAs: chunk c+1 must have landed (chunk c+2 may still be on its way) and, past the
-        // barrier, nobody reads the stage of chunk c any more, so it takes chunk c+3.  The loads of chunk c+3 and the
-        // fragment reads of chunk c+1 are then issued one by one between the remaining MFMAs, which keeps the matrix
-        // pipe fed while a single wavefront per SIMD does the issuing.
+        // first half of the MFMAs: chunk c+1 must have landed (later chunks may still be on their way) and, past the
+        // barrier, nobody reads the stage of chunk c any more, so it takes chunk c+NST.  The loads of that chunk and
+        // the fragment reads of chunk c+1 are then issued one by one between the remaining MFMAs, which keeps the
+        // matrix pipe fed while a single wavefront per SIMD does the issuing.
         constexpr int H = NT / 2, REST = NT - H;
         auto iteration = [&](int c, const float4* cur, float4* nxt, auto STEADY) {
-            constexpr bool steady = decltype(STEADY)::value;   // c + 3 < nfull known: no branches around the MFMAs
-            const int sn = sc == 2 ? 0 : sc + 1;
+            constexpr bool steady = decltype(STEADY)::value;   // c + NST < nfull known: no branches around the MFMAs
+            const int sn = sc == K::NST - 1 ? 0 : sc + 1;
             FW_GEMM_WAIT_LGKM0();
 #pragma unroll
             for (int t = 0; t < H; ++t) mfma_one(cur, t);
             __builtin_amdgcn_sched_barrier(0);
-            if (steady || c + 2 < nfull) FW_GEMM_WAIT_VM(K::IPW);
+            if (K::NST > 2 && (steady || c + 2 < nfull)) FW_GEMM_WAIT_VM(K::IPW);
             else FW_GEMM_WAIT_VM(0);
             __builtin_amdgcn_s_barrier();
             FW_COMPILER_FENCE();
 #pragma unroll
             for (int i = 0; i < K::IPW; ++i) {
-                if (steady || c + 3 < nfull) dma_one((c + 3) * K::KC, sc, i);
+                if (steady || c + K::NST < nfull) dma_one((c + K::NST) * K::KC, sc, i);
                 if (steady || c + 1 < nfull) read_one(sn, nxt, i);
 #pragma unroll
                 for (int t = H + i * REST / K::IPW; t < H + (i + 1) * REST / K::IPW; ++t) mfma_one(cur, t);
@@ -179,11 +185,11 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
             sc = sn;
         };
         int c = 0;
-        for (; c + 4 < nfull; c += 2) {
+        for (; c + 1 + K::NST < nfull; c += 2) {
             iteration(c, fr[0], fr[1], std::true_type());
             iteration(c + 1, fr[1], fr[0], std::true_type());
         }
-        for (; c < nfull; c += 2) {   // the last one to four chunks
+        for (; c < nfull; c += 2) {   // the last few chunks
             iteration(c, fr[0], fr[1], std::false_type());
             if (c + 1 < nfull) iteration(c + 1, fr[1], fr[0], std::false_type());
         }
@@ -245,7 +251,7 @@ inline StripChoice pick_strip(int S, int M) {
     for (int mf = 32; mf >= 16; mf -= 16)
         for (int ci = 0; ci < 6; ++ci) {
             const int c = cs[ci];
-            const int kw = mf == 32 ? 8 : 16, u = c >= 3 ? 1 : (c == 2 ? 2 : 4), kc = 4 * kw * u;
+            const int kw = mf == 32 ? 8 : 16, u = strip_u(mf, c), kc = 4 * kw * u;
             const long long tr = (S + mf - 1) / mf, tc = (M + mf - 1) / mf;
             const long long wgs = tr * ((tc + c - 1) / c);
             const double rounds = (double)((wgs + 255) / 256);
