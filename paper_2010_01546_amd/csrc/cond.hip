@@ -4,6 +4,9 @@
 //   estimate (Sec. 4.2):  m' = argmax xi   ->  c = Phi_y Phi_y e_m'  ->  coherence set, weights w  ->
 //                         v~ = Phi_y w  ->  v = v~/|v~|   [optional refinements v <- Phi_y v / |Phi_y v|]
 //   step (Sec. 4.1):      u = Phi_y v, lambda_e = v^T u, g_e, a_e;  t = T^T v;  p = Phi_x t (only if gamma < 1)
+//   The small reductions in between (arg-max, size of the set, |v~|) are done by every workgroup of the pass that
+//   needs them, for itself, from vectors of M entries, so that a step is seven launches:
+//   c | v~ | u and the partial products of t | t and the scalars | p | update | squared row norms.
 //   update, one fused pass over pairs of mirrored 32x32 tiles:
 //       T'     = gamma (T + a v t^T) + (1-gamma) I                                               eq. (vT_rec)
 //       Q'     = gamma^2 (Q + a(a+2) t t^T) + (1-gamma)^2 I
@@ -54,7 +57,7 @@ inline WsLayout ws_layout(int M) {
     return L;
 }
 
-// block-wide helpers for single-workgroup kernels of 1024 threads
+// sum over the workgroup, the same value in every thread
 __device__ __forceinline__ float block_sum(float v, float* red) {
     v = wave_sum(v);
     __syncthreads();
@@ -65,15 +68,33 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
     return t;
 }
 
-// m' = argmax_m xi2[m], lowest index on ties (eq. (mt))
-__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ xi2, int M, Scal* __restrict__ sc) {
-    __shared__ float bv[16];
-    __shared__ int bi[16];
+// m' = argmax_m xi2[m], lowest index on ties (eq. (mt)), computed by a whole workgroup of 256 threads; every
+// workgroup that calls it gets the same answer
+__device__ __forceinline__ void block_argmax(const float* __restrict__ xi2, int M, float* bv, int* bi, float* best_out, int* idx_out) {
     float best = -1.f;
     int idx = 0x7fffffff;
-    for (int m = threadIdx.x; m < M; m += blockDim.x) {
-        const float v = xi2[m];
-        if (v > best) { best = v; idx = m; }   // strided ascending scan keeps the lowest index per thread
+    // ascending scan per thread with a strict comparison keeps the lowest index; four 16-byte loads in flight
+    if ((M & 3) == 0) {
+        const float4* x4 = reinterpret_cast<const float4*>(xi2);
+        const int n4 = M >> 2, nt = blockDim.x;
+        for (int k = threadIdx.x; k < n4; k += 4 * nt) {
+            float4 q[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) q[j] = (k + j * nt < n4) ? x4[k + j * nt] : make_float4(-1.f, -1.f, -1.f, -1.f);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int m = 4 * (k + j * nt);
+                if (q[j].x > best) { best = q[j].x; idx = m; }
+                if (q[j].y > best) { best = q[j].y; idx = m + 1; }
+                if (q[j].z > best) { best = q[j].z; idx = m + 2; }
+                if (q[j].w > best) { best = q[j].w; idx = m + 3; }
+            }
+        }
+    } else {
+        for (int m = threadIdx.x; m < M; m += blockDim.x) {
+            const float v = xi2[m];
+            if (v > best) { best = v; idx = m; }
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -83,80 +104,177 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
     }
     if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = idx; }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int i = 1; i < (int)(blockDim.x >> 6); ++i)
-            if (bv[i] > best || (bv[i] == best && bi[i] < idx)) { best = bv[i]; idx = bi[i]; }
-        if (idx < 0 || idx >= M) idx = 0;  // every norm was NaN: keep the index in range
-        sc->m_prime = idx;
-        sc->xi_mp = sqrtf(fmaxf(best, 0.f));
-        sc->flags = 0;
-    }
+    best = bv[0]; idx = bi[0];
+    for (int i = 1; i < (int)(blockDim.x >> 6); ++i)
+        if (bv[i] > best || (bv[i] == best && bi[i] < idx)) { best = bv[i]; idx = bi[i]; }
+    if (idx < 0 || idx >= M) idx = 0;  // every norm was NaN: keep the index in range
+    *best_out = best; *idx_out = idx;
 }
 
-// y[r] = P[r,:] . x, one wavefront per row.  x_row_from_scal: x is row sc->m_prime of P (c of eq. (vc)).
-__global__ __launch_bounds__(256) void matvec_kernel(const float* __restrict__ P, const float* __restrict__ x, const Scal* __restrict__ sc,
-                                                     int x_row_from_scal, int M, float* __restrict__ y) {
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= M) return;
-    const float* xv = x_row_from_scal ? P + (size_t)sc->m_prime * M : x;
-    const float* row = P + (size_t)r * M;
+// dot product of a row of P with x (global memory or LDS), one wavefront per row, four 16-byte loads of the row in flight
+__device__ __forceinline__ float row_dot(const float* __restrict__ row, const float* __restrict__ x, int M, int lane) {
     float acc = 0.f;
     if ((M & 3) == 0) {
         const float4* r4 = reinterpret_cast<const float4*>(row);
-        const float4* x4 = reinterpret_cast<const float4*>(xv);
-        for (int k = lane; k < (M >> 2); k += 64) {
+        const float4* x4 = reinterpret_cast<const float4*>(x);
+        const int n4 = M >> 2;
+        int k = lane;
+        for (; k + 192 < n4; k += 256) {
+            float4 a[4], b[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { a[j] = r4[k + 64 * j]; b[j] = x4[k + 64 * j]; }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc += a[j].x * b[j].x + a[j].y * b[j].y + a[j].z * b[j].z + a[j].w * b[j].w;
+        }
+        for (; k < n4; k += 64) {
             const float4 a = r4[k], b = x4[k];
             acc += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
         }
     } else {
-        for (int k = lane; k < M; k += 64) acc += row[k] * xv[k];
+        for (int k = lane; k < M; k += 64) acc += row[k] * x[k];
     }
-    acc = wave_sum(acc);
+    return wave_sum(acc);
+}
+
+// c = Phi_y (Phi_y e_m') (eq. (vc)) with the arg-max of eq. (mt) found by every workgroup for itself; four rows per
+// workgroup, one wavefront each.  Workgroup 0 records m' and xi_m'.
+__global__ __launch_bounds__(256) void matvec_c_kernel(const float* __restrict__ P, const float* __restrict__ xi2, int M,
+                                                       Scal* __restrict__ sc, float* __restrict__ c) {
+    __shared__ float bv[4];
+    __shared__ int bi[4];
+    float best; int mp;
+    block_argmax(xi2, M, bv, bi, &best, &mp);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        sc->m_prime = mp;
+        sc->xi_mp = sqrtf(fmaxf(best, 0.f));
+        sc->flags = 0;
+    }
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;
+    const float acc = row_dot(P + (size_t)r * M, P + (size_t)mp * M, M, lane);
+    if (lane == 0) c[r] = acc;
+}
+
+// y[r] = P[r,:] . x, one wavefront per row
+__global__ __launch_bounds__(256) void matvec_kernel(const float* __restrict__ P, const float* __restrict__ x, int M, float* __restrict__ y) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;
+    const float acc = row_dot(P + (size_t)r * M, x, M, lane);
     if (lane == 0) y[r] = acc;
 }
 
-// coherence set and alignment weights: w_m = 1/(|set| c_m) on the set, 0 elsewhere (rule after eq. (vc), eq. (tve))
-__global__ __launch_bounds__(1024) void build_w_kernel(const float* __restrict__ c, const float* __restrict__ xi2, int M, float c_rel,
-                                                       float c_abs, Scal* __restrict__ sc, float* __restrict__ w) {
-    __shared__ float red[16];
+// v~ = Phi_y w (first line of eq. (tve)) with the coherence set and the alignment weights w_m = 1/(|set| c_m) on the
+// set, 0 elsewhere (rule after eq. (vc)) formed on the fly: every workgroup counts the set for itself.
+__global__ __launch_bounds__(256) void matvec_vt_kernel(const float* __restrict__ P, const float* __restrict__ c,
+                                                        const float* __restrict__ xi2, int M, float c_rel, float c_abs,
+                                                        Scal* __restrict__ sc, float* __restrict__ vt) {
+    extern __shared__ __attribute__((aligned(16))) float wl[];   // M weights
+    __shared__ float red[4];
     const float xi_mp = sc->xi_mp;
+    // first pass: c_m on the set and 0 elsewhere into LDS, and the size of the set
     float cnt = 0.f;
-    for (int m = threadIdx.x; m < M; m += blockDim.x) {
-        const float thr = fmaxf(c_rel * xi_mp * sqrtf(fmaxf(xi2[m], 0.f)), c_abs);
-        cnt += (fabsf(c[m]) >= thr) ? 1.f : 0.f;
+    auto weight = [&](float cm, float x2) {
+        const float thr = fmaxf(c_rel * xi_mp * sqrtf(fmaxf(x2, 0.f)), c_abs);
+        const bool in = fabsf(cm) >= thr;
+        cnt += in ? 1.f : 0.f;
+        return in ? cm : 0.f;
+    };
+    if ((M & 3) == 0) {
+        const float4* c4 = reinterpret_cast<const float4*>(c);
+        const float4* x4 = reinterpret_cast<const float4*>(xi2);
+        float4* w4 = reinterpret_cast<float4*>(wl);
+        const int n4 = M >> 2, nt = blockDim.x;
+        for (int k = threadIdx.x; k < n4; k += 2 * nt) {
+            const bool two = k + nt < n4;
+            const float4 ca = c4[k], xa = x4[k];
+            const float4 cb = two ? c4[k + nt] : ca, xb = two ? x4[k + nt] : xa;
+            w4[k] = make_float4(weight(ca.x, xa.x), weight(ca.y, xa.y), weight(ca.z, xa.z), weight(ca.w, xa.w));
+            if (two) w4[k + nt] = make_float4(weight(cb.x, xb.x), weight(cb.y, xb.y), weight(cb.z, xb.z), weight(cb.w, xb.w));
+        }
+    } else {
+        for (int m = threadIdx.x; m < M; m += blockDim.x) wl[m] = weight(c[m], xi2[m]);
     }
-    const float total = block_sum(cnt, red);
-    for (int m = threadIdx.x; m < M; m += blockDim.x) {
-        const float thr = fmaxf(c_rel * xi_mp * sqrtf(fmaxf(xi2[m], 0.f)), c_abs);
-        const float cm = c[m];
-        w[m] = (fabsf(cm) >= thr) ? 1.f / (total * cm) : 0.f;
-    }
-    if (threadIdx.x == 0) {
+    const float total = block_sum(cnt, red);   // has the barriers that publish wl
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         sc->set_size = (int)total;
         if (total == 0.f) sc->flags |= 1;
     }
+    // second pass over LDS: w_m = 1/(|set| c_m) on the set
+    for (int m = threadIdx.x; m < M; m += blockDim.x) {
+        const float cm = wl[m];
+        wl[m] = cm != 0.f ? 1.f / (total * cm) : 0.f;
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;
+    const float acc = row_dot(P + (size_t)r * M, wl, M, lane);
+    if (lane == 0) vt[r] = acc;
 }
 
-// v = vt / |vt| (second line of eq. (tve)); an empty set gives v = 0
-__global__ __launch_bounds__(1024) void normalize_kernel(const float* __restrict__ vt, int M, Scal* __restrict__ sc, float* __restrict__ v) {
-    __shared__ float red[16];
+// |v~| by a whole workgroup (the same value in every workgroup) and the factor that normalises it (second line of
+// eq. (tve)); an empty set gives v = 0
+__device__ __forceinline__ float block_inv_norm(const float* __restrict__ vt, int M, const Scal* __restrict__ sc, float* red, float* nrm_out) {
     float ss = 0.f;
-    for (int m = threadIdx.x; m < M; m += blockDim.x) ss += vt[m] * vt[m];
+    if ((M & 3) == 0) {
+        const float4* v4 = reinterpret_cast<const float4*>(vt);
+        const int n4 = M >> 2, nt = blockDim.x;
+        for (int k = threadIdx.x; k < n4; k += 4 * nt) {
+            float4 q[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) q[j] = (k + j * nt < n4) ? v4[k + j * nt] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ss += q[j].x * q[j].x + q[j].y * q[j].y + q[j].z * q[j].z + q[j].w * q[j].w;
+        }
+    } else {
+        for (int m = threadIdx.x; m < M; m += blockDim.x) ss += vt[m] * vt[m];
+    }
     const float nrm = sqrtf(block_sum(ss, red));
-    const float inv = (nrm > 0.f && (sc->flags & 1) == 0) ? 1.f / nrm : 0.f;
-    for (int m = threadIdx.x; m < M; m += blockDim.x) v[m] = vt[m] * inv;
-    if (threadIdx.x == 0) {
+    *nrm_out = nrm;
+    return (nrm > 0.f && (sc->flags & 1) == 0) ? 1.f / nrm : 0.f;
+}
+
+// One refinement v <- Phi_y v / |Phi_y v| in unnormalised form: out = Phi_y (v~ / |v~|)
+__global__ __launch_bounds__(256) void matvec_refine_kernel(const float* __restrict__ P, const float* __restrict__ vt, int M,
+                                                            const Scal* __restrict__ sc, float* __restrict__ out) {
+    __shared__ float red[4];
+    float nrm;
+    const float inv = block_inv_norm(vt, M, sc, red, &nrm);
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;
+    const float acc = row_dot(P + (size_t)r * M, vt, M, lane) * inv;
+    if (lane == 0) out[r] = acc;
+}
+
+// v = v~/|v~|, u = Phi_y v (workgroups below nmv: four rows each) and the partial products of t = T^T v over bands of
+// vm_rows rows, tpart[band][j] = sum_{i in band} T[i][j] v[i] (the other workgroups), in one launch.
+__global__ __launch_bounds__(256) void matvec_u_vecmat_kernel(const float* __restrict__ P, const float* __restrict__ T,
+                                                              const float* __restrict__ vt, int M, int Mp, int vm_rows, int nmv,
+                                                              Scal* __restrict__ sc, float* __restrict__ v, float* __restrict__ u,
+                                                              float* __restrict__ tpart) {
+    __shared__ float red[4];
+    float nrm;
+    const float inv = block_inv_norm(vt, M, sc, red, &nrm);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         sc->vnorm = nrm;
         if (!(nrm == nrm) || nrm > 3.0e38f) sc->flags |= 4;
     }
-}
-
-// partial products of t = T^T v over blocks of VM_ROWS rows: tpart[rb][j] = sum_{i in rb} T[i][j] v[i]
-__global__ __launch_bounds__(256) void vecmat_partial_kernel(const float* __restrict__ T, const float* __restrict__ v, int M, int Mp,
-                                                             int vm_rows, float* __restrict__ tpart) {
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    const int i0 = blockIdx.y * vm_rows;
+    if ((int)blockIdx.x < nmv) {
+        const int lane = threadIdx.x & 63;
+        const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+        if (r >= M) return;
+        const float acc = row_dot(P + (size_t)r * M, vt, M, lane) * inv;
+        if (lane == 0) { u[r] = acc; v[r] = vt[r] * inv; }
+        return;
+    }
+    const int ncol = (M + 255) / 256;
+    const int b = (int)blockIdx.x - nmv;
+    const int j = (b % ncol) * 256 + threadIdx.x;
+    const int band = b / ncol;
+    const int i0 = band * vm_rows;
     const int i1 = min(M, i0 + vm_rows);
     if (j >= M) return;
     float acc = 0.f;
@@ -166,33 +284,60 @@ __global__ __launch_bounds__(256) void vecmat_partial_kernel(const float* __rest
 #pragma unroll
         for (int q = 0; q < 8; ++q) x[q] = T[(size_t)(i + q) * M + j];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) acc += x[q] * v[i + q];
+        for (int q = 0; q < 8; ++q) acc += x[q] * vt[i + q];
     }
-    for (; i < i1; ++i) acc += T[(size_t)i * M + j] * v[i];
-    tpart[(size_t)blockIdx.y * Mp + j] = acc;
+    for (; i < i1; ++i) acc += T[(size_t)i * M + j] * vt[i];
+    tpart[(size_t)band * Mp + j] = acc * inv;
 }
 
-// out[m] = sum over b < nparts of part[b][m]: 64 entries per workgroup, the parts dealt to four groups of threads in
-// a fixed order and combined through LDS (used for t = T^T v and for the squared row norms of Phi_y)
-__global__ __launch_bounds__(256) void partial_sum_kernel(const float* __restrict__ part, int nparts, int M, int Mp, float* __restrict__ out) {
-    __shared__ float red[4][64];
-    const int m = blockIdx.x * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
+// out[m] = sum over b < nparts of part[b][m]: 16 entries per workgroup, the parts dealt to sixteen groups of threads
+// (eight loads in flight each) in a fixed order and combined through LDS
+__device__ __forceinline__ void partial_sum_block(const float* __restrict__ part, int nparts, int M, int Mp, int blk, float* __restrict__ out,
+                                                  float (*red)[16]) {
+    const int e = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int m = blk * 16 + e;
     float acc = 0.f;
-    if (m < M)
-        for (int b = grp; b < nparts; b += 4) acc += part[(size_t)b * Mp + m];
-    red[grp][threadIdx.x & 63] = acc;
+    if (m < M) {
+        int b = grp;
+        for (; b + 7 * 16 < nparts; b += 8 * 16) {
+            float x[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) x[q] = part[(size_t)(b + 16 * q) * Mp + m];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc += x[q];
+        }
+        for (; b < nparts; b += 16) acc += part[(size_t)b * Mp + m];
+    }
+    red[grp][e] = acc;
     __syncthreads();
-    if (grp == 0 && m < M) out[m] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+    if (grp == 0 && m < M) {
+        float t = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) t += red[g][e];
+        out[m] = t;
+    }
 }
 
-// lambda_e = v^T u (eq. (lambda)); g_e, a_e (eqs. (ge), (xi)); guard; diagnostics
-__global__ __launch_bounds__(1024) void scalars_kernel(const float* __restrict__ v, const float* __restrict__ u, int M,
-                                                       const float* __restrict__ lambda_bar, fw_cond_params prm, Scal* __restrict__ sc,
-                                                       fw_cond_info* __restrict__ info) {
-    __shared__ float red[16];
+// squared row norms of the new Phi_y from the partial sums of the update pass
+__global__ __launch_bounds__(256) void partial_sum_kernel(const float* __restrict__ part, int nparts, int M, int Mp, float* __restrict__ out) {
+    __shared__ float red[16][16];
+    partial_sum_block(part, nparts, M, Mp, blockIdx.x, out, red);
+}
+
+// t = T^T v from its partial products (workgroups below nred), and in the last workgroup lambda_e = v^T u
+// (eq. (lambda)), g_e, a_e (eqs. (ge), (xi)), the guard and the diagnostics
+__global__ __launch_bounds__(256) void t_reduce_scalars_kernel(const float* __restrict__ tpart, int nparts, int M, int Mp, int nred,
+                                                               float* __restrict__ t, const float* __restrict__ v,
+                                                               const float* __restrict__ u, const float* __restrict__ lambda_bar,
+                                                               fw_cond_params prm, Scal* __restrict__ sc, fw_cond_info* __restrict__ info) {
+    __shared__ float red[16][16];
+    if ((int)blockIdx.x < nred) {
+        partial_sum_block(tpart, nparts, M, Mp, blockIdx.x, t, red);
+        return;
+    }
     float dot = 0.f;
     for (int m = threadIdx.x; m < M; m += blockDim.x) dot += v[m] * u[m];
-    const float lam_e = block_sum(dot, red);
+    const float lam_e = block_sum(dot, &red[0][0]);
     if (threadIdx.x == 0) {
         int flags = sc->flags;
         float g_e = 1.f, a_e = 0.f;
@@ -345,23 +490,23 @@ fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_c
     Scal* sc = reinterpret_cast<Scal*>(base + L.scal);
     const dim3 mv_grid((M + 3) / 4), mv_blk(256);
 
-    hipLaunchKernelGGL(argmax_kernel, dim3(1), dim3(1024), 0, st, s->xi2, M, sc);
-    hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, (const float*)nullptr, sc, 1, M, c);
-    hipLaunchKernelGGL(build_w_kernel, dim3(1), dim3(1024), 0, st, c, s->xi2, M, p->c_rel, p->c_abs, sc, w);
-    hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, w, sc, 0, M, vt);
-    hipLaunchKernelGGL(normalize_kernel, dim3(1), dim3(1024), 0, st, vt, M, sc, v);
+    const int nmv = (M + 3) / 4, ncol = (M + 255) / 256, nred = (M + 15) / 16;
+    hipLaunchKernelGGL(matvec_c_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, s->xi2, M, sc, c);
+    hipLaunchKernelGGL(matvec_vt_kernel, mv_grid, mv_blk, (size_t)L.Mp * sizeof(float), st, s->Phi_y, c, s->xi2, M, p->c_rel, p->c_abs, sc, vt);
+    float* cur = vt;
+    float* other = w;   // scratch vector for the optional refinements
     for (int it = 0; it < p->n_power_iters; ++it) {
-        hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, v, sc, 0, M, vt);
-        hipLaunchKernelGGL(normalize_kernel, dim3(1), dim3(1024), 0, st, vt, M, sc, v);
+        hipLaunchKernelGGL(matvec_refine_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, cur, M, sc, other);
+        float* tmp = cur; cur = other; other = tmp;
     }
-    hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, v, sc, 0, M, u);
-    hipLaunchKernelGGL(vecmat_partial_kernel, dim3((M + 255) / 256, L.nrb), dim3(256), 0, st, s->T, v, M, L.Mp, L.vm_rows, tpart);
-    hipLaunchKernelGGL(partial_sum_kernel, dim3((M + 63) / 64), dim3(256), 0, st, tpart, L.nrb, M, L.Mp, t);
-    hipLaunchKernelGGL(scalars_kernel, dim3(1), dim3(1024), 0, st, v, u, M, s->lambda_bar, *p, sc, info);
+    hipLaunchKernelGGL(matvec_u_vecmat_kernel, dim3(nmv + ncol * L.nrb), mv_blk, 0, st, s->Phi_y, s->T, cur, M, L.Mp, L.vm_rows, nmv, sc,
+                       v, u, tpart);
+    hipLaunchKernelGGL(t_reduce_scalars_kernel, dim3(nred + 1), mv_blk, 0, st, tpart, L.nrb, M, L.Mp, nred, t, v, u, s->lambda_bar, *p, sc,
+                       info);
     if (p->gamma < 1.f)
-        hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_x, t, sc, 0, M, pv);
+        hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_x, t, M, pv);
     hipLaunchKernelGGL(update_kernel, dim3(L.nt, L.nt), dim3(256), 0, st, *s, v, u, t, pv, sc, p->gamma, p->beta, L.Mp, xpart);
-    hipLaunchKernelGGL(partial_sum_kernel, dim3((M + 63) / 64), dim3(256), 0, st, xpart, L.nt, M, L.Mp, s->xi2);
+    hipLaunchKernelGGL(partial_sum_kernel, dim3(nred), dim3(256), 0, st, xpart, L.nt, M, L.Mp, s->xi2);
     FW_LAUNCH_CHECK();
     return FW_OK;
 }
