@@ -11,11 +11,16 @@
 // The same pass adds up, per padded pixel and channel, the values it packs; the column sums s are sums of those
 // per-pixel sums over the output positions of a tap, so the contraction kernel does not touch them.
 //
-// The contraction kernel cuts the lower triangle of A into 256x256 tiles.  A workgroup of 8 wavefronts (2 x 4, each
-// 128x64 = 4x2 MFMA tiles) owns one tile over a range of units.  Panels of 4 units travel from global memory
-// straight into LDS (global_load_lds_dwordx4, no register staging) into a ring of four stages laid out as
-// [unit][feature][16 B], three chunks ahead of the MFMAs; a chunk costs one s_waitcnt and one barrier, and the
-// operand fragments of every group of eight MFMAs are read from LDS while the previous group executes.
+// The contraction kernel covers the lower triangle of A with tiles of 256 rows x 64 NCT columns (NCT = 4, 3 or 2; the
+// host takes the shape and the number of unit ranges per tile that fill the 256 compute units best).  A workgroup of
+// 4 wavefronts, one per SIMD, each with 128 x 32 NCT outputs (4 x NCT MFMA tiles in accumulation registers), owns
+// one tile over a range of units.  Chunks of 4 units travel from global memory straight into LDS
+// (global_load_lds_dwordx4, no register staging; wavefront w brings unit w) into a ring of five or six stages (all of
+// the 160 KB of LDS) laid out as [unit][feature][16 B], four or five chunks ahead of the MFMAs: in flight is what
+// covers the latency of the loads, which all workgroups of an XCD see at full length because they stream through
+// the units in step.  A chunk costs one barrier; the loads of the chunk
+// after next, and the fragment reads of the next 16-entry step, are issued one by one between the MFMAs of the
+// current step, so that the matrix pipe stays busy while a single wavefront per SIMD does all the issuing.
 // With one range per tile and the feature order kept, the result is added straight into A; otherwise partial
 // tiles go to the workspace and are summed in float64 (and permuted to the caller's feature order).
 #include "fw_internal.h"
@@ -24,31 +29,51 @@
 namespace fw {
 namespace {
 
-constexpr int TB = 256;  // tile edge (features)
-constexpr int KU = 4;    // units per staged chunk (32 reduction entries)
-constexpr int NST = 4;   // stages of the LDS ring
+constexpr int TR = 256;  // tile rows (features)
+constexpr int KU = 4;    // units per staged chunk (32 reduction entries) = wavefronts of a workgroup
 
 struct TileGeom {
-    int M, nb, ntiles;
+    int M, ntiles;
+    int nct, tc, ncb, nrb;  // MFMA column tiles per wavefront, tile columns = 64 nct, column / row blocks of A
     int B, Bg, Cin, H, W, Hp, Wp, kh, kw, stride, pad, Ho, Wo;
     int layout;
-    int n_units, units_per_split, nsplit;
+    int n_units, nchunks, chunks_per_split, nsplit;
     int direct;   // one range per tile and external order == internal order: tiles are added straight into A
     int bg_chunks, bg_per_chunk;   // the pre-pass deals the image groups to this many thread groups
     int zero_off;                  // 16-byte element of P that is always zero (target of masked-off loads)
 };
+
+// column blocks of row block I that touch the lower triangle
+__host__ __device__ inline int cols_of_row(int I, int tc, int ncb) {
+    const int n = (I * TR + TR - 1) / tc + 1;
+    return n < ncb ? n : ncb;
+}
 
 typedef unsigned short u16;
 
 // ---- pre-pass: pack 8 images per 16 bytes, zero border; per-pixel sums for the column sums ----------------------
 // One thread per (chunk of image groups, padded pixel, channel); it walks its image groups, so the sum it leaves in
 // S8[chunk][yp][xp][c] has a fixed order of additions.
+// The first row of workgroups also writes the unit table: offset (in 16-byte elements) of the top-left tap of every
+// unit, -1 for the padding up to a whole number of chunks.
 __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict__ X, TileGeom g, uint4* __restrict__ P,
-                                                          float* __restrict__ S8) {
+                                                          float* __restrict__ S8, int* __restrict__ utab) {
     const int per_img = g.Hp * g.Wp * g.Cin;
     const int e = blockIdx.x * 256 + threadIdx.x;
     const int chunk = blockIdx.y;
     if (blockIdx.x == 0 && chunk == 0 && threadIdx.x < 16) P[g.zero_off + threadIdx.x] = make_uint4(0, 0, 0, 0);
+    if (chunk == 0) {
+        const int npos = g.Ho * g.Wo;
+        for (int u = e; u < g.nchunks * KU; u += gridDim.x * 256) {
+            int v = -1;
+            if (u < g.n_units) {
+                const int bg = u / npos, p = u - bg * npos;
+                const int oy = p / g.Wo, ox = p - oy * g.Wo;
+                v = ((bg * g.Hp + oy * g.stride) * g.Wp + ox * g.stride) * g.Cin;
+            }
+            utab[u] = v;
+        }
+    }
     if (e >= per_img) return;
     int c, xp, yp;
     if (g.layout == FW_LAYOUT_NCHW) {  // walk the source along x for coalescing; the packed order stays [yp][xp][c]
@@ -81,19 +106,6 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
     S8[(size_t)chunk * per_img + dst0] = acc;
 }
 
-// s[m] += sum over the output positions of the per-pixel sums under tap (ky,kx): one workgroup per feature
-__global__ __launch_bounds__(256) void column_sums_kernel(TileGeom g, const float* __restrict__ S8, float* __restrict__ s);
-
-// offset (in 16-byte elements) of the top-left tap of every unit
-__global__ __launch_bounds__(256) void unit_table_kernel(TileGeom g, int* __restrict__ utab) {
-    const int u = blockIdx.x * 256 + threadIdx.x;
-    if (u >= g.n_units) return;
-    const int P = g.Ho * g.Wo;
-    const int bg = u / P, p = u - bg * P;
-    const int oy = p / g.Wo, ox = p - oy * g.Wo;
-    utab[u] = ((bg * g.Hp + oy * g.stride) * g.Wp + ox * g.stride) * g.Cin;
-}
-
 // internal feature (tap-major, channel-minor) -> offset inside a unit, external index m = (c*kh + ky)*kw + kx
 // (or the internal index itself when the caller works in channels-last feature order)
 __device__ __forceinline__ void feat_map(int fi, const TileGeom& g, int* off, int* ext) {
@@ -103,21 +115,28 @@ __device__ __forceinline__ void feat_map(int fi, const TileGeom& g, int* off, in
     *ext = g.layout == FW_LAYOUT_NHWC_KKC ? fi : c * (g.kh * g.kw) + t;
 }
 
-struct SmemTile {
-    alignas(16) uint4 pan[NST][2][KU][TB];  // [stage][row panel / column panel][unit][feature], 128 KB
-};
+__device__ __forceinline__ void tile_coords(int tile, const TileGeom& g, int* I, int* J) {
+    int i = 0;
+    for (;;) {
+        const int n = cols_of_row(i, g.tc, g.ncb);
+        if (tile < n) break;
+        tile -= n; ++i;
+    }
+    *I = i; *J = tile;
+}
 
-// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
-#define FW_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
-// the same, and lgkmcnt(0): LDS reads of this wavefront have returned as well
-#define FW_WAIT_VM_LGKM0(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0070)
-
-__global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restrict__ P, const int* __restrict__ utab, TileGeom g,
+template <int NCT>
+__global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restrict__ P, const int* __restrict__ utab, TileGeom g,
                                                             float* __restrict__ part, float* __restrict__ A) {
-    __shared__ SmemTile sm;
+    constexpr int TC = 64 * NCT;      // tile columns
+    constexpr int NF = 4 + NCT;       // groups of 64 features per unit: 4 of the row panel, NCT of the column panel
+    constexpr int ROW = TR + TC;      // 16-byte elements per unit
+    constexpr int NM = 4 * NCT;       // MFMAs per 16-entry step and wavefront
+    constexpr int NST = 160 * 1024 / (KU * ROW * 16);   // stages of the LDS ring: all of the 160 KB (5, 5, 6)
+    __shared__ uint4 pan[NST][KU][ROW];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wi = wave >> 2, wj = wave & 3;
+    const int wi = wave >> 1, wj = wave & 1;
     const int half = lane >> 5, l32 = lane & 31;
     // Workgroups are handed to the 8 XCDs round-robin by their linear index.  Re-index so that each XCD works on a
     // contiguous run of (range, tile) pairs: neighbours in that run share the unit range and mostly the row panel, which
@@ -132,181 +151,193 @@ __global__ __launch_bounds__(512) void cov_bf16_tile_kernel(const uint4* __restr
         split = n / g.ntiles;
         tile = n - split * g.ntiles;
     }
-    int I = (int)((sqrtf(8.f * tile + 1.f) - 1.f) * 0.5f);
-    while ((I + 1) * (I + 2) / 2 <= tile) ++I;
-    while (I * (I + 1) / 2 > tile) --I;
-    const int J = tile - I * (I + 1) / 2;
-    const bool diag = I == J;
+    int I, J;
+    tile_coords(tile, g, &I, &J);
 
-    // Staging: a wavefront-wide 16-byte load fills 64 consecutive features of one unit of one panel (1 KB of LDS).
-    // Wavefront w always takes feature quarter w & 3; its loads of a chunk are (panel, unit) = (0, g2), (0, g2 + 2),
-    // (1, g2), (1, g2 + 2) with g2 = w >> 2.  Lanes whose feature lies beyond M, and units beyond the range, read
-    // the zero element instead, so every stage is completely rewritten by every chunk.
-    const int q = wave & 3, g2 = wave >> 2;
-    int off[2], ext_unused;
-    bool ok[2];
-    {
-        const int fA = I * TB + 64 * q + lane, fB = J * TB + 64 * q + lane;
-        ok[0] = fA < g.M; ok[1] = fB < g.M;
-        feat_map(ok[0] ? fA : 0, g, &off[0], &ext_unused);
-        feat_map(ok[1] ? fB : 0, g, &off[1], &ext_unused);
+    // Staging: a wavefront-wide 16-byte load fills 64 consecutive features of one unit (1 KB of LDS); wavefront w
+    // brings unit w of every chunk, NF loads.  Lanes whose feature lies beyond M, and units beyond the range, read the
+    // zero element instead, so every stage is completely rewritten by every chunk.
+    int off[NF];
+    unsigned okmask = 0;
+#pragma unroll
+    for (int k = 0; k < NF; ++k) {
+        const int f = k < 4 ? I * TR + 64 * k + lane : J * TC + 64 * (k - 4) + lane;
+        const bool ok = f < g.M;
+        int ext_unused;
+        feat_map(ok ? f : 0, g, &off[k], &ext_unused);
+        okmask |= (ok ? 1u : 0u) << k;
     }
 
-    floatx16 acc[4][2];
+    floatx16 acc[4][NCT];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NCT; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    const int u_begin = split * g.units_per_split;
-    const int u_end = min(g.n_units, u_begin + g.units_per_split);
-    const int nchunks = (u_end - u_begin + KU - 1) / KU;
-    const int npanels = diag ? 1 : 2;
+    const int c_begin = split * g.chunks_per_split;
+    const int nchunks = min(g.nchunks, c_begin + g.chunks_per_split) - c_begin;
 
-    // unit offsets of the chunk whose loads are issued next (wavefront-uniform, fetched one iteration early)
-    int nbase[2];
-    auto fetch_bases = [&](int c) {
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int uu = u_begin + c * KU + g2 + 2 * k;
-            nbase[k] = (c < nchunks && uu < u_end) ? utab[uu] : -1;
-        }
+    // offset of the unit this wavefront loads next (wavefront-uniform; -1 past the end of the range)
+    int nb = -1;
+    auto fetch_base = [&](int c) { nb = c < nchunks ? utab[(c_begin + c) * KU + wave] : -1; };
+    auto dma_one = [&](int stage, int k) {   // k is a compile-time constant after unrolling
+        const int idx = (nb >= 0 && ((okmask >> k) & 1u)) ? nb + off[k] : g.zero_off;
+        dma16(P + idx, &pan[stage][wave][64 * k]);
     };
-    auto issue = [&](int c) {
-        const int stage = c & (NST - 1);
+    auto issue = [&](int stage) {
 #pragma unroll
-        for (int pnl = 0; pnl < 2; ++pnl) {
-            if (pnl >= npanels) break;
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                const int u = g2 + 2 * k;
-                const int idx = (nbase[k] >= 0 && ok[pnl]) ? nbase[k] + off[pnl] : g.zero_off;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(P + idx),
-                                                 (__attribute__((address_space(3))) void*)(&sm.pan[stage][pnl][u][64 * q]), 16, 0, 0);
-            }
-        }
-        fetch_bases(c + 1);
+        for (int k = 0; k < NF; ++k) dma_one(stage, k);
     };
 
-    const int pj = diag ? 0 : 1;
-    // Operand fragments of k-step ks (units 2ks, 2ks+1) of chunk c; two register sets alternate so that the reads
-    // for the next group of MFMAs are always issued before the current group.
-    bf16x8 fa[2][4], fb[2][2];
-    auto read_frags = [&](int c, int ks, int set) {
-        const int stage = c & (NST - 1);
-        const int unit = 2 * ks + half;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) fa[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[stage][0][unit][128 * wi + 32 * t + l32]);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) fb[set][t] = *reinterpret_cast<const bf16x8*>(&sm.pan[stage][pj][unit][64 * wj + 32 * t + l32]);
+    // Operand fragments of 16-entry step ks (units 2ks, 2ks+1) of a stage; fragment r < 4 is row tile r, the others
+    // are the column tiles.  Two register sets alternate between the two steps of a chunk.
+    bf16x8 fr[2][NF];
+    auto read_one = [&](int stage, int ks, int set, int r) {
+        const int col = r < 4 ? 128 * wi + 32 * r : TR + 32 * NCT * wj + 32 * (r - 4);
+        fr[set][r] = *reinterpret_cast<const bf16x8*>(&pan[stage][2 * ks + half][col + l32]);
     };
-    auto mfma_group = [&](int set) {
-#pragma unroll
-        for (int ta = 0; ta < 4; ++ta)
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][ta], fb[set][tb], acc[ta][tb], 0, 0, 0);
+    auto mfma_one = [&](int set, int m) {   // m = ta * NCT + tb
+        const int ta = m / NCT, tb = m % NCT;
+        acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][ta], fr[set][4 + tb], acc[ta][tb], 0, 0, 0);
     };
-    static_assert(KU == 4 && NST == 4, "the loop below is written for two k-steps per chunk and a ring of four");
 
-    // Ring protocol.  Loads of one wavefront complete in order, so "at most the loads of two chunks outstanding" means
-    // the chunk before those two has landed for this wavefront; the barrier extends that to all wavefronts.  The
+    // Ring protocol.  Loads of one wavefront complete in order, so "at most the loads of NST-2 chunks outstanding" means
+    // the chunk before those has landed for this wavefront; the barrier extends that to all wavefronts.  The
     // barrier sits in the middle of a chunk: by then every wavefront has its last fragments of chunk c in registers
-    // (lgkmcnt 0), so the stage of chunk c is free for the loads of chunk c+4, and chunk c+1 is ready to be read while
-    // the second half of chunk c is still being multiplied.  Every iteration issues the same number of loads (past the
+    // (lgkmcnt 0), so the stage of chunk c is free for the loads of chunk c+NST, and chunk c+1 is ready to be read while
+    // the second step of chunk c is still being multiplied.  Every iteration issues the same number of loads (past the
     // end they fetch the zero element), which keeps the outstanding-load arithmetic valid in the tail.
-    // The barrier is the bare instruction: __syncthreads() would first drain every outstanding load, which is exactly
-    // what the ring is there to avoid.
-    fetch_bases(0);
-    issue(0); issue(1); issue(2);
-    if (diag) FW_WAIT_VMCNT(4); else FW_WAIT_VMCNT(8);
+#pragma unroll
+    for (int i = 0; i < NST - 1; ++i) { fetch_base(i); issue(i); }
+    fetch_base(NST - 1);
+    FW_WAIT_VM((NST - 2) * NF);
     __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    issue(3);
-    read_frags(0, 0, 0);
+    FW_COMPILER_FENCE();
+    issue(NST - 1);
+#pragma unroll
+    for (int r = 0; r < NF; ++r) read_one(0, 0, 0, r);
+    int sc = 0;   // stage of chunk c
     for (int c = 0; c < nchunks; ++c) {
-        read_frags(c, 1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_group(0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (diag) FW_WAIT_VM_LGKM0(4); else FW_WAIT_VM_LGKM0(8);
+        const int sn = sc == NST - 1 ? 0 : sc + 1;
+        fetch_base(c + NST);
+        // step 0 of chunk c; the fragment reads of step 1 go out between its first MFMAs, so that they have returned
+        // by the time the last one is issued
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            if (m < NF) read_one(sc, 1, 1, m);
+            mfma_one(0, m);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        FW_WAIT_LGKM0();
+        FW_WAIT_VM((NST - 2) * NF);
         __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        issue(c + 4);
-        read_frags(c + 1, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_group(1);
-        __builtin_amdgcn_sched_barrier(0);
+        FW_COMPILER_FENCE();
+        // step 1 of chunk c; first the fragment reads of step 0 of chunk c+1, then the loads of chunk c+NST, one
+        // between every two MFMAs
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            if (m < NF) read_one(sn, 0, 0, m);
+            else if (m - NF < NF) dma_one(sc, m - NF);
+            mfma_one(1, m);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int k = NM - NF; k < NF; ++k) dma_one(sc, k);   // loads that did not fit between the MFMAs
+        sc = sn;
     }
-    FW_WAIT_VMCNT(0);
+    FW_WAIT_VM(0);
+    FW_WAIT_LGKM0();
     __syncthreads();
 
     // ---- epilogue
     if (!g.direct) {
-        float* dst = part + ((size_t)split * g.ntiles + tile) * (TB * TB);
+        float* dst = part + ((size_t)split * g.ntiles + tile) * (TR * TC);
 #pragma unroll
         for (int ta = 0; ta < 4; ++ta)
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
+            for (int tb = 0; tb < NCT; ++tb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int row = 128 * wi + 32 * ta + 8 * (i >> 2) + 4 * half + (i & 3);
-                    const int col = 64 * wj + 32 * tb + l32;
-                    dst[row * TB + col] = acc[ta][tb][i];
+                    const int col = 32 * NCT * wj + 32 * tb + l32;
+                    dst[row * TC + col] = acc[ta][tb][i];
                 }
     } else {
-        // one range per tile, feature order kept: add into the lower triangle of A, 32 lanes along a row
+        // one range per tile, feature order kept: add into the lower triangle of A, 32 lanes along a row, the 16 loads of
+        // an MFMA tile in flight together
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            const int col = 64 * wj + 32 * tb + l32;
-            const int gj = J * TB + col;
+        for (int tb = 0; tb < NCT; ++tb) {
+            const int gj = J * TC + 32 * NCT * wj + 32 * tb + l32;
 #pragma unroll
-            for (int ta = 0; ta < 4; ++ta)
+            for (int ta = 0; ta < 4; ++ta) {
+                const int gi0 = I * TR + 128 * wi + 32 * ta + 4 * half;
+                if (gi0 + 27 < J * TC + 32 * NCT * wj + 32 * tb) continue;   // MFMA tile entirely above the diagonal
+                float old[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int row = 128 * wi + 32 * ta + 8 * (i >> 2) + 4 * half + (i & 3);
-                    const int gi = I * TB + row;
-                    if (gi >= g.M || gj >= g.M || gj > gi) continue;
-                    A[(size_t)gi * g.M + gj] += acc[ta][tb][i];
+                    const int gi = gi0 + 8 * (i >> 2) + (i & 3);
+                    old[i] = (gi < g.M && gj < g.M && gj <= gi) ? A[(size_t)gi * g.M + gj] : 0.f;
                 }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int gi = gi0 + 8 * (i >> 2) + (i & 3);
+                    if (gi < g.M && gj < g.M && gj <= gi) A[(size_t)gi * g.M + gj] = old[i] + acc[ta][tb][i];
+                }
+            }
         }
     }
 }
 
-__global__ __launch_bounds__(256) void column_sums_kernel(TileGeom g, const float* __restrict__ S8, float* __restrict__ s) {
-    __shared__ double red[4];
-    const int fi = blockIdx.x;
-    int off, ext;
-    feat_map(fi, g, &off, &ext);
+// s[m] += sum over the output positions of the per-pixel sums under the tap of feature m: 16 features per workgroup
+// of 1024 threads, 64 lanes per feature over (position, image-group chunk), four loads in flight, float64
+__global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const float* __restrict__ S8, float* __restrict__ s) {
+    __shared__ double red[64][16];
+    const int fl = threadIdx.x & 15, pl = threadIdx.x >> 4;
+    const int fi = blockIdx.x * 16 + fl;
+    const bool ok = fi < g.M;
+    int off = 0, ext = 0;
+    if (ok) feat_map(fi, g, &off, &ext);
     const int per_img = g.Hp * g.Wp * g.Cin;
     const int npos = g.Ho * g.Wo;
+    const int total = npos * g.bg_chunks;
+    auto at = [&](int idx) {
+        const int k = idx / npos, p = idx - k * npos;
+        const int oy = p / g.Wo, ox = p - oy * g.Wo;
+        return S8[(size_t)k * per_img + ((oy * g.stride) * g.Wp + ox * g.stride) * g.Cin + off];
+    };
     double v = 0.0;
-    for (int k = 0; k < g.bg_chunks; ++k)
-        for (int p = threadIdx.x; p < npos; p += 256) {
-            const int oy = p / g.Wo, ox = p - oy * g.Wo;
-            v += (double)S8[(size_t)k * per_img + ((oy * g.stride) * g.Wp + ox * g.stride) * g.Cin + off];
+    if (ok) {
+        int idx = pl;
+        for (; idx + 192 < total; idx += 256) {
+            const float x0 = at(idx), x1 = at(idx + 64), x2 = at(idx + 128), x3 = at(idx + 192);
+            v += ((double)x0 + (double)x1) + ((double)x2 + (double)x3);
         }
-    v = wave_sum(v);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+        for (; idx < total; idx += 64) v += (double)at(idx);
+    }
+    red[pl][fl] = v;
     __syncthreads();
-    if (threadIdx.x == 0) s[ext] = (float)((double)s[ext] + red[0] + red[1] + red[2] + red[3]);
+    if (pl == 0 && ok) {
+        double t = 0.0;
+#pragma unroll 8
+        for (int q = 0; q < 64; ++q) t += red[q][fl];
+        s[ext] = (float)((double)s[ext] + t);
+    }
 }
 
 // partial tiles -> A (float64 sum over the ranges), one thread per tile element
 __global__ __launch_bounds__(256) void tile_reduce_kernel(TileGeom g, const float* __restrict__ part, float* __restrict__ A) {
-    const int tile = blockIdx.x >> 8;            // 256 blocks of 256 threads per tile
-    const int e = ((blockIdx.x & 255) << 8) + threadIdx.x;
-    int I = (int)((sqrtf(8.f * tile + 1.f) - 1.f) * 0.5f);
-    while ((I + 1) * (I + 2) / 2 <= tile) ++I;
-    while (I * (I + 1) / 2 > tile) --I;
-    const int J = tile - I * (I + 1) / 2;
-    const int row = e >> 8, col = e & 255;
-    const int fi = I * TB + row, fj = J * TB + col;
-    if (fi >= g.M || fj >= g.M || (I == J && row < col)) return;
-    const size_t stride = (size_t)g.ntiles * TB * TB;
-    const float* src = part + (size_t)tile * (TB * TB) + e;
+    const int tile = blockIdx.x / g.tc;            // tc blocks of 256 threads per tile of 256 x tc
+    const int e = (blockIdx.x - tile * g.tc) * 256 + threadIdx.x;
+    int I, J;
+    tile_coords(tile, g, &I, &J);
+    const int row = e / g.tc, col = e - row * g.tc;
+    const int fi = I * TR + row, fj = J * g.tc + col;
+    if (fi >= g.M || fj >= g.M || fj > fi) return;
+    const size_t tsz = (size_t)TR * g.tc;
+    const size_t stride = (size_t)g.ntiles * tsz;
+    const float* src = part + (size_t)tile * tsz + e;
     double v = 0.0;
     for (int sp = 0; sp < g.nsplit; ++sp) v += (double)src[sp * stride];
     int o, ei, ej;
@@ -327,28 +358,41 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     const long long M = (long long)d->Cin * d->kh * d->kw;
     const long long n_units = (long long)g->Bg * g->Ho * g->Wo;
     const long long packed = (long long)g->Bg * g->Hp * g->Wp * d->Cin;
-    if (M <= 0 || M > 16384 || n_units <= 0 || n_units >= (1ll << 31) || packed + 16 >= (1ll << 31)) return false;
+    if (M <= 0 || M > 16384 || n_units <= 0 || n_units >= (1ll << 31) - KU || packed + 16 >= (1ll << 31)) return false;
     if ((long long)d->B * d->Cin * d->H * d->W >= (1ll << 31)) return false;
-    g->M = (int)M; g->nb = (int)((M + TB - 1) / TB); g->ntiles = g->nb * (g->nb + 1) / 2;
+    g->M = (int)M;
     g->n_units = (int)n_units;
-    // Number of unit ranges per tile: minimise  rounds x units per range x t_unit  +  traffic of the partial tiles,
-    // with rounds = ceil(tiles x ranges / 256 compute units); one range means no partial tiles at all.
-    const double t_unit = 0.15e-6, bw = 4.0e12;
-    const long long nchunks = (n_units + KU - 1) / KU;
-    double best = 1e30;
-    int best_ns = 1;
-    for (int ns = 1; ns <= 512 && ns <= nchunks; ++ns) {
-        const long long wgs = (long long)g->ntiles * ns;
-        const long long rounds = (wgs + 255) / 256;
-        const long long cps = (nchunks + ns - 1) / ns;
-        double cost = (double)rounds * (double)cps * KU * t_unit;
-        if (ns > 1) cost += (double)wgs * TB * TB * 4.0 * 2.0 / bw;
-        if (cost < best * 0.999) { best = cost; best_ns = ns; }
+    g->nchunks = (int)((n_units + KU - 1) / KU);
+    g->nrb = (int)((M + TR - 1) / TR);
+    const bool ident = lay == FW_LAYOUT_NHWC_KKC || lay == FW_LAYOUT_ROWS || d->kh * d->kw == 1;
+    // Tile shape (256 x 64 nct) and number of unit ranges per tile: minimise
+    //   rounds x chunks per range x time of a chunk  +  traffic of the partial tiles,
+    // with rounds = ceil(tiles x ranges / 256 compute units).  A chunk costs the larger of its MFMAs (2 steps x 4 nct
+    // x 32 cycles, plus a share for the barrier) and its loads into LDS, which a compute unit sustains at about 23 bytes
+    // per cycle next to the fragment reads; one range per tile in the caller's feature order needs no partial tiles.
+    const double clk = 2.0e9, bw = 4.0e12, lds_load_rate = 23.0;
+    double best = 1e300;
+    int best_nct = 4, best_ns = 1;
+    for (int nct = 4; nct >= 2; --nct) {
+        const int tc = 64 * nct, ncb = (int)((M + tc - 1) / tc);
+        long long ntiles = 0;
+        for (int I = 0; I < g->nrb; ++I) ntiles += cols_of_row(I, tc, ncb);
+        const double t_mfma = 256.0 * nct + 150.0, t_load = (double)(TR + tc) * KU * 16.0 / lds_load_rate;
+        const double t_chunk = (t_mfma > t_load ? t_mfma : t_load) / clk;
+        for (int ns = 1; ns <= 512 && ns <= g->nchunks; ++ns) {
+            const long long wgs = ntiles * ns;
+            const long long rounds = (wgs + 255) / 256;
+            const long long cps = (g->nchunks + ns - 1) / ns;
+            double cost = (double)rounds * (double)cps * t_chunk;
+            if (ns > 1 || !ident) cost += (double)wgs * TR * tc * 4.0 * 2.0 / bw;
+            if (cost < best * 0.999) { best = cost; best_nct = nct; best_ns = ns; }
+        }
     }
-    if (best_ns > nchunks) best_ns = (int)nchunks;
-    const long long cps = (nchunks + best_ns - 1) / best_ns;
-    g->units_per_split = (int)(cps * KU);
-    g->nsplit = (int)((n_units + g->units_per_split - 1) / g->units_per_split);
+    g->nct = best_nct; g->tc = 64 * best_nct; g->ncb = (int)((M + g->tc - 1) / g->tc);
+    g->ntiles = 0;
+    for (int I = 0; I < g->nrb; ++I) g->ntiles += cols_of_row(I, g->tc, g->ncb);
+    g->chunks_per_split = (g->nchunks + best_ns - 1) / best_ns;
+    g->nsplit = (g->nchunks + g->chunks_per_split - 1) / g->chunks_per_split;
     // the pre-pass wants about half a million threads: split the image groups when one image gives fewer
     {
         const long long per_img = (long long)g->Hp * g->Wp * d->Cin;
@@ -359,7 +403,6 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
         g->bg_chunks = (g->Bg + g->bg_per_chunk - 1) / g->bg_per_chunk;
         g->zero_off = (int)packed;
     }
-    const bool ident = lay == FW_LAYOUT_NHWC_KKC || lay == FW_LAYOUT_ROWS || d->kh * d->kw == 1;
     g->direct = (g->nsplit == 1 && ident) ? 1 : 0;
     return true;
 }
@@ -370,8 +413,8 @@ Bf16Ws ws_layout(const TileGeom& g) {
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
     L.packed = take(((size_t)g.Bg * g.Hp * g.Wp * g.Cin + 16) * 16);
-    L.utab = take((size_t)g.n_units * 4);
-    L.part = take(g.direct ? 0 : (size_t)g.nsplit * g.ntiles * TB * TB * 4);
+    L.utab = take((size_t)g.nchunks * KU * 4);
+    L.part = take(g.direct ? 0 : (size_t)g.nsplit * g.ntiles * TR * g.tc * 4);
     L.s8 = take((size_t)g.bg_chunks * g.Hp * g.Wp * g.Cin * 4);
     L.total = o;
     return L;
@@ -398,14 +441,15 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     float* S8 = reinterpret_cast<float*>(base + L.s8);
     const int per_img = g.Hp * g.Wp * g.Cin;
     hipLaunchKernelGGL(pack_images_kernel, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st, reinterpret_cast<const u16*>(X),
-                       g, P, S8);
-    hipLaunchKernelGGL(unit_table_kernel, dim3((g.n_units + 255) / 256), dim3(256), 0, st, g, utab);
+                       g, P, S8, utab);
     FW_LAUNCH_CHECK();
-    const int per_xcd = (g.ntiles * g.nsplit + 7) / 8;
-    hipLaunchKernelGGL(cov_bf16_tile_kernel, dim3(per_xcd * 8), dim3(512), 0, st, P, utab, g, part, A);
+    const dim3 grid((g.ntiles * g.nsplit + 7) / 8 * 8);
+    if (g.nct == 4) hipLaunchKernelGGL(cov_bf16_tile_kernel<4>, grid, dim3(256), 0, st, P, utab, g, part, A);
+    else if (g.nct == 3) hipLaunchKernelGGL(cov_bf16_tile_kernel<3>, grid, dim3(256), 0, st, P, utab, g, part, A);
+    else hipLaunchKernelGGL(cov_bf16_tile_kernel<2>, grid, dim3(256), 0, st, P, utab, g, part, A);
     FW_LAUNCH_CHECK();
-    if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * 256), dim3(256), 0, st, g, part, A);
-    hipLaunchKernelGGL(column_sums_kernel, dim3(g.M), dim3(256), 0, st, g, S8, s);
+    if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * g.tc), dim3(256), 0, st, g, part, A);
+    hipLaunchKernelGGL(column_sums_kernel, dim3((g.M + 15) / 16), dim3(1024), 0, st, g, S8, s);
     FW_LAUNCH_CHECK();
     return FW_OK;
 }

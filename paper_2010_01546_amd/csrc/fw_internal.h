@@ -48,6 +48,23 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
+// ---- direct global-to-LDS loads with hand-counted completion
+// s_waitcnt vmcnt(n), the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+#define FW_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+// s_waitcnt lgkmcnt(0): the LDS reads (and scalar loads) of this wavefront have returned
+#define FW_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+// keeps the compiler from moving memory accesses across this point (no instruction)
+#define FW_COMPILER_FENCE() asm volatile("" ::: "memory")
+
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds_base + 16 l (lds_base is
+// wavefront-uniform and travels in M0).  Written as assembly so that the compiler does not track it as a pending LDS
+// store (it would then wait for ALL outstanding loads before every LDS read): completion is awaited by hand with
+// FW_WAIT_VM, counting these loads in issue order, followed by a workgroup barrier.
+__device__ __forceinline__ void dma16(const void* src, void* lds_dst) {
+    const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds_dst;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
+}
+
 // ---- cov.hip
 size_t cov_workspace_bytes(int M, const fw_conv_desc* d, fw_dtype dt, fw_layout lay);
 fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d, float* A, float* s,

@@ -68,22 +68,6 @@ struct StripCfg {
     static __device__ __forceinline__ int swz(int r) { return QR == 8 ? (r >> 1) & 7 : r & 15; }
 };
 
-// s_waitcnt vmcnt(n), the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
-#define FW_GEMM_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
-// s_waitcnt lgkmcnt(0): the LDS reads of this wavefront have returned
-#define FW_GEMM_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
-// keeps the compiler from moving memory accesses across this point (no instruction)
-#define FW_COMPILER_FENCE() asm volatile("" ::: "memory")
-
-// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds_base + 16 l (lds_base is
-// wavefront-uniform and travels in M0).  Written as assembly so that the compiler does not track it as a pending LDS
-// store (it would wait for ALL outstanding loads before every LDS read): completion is awaited by hand with
-// FW_GEMM_WAIT_VM, counting these loads in issue order, followed by a workgroup barrier.
-__device__ __forceinline__ void dma16(const float* src, float* lds_dst) {
-    const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds_dst;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
-}
-
 template <int MF, int C>
 __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* __restrict__ G, const float* __restrict__ Q,
                                                                   float* __restrict__ Out, int S, int M) {
@@ -150,9 +134,9 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
         issue(0, 0);
         if (nfull > 1) issue(1, 1);
         if (K::NST > 2 && nfull > 2) issue(2, 2);
-        if (K::NST > 2 && nfull > 2) FW_GEMM_WAIT_VM(2 * K::IPW);
-        else if (nfull > 1) FW_GEMM_WAIT_VM(K::IPW);
-        else FW_GEMM_WAIT_VM(0);
+        if (K::NST > 2 && nfull > 2) FW_WAIT_VM(2 * K::IPW);
+        else if (nfull > 1) FW_WAIT_VM(K::IPW);
+        else FW_WAIT_VM(0);
         __builtin_amdgcn_s_barrier();
         FW_COMPILER_FENCE();
         read_frags(0, fr[0]);
@@ -166,12 +150,12 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
         auto iteration = [&](int c, const float4* cur, float4* nxt, auto STEADY) {
             constexpr bool steady = decltype(STEADY)::value;   // c + NST < nfull known: no branches around the MFMAs
             const int sn = sc == K::NST - 1 ? 0 : sc + 1;
-            FW_GEMM_WAIT_LGKM0();
+            FW_WAIT_LGKM0();
 #pragma unroll
             for (int t = 0; t < H; ++t) mfma_one(cur, t);
             __builtin_amdgcn_sched_barrier(0);
-            if (K::NST > 2 && (steady || c + 2 < nfull)) FW_GEMM_WAIT_VM(K::IPW);
-            else FW_GEMM_WAIT_VM(0);
+            if (K::NST > 2 && (steady || c + 2 < nfull)) FW_WAIT_VM(K::IPW);
+            else FW_WAIT_VM(0);
             __builtin_amdgcn_s_barrier();
             FW_COMPILER_FENCE();
 #pragma unroll
