@@ -493,53 +493,77 @@ bool make_geom(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, CovGeom* g) {
     return true;
 }
 
-// mu and phi_x are updated in place AFTER finalize_phi_kernel has consumed the old mean.
-__global__ void finalize_mu_kernel(const float* __restrict__ A, const float* __restrict__ s, double inv_n, int M, float alpha,
-                                   int first, float* __restrict__ mu, float* __restrict__ phi) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= M) return;
-    const double mh = (double)s[i] * inv_n;
-    const double raw = (double)A[(size_t)i * M + i] * inv_n;
-    double m, p;
-    if (first) { m = mh; p = raw; }
-    else {
-        m = (double)alpha * (double)mu[i] + (1.0 - (double)alpha) * mh;
-        p = (double)alpha * (double)phi[i] + (1.0 - (double)alpha) * raw;
+// mu, phi_x (updated in place AFTER finalize_phi_kernel has consumed the old mean) and lambda_bar = mean(phi_x): one
+// workgroup
+__global__ __launch_bounds__(1024) void finalize_vec_kernel(const float* __restrict__ A, const float* __restrict__ s, double inv_n, int M,
+                                                            float alpha, int first, float* __restrict__ mu, float* __restrict__ phi,
+                                                            float* __restrict__ lambda_bar) {
+    __shared__ double red[16];
+    double sum = 0.0;
+    for (int i = threadIdx.x; i < M; i += 1024) {
+        const double mh = (double)s[i] * inv_n;
+        const double raw = (double)A[(size_t)i * M + i] * inv_n;
+        double m, p;
+        if (first) { m = mh; p = raw; }
+        else {
+            m = (double)alpha * (double)mu[i] + (1.0 - (double)alpha) * mh;
+            p = (double)alpha * (double)phi[i] + (1.0 - (double)alpha) * raw;
+        }
+        const float pf = (float)p;
+        mu[i] = (float)m;
+        phi[i] = pf;
+        sum += (double)pf;
     }
-    mu[i] = (float)m;
-    phi[i] = (float)p;
-}
-
-// one workgroup: lambda_bar = mean(phi)
-__global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ phi, int M, float* __restrict__ out) {
-    __shared__ double red[4];
-    double v = 0.0;
-    for (int i = threadIdx.x; i < M; i += 256) v += (double)phi[i];
-    v = wave_sum(v);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    sum = wave_sum(sum);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
     __syncthreads();
-    if (threadIdx.x == 0) *out = (float)((red[0] + red[1] + red[2] + red[3]) / (double)M);
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int w = 0; w < 16; ++w) t += red[w];
+        *lambda_bar = (float)(t / (double)M);
+    }
 }
 
 // Covariance centred on the updated mean, expanded into the raw sums (float64 per element):
 //   C_ij = A_ij/n - mhat_i mu_j - mu_i mhat_j + mu_i mu_j,  mhat = s/n,  mu = alpha*mu_old + (1-alpha)*mhat.
-// 16x16 threads cover a tile with i >= j; each thread writes (i,j) and its mirror.
+// A workgroup takes a 32x32 tile (I, J) of the lower triangle: rows of 32 lanes read A and the old Phi_x and write the
+// new values; the mirrored tile (J, I) is written from a transposed copy in LDS, again along rows.
 __global__ __launch_bounds__(256) void finalize_phi_kernel(const float* __restrict__ A, const float* __restrict__ s,
                                                            const float* __restrict__ mu_old, double inv_n, int M, float alpha,
                                                            int first, float* __restrict__ Phi) {
-    const int i = blockIdx.y * 16 + threadIdx.y, j = blockIdx.x * 16 + threadIdx.x;
-    if (blockIdx.x > blockIdx.y || i >= M || j >= M || j > i) return;
-    const double mhi = (double)s[i] * inv_n, mhj = (double)s[j] * inv_n;
-    double mi = mhi, mj = mhj;
-    if (!first) {
-        mi = (double)alpha * (double)mu_old[i] + (1.0 - (double)alpha) * mhi;
-        mj = (double)alpha * (double)mu_old[j] + (1.0 - (double)alpha) * mhj;
+    const int I = blockIdx.y, J = blockIdx.x;
+    if (J > I) return;
+    __shared__ float tr[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int j = J * 32 + tx;
+    double mhj = 0.0, mj = 0.0;
+    if (j < M) {
+        mhj = (double)s[j] * inv_n;
+        mj = first ? mhj : (double)alpha * (double)mu_old[j] + (1.0 - (double)alpha) * mhj;
     }
-    double c = (double)A[(size_t)i * M + j] * inv_n - mhi * mj - mi * mhj + mi * mj;
-    if (!first) c = (double)alpha * (double)Phi[(size_t)i * M + j] + (1.0 - (double)alpha) * c;
-    const float o = (float)c;
-    Phi[(size_t)i * M + j] = o;
-    Phi[(size_t)j * M + i] = o;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int yy = ty + 8 * r;
+        const int i = I * 32 + yy;
+        float o = 0.f;
+        if (i < M && j < M && j <= i) {
+            const double mhi = (double)s[i] * inv_n;
+            const double mi = first ? mhi : (double)alpha * (double)mu_old[i] + (1.0 - (double)alpha) * mhi;
+            double c = (double)A[(size_t)i * M + j] * inv_n - mhi * mj - mi * mhj + mi * mj;
+            if (!first) c = (double)alpha * (double)Phi[(size_t)i * M + j] + (1.0 - (double)alpha) * c;
+            o = (float)c;
+            Phi[(size_t)i * M + j] = o;
+        }
+        tr[yy][tx] = o;
+    }
+    __syncthreads();
+    // mirror: element (J*32 + yy, I*32 + tx) = tile element (tx, yy); on a diagonal tile only the part above the diagonal
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int yy = ty + 8 * r;
+        const int mi_row = J * 32 + yy, mj_col = I * 32 + tx;
+        if (mi_row < M && mj_col < M && mj_col > mi_row) Phi[(size_t)mi_row * M + mj_col] = tr[tx][yy];
+    }
 }
 
 __global__ __launch_bounds__(256) void mirror_lower_kernel(float* __restrict__ A, int M) {
@@ -598,12 +622,10 @@ fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_con
 fw_status cov_finalize(const float* A, const float* s, long long n, int M, float alpha, int first_block, float* mu, float* Phi_x,
                        float* phi_x, float* lambda_bar, hipStream_t st) {
     const double inv_n = 1.0 / (double)n;
-    const int tb = (M + 15) / 16;
-    hipLaunchKernelGGL(finalize_phi_kernel, dim3(tb, tb), dim3(16, 16), 0, st, A, s, mu, inv_n, M, alpha, first_block, Phi_x);
+    const int tb = (M + 31) / 32;
+    hipLaunchKernelGGL(finalize_phi_kernel, dim3(tb, tb), dim3(256), 0, st, A, s, mu, inv_n, M, alpha, first_block, Phi_x);
     FW_LAUNCH_CHECK();
-    hipLaunchKernelGGL(finalize_mu_kernel, dim3((M + 255) / 256), dim3(256), 0, st, A, s, inv_n, M, alpha, first_block, mu, phi_x);
-    FW_LAUNCH_CHECK();
-    hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st, phi_x, M, lambda_bar);
+    hipLaunchKernelGGL(finalize_vec_kernel, dim3(1), dim3(1024), 0, st, A, s, inv_n, M, alpha, first_block, mu, phi_x, lambda_bar);
     FW_LAUNCH_CHECK();
     return FW_OK;
 }
