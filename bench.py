@@ -30,8 +30,8 @@ HBM_PEAK = 8.0e12
 # counter scaled by what it reads on a 256 MiB device copy (2 KiB per FETCH_SIZE count, 1 KiB per WRITE_SIZE count).
 # Measured with the default layout (kkc); other layouts report null.
 MEASURED_TRAFFIC = {"c2": {"read": 79.5e6, "written": 48.0e6},
-                    "c3": {"read": 186.9e6, "written": 105.4e6},
-                    "c4": {"read": 229.6e6, "written": 65.8e6}}
+                    "c3": {"read": 174.4e6, "written": 112.9e6},
+                    "c4": {"read": 217.8e6, "written": 65.6e6}}
 
 
 def parse():
