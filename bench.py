@@ -39,7 +39,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"],
+                    help="c2 is the headline workload; c5 sweeps the 21 ResNet-18 layers and reports the aggregate")
+    ap.add_argument("--evd", action="store_true", help="also time one fw_whiten_evd call (outside the headline)")
     ap.add_argument("--layout", default="kkc", choices=["kkc", "nhwc", "nchw"],
                     help="kkc: NHWC tensor with channels-last feature order (ky,kx,c); nhwc/nchw: feature order (c,ky,kx)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -49,20 +51,9 @@ def parse():
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
-
-    import workloads as wl
-    from paper_2010_01546_amd import binding as b
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
+def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False):
+    """One whitened layer: K timed steps of the whole hot path plus a per-export breakdown.  Returns a dict of timings."""
     dev = "cuda:0"
-    layer = {"c1": wl.config1, "c2": wl.config2, "c3": wl.config3, "c4": wl.config4}[args.config]()
     d = layer.desc
     M, S, n_rows = d.M, layer.S, d.n_rows
     bf16 = layer.dtype == "bf16"
@@ -72,10 +63,10 @@ def main():
         lay = b.FW_LAYOUT_ROWS
         X = torch.as_tensor(layer.act).to(dev).to(tdt).contiguous()
     else:
-        lay = {"kkc": b.FW_LAYOUT_NHWC_KKC, "nhwc": b.FW_LAYOUT_NHWC, "nchw": b.FW_LAYOUT_NCHW}[args.layout]
+        lay = {"kkc": b.FW_LAYOUT_NHWC_KKC, "nhwc": b.FW_LAYOUT_NHWC, "nchw": b.FW_LAYOUT_NCHW}[layout_name]
         X = torch.as_tensor(wl.to_layout(layer.act, lay)).to(dev).to(tdt).contiguous()
     desc = b.conv_desc(*d.astuple())
-    G = torch.as_tensor(layer.G).to(dev)          # float32 gradient (configs 3-5 cast inside a bf16 variant; fp32 here)
+    G = torch.as_tensor(layer.G).to(dev)          # float32 gradient
     Gout = torch.empty_like(G)
 
     A = torch.zeros(M, M, device=dev); s = torch.zeros(M, device=dev)
@@ -107,17 +98,17 @@ def main():
         b.fw_cond_reduce_step(st, prm, info, ws_cond)
         b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     t0 = time.perf_counter()
-    for k in range(args.steps):
+    for k in range(steps):
         step(events[k])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    cov_ms = sum(e0.elapsed_time(e1) for e0, e1 in events) / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    cov_ms = sum(e0.elapsed_time(e1) for e0, e1 in events) / steps
     assert torch.isfinite(Gout).all() and torch.isfinite(T).all()
 
     # separate, untimed-for-the-headline breakdown of the other exports
@@ -129,17 +120,72 @@ def main():
             fn()
         e1.record(); torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
-    cond_ms = time_call(lambda: b.fw_cond_reduce_step(st, prm, info, ws_cond))
-    grad_ms = time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout))
-    fin_ms = time_call(lambda: b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar))
+    out = {"M": M, "S": S, "n_rows": n_rows, "bf16": bf16, "ms_per_step": ms_per_step, "cov_ms": cov_ms,
+           "cond_ms": time_call(lambda: b.fw_cond_reduce_step(st, prm, info, ws_cond)),
+           "grad_ms": time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)),
+           "fin_ms": time_call(lambda: b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar)),
+           "gamma": prm.gamma, "act_bytes": float(X.numel() * X.element_size())}
+    if evd:   # the EVD / ZCA reference construction replaces the recursive step; timed once, outside the headline
+        ws_evd = torch.empty(b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, M), dtype=torch.uint8, device=dev)
+        lam = torch.empty(M, device=dev)
+        b.fw_whiten_evd(Phi, M, b.evd_params(), T, Q, None, lam, ws_evd); torch.cuda.synchronize()
+        te = time.perf_counter()
+        b.fw_whiten_evd(Phi, M, b.evd_params(), T, Q, None, lam, ws_evd); torch.cuda.synchronize()
+        out["evd_ms"] = (time.perf_counter() - te) * 1e3
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import workloads as wl
+    from paper_2010_01546_amd import binding as b
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    if args.config == "c5":
+        # ResNet-18 sweep: one whitened update of every layer per batch; aggregate = layers x steps / total time
+        rows, total_ms = [], 0.0
+        for index in range(len(wl.RESNET18_LAYERS)):
+            layer = wl.config5_layer(index)
+            r = time_layer(layer, args.layout, args.steps, args.warmup, torch, b, wl)
+            total_ms += r["ms_per_step"]
+            flops = float(r["n_rows"]) * r["M"] * (r["M"] + 1)
+            rows.append({"layer": layer.name, "M": r["M"], "S": r["S"], "n_rows": r["n_rows"], "ms_per_step": round(r["ms_per_step"], 4),
+                         "cov_ms": round(r["cov_ms"], 4), "cov_frac_of_bf16_peak": round(flops / (r["cov_ms"] * 1e-3) / PEAK["bf16"], 4),
+                         "cond_ms": round(r["cond_ms"], 4), "grad_ms": round(r["grad_ms"], 4)})
+            del layer
+        cov_flops = sum(float(x["n_rows"]) * x["M"] * (x["M"] + 1) for x in rows)
+        cov_s = sum(x["cov_ms"] for x in rows) * 1e-3
+        out = {"metric": "whitened grad-updates/s per layer", "value": len(rows) * 1e3 / total_ms, "unit": "updates/s",
+               "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total_ms,
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": "C5: ResNet-18 sweep, 21 layers at batch 256, one update of every layer per step",
+                          "block_length": 1, "cond_params": "gamma=0.99 beta=0.1 delta=0.25 (paper defaults)"},
+               "roofline": {"bound": "mfma", "kernel": "fw_cov_accumulate over the 21 layers", "achieved": cov_flops / cov_s / 1e12,
+                            "peak": PEAK["bf16"] / 1e12, "unit": "TFLOP/s", "frac": cov_flops / cov_s / PEAK["bf16"], "traffic": None},
+               "layers": rows}
+        print(json.dumps(out))
+        return
+
+    layer = {"c1": wl.config1, "c2": wl.config2, "c3": wl.config3, "c4": wl.config4}[args.config]()
+    d = layer.desc
+    r = time_layer(layer, args.layout, args.steps, args.warmup, torch, b, wl, evd=args.evd)
+    M, S, n_rows, bf16 = r["M"], r["S"], r["n_rows"], r["bf16"]
+    ms_per_step, cov_ms, cond_ms, grad_ms, fin_ms = r["ms_per_step"], r["cov_ms"], r["cond_ms"], r["grad_ms"], r["fin_ms"]
 
     cov_flops = float(n_rows) * M * (M + 1)                 # lower triangle incl. diagonal, 2 flops per product
     achieved = cov_flops / (cov_ms * 1e-3)
     peak = PEAK[layer.dtype]
     tr = MEASURED_TRAFFIC.get(args.config) if (layer.is_rows or args.layout == "kkc") else None
     traffic = tr["read"] + tr["written"] if tr else None
-    alg_bytes = float(X.numel() * X.element_size() + 4 * M * M)   # activation once + A once
-    cond_words = 16 if prm.gamma < 1.0 else 10
+    alg_bytes = r["act_bytes"] + 4.0 * M * M   # activation once + A once
+    cond_words = 16 if r["gamma"] < 1.0 else 10
     cond_bytes = cond_words * M * M * 4.0
     out = {
         "metric": "whitened grad-updates/s per layer",
@@ -161,6 +207,10 @@ def main():
         "cond_step_GBps": cond_bytes / (cond_ms * 1e-3) / 1e9,
         "grad_transform_TFLOPs": 2.0 * S * M * M / (grad_ms * 1e-3) / 1e12,
     }
+    if "evd_ms" in r:
+        out["breakdown_ms"]["whiten_evd"] = r["evd_ms"]
+    alpha = 0.1
+    dev = "cuda:0"
 
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, device=dev)      # 256 MiB read + 256 MiB written per copy
