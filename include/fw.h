@@ -106,9 +106,13 @@ fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, fl
  *   Q      in   [M, M] float32, symmetric (Q or its smoothed version Q_s, eq. (vQs)); may be NULL if T is given
  *   T      in   [M, M] float32 or NULL.  Used only when Q is NULL: Q = T^T T is then built in the workspace first.
  *   G_out  out  [S, M] element type `dt`; must not overlap G
- *   ws     scratch, fw_workspace_bytes(FW_OP_GRAD_TRANSFORM, M, S, NULL, dt) bytes (only needed when Q is NULL)
- * dt = FW_F32: float32 matrix-core products.  dt = FW_BF16: Q is rounded to bfloat16 on the fly, products are
- * bf16 x bf16 accumulated in float32, G_out is rounded to bfloat16 (nearest even).
+ *   ws     scratch, fw_workspace_bytes(FW_OP_GRAD_TRANSFORM, M, S, NULL, dt) bytes; required when Q is NULL,
+ *               optional (but several times faster) for dt = FW_BF16 with Q given
+ * dt = FW_F32: float32 matrix-core products.
+ * dt = FW_BF16 with the workspace: G is widened to float32 in the workspace, the products are float32 on the matrix
+ *   cores with Q as it is, G_out is rounded to bfloat16 (nearest even).
+ * dt = FW_BF16 without it: Q is rounded to bfloat16 on the fly, products are bf16 x bf16 accumulated in float32,
+ *   G_out is rounded to bfloat16.  Q must be symmetric in every mode (its rows are read as its columns).
  */
 fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const float* T, const float* Q,
                             void* G_out, void* ws, size_t ws_bytes, void* stream);

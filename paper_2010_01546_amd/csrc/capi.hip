@@ -23,6 +23,9 @@ size_t grad_ws_bytes(int M) {
            cov_workspace_bytes(M, &d, FW_F32, FW_LAYOUT_ROWS);
 }
 
+// bfloat16 gradients: two [S, M] float32 copies behind the area of the Q build
+size_t grad_wide_bytes(int S, int M) { return 2 * align_up((size_t)S * M * sizeof(float), 256); }
+
 }  // namespace
 
 extern "C" {
@@ -70,6 +73,11 @@ fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const floa
         rc = symmetrize_from_lower(Qb, M, st);
         if (rc != FW_OK) return rc;
         Q = Qb;
+    }
+    if (dt == FW_BF16 && ws && ws_bytes >= grad_ws_bytes(M) + grad_wide_bytes(S, M)) {
+        float* G32 = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + grad_ws_bytes(M));
+        float* O32 = reinterpret_cast<float*>(reinterpret_cast<char*>(G32) + grad_wide_bytes(S, M) / 2);
+        return grad_gemm_bf16_widened(G, S, M, Q, G_out, G32, O32, st);
     }
     return grad_gemm(G, dt, S, M, Q, G_out, st);
 }
@@ -121,7 +129,9 @@ size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtyp
             if (!desc_ok(d, rows ? FW_LAYOUT_ROWS : FW_LAYOUT_NHWC)) return 0;
             return cov_workspace_bytes(M, d, dt, FW_LAYOUT_NHWC);
         }
-        case FW_OP_GRAD_TRANSFORM: return M > 0 && M <= 16384 ? grad_ws_bytes(M) : 0;
+        case FW_OP_GRAD_TRANSFORM:
+            if (M <= 0 || M > 16384) return 0;
+            return grad_ws_bytes(M) + ((dt == FW_BF16 && S > 0) ? grad_wide_bytes(S, M) : 0);
         case FW_OP_COND_REDUCE_STEP: return M > 0 && M <= 16384 ? cond_workspace_bytes(M) : 0;
         case FW_OP_WHITEN_EVD: return M > 0 && M <= 16384 ? evd_workspace_bytes(M) : 0;
     }

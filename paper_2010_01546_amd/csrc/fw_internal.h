@@ -81,6 +81,7 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
 
 // ---- gemm.hip
 fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st);
+fw_status grad_gemm_bf16_widened(const void* G, int S, int M, const float* Q, void* G_out, float* G32, float* O32, hipStream_t st);
 
 // ---- cond.hip
 size_t cond_workspace_bytes(int M);

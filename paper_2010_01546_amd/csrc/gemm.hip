@@ -365,6 +365,39 @@ __global__ __launch_bounds__(256) void grad_gemm_bf16_kernel(const unsigned shor
         }
 }
 
+// bfloat16 <-> float32 copies of G and G_out for the widened path of the bfloat16 gradient transform
+__global__ __launch_bounds__(256) void widen_bf16_kernel(const unsigned short* __restrict__ src, float* __restrict__ dst, size_t n) {
+    for (size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8; e < n; e += (size_t)gridDim.x * 256 * 8) {
+        if (e + 8 <= n) {
+            const uint4 v = *reinterpret_cast<const uint4*>(src + e);
+            float4 lo, hi;
+            lo.x = __uint_as_float(v.x << 16); lo.y = __uint_as_float(v.x & 0xffff0000u);
+            lo.z = __uint_as_float(v.y << 16); lo.w = __uint_as_float(v.y & 0xffff0000u);
+            hi.x = __uint_as_float(v.z << 16); hi.y = __uint_as_float(v.z & 0xffff0000u);
+            hi.z = __uint_as_float(v.w << 16); hi.w = __uint_as_float(v.w & 0xffff0000u);
+            *reinterpret_cast<float4*>(dst + e) = lo;
+            *reinterpret_cast<float4*>(dst + e + 4) = hi;
+        } else {
+            for (size_t k = e; k < n; ++k) dst[k] = bf16_to_f32(src[k]);
+        }
+    }
+}
+__global__ __launch_bounds__(256) void narrow_bf16_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst, size_t n) {
+    for (size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8; e < n; e += (size_t)gridDim.x * 256 * 8) {
+        if (e + 8 <= n) {
+            const float4 lo = *reinterpret_cast<const float4*>(src + e), hi = *reinterpret_cast<const float4*>(src + e + 4);
+            uint4 v;
+            v.x = (unsigned)f32_to_bf16_rne(lo.x) | ((unsigned)f32_to_bf16_rne(lo.y) << 16);
+            v.y = (unsigned)f32_to_bf16_rne(lo.z) | ((unsigned)f32_to_bf16_rne(lo.w) << 16);
+            v.z = (unsigned)f32_to_bf16_rne(hi.x) | ((unsigned)f32_to_bf16_rne(hi.y) << 16);
+            v.w = (unsigned)f32_to_bf16_rne(hi.z) | ((unsigned)f32_to_bf16_rne(hi.w) << 16);
+            *reinterpret_cast<uint4*>(dst + e) = v;
+        } else {
+            for (size_t k = e; k < n; ++k) dst[k] = f32_to_bf16_rne(src[k]);
+        }
+    }
+}
+
 }  // namespace
 
 fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st) {
@@ -380,6 +413,22 @@ fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, vo
         if (ch.mf == 32) launch_strip<32>(ch.c, reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M, st);
         else launch_strip<16>(ch.c, reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M, st);
     }
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
+// G (bfloat16) widened to float32, multiplied by Q in float32 on the matrix cores, rounded back to bfloat16:
+// G32 and O32 are [S, M] float32 scratch.  S*M is a multiple of 8 elements apart from a scalar tail.
+fw_status grad_gemm_bf16_widened(const void* G, int S, int M, const float* Q, void* G_out, float* G32, float* O32, hipStream_t st) {
+    const size_t n = (size_t)S * M;
+    size_t blocks = (n / 8 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(widen_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<const unsigned short*>(G), G32, n);
+    FW_LAUNCH_CHECK();
+    const fw_status rc = grad_gemm(G32, FW_F32, S, M, Q, O32, st);
+    if (rc != FW_OK) return rc;
+    hipLaunchKernelGGL(narrow_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, O32, reinterpret_cast<unsigned short*>(G_out), n);
     FW_LAUNCH_CHECK();
     return FW_OK;
 }

@@ -49,6 +49,8 @@ def test_workspace_sizes():
     assert b.fw_workspace_bytes(b.FW_OP_COND_REDUCE_STEP, 4608) > 7 * 4608 * 4
     assert b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, 64) >= 2 * 64 * 64 * 8
     assert b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, 64, 32) >= 64 * 64 * 4
+    assert (b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, 64, 32, None, b.FW_BF16)
+            >= b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, 64, 32) + 2 * 32 * 64 * 4)
     assert b.fw_workspace_bytes(b.FW_OP_COND_REDUCE_STEP, 0) == 0
     assert b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, 1 << 20) == 0
 

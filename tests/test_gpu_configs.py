@@ -68,6 +68,10 @@ def full_config_check(layer, layouts, n_forced, n_free, evd, prm_kw=None):
         b.fw_grad_transform(dev(Gb, torch.bfloat16), b.FW_BF16, S, M, None, Qs, outb)
         torch.cuda.synchronize()
         assert relF(outb.float().cpu().numpy(), ora.grad_transform(Gb, Qs.cpu().numpy())) < 2e-2
+        wsb = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S, None, b.FW_BF16))
+        b.fw_grad_transform(dev(Gb, torch.bfloat16), b.FW_BF16, S, M, None, Qs, outb, wsb)
+        torch.cuda.synchronize()
+        assert relF(outb.float().cpu().numpy(), ora.grad_transform(Gb, Qs.cpu().numpy())) < 3e-3
 
     if evd:
         Tt = torch.empty(M, M, device=DEV); Qt = torch.empty(M, M, device=DEV); lam = torch.empty(M, device=DEV)

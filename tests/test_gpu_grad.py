@@ -29,7 +29,7 @@ def test_f32_with_Q(S, M):
     assert relF(out.cpu().numpy(), want) < 1e-5
 
 
-@pytest.mark.parametrize("S,M", [(32, 64), (5, 7), (64, 576), (70, 200), (130, 147)])
+@pytest.mark.parametrize("S,M", [(32, 64), (5, 7), (64, 576), (70, 200), (130, 147), (33, 260)])
 def test_bf16_with_Q(S, M):
     T32, Q64 = sym_Q(M, M + 1)
     Q32 = Q64.astype(np.float32)
@@ -42,6 +42,14 @@ def test_bf16_with_Q(S, M):
     # against the same computation with Q rounded to bf16 the only error left is accumulation order and output rounding
     want_r = ora.grad_transform(G, wl.round_to_bf16(Q32))
     assert relF(out.float().cpu().numpy(), want_r) < 4e-3
+    # with the workspace G is widened and Q is used as it is: only the rounding of the output is left
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S, None, b.FW_BF16))
+    out2 = torch.zeros(S, M, device=DEV, dtype=torch.bfloat16)
+    b.fw_grad_transform(dev(G, torch.bfloat16), b.FW_BF16, S, M, None, dev(Q32), out2, ws)
+    torch.cuda.synchronize()
+    assert relF(out2.float().cpu().numpy(), want) < 3e-3
+    assert np.array_equal(out2.float().cpu().numpy(), wl.round_to_bf16(ora.grad_transform(G, Q32).astype(np.float32))) or \
+        relF(out2.float().cpu().numpy(), wl.round_to_bf16(ora.grad_transform(G, Q32).astype(np.float32))) < 1e-3
 
 
 @pytest.mark.parametrize("S,M", [(8, 64), (33, 150), (64, 576)])
