@@ -81,6 +81,13 @@ def test_several_tiles_and_single_range(B, Cin, HW, dtype, layout):
     check_layer(wl.small_conv(B + Cin, B, Cin, HW, HW, 3, 1, 1, 8, dtype=dtype), layout)
 
 
+@pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NHWC_KKC])
+@pytest.mark.parametrize("B,Cin,HW,dtype", [(8, 1024, 4, "bf16"), (4, 1024, 3, "f32")])
+def test_large_feature_count(B, Cin, HW, dtype, layout):
+    """M = 9216 features (more than half of the limit of 16384): dozens of tile rows, few patch rows."""
+    check_layer(wl.small_conv(41, B, Cin, HW, HW, 3, 1, 1, 8, dtype=dtype), layout)
+
+
 def test_config1_covariance():
     check_layer(wl.config1(), b.FW_LAYOUT_ROWS)
 

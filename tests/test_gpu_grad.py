@@ -68,6 +68,29 @@ def test_f32_from_nonsymmetric_T(S, M):
     assert relF(out.cpu().numpy(), wrong) > 1e-3
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_large_feature_count(dtype):
+    """M = 9216: Q = I + u u^T keeps the float64 reference cheap."""
+    S, M = 24, 9216
+    r = np.random.default_rng(9)
+    u = (r.standard_normal(M) / np.sqrt(M)).astype(np.float32)
+    Q32 = (np.eye(M, dtype=np.float32) + np.outer(u, u)).astype(np.float32)
+    Q32 = np.maximum(Q32, Q32.T)   # exactly symmetric
+    G = (r.standard_normal((S, M)) * 0.1).astype(np.float32)
+    want = ora.grad_transform(wl.round_to_bf16(G) if dtype == "bf16" else G, Q32)
+    if dtype == "f32":
+        out = torch.zeros(S, M, device=DEV)
+        b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, dev(Q32), out)
+        torch.cuda.synchronize()
+        assert relF(out.cpu().numpy(), want) < 1e-5
+    else:
+        ws = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S, None, b.FW_BF16))
+        out = torch.zeros(S, M, device=DEV, dtype=torch.bfloat16)
+        b.fw_grad_transform(dev(wl.round_to_bf16(G), torch.bfloat16), b.FW_BF16, S, M, None, dev(Q32), out, ws)
+        torch.cuda.synchronize()
+        assert relF(out.float().cpu().numpy(), want) < 3e-3
+
+
 def test_config1_gradient_with_identity_is_copy():
     L = wl.config1()
     S, M = L.G.shape
