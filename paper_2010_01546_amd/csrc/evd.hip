@@ -1,19 +1,28 @@
 // EVD / ZCA whitening matrix (Sec. 2, eqs. (vPhix_evd), (vT_EVD), (vg); Sec. 3.2, eqs. (hMs), (g_mod)) for gfx950.
 //
 // Phi_x is symmetric positive semi-definite, so a one-sided Jacobi iteration on its rows yields the decomposition:
-// plane rotations J are applied to the rows of W (initially Phi_x) and of V (initially I) until the rows of W are
-// mutually orthogonal; then W = Lambda V, the rows of V are the eigenvectors and lambda_k = w_k . v_k.
-// A round of the round-robin schedule rotates M/2 disjoint row pairs, one workgroup per pair; rotations are
-// independent inside a round.  All of it runs in float64 inside the workspace so that small eigenvalues, which
-// carry the largest gains, keep their relative accuracy.  T = V^T diag(sqrt g) V and Q = V^T diag(g) V are then
-// symmetric rank-M updates of row-scaled copies of V and reuse the float32 matrix-core covariance kernel.
+// orthogonal transformations are applied to the rows of W (initially Phi_x) and of V (initially I) until the rows of
+// W are mutually orthogonal; then W = Lambda V, the rows of V are the eigenvectors and lambda_k = w_k . v_k.
+// The iteration is blocked: rows are cut into blocks of 32, a round of the round-robin schedule takes disjoint pairs
+// of blocks, and for every pair (64 rows) three kernels run: the 64x64 Gram matrix of the rows (partial sums over
+// column slices), its diagonalisation by a cyclic two-sided Jacobi iteration in LDS, which yields the 64x64 rotation
+// that makes the 64 rows orthogonal to each other, and the application of that rotation to the rows of W and V.
+// A round therefore streams W and V once for 64 rows per pair instead of once per single row pair.  All of it runs
+// in float64 inside the workspace so that small eigenvalues, which carry the largest gains, keep their relative
+// accuracy.  T = V^T diag(sqrt g) V and Q = V^T diag(g) V are then symmetric rank-M updates of row-scaled copies of V
+// and reuse the float32 matrix-core covariance kernel.
 #include "fw_internal.h"
 
 namespace fw {
 namespace {
 
+constexpr int JB = 32;        // rows per block
+constexpr int JP = 2 * JB;    // rows per pair of blocks
+constexpr int JSW = 512;      // columns per slice of the Gram kernel
+
 struct EvdWs {
-    size_t W, V, lam, gq, gh, cnt, X, dummy_s, cov, total;
+    size_t W, V, lam, gq, gh, cnt, X, dummy_s, cov, gpart, rot, flags, total;
+    int nblk, nblk_even, npairs, nslices;
 };
 inline size_t cov_ws_for(int M) {
     fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0};
@@ -32,6 +41,13 @@ inline EvdWs evd_layout(int M) {
     L.X = take((size_t)M * M * sizeof(float));
     L.dummy_s = take((size_t)M * sizeof(float));
     L.cov = take(cov_ws_for(M));
+    L.nblk = (M + JB - 1) / JB;
+    L.nblk_even = (L.nblk + 1) & ~1;
+    L.npairs = L.nblk_even / 2;
+    L.nslices = (M + JSW - 1) / JSW;
+    L.gpart = take((size_t)L.npairs * L.nslices * JP * JP * sizeof(double));
+    L.rot = take((size_t)L.npairs * JP * JP * sizeof(double));
+    L.flags = take((size_t)L.npairs * sizeof(int));
     L.total = o;
     return L;
 }
@@ -61,38 +77,205 @@ __device__ __forceinline__ void rr_pair(int n, int r, int k, int* a, int* b) {
     else { *a = (r + k) % m; *b = (r - k + m) % m; }
 }
 
-__global__ __launch_bounds__(256) void jacobi_round_kernel(double* __restrict__ W, double* __restrict__ V, int M, int n_even, int round,
-                                                           double tol, int* __restrict__ counter) {
-    __shared__ double red[4];
+// global row of member k (0..63) of the block pair (p, q); -1 if it does not exist
+__device__ __forceinline__ int pair_row(int p, int q, int nblk, int M, int k) {
+    const int blk = k < JB ? p : q;
+    const int r = blk * JB + (k & (JB - 1));
+    return (blk < nblk && r < M) ? r : -1;
+}
+
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+// Partial Gram matrices: Gpart[pair][slice] = R_slice R_slice^T for the 64 rows R of the pair restricted to a slice of
+// JSW columns, on v_mfma_f64_16x16x4_f64 (operand lane l: row l % 16, contraction entry l / 16; result register v of
+// lane l: row 4 v + l / 16, column l % 16).  Chunks of 32 columns are staged in LDS; the four wavefronts take
+// different 4-column steps of a chunk and each of them updates the ten 16x16 tiles of the lower triangle, both
+// operands of a tile being fragments of the same staged rows; the four partial results are summed through LDS in
+// wavefront order.
+__global__ __launch_bounds__(256) void gram_kernel(const double* __restrict__ W, int M, int nblk, int nblk_even, int round, int nslices,
+                                                   double* __restrict__ Gpart) {
+    __shared__ double Xs[JP][33];
+    __shared__ double red[40][64];
     int a, b;
-    rr_pair(n_even, round, blockIdx.x, &a, &b);
+    rr_pair(nblk_even, round, blockIdx.y, &a, &b);
     const int p = min(a, b), q = max(a, b);
-    if (q >= M) return;  // pair with the padding player
-    double* wp = W + (size_t)p * M;
-    double* wq = W + (size_t)q * M;
-    double al = 0.0, be = 0.0, ga = 0.0;
-    for (int j = threadIdx.x; j < M; j += 256) {
-        const double x = wp[j], y = wq[j];
-        al += x * x; be += y * y; ga += x * y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lr = lane & 15, lq = lane >> 4;
+    doublex4 acc[10];
+#pragma unroll
+    for (int t = 0; t < 10; ++t) acc[t] = doublex4{0.0, 0.0, 0.0, 0.0};
+    const int c_begin = blockIdx.x * JSW, c_end = min(M, c_begin + JSW);
+    for (int c0 = c_begin; c0 < c_end; c0 += 32) {
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            const int idx = threadIdx.x + 256 * m;
+            const int r = idx >> 5, cc = idx & 31;
+            const int gr = pair_row(p, q, nblk, M, r);
+            Xs[r][cc] = (gr >= 0 && c0 + cc < c_end) ? W[(size_t)gr * M + c0 + cc] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int ks = wave + 4 * h;
+            double f[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) f[t] = Xs[16 * t + lr][4 * ks + lq];
+            int n = 0;
+#pragma unroll
+            for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+                for (int tb = 0; tb <= ta; ++tb, ++n) acc[n] = __builtin_amdgcn_mfma_f64_16x16x4f64(f[ta], f[tb], acc[n], 0, 0, 0);
+        }
+        __syncthreads();
     }
-    al = block_sum256(al, red);
-    be = block_sum256(be, red);
-    ga = block_sum256(ga, red);
-    if (!(fabs(ga) > tol * sqrt(al * be)) || ga == 0.0) return;
-    const double zeta = (be - al) / (2.0 * ga);
-    const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-    const double c = 1.0 / sqrt(1.0 + tt * tt), s = c * tt;
-    double* vp = V + (size_t)p * M;
-    double* vq = V + (size_t)q * M;
-    for (int j = threadIdx.x; j < M; j += 256) {
-        const double x = wp[j], y = wq[j];
-        wp[j] = c * x - s * y;
-        wq[j] = s * x + c * y;
-        const double e = vp[j], f = vq[j];
-        vp[j] = c * e - s * f;
-        vq[j] = s * e + c * f;
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int t = 0; t < 10; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    double* slot = &red[t * 4 + v][lane];
+                    *slot = w == 0 ? acc[t][v] : *slot + acc[t][v];
+                }
+        }
+        __syncthreads();
     }
-    if (threadIdx.x == 0) atomicAdd(counter, 1);
+    double* dst = Gpart + ((size_t)blockIdx.y * nslices + blockIdx.x) * (JP * JP);
+    for (int e = threadIdx.x; e < 40 * 64; e += 256) {
+        const int tv = e >> 6, l = e & 63;
+        const int t = tv >> 2, v = tv & 3;
+        int ta = 0, base = 0;
+        while (base + ta + 1 <= t) { base += ta + 1; ++ta; }   // tile t = ta (ta + 1) / 2 + tb
+        const int tb = t - base;
+        const int i = 16 * ta + 4 * v + (l >> 4), j = 16 * tb + (l & 15);
+        const double g = red[tv][l];
+        dst[i * JP + j] = g;
+        dst[j * JP + i] = g;
+    }
+}
+
+// Diagonalisation of the 64x64 Gram matrix of a pair: cyclic Jacobi with 32 disjoint index pairs per step (8 threads
+// per index pair).  The accumulated rotation R (new rows = R old rows, R G R^T diagonal) goes to Rot[pair];
+// flags[pair] = 1 if any rotation was applied, and the counter gets the number applied in the first inner sweep.
+__global__ __launch_bounds__(256) void pair_evd_kernel(const double* __restrict__ Gpart, int nslices, double tol, int inner_sweeps,
+                                                       double* __restrict__ Rot,
+                                                       int* __restrict__ flags, int* __restrict__ counter) {
+    __shared__ double Gs[JP][JP + 1], Rs[JP][JP + 1];
+    __shared__ double cs[JB], sn[JB];
+    __shared__ int n_rot, n_first;
+    const int tid = threadIdx.x;
+    const int kk = tid >> 3, sub = tid & 7;
+    for (int e = tid; e < JP * JP; e += 256) {
+        const double* src = Gpart + (size_t)blockIdx.x * nslices * (JP * JP) + e;
+        double g = 0.0;
+        for (int sl = 0; sl < nslices; ++sl) g += src[(size_t)sl * (JP * JP)];
+        Gs[e >> 6][e & 63] = g;
+        Rs[e >> 6][e & 63] = (e >> 6) == (e & 63) ? 1.0 : 0.0;
+    }
+    if (tid == 0) { n_rot = 0; n_first = 0; }
+    __syncthreads();
+    int total = 0;
+    for (int sweep = 0; sweep < inner_sweeps; ++sweep) {
+        for (int step = 0; step < JP - 1; ++step) {
+            int i, j;
+            rr_pair(JP, step, kk, &i, &j);
+            if (i > j) { const int t = i; i = j; j = t; }
+            if (sub == 0) {
+                const double al = Gs[i][i], be = Gs[j][j], ga = Gs[i][j];
+                double c = 1.0, s = 0.0;
+                if (fabs(ga) > tol * sqrt(fabs(al * be)) && ga != 0.0) {
+                    const double zeta = (be - al) / (2.0 * ga);
+                    const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+                    c = 1.0 / sqrt(1.0 + tt * tt);
+                    s = c * tt;
+                    atomicAdd(&n_rot, 1);
+                }
+                cs[kk] = c; sn[kk] = s;
+            }
+            __syncthreads();
+            const double c = cs[kk], s = sn[kk];
+            if (s != 0.0) {   // rows i, j of G and of R
+#pragma unroll
+                for (int m = 0; m < 8; ++m) {
+                    const int col = sub + 8 * m;
+                    const double x = Gs[i][col], y = Gs[j][col];
+                    Gs[i][col] = c * x - s * y; Gs[j][col] = s * x + c * y;
+                    const double e = Rs[i][col], f = Rs[j][col];
+                    Rs[i][col] = c * e - s * f; Rs[j][col] = s * e + c * f;
+                }
+            }
+            __syncthreads();
+            if (s != 0.0) {   // columns i, j of G
+#pragma unroll
+                for (int m = 0; m < 8; ++m) {
+                    const int row = sub + 8 * m;
+                    const double x = Gs[row][i], y = Gs[row][j];
+                    Gs[row][i] = c * x - s * y; Gs[row][j] = s * x + c * y;
+                }
+            }
+            __syncthreads();
+        }
+        const int r = n_rot;      // every thread reads the same value: the last barrier of the step loop has passed
+        __syncthreads();
+        if (tid == 0) { if (sweep == 0) n_first = r; n_rot = 0; }
+        __syncthreads();
+        total += r;
+        if (r == 0) break;
+    }
+    if (total > 0)
+        for (int e = tid; e < JP * JP; e += 256) Rot[(size_t)blockIdx.x * (JP * JP) + e] = Rs[e >> 6][e & 63];
+    if (tid == 0) {
+        flags[blockIdx.x] = total > 0 ? 1 : 0;
+        if (n_first > 0) atomicAdd(counter, n_first);
+    }
+}
+
+// rows of the pair <- R rows, for W (blockIdx.z = 0) and V (1), on v_mfma_f64_16x16x4_f64: a wavefront keeps all
+// fragments of R in registers and takes groups of 16 columns; the 64 x 16 block of a group is read into registers
+// before any of it is written back.
+__global__ __launch_bounds__(256) void rotate_rows_kernel(double* __restrict__ W, double* __restrict__ V, int M, int nblk, int nblk_even,
+                                                          int round, const double* __restrict__ Rot, const int* __restrict__ flags) {
+    __shared__ double Rs[JP][JP + 1];
+    if (flags[blockIdx.y] == 0) return;
+    int a, b;
+    rr_pair(nblk_even, round, blockIdx.y, &a, &b);
+    const int p = min(a, b), q = max(a, b);
+    for (int e = threadIdx.x; e < JP * JP; e += 256) Rs[e >> 6][e & 63] = Rot[(size_t)blockIdx.y * (JP * JP) + e];
+    __syncthreads();
+    double* Mat = blockIdx.z == 0 ? W : V;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lr = lane & 15, lq = lane >> 4;
+    double ra[4][16];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks) ra[t][ks] = Rs[16 * t + lr][4 * ks + lq];
+    int rowk[16];   // global rows of this lane's contraction entries 4 ks + lq
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) rowk[ks] = pair_row(p, q, nblk, M, 4 * ks + lq);
+    for (int gi = 0; gi < 4; ++gi) {
+        const int col0 = blockIdx.x * 256 + (wave * 4 + gi) * 16;
+        if (col0 >= M) break;
+        const int col = col0 + lr;
+        const bool cok = col < M;
+        double xb[16];
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks) xb[ks] = (rowk[ks] >= 0 && cok) ? Mat[(size_t)rowk[ks] * M + col] : 0.0;
+        doublex4 acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = doublex4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(ra[t][ks], xb[ks], acc[t], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int gr = pair_row(p, q, nblk, M, 16 * t + 4 * v + lq);
+                if (gr >= 0 && cok) Mat[(size_t)gr * M + col] = acc[t][v];
+            }
+    }
 }
 
 __global__ void zero_int_kernel(int* p) { *p = 0; }
@@ -208,12 +391,20 @@ fw_status whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float* T
 
     hipLaunchKernelGGL(evd_init_kernel, dim3(grid_for(n)), dim3(256), 0, st, Phi_x, M, W, V);
     FW_LAUNCH_CHECK();
-    const int n_even = (M + 1) & ~1;
-    bool converged = M == 1;
+    double* Gpart = reinterpret_cast<double*>(base + L.gpart);
+    double* Rot = reinterpret_cast<double*>(base + L.rot);
+    int* flags = reinterpret_cast<int*>(base + L.flags);
+    const int ncolblk = (M + 255) / 256;
+    const int inner = 1;   // inner sweeps per visit of a pair: one was the fastest overall (more inner sweeps, fewer outer ones)
+    bool converged = false;
     for (int sweep = 0; sweep < max_sweeps && !converged; ++sweep) {
         hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, cnt);
-        for (int r = 0; r < n_even - 1; ++r)
-            hipLaunchKernelGGL(jacobi_round_kernel, dim3(n_even / 2), dim3(256), 0, st, W, V, M, n_even, r, tol, cnt);
+        for (int r = 0; r < L.nblk_even - 1; ++r) {
+            hipLaunchKernelGGL(gram_kernel, dim3(L.nslices, L.npairs), dim3(256), 0, st, W, M, L.nblk, L.nblk_even, r, L.nslices, Gpart);
+            hipLaunchKernelGGL(pair_evd_kernel, dim3(L.npairs), dim3(256), 0, st, Gpart, L.nslices, tol, inner, Rot, flags, cnt);
+            hipLaunchKernelGGL(rotate_rows_kernel, dim3(ncolblk, L.npairs, 2), dim3(256), 0, st, W, V, M, L.nblk, L.nblk_even, r, Rot,
+                               flags);
+        }
         FW_LAUNCH_CHECK();
         int rotations = -1;
         FW_HIP_TRY(hipMemcpyAsync(&rotations, cnt, sizeof(int), hipMemcpyDeviceToHost, st));
