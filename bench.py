@@ -124,7 +124,7 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False):
            "cond_ms": time_call(lambda: b.fw_cond_reduce_step(st, prm, info, ws_cond)),
            "grad_ms": time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)),
            "fin_ms": time_call(lambda: b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar)),
-           "gamma": prm.gamma, "act_bytes": float(X.numel() * X.element_size())}
+           "gamma": prm.gamma, "act_bytes": float(X.numel() * X.element_size()), "step": step}
     if evd:   # the EVD / ZCA reference construction replaces the recursive step; timed once, outside the headline
         ws_evd = torch.empty(b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, M), dtype=torch.uint8, device=dev)
         lam = torch.empty(M, device=dev)
@@ -150,22 +150,41 @@ def main():
 
     if args.config == "c5":
         # ResNet-18 sweep: one whitened update of every layer per batch; aggregate = layers x steps / total time
-        rows, total_ms = [], 0.0
+        rows, total_ms, step_fns = [], 0.0, []
         for index in range(len(wl.RESNET18_LAYERS)):
             layer = wl.config5_layer(index)
             r = time_layer(layer, args.layout, args.steps, args.warmup, torch, b, wl)
             total_ms += r["ms_per_step"]
+            step_fns.append(r["step"])   # keeps the layer's device state alive for the concurrent pass below
             flops = float(r["n_rows"]) * r["M"] * (r["M"] + 1)
             rows.append({"layer": layer.name, "M": r["M"], "S": r["S"], "n_rows": r["n_rows"], "ms_per_step": round(r["ms_per_step"], 4),
                          "cov_ms": round(r["cov_ms"], 4), "cov_frac_of_bf16_peak": round(flops / (r["cov_ms"] * 1e-3) / PEAK["bf16"], 4),
                          "cond_ms": round(r["cond_ms"], 4), "grad_ms": round(r["grad_ms"], 4)})
             del layer
+        # The layers are independent: the same updates issued round-robin on four streams (default priority), so that
+        # the launch- and latency-bound small layers run under the large ones.
+        streams = [torch.cuda.Stream() for _ in range(4)]
+
+        def sweep():
+            for i, fn in enumerate(step_fns):
+                with torch.cuda.stream(streams[i % 4]):
+                    fn()
+        for _ in range(args.warmup):
+            sweep()
+        torch.cuda.synchronize()
+        tc0 = time.perf_counter()
+        for _ in range(args.steps):
+            sweep()
+        torch.cuda.synchronize()
+        conc_ms = (time.perf_counter() - tc0) * 1e3 / args.steps
         cov_flops = sum(float(x["n_rows"]) * x["M"] * (x["M"] + 1) for x in rows)
         cov_s = sum(x["cov_ms"] for x in rows) * 1e-3
-        out = {"metric": "whitened grad-updates/s per layer", "value": len(rows) * 1e3 / total_ms, "unit": "updates/s",
-               "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total_ms,
+        out = {"metric": "whitened grad-updates/s per layer", "value": len(rows) * 1e3 / conc_ms, "unit": "updates/s",
+               "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": conc_ms,
+               "ms_per_step_one_layer_at_a_time": total_ms,
                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
                "config": {"workload": "C5: ResNet-18 sweep, 21 layers at batch 256, one update of every layer per step",
+                          "streams": 4,
                           "block_length": 1, "cond_params": "gamma=0.99 beta=0.1 delta=0.25 (paper defaults)"},
                "roofline": {"bound": "mfma", "kernel": "fw_cov_accumulate over the 21 layers", "achieved": cov_flops / cov_s / 1e12,
                             "peak": PEAK["bf16"] / 1e12, "unit": "TFLOP/s", "frac": cov_flops / cov_s / PEAK["bf16"], "traffic": None},
