@@ -120,14 +120,17 @@ fw_status fw_whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float
 }
 
 size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtype dt) {
-    (void)S;
     switch (op) {
         case FW_OP_COV_ACCUMULATE: {
             if (!d || !dtype_ok(dt)) return 0;
-            // the layout does not change the size: rows and tensors of one geometry split alike
+            // the call has no layout argument: the largest need over the tensor layouts (rows split like a 1x1 tensor)
             const bool rows = d->H == 1 && d->W == 1 && d->kh == 1 && d->kw == 1;
             if (!desc_ok(d, rows ? FW_LAYOUT_ROWS : FW_LAYOUT_NHWC)) return 0;
-            return cov_workspace_bytes(M, d, dt, FW_LAYOUT_NHWC);
+            size_t need = cov_workspace_bytes(M, d, dt, FW_LAYOUT_NHWC);
+            const size_t n1 = cov_workspace_bytes(M, d, dt, FW_LAYOUT_NCHW), n2 = cov_workspace_bytes(M, d, dt, FW_LAYOUT_NHWC_KKC);
+            if (n1 > need) need = n1;
+            if (n2 > need) need = n2;
+            return need;
         }
         case FW_OP_GRAD_TRANSFORM:
             if (M <= 0 || M > 16384) return 0;

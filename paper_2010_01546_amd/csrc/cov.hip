@@ -572,6 +572,26 @@ __global__ __launch_bounds__(256) void mirror_lower_kernel(float* __restrict__ A
     A[(size_t)j * M + i] = A[(size_t)i * M + j];
 }
 
+// [B][C][HW] -> [B][HW][C] through 32x32 LDS tiles: float32 activations in NCHW order are brought into the
+// channels-last order that the fast accumulation kernel reads with 16-byte loads
+__global__ __launch_bounds__(256) void nchw_to_nhwc_kernel(const float* __restrict__ src, float* __restrict__ dst, int C, int HW) {
+    __shared__ float t[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const size_t img = (size_t)blockIdx.z * C * HW;
+    const int p0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int c = c0 + ty + 8 * r, p = p0 + tx;
+        t[ty + 8 * r][tx] = (c < C && p < HW) ? src[img + (size_t)c * HW + p] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int p = p0 + ty + 8 * r, c = c0 + tx;
+        if (p < HW && c < C) dst[img + (size_t)p * C + c] = t[tx][ty + 8 * r];
+    }
+}
+
 __global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ p, size_t n, float v) {
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256) p[e] = v;
 }
@@ -587,25 +607,45 @@ fw_status fill_f32(float* p, size_t n, float v, hipStream_t st) {
     return FW_OK;
 }
 
+// float32 NCHW input with Cin % 4 == 0 is transposed into the workspace and then treated as NHWC (the feature order
+// m = (c*kh + ky)*kw + kx is the same for both tensor layouts)
+static bool nchw_through_copy(const fw_conv_desc* d, fw_dtype dt, fw_layout lay) {
+    return dt == FW_F32 && lay == FW_LAYOUT_NCHW && (d->Cin % 4) == 0 && d->B <= 65535;
+}
+static size_t act_copy_bytes(const fw_conv_desc* d) { return align_up((size_t)d->B * d->Cin * d->H * d->W * sizeof(float), 256); }
+
 size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_layout lay) {
     if (dt == FW_BF16) return cov_bf16_workspace_bytes(d, lay);
+    if (!d) return 0;
+    const bool copy = nchw_through_copy(d, dt, lay);
     CovGeom g;
-    if (!d || !make_geom(d, dt, lay, &g)) return 0;
+    if (!make_geom(d, dt, copy ? FW_LAYOUT_NHWC : lay, &g)) return 0;
     const size_t part = (size_t)g.nsplit * g.nitems * 4 * BLK * BLK * sizeof(float);
     const size_t sp = (size_t)g.nsplit * g.nb * BLK * sizeof(float);
-    return align_up(part, 256) + align_up(sp, 256);
+    return align_up(part, 256) + align_up(sp, 256) + (copy ? act_copy_bytes(d) : 0);
 }
 
 fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,
                          size_t ws_bytes, hipStream_t st) {
     if (dt == FW_BF16) return cov_bf16_accumulate(X, lay, d, A, s, ws, ws_bytes, st);
+    const bool copy = nchw_through_copy(d, dt, lay);
+    if (copy) lay = FW_LAYOUT_NHWC;
     CovGeom g;
     if (!make_geom(d, dt, lay, &g)) return FW_ERR_UNSUPPORTED;
     const size_t part_bytes = align_up((size_t)g.nsplit * g.nitems * 4 * BLK * BLK * sizeof(float), 256);
-    const size_t need = part_bytes + align_up((size_t)g.nsplit * g.nb * BLK * sizeof(float), 256);
+    const size_t sp_bytes = align_up((size_t)g.nsplit * g.nb * BLK * sizeof(float), 256);
+    const size_t need = part_bytes + sp_bytes + (copy ? act_copy_bytes(d) : 0);
     if (!ws || ws_bytes < need) return FW_ERR_WORKSPACE;
     float* part = reinterpret_cast<float*>(ws);
     float* spart = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + part_bytes);
+    if (copy) {
+        float* Xc = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + part_bytes + sp_bytes);
+        const int HW = d->H * d->W;
+        hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3((HW + 31) / 32, (d->Cin + 31) / 32, d->B), dim3(256), 0, st,
+                           reinterpret_cast<const float*>(X), Xc, d->Cin, HW);
+        FW_LAUNCH_CHECK();
+        X = Xc;
+    }
     const dim3 grid(g.nitems, g.nsplit);
     const bool vec4 = dt == FW_F32 && lay != FW_LAYOUT_NCHW && (g.Cin % 4) == 0;
     if (vec4)
