@@ -11,9 +11,9 @@
 // The same pass adds up, per padded pixel and channel, the values it packs; the column sums s are sums of those
 // per-pixel sums over the output positions of a tap, so the contraction kernel does not touch them.
 //
-// The contraction kernel covers the lower triangle of A with tiles of 256 rows x 64 NCT columns (NCT = 4, 3 or 2; the
-// host takes the shape and the number of unit ranges per tile that fill the 256 compute units best).  A workgroup of
-// 4 wavefronts, one per SIMD, each with 128 x 32 NCT outputs (4 x NCT MFMA tiles in accumulation registers), owns
+// The contraction kernel covers the lower triangle of A with tiles of 64 NRT rows x 64 NCT columns (4 >= NRT >= NCT >= 2;
+// the host takes the shape and the number of unit ranges per tile that fill the 256 compute units best).  A workgroup
+// of 4 wavefronts, one per SIMD, each with 32 NRT x 32 NCT outputs (NRT x NCT MFMA tiles in accumulation registers), owns
 // one tile over a range of units.  Chunks of 4 units travel from global memory straight into LDS
 // (global_load_lds_dwordx4, no register staging; wavefront w brings unit w) into a ring of five or six stages (all of
 // the 160 KB of LDS) laid out as [unit][feature][16 B], four or five chunks ahead of the MFMAs: in flight is what
@@ -29,12 +29,11 @@
 namespace fw {
 namespace {
 
-constexpr int TR = 256;  // tile rows (features)
 constexpr int KU = 4;    // units per staged chunk (32 reduction entries) = wavefronts of a workgroup
 
 struct TileGeom {
     int M, ntiles;
-    int nct, tc, ncb, nrb;  // MFMA column tiles per wavefront, tile columns = 64 nct, column / row blocks of A
+    int nrt, nct, tr, tc, ncb, nrb;  // MFMA row / column tiles per wavefront, tile = 64 nrt x 64 nct, column / row blocks of A
     int B, Bg, Cin, H, W, Hp, Wp, kh, kw, stride, pad, Ho, Wo;
     int layout;
     int n_units, nchunks, chunks_per_split, nsplit;
@@ -44,8 +43,8 @@ struct TileGeom {
 };
 
 // column blocks of row block I that touch the lower triangle
-__host__ __device__ inline int cols_of_row(int I, int tc, int ncb) {
-    const int n = (I * TR + TR - 1) / tc + 1;
+__host__ __device__ inline int cols_of_row(int I, int tr, int tc, int ncb) {
+    const int n = (I * tr + tr - 1) / tc + 1;
     return n < ncb ? n : ncb;
 }
 
@@ -118,20 +117,21 @@ __device__ __forceinline__ void feat_map(int fi, const TileGeom& g, int* off, in
 __device__ __forceinline__ void tile_coords(int tile, const TileGeom& g, int* I, int* J) {
     int i = 0;
     for (;;) {
-        const int n = cols_of_row(i, g.tc, g.ncb);
+        const int n = cols_of_row(i, g.tr, g.tc, g.ncb);
         if (tile < n) break;
         tile -= n; ++i;
     }
     *I = i; *J = tile;
 }
 
-template <int NCT>
+template <int NRT, int NCT>
 __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restrict__ P, const int* __restrict__ utab, TileGeom g,
                                                             float* __restrict__ part, float* __restrict__ A) {
+    constexpr int TR = 64 * NRT;      // tile rows
     constexpr int TC = 64 * NCT;      // tile columns
-    constexpr int NF = 4 + NCT;       // groups of 64 features per unit: 4 of the row panel, NCT of the column panel
+    constexpr int NF = NRT + NCT;     // groups of 64 features per unit: NRT of the row panel, NCT of the column panel
     constexpr int ROW = TR + TC;      // 16-byte elements per unit
-    constexpr int NM = 4 * NCT;       // MFMAs per 16-entry step and wavefront
+    constexpr int NM = NRT * NCT;     // MFMAs per 16-entry step and wavefront
     constexpr int NST = 160 * 1024 / (KU * ROW * 16);   // stages of the LDS ring: all of the 160 KB (5, 5, 6)
     __shared__ uint4 pan[NST][KU][ROW];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -161,16 +161,16 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
     unsigned okmask = 0;
 #pragma unroll
     for (int k = 0; k < NF; ++k) {
-        const int f = k < 4 ? I * TR + 64 * k + lane : J * TC + 64 * (k - 4) + lane;
+        const int f = k < NRT ? I * TR + 64 * k + lane : J * TC + 64 * (k - NRT) + lane;
         const bool ok = f < g.M;
         int ext_unused;
         feat_map(ok ? f : 0, g, &off[k], &ext_unused);
         okmask |= (ok ? 1u : 0u) << k;
     }
 
-    floatx16 acc[4][NCT];
+    floatx16 acc[NRT][NCT];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < NRT; ++a)
 #pragma unroll
         for (int b = 0; b < NCT; ++b)
 #pragma unroll
@@ -191,16 +191,16 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
         for (int k = 0; k < NF; ++k) dma_one(stage, k);
     };
 
-    // Operand fragments of 16-entry step ks (units 2ks, 2ks+1) of a stage; fragment r < 4 is row tile r, the others
+    // Operand fragments of 16-entry step ks (units 2ks, 2ks+1) of a stage; fragment r < NRT is row tile r, the others
     // are the column tiles.  Two register sets alternate between the two steps of a chunk.
     bf16x8 fr[2][NF];
     auto read_one = [&](int stage, int ks, int set, int r) {
-        const int col = r < 4 ? 128 * wi + 32 * r : TR + 32 * NCT * wj + 32 * (r - 4);
+        const int col = r < NRT ? 32 * NRT * wi + 32 * r : TR + 32 * NCT * wj + 32 * (r - NRT);
         fr[set][r] = *reinterpret_cast<const bf16x8*>(&pan[stage][2 * ks + half][col + l32]);
     };
     auto mfma_one = [&](int set, int m) {   // m = ta * NCT + tb
         const int ta = m / NCT, tb = m % NCT;
-        acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][ta], fr[set][4 + tb], acc[ta][tb], 0, 0, 0);
+        acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][ta], fr[set][NRT + tb], acc[ta][tb], 0, 0, 0);
     };
 
     // Ring protocol.  Loads of one wavefront complete in order, so "at most the loads of NST-2 chunks outstanding" means
@@ -255,12 +255,12 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
     if (!g.direct) {
         float* dst = part + ((size_t)split * g.ntiles + tile) * (TR * TC);
 #pragma unroll
-        for (int ta = 0; ta < 4; ++ta)
+        for (int ta = 0; ta < NRT; ++ta)
 #pragma unroll
             for (int tb = 0; tb < NCT; ++tb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int row = 128 * wi + 32 * ta + 8 * (i >> 2) + 4 * half + (i & 3);
+                    const int row = 32 * NRT * wi + 32 * ta + 8 * (i >> 2) + 4 * half + (i & 3);
                     const int col = 32 * NCT * wj + 32 * tb + l32;
                     dst[row * TC + col] = acc[ta][tb][i];
                 }
@@ -271,8 +271,8 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
         for (int tb = 0; tb < NCT; ++tb) {
             const int gj = J * TC + 32 * NCT * wj + 32 * tb + l32;
 #pragma unroll
-            for (int ta = 0; ta < 4; ++ta) {
-                const int gi0 = I * TR + 128 * wi + 32 * ta + 4 * half;
+            for (int ta = 0; ta < NRT; ++ta) {
+                const int gi0 = I * TR + 32 * NRT * wi + 32 * ta + 4 * half;
                 if (gi0 + 27 < J * TC + 32 * NCT * wj + 32 * tb) continue;   // MFMA tile entirely above the diagonal
                 float old[16];
 #pragma unroll
@@ -328,14 +328,15 @@ __global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const flo
 
 // partial tiles -> A (float64 sum over the ranges), one thread per tile element
 __global__ __launch_bounds__(256) void tile_reduce_kernel(TileGeom g, const float* __restrict__ part, float* __restrict__ A) {
-    const int tile = blockIdx.x / g.tc;            // tc blocks of 256 threads per tile of 256 x tc
-    const int e = (blockIdx.x - tile * g.tc) * 256 + threadIdx.x;
+    const int bpt = g.tr * g.tc / 256;             // blocks of 256 threads per tile of tr x tc
+    const int tile = blockIdx.x / bpt;
+    const int e = (blockIdx.x - tile * bpt) * 256 + threadIdx.x;
     int I, J;
     tile_coords(tile, g, &I, &J);
     const int row = e / g.tc, col = e - row * g.tc;
-    const int fi = I * TR + row, fj = J * g.tc + col;
+    const int fi = I * g.tr + row, fj = J * g.tc + col;
     if (fi >= g.M || fj >= g.M || fj > fi) return;
-    const size_t tsz = (size_t)TR * g.tc;
+    const size_t tsz = (size_t)g.tr * g.tc;
     const size_t stride = (size_t)g.ntiles * tsz;
     const float* src = part + (size_t)tile * tsz + e;
     double v = 0.0;
@@ -363,34 +364,35 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     g->M = (int)M;
     g->n_units = (int)n_units;
     g->nchunks = (int)((n_units + KU - 1) / KU);
-    g->nrb = (int)((M + TR - 1) / TR);
     const bool ident = lay == FW_LAYOUT_NHWC_KKC || lay == FW_LAYOUT_ROWS || d->kh * d->kw == 1;
-    // Tile shape (256 x 64 nct) and number of unit ranges per tile: minimise
+    // Tile shape (64 nrt x 64 nct, nct <= nrt) and number of unit ranges per tile: minimise
     //   rounds x chunks per range x time of a chunk  +  traffic of the partial tiles,
-    // with rounds = ceil(tiles x ranges / 256 compute units).  A chunk costs the larger of its MFMAs (2 steps x 4 nct
+    // with rounds = ceil(tiles x ranges / 256 compute units).  A chunk costs the larger of its MFMAs (2 steps x nrt nct
     // x 32 cycles, plus a share for the barrier) and its loads into LDS, which a compute unit sustains at about 23 bytes
     // per cycle next to the fragment reads; one range per tile in the caller's feature order needs no partial tiles.
     const double clk = 2.0e9, bw = 4.0e12, lds_load_rate = 23.0;
     double best = 1e300;
-    int best_nct = 4, best_ns = 1;
-    for (int nct = 4; nct >= 2; --nct) {
-        const int tc = 64 * nct, ncb = (int)((M + tc - 1) / tc);
-        long long ntiles = 0;
-        for (int I = 0; I < g->nrb; ++I) ntiles += cols_of_row(I, tc, ncb);
-        const double t_mfma = 256.0 * nct + 150.0, t_load = (double)(TR + tc) * KU * 16.0 / lds_load_rate;
-        const double t_chunk = (t_mfma > t_load ? t_mfma : t_load) / clk;
-        for (int ns = 1; ns <= 512 && ns <= g->nchunks; ++ns) {
-            const long long wgs = ntiles * ns;
-            const long long rounds = (wgs + 255) / 256;
-            const long long cps = (g->nchunks + ns - 1) / ns;
-            double cost = (double)rounds * (double)cps * t_chunk;
-            if (ns > 1 || !ident) cost += (double)wgs * TR * tc * 4.0 * 2.0 / bw;
-            if (cost < best * 0.999) { best = cost; best_nct = nct; best_ns = ns; }
+    int best_nrt = 4, best_nct = 4, best_ns = 1;
+    for (int nrt = 4; nrt >= 2; --nrt)
+        for (int nct = nrt; nct >= 2; --nct) {
+            const int tr = 64 * nrt, tc = 64 * nct, ncb = (int)((M + tc - 1) / tc), nrb = (int)((M + tr - 1) / tr);
+            long long ntiles = 0;
+            for (int I = 0; I < nrb; ++I) ntiles += cols_of_row(I, tr, tc, ncb);
+            const double t_mfma = 64.0 * nrt * nct + 150.0, t_load = (double)(tr + tc) * KU * 16.0 / lds_load_rate;
+            const double t_chunk = (t_mfma > t_load ? t_mfma : t_load) / clk;
+            for (int ns = 1; ns <= 512 && ns <= g->nchunks; ++ns) {
+                const long long wgs = ntiles * ns;
+                const long long rounds = (wgs + 255) / 256;
+                const long long cps = (g->nchunks + ns - 1) / ns;
+                double cost = (double)rounds * (double)cps * t_chunk;
+                if (ns > 1 || !ident) cost += (double)wgs * tr * tc * 4.0 * 2.0 / bw;
+                if (cost < best * 0.999) { best = cost; best_nrt = nrt; best_nct = nct; best_ns = ns; }
+            }
         }
-    }
-    g->nct = best_nct; g->tc = 64 * best_nct; g->ncb = (int)((M + g->tc - 1) / g->tc);
+    g->nrt = best_nrt; g->nct = best_nct; g->tr = 64 * best_nrt; g->tc = 64 * best_nct;
+    g->ncb = (int)((M + g->tc - 1) / g->tc); g->nrb = (int)((M + g->tr - 1) / g->tr);
     g->ntiles = 0;
-    for (int I = 0; I < g->nrb; ++I) g->ntiles += cols_of_row(I, g->tc, g->ncb);
+    for (int I = 0; I < g->nrb; ++I) g->ntiles += cols_of_row(I, g->tr, g->tc, g->ncb);
     g->chunks_per_split = (g->nchunks + best_ns - 1) / best_ns;
     g->nsplit = (g->nchunks + g->chunks_per_split - 1) / g->chunks_per_split;
     // the pre-pass wants about half a million threads: split the image groups when one image gives fewer
@@ -414,7 +416,7 @@ Bf16Ws ws_layout(const TileGeom& g) {
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
     L.packed = take(((size_t)g.Bg * g.Hp * g.Wp * g.Cin + 16) * 16);
     L.utab = take((size_t)g.nchunks * KU * 4);
-    L.part = take(g.direct ? 0 : (size_t)g.nsplit * g.ntiles * TR * g.tc * 4);
+    L.part = take(g.direct ? 0 : (size_t)g.nsplit * g.ntiles * g.tr * g.tc * 4);
     L.s8 = take((size_t)g.bg_chunks * g.Hp * g.Wp * g.Cin * 4);
     L.total = o;
     return L;
@@ -444,11 +446,18 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
                        g, P, S8, utab);
     FW_LAUNCH_CHECK();
     const dim3 grid((g.ntiles * g.nsplit + 7) / 8 * 8);
-    if (g.nct == 4) hipLaunchKernelGGL(cov_bf16_tile_kernel<4>, grid, dim3(256), 0, st, P, utab, g, part, A);
-    else if (g.nct == 3) hipLaunchKernelGGL(cov_bf16_tile_kernel<3>, grid, dim3(256), 0, st, P, utab, g, part, A);
-    else hipLaunchKernelGGL(cov_bf16_tile_kernel<2>, grid, dim3(256), 0, st, P, utab, g, part, A);
+#define FW_TILE_LAUNCH(R, C) hipLaunchKernelGGL((cov_bf16_tile_kernel<R, C>), grid, dim3(256), 0, st, P, utab, g, part, A)
+    switch (g.nrt * 10 + g.nct) {
+        case 44: FW_TILE_LAUNCH(4, 4); break;
+        case 43: FW_TILE_LAUNCH(4, 3); break;
+        case 42: FW_TILE_LAUNCH(4, 2); break;
+        case 33: FW_TILE_LAUNCH(3, 3); break;
+        case 32: FW_TILE_LAUNCH(3, 2); break;
+        default: FW_TILE_LAUNCH(2, 2); break;
+    }
+#undef FW_TILE_LAUNCH
     FW_LAUNCH_CHECK();
-    if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * g.tc), dim3(256), 0, st, g, part, A);
+    if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * (g.tr * g.tc / 256)), dim3(256), 0, st, g, part, A);
     hipLaunchKernelGGL(column_sums_kernel, dim3((g.M + 15) / 16), dim3(1024), 0, st, g, S8, s);
     FW_LAUNCH_CHECK();
     return FW_OK;
