@@ -82,6 +82,13 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
         c = e % g.Cin; const int t = e / g.Cin;
         xp = t % g.Wp; yp = t / g.Wp;
     }
+    // a padded pixel that no window touches (stride larger than the window) is neither read nor written
+    if (g.stride > g.kh || g.stride > g.kw) {
+        bool ry = false, rx = false;
+        for (int ky = 0; ky < g.kh; ++ky) { const int o = yp - ky; ry |= o >= 0 && o % g.stride == 0 && o / g.stride < g.Ho; }
+        for (int kx = 0; kx < g.kw; ++kx) { const int o = xp - kx; rx |= o >= 0 && o % g.stride == 0 && o / g.stride < g.Wo; }
+        if (!(ry && rx)) return;
+    }
     const int y = yp - g.pad, x = xp - g.pad;
     const bool inside = (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
     const long long img_stride = (long long)g.Cin * g.H * g.W;
