@@ -18,7 +18,7 @@ def run_evd(Phi32, Qs=None, **kw):
     return T.cpu().numpy(), Q.cpu().numpy(), lam.cpu().numpy()
 
 
-@pytest.mark.parametrize("M,lo", [(2, -1), (7, -2), (64, -4), (65, -3), (130, -5), (256, -3)])
+@pytest.mark.parametrize("M,lo", [(2, -1), (7, -2), (64, -4), (65, -3), (130, -5), (256, -3), (1100, -4)])
 def test_plain_gains(M, lo):
     Phi32 = wl.spd_matrix(M, M, np.logspace(0, lo, M)).astype(np.float32)
     T, Q, lam = run_evd(Phi32, eps=1e-5)
