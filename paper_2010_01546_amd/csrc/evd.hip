@@ -105,15 +105,22 @@ __global__ __launch_bounds__(256) void gram_kernel(const double* __restrict__ W,
 #pragma unroll
     for (int t = 0; t < 10; ++t) acc[t] = doublex4{0.0, 0.0, 0.0, 0.0};
     const int c_begin = blockIdx.x * JSW, c_end = min(M, c_begin + JSW);
+    // this thread's eight entries of a chunk: row (tid + 256 m) / 32, column (tid + 256 m) % 32; fetched one chunk ahead
+    int grow[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) grow[m] = pair_row(p, q, nblk, M, (threadIdx.x + 256 * m) >> 5);
+    const int cc = threadIdx.x & 31;
+    double nxt[8];
+    auto fetch = [&](int c0) {
+#pragma unroll
+        for (int m = 0; m < 8; ++m) nxt[m] = (grow[m] >= 0 && c0 + cc < c_end) ? W[(size_t)grow[m] * M + c0 + cc] : 0.0;
+    };
+    fetch(c_begin);
     for (int c0 = c_begin; c0 < c_end; c0 += 32) {
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
-            const int idx = threadIdx.x + 256 * m;
-            const int r = idx >> 5, cc = idx & 31;
-            const int gr = pair_row(p, q, nblk, M, r);
-            Xs[r][cc] = (gr >= 0 && c0 + cc < c_end) ? W[(size_t)gr * M + c0 + cc] : 0.0;
-        }
+        for (int m = 0; m < 8; ++m) Xs[(threadIdx.x + 256 * m) >> 5][cc] = nxt[m];
         __syncthreads();
+        if (c0 + 32 < c_end) fetch(c0 + 32);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int ks = wave + 4 * h;
@@ -161,7 +168,6 @@ __global__ __launch_bounds__(256) void pair_evd_kernel(const double* __restrict_
                                                        double* __restrict__ Rot,
                                                        int* __restrict__ flags, int* __restrict__ counter) {
     __shared__ double Gs[JP][JP + 1], Rs[JP][JP + 1];
-    __shared__ double cs[JB], sn[JB];
     __shared__ int n_rot, n_first;
     const int tid = threadIdx.x;
     const int kk = tid >> 3, sub = tid & 7;
@@ -180,20 +186,17 @@ __global__ __launch_bounds__(256) void pair_evd_kernel(const double* __restrict_
             int i, j;
             rr_pair(JP, step, kk, &i, &j);
             if (i > j) { const int t = i; i = j; j = t; }
-            if (sub == 0) {
-                const double al = Gs[i][i], be = Gs[j][j], ga = Gs[i][j];
-                double c = 1.0, s = 0.0;
-                if (fabs(ga) > tol * sqrt(fabs(al * be)) && ga != 0.0) {
-                    const double zeta = (be - al) / (2.0 * ga);
-                    const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                    c = 1.0 / sqrt(1.0 + tt * tt);
-                    s = c * tt;
-                    atomicAdd(&n_rot, 1);
-                }
-                cs[kk] = c; sn[kk] = s;
+            // every thread of the index pair works out the rotation for itself: the eight of them sit in one wavefront,
+            // so all of them have read the three entries before any of them rewrites rows i and j
+            const double al = Gs[i][i], be = Gs[j][j], ga = Gs[i][j];
+            double c = 1.0, s = 0.0;
+            if (fabs(ga) > tol * sqrt(fabs(al * be)) && ga != 0.0) {
+                const double tau = be - al;
+                const double tt = (tau >= 0.0 ? 2.0 : -2.0) * ga / (fabs(tau) + sqrt(tau * tau + 4.0 * ga * ga));
+                c = rsqrt(1.0 + tt * tt);
+                s = c * tt;
+                if (sub == 0) atomicAdd(&n_rot, 1);
             }
-            __syncthreads();
-            const double c = cs[kk], s = sn[kk];
             if (s != 0.0) {   // rows i, j of G and of R
 #pragma unroll
                 for (int m = 0; m < 8; ++m) {
