@@ -256,8 +256,8 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(double* __restrict__ W
     int rowk[16];   // global rows of this lane's contraction entries 4 ks + lq
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) rowk[ks] = pair_row(p, q, nblk, M, 4 * ks + lq);
-    for (int gi = 0; gi < 4; ++gi) {
-        const int col0 = blockIdx.x * 256 + (wave * 4 + gi) * 16;
+    for (int gi = 0; gi < 8; ++gi) {
+        const int col0 = blockIdx.x * 512 + (wave * 8 + gi) * 16;
         if (col0 >= M) break;
         const int col = col0 + lr;
         const bool cok = col < M;
@@ -397,7 +397,7 @@ fw_status whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float* T
     double* Gpart = reinterpret_cast<double*>(base + L.gpart);
     double* Rot = reinterpret_cast<double*>(base + L.rot);
     int* flags = reinterpret_cast<int*>(base + L.flags);
-    const int ncolblk = (M + 255) / 256;
+    const int ncolblk = (M + 511) / 512;
     const int inner = 1;   // inner sweeps per visit of a pair: one was the fastest overall (more inner sweeps, fewer outer ones)
     bool converged = false;
     for (int sweep = 0; sweep < max_sweeps && !converged; ++sweep) {
