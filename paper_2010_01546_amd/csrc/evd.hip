@@ -62,14 +62,6 @@ __global__ __launch_bounds__(256) void evd_init_kernel(const float* __restrict__
     }
 }
 
-__device__ __forceinline__ double block_sum256(double v, double* red) {
-    v = wave_sum(v);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return red[0] + red[1] + red[2] + red[3];
-}
-
 // One round of the round-robin ordering over n (even) players; pair k of round r.
 __device__ __forceinline__ void rr_pair(int n, int r, int k, int* a, int* b) {
     const int m = n - 1;
