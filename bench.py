@@ -124,6 +124,7 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False):
            "cond_ms": time_call(lambda: b.fw_cond_reduce_step(st, prm, info, ws_cond)),
            "grad_ms": time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)),
            "fin_ms": time_call(lambda: b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar)),
+           "refresh_ms": time_call(lambda: b.fw_cond_state_refresh(st), reps=5),
            "gamma": prm.gamma, "act_bytes": float(X.numel() * X.element_size()), "step": step}
     if evd:   # the EVD / ZCA reference construction replaces the recursive step; timed once, outside the headline
         ws_evd = torch.empty(b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, M), dtype=torch.uint8, device=dev)
@@ -226,6 +227,10 @@ def main():
         "cond_step_GBps": cond_bytes / (cond_ms * 1e-3) / 1e9,
         "grad_transform_TFLOPs": 2.0 * S * M * M / (grad_ms * 1e-3) / 1e12,
     }
+    # once per block when the data (hence Phi_x) changes between blocks; the timed step feeds the same batch again, so
+    # Phi_x is stationary there and the call is not part of the step
+    out["breakdown_ms"]["cond_state_refresh_per_block"] = r["refresh_ms"]
+    out["cond_state_refresh_TFLOPs"] = 4.0 * M * M * M / (r["refresh_ms"] * 1e-3) / 1e12
     if "evd_ms" in r:
         out["breakdown_ms"]["whiten_evd"] = r["evd_ms"]
     alpha = 0.1

@@ -60,7 +60,9 @@ typedef enum {
 typedef struct { int B, Cin, H, W, kh, kw, stride, pad; } fw_conv_desc;
 
 /* Operations for fw_workspace_bytes. */
-typedef enum { FW_OP_COV_ACCUMULATE = 0, FW_OP_GRAD_TRANSFORM = 1, FW_OP_COND_REDUCE_STEP = 2, FW_OP_WHITEN_EVD = 3 } fw_op;
+typedef enum {
+    FW_OP_COV_ACCUMULATE = 0, FW_OP_GRAD_TRANSFORM = 1, FW_OP_COND_REDUCE_STEP = 2, FW_OP_WHITEN_EVD = 3, FW_OP_COND_STATE_REFRESH = 4
+} fw_op;
 
 /* ------------------------------------------------------------------------------------------------------------
  * (1) Moment accumulation -- the sums inside eqs. (vmuxi), (vPhixi) of Sec. 2 and eq. (phixmi) of Sec. 4.1.
@@ -154,6 +156,14 @@ typedef struct {
 
 /* T = Q = Qs = I, Phi_y = Psi = Phi_x, xi2 = squared column norms of Phi_x  (eqs. (vT_init), Qs(-1) = I). */
 fw_status fw_cond_state_init(const fw_cond_state* st, void* stream);
+
+/* A new block brings a new Phi_x while T, Q, Qs carry over (Sec. 2: the moments are re-estimated block by block; Sec. 4:
+ * the recursion works on the covariance of the transformed input).  Recomputes, for the T at hand,
+ *   Psi = T Phi_x,   Phi_y = T Phi_x T^T (written exactly symmetric),   xi2 = squared column norms of Phi_y
+ * by two M x M x M float32 products on the matrix cores.  T, Q, Qs are not touched.
+ *   ws   scratch of fw_workspace_bytes(FW_OP_COND_STATE_REFRESH, M, 0, NULL, FW_F32) bytes, needed only when st->Psi is NULL
+ */
+fw_status fw_cond_state_refresh(const fw_cond_state* st, void* ws, size_t ws_bytes, void* stream);
 
 /* One step: estimate the high-power direction v of Phi_y (Sec. 4.2), lambda_e, g_e, a_e (eqs. (lambda), (ge), (xi)),
  * t = T^T v, then in one pass T <- gamma (T + a v t^T) + (1-gamma) I (eq. (vT_rec)), Q by eq. (vQ_rec),

@@ -21,10 +21,10 @@ lib = C.CDLL(LIB_PATH)
 FW_OK, FW_ERR_INVALID_ARG, FW_ERR_UNSUPPORTED, FW_ERR_ALIGNMENT, FW_ERR_WORKSPACE, FW_ERR_HIP, FW_ERR_NOT_CONVERGED = range(7)
 FW_F32, FW_BF16 = 0, 1
 FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
-FW_OP_COV_ACCUMULATE, FW_OP_GRAD_TRANSFORM, FW_OP_COND_REDUCE_STEP, FW_OP_WHITEN_EVD = range(4)
+FW_OP_COV_ACCUMULATE, FW_OP_GRAD_TRANSFORM, FW_OP_COND_REDUCE_STEP, FW_OP_WHITEN_EVD, FW_OP_COND_STATE_REFRESH = range(5)
 
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",
-           "fw_whiten_evd", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+           "fw_whiten_evd", "fw_cond_state_refresh", "fw_workspace_bytes", "fw_status_string", "fw_version"]
 
 
 class fw_conv_desc(C.Structure):
@@ -56,6 +56,7 @@ lib.fw_cov_accumulate.argtypes = [_P, C.c_int, C.c_int, C.POINTER(fw_conv_desc),
 lib.fw_cov_finalize.argtypes = [_P, _P, C.c_longlong, C.c_int, C.c_float, C.c_int, _P, _P, _P, _P, _P]
 lib.fw_grad_transform.argtypes = [_P, C.c_int, C.c_int, C.c_int, _P, _P, _P, _P, C.c_size_t, _P]
 lib.fw_cond_state_init.argtypes = [C.POINTER(fw_cond_state), _P]
+lib.fw_cond_state_refresh.argtypes = [C.POINTER(fw_cond_state), _P, C.c_size_t, _P]
 lib.fw_cond_reduce_step.argtypes = [C.POINTER(fw_cond_state), C.POINTER(fw_cond_params), _P, _P, C.c_size_t, _P]
 lib.fw_whiten_evd.argtypes = [_P, C.c_int, C.POINTER(fw_evd_params), _P, _P, _P, _P, _P, C.c_size_t, _P]
 lib.fw_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.c_int]
@@ -63,7 +64,7 @@ lib.fw_workspace_bytes.restype = C.c_size_t
 lib.fw_status_string.argtypes = [C.c_int]
 lib.fw_status_string.restype = C.c_char_p
 lib.fw_version.restype = C.c_int
-for _n in EXPORTS[:6]:
+for _n in EXPORTS[:7]:
     getattr(lib, _n).restype = C.c_int
 
 
@@ -148,6 +149,11 @@ def evd_params(eps=1e-5, g_max=10.0, beta=0.95, tol=0.0, gain_mode=0, max_sweeps
 
 def fw_cond_state_init(st, stream=None):
     return _check(lib.fw_cond_state_init(C.byref(st), _stream(stream)), "fw_cond_state_init")
+
+
+def fw_cond_state_refresh(st, ws=None, stream=None):
+    wp, n = _ws(ws)
+    return _check(lib.fw_cond_state_refresh(C.byref(st), wp, n, _stream(stream)), "fw_cond_state_refresh")
 
 
 def fw_cond_reduce_step(st, p, info_dev, ws, stream=None):

@@ -90,6 +90,16 @@ fw_status fw_cond_state_init(const fw_cond_state* st, void* stream) {
     return cond_state_init(st, reinterpret_cast<hipStream_t>(stream));
 }
 
+fw_status fw_cond_state_refresh(const fw_cond_state* st, void* ws, size_t ws_bytes, void* stream) {
+    if (!st || st->M <= 0 || !st->Phi_x || !st->T || !st->Phi_y || !st->xi2) return FW_ERR_INVALID_ARG;
+    if (st->M > 16384) return FW_ERR_UNSUPPORTED;
+    if (!aligned16(st->Phi_x) || !aligned16(st->T) || !aligned16(st->Phi_y) || !aligned16(st->xi2) || (st->Psi && !aligned16(st->Psi)) ||
+        (ws && !aligned16(ws)))
+        return FW_ERR_ALIGNMENT;
+    if (!st->Psi && (!ws || ws_bytes < align_up((size_t)st->M * st->M * sizeof(float), 256))) return FW_ERR_WORKSPACE;
+    return cond_state_refresh(st, reinterpret_cast<float*>(ws), reinterpret_cast<hipStream_t>(stream));
+}
+
 fw_status fw_cond_reduce_step(const fw_cond_state* st, const fw_cond_params* p, fw_cond_info* info_dev, void* ws, size_t ws_bytes,
                               void* stream) {
     if (!st || !p || st->M <= 0 || !st->Phi_x || !st->lambda_bar || !st->T || !st->Q || !st->Qs || !st->Phi_y || !st->xi2)
@@ -137,6 +147,7 @@ size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtyp
             return grad_ws_bytes(M) + ((dt == FW_BF16 && S > 0) ? grad_wide_bytes(S, M) : 0);
         case FW_OP_COND_REDUCE_STEP: return M > 0 && M <= 16384 ? cond_workspace_bytes(M) : 0;
         case FW_OP_WHITEN_EVD: return M > 0 && M <= 16384 ? evd_workspace_bytes(M) : 0;
+        case FW_OP_COND_STATE_REFRESH: return M > 0 && M <= 16384 ? align_up((size_t)M * M * sizeof(float), 256) : 0;
     }
     return 0;
 }

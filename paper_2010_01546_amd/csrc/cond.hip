@@ -474,6 +474,23 @@ fw_status cond_state_init(const fw_cond_state* s, hipStream_t st) {
     return FW_OK;
 }
 
+// New block, new Phi_x: Psi = T Phi_x and Phi_y = T Phi_x T^T = Psi T^T by two M x M x M products on the matrix cores
+// (the gradient GEMM computes G Q^T with Q read along its rows: Phi_x is symmetric, and T is exactly the factor
+// wanted), Phi_y made exactly symmetric from its lower triangle, and the squared row norms for the arg-max.
+fw_status cond_state_refresh(const fw_cond_state* s, float* psi_scratch, hipStream_t st) {
+    const int M = s->M;
+    float* Psi = s->Psi ? s->Psi : psi_scratch;
+    fw_status rc = grad_gemm(s->T, FW_F32, M, M, s->Phi_x, Psi, st);
+    if (rc != FW_OK) return rc;
+    rc = grad_gemm(Psi, FW_F32, M, M, s->T, s->Phi_y, st);
+    if (rc != FW_OK) return rc;
+    rc = symmetrize_from_lower(s->Phi_y, M, st);
+    if (rc != FW_OK) return rc;
+    hipLaunchKernelGGL(rownorm2_kernel, dim3((M + 3) / 4), dim3(256), 0, st, s->Phi_y, M, s->xi2);
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
 fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_cond_info* info, void* ws, hipStream_t st) {
     const int M = s->M;
     const WsLayout L = ws_layout(M);

@@ -263,7 +263,7 @@ void launch_strip(int c, const float* G, const float* Q, float* Out, int S, int 
 
 // M not a multiple of 4 (rows of G and Q not 16-byte aligned): a workgroup owns a 32x32 tile of G_out and its four
 // wavefronts split the contraction index four ways; operands come straight from global memory / L2 with scalar
-// loads, partial tiles are combined through LDS.
+// loads (Q along its rows, like the other kernels), partial tiles are combined through LDS.
 __global__ __launch_bounds__(256) void grad_gemm_f32_small_kernel(const float* __restrict__ G, const float* __restrict__ Q,
                                                                   float* __restrict__ Out, int S, int M) {
     __shared__ float red[3][32 * 32];
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_small_kernel(const float* _
     const int r = row0 + l32, c = col0 + l32;
     const bool r_ok = r < S, c_ok = c < M;
     const float* gp = G + (size_t)(r_ok ? r : 0) * M;
-    const float* qp = Q + (c_ok ? c : 0);
+    const float* qp = Q + (size_t)(c_ok ? c : 0) * M;   // row c of Q stands for its column c (Q is symmetric)
     floatx16 acc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_small_kernel(const float* _
         for (int j = 0; j < 8; ++j) {
             const int kk = k + 2 * j + half;
             a[j] = r_ok ? gp[kk] : 0.f;
-            b[j] = c_ok ? qp[(size_t)kk * M] : 0.f;
+            b[j] = c_ok ? qp[kk] : 0.f;
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b[j], acc, 0, 0, 0);
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_small_kernel(const float* _
         const int kk = k + half;
         const bool k_ok = kk < ke;
         const float a = (r_ok && k_ok) ? gp[kk] : 0.f;
-        const float b = (c_ok && k_ok) ? qp[(size_t)kk * M] : 0.f;
+        const float b = (c_ok && k_ok) ? qp[kk] : 0.f;
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
     }
     if (wave > 0) {

@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_common import CondRunner, b, ora, relF
+from gpu_common import CondRunner, b, dev, ora, relF, workspace
 
 pytestmark = pytest.mark.gpu
 BAND = 2e-5   # relative guard band of a float32 decision
@@ -109,3 +109,41 @@ def test_config1_sixteen_steps():
     mu, Phi, phi, lbar = ora.block_moments(L.act, 0.0, True)
     run, applied, worst = teacher_forced(Phi, lbar, dict(), steps=16)
     assert applied >= 8
+
+
+@pytest.mark.parametrize("M,leak", [(96, True), (130, True), (64, False), (70, False)])
+def test_refresh_for_a_new_block(M, leak):
+    """A new block changes Phi_x while T carries over: Psi, Phi_y and the column norms are rebuilt for the T at hand, and
+    the next steps agree with the oracle, which forms T Phi_x T^T explicitly from the new Phi_x."""
+    Phi1 = spd(M, 11).astype(np.float32).astype(np.float64)
+    Phi2 = spd(M, 12, hi=1.5, lo=-1.0).astype(np.float32).astype(np.float64)
+    kw = dict() if leak else dict(gamma=1.0, beta=0.0)
+    gp = b.cond_params(**kw)
+    op = ora.CondParams(gamma=gp.gamma, delta=gp.delta, eps=gp.eps, c_rel=gp.c_rel, c_abs=gp.c_abs, beta=gp.beta)
+    run = CondRunner(Phi1, np.trace(Phi1) / M, gamma_lt_one=leak)
+    for _ in range(6):
+        run.step(gp)
+    T = run.host("T")
+    assert not np.allclose(T, np.eye(M))
+    run.Phi_x.copy_(dev(Phi2))
+    lbar2 = float(np.float32(np.trace(Phi2) / M))
+    run.lbar.fill_(lbar2)
+    ws = None if leak else workspace(b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, M))
+    b.fw_cond_state_refresh(run.st, ws)
+    torch.cuda.synchronize()
+    want = ora.transformed_covariance(T, Phi2)
+    Py = run.host("Phi_y")
+    assert relF(Py, want) < 1e-5 and np.array_equal(Py, Py.T)
+    if leak:
+        assert relF(run.host("Psi"), T @ Phi2) < 1e-5
+    assert relF(run.host("xi2"), np.sum(want ** 2, axis=0)) < 1e-5
+    assert np.array_equal(run.host("T"), T)
+    for _ in range(3):   # teacher-forced steps on the new block
+        st = ora.CondState(Phi2, run.host("T"), run.host("Q"), run.host("Qs"))
+        info = run.step(gp)
+        new, oi = ora.cond_reduce_step(st, lbar2, op)
+        if info.m_prime != oi.m_prime or info.set_size != oi.set_size:
+            continue
+        assert max(relF(run.host("T"), new.T), relF(run.host("Q"), new.Q), relF(run.host("Qs"), new.Qs)) < 1e-4
+    Tn = run.host("T")
+    assert relF(run.host("Phi_y"), Tn @ Phi2 @ Tn.T) < 1e-4
