@@ -259,6 +259,37 @@ def grad_transform(G: np.ndarray, Q: np.ndarray) -> np.ndarray:
     return np.asarray(G, dtype=F64) @ np.asarray(Q, dtype=F64)
 
 
+def grad_transform_taps(G4: np.ndarray, Q: np.ndarray) -> np.ndarray:
+    """Per-channel form of eq. (mod_weight_grad): a layer of eq. (vzrp3) has one S x M weight matrix W~_rn per spatial
+    offset n (for a convolution: per kernel tap, M = Cin), and every one of them is multiplied by the same M x M Q.
+    G4 is [S, Cin, kh, kw] (the layout of a convolution weight); Q is [Cin, Cin]."""
+    G4 = np.asarray(G4, dtype=F64)
+    Q = np.asarray(Q, dtype=F64)
+    out = np.empty_like(G4)
+    for ky in range(G4.shape[2]):
+        for kx in range(G4.shape[3]):
+            out[:, :, ky, kx] = G4[:, :, ky, kx] @ Q
+    return out
+
+
+def sgd_update(W: np.ndarray, V, G: np.ndarray, Q: np.ndarray, lr: float, momentum: float = 0.0, weight_decay: float = 0.0):
+    """One update of the stored weights W~ [S, M] from the raw gradient G [S, M]:
+
+        d  = G Q + weight_decay * W~          eq. (mod_weight_grad), plus the decay term of Sec. 6
+        V' = momentum * V + d                 (V' = d when there is no momentum buffer yet: V is None)
+        W~' = W~ - lr * V'                    eq. (vtWrn_SGD)
+
+    With momentum = weight_decay = 0 this is exactly eqs. (vtWrn_SGD), (mod_weight_grad).  Sec. 6 only names "momentum
+    0.9" and "weight decay" without formulas; the reading is the common heavy-ball form with the decay term added to
+    the already transformed gradient (it acts on the stored parameter W~).  That convention is parity unpinned by the
+    paper; its arithmetic is pinned by closed forms (geometric sums) in the tests.
+    Returns (W~', V')."""
+    W = np.asarray(W, dtype=F64)
+    d = grad_transform(G, Q) + weight_decay * W
+    Vn = d if V is None else momentum * np.asarray(V, dtype=F64) + d
+    return W - lr * Vn, Vn
+
+
 # --- the direct method of Sec. 2, used only to pin the equivalence claimed in Sec. 3.1 ---------
 def direct_whiten_forward(X: np.ndarray, mu: np.ndarray, T: np.ndarray) -> np.ndarray:
     """y = T (x - mu) for every row, eq. (vyn)."""

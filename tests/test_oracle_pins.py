@@ -237,6 +237,75 @@ def test_bias_compensation_keeps_the_layer_output():
     assert np.allclose(W @ (x - mu0) + b, W @ (x - mu1) + b1)
 
 
+def test_sgd_update_reduces_to_the_plain_rule_and_to_geometric_sums():
+    """Momentum and decay arithmetic against closed forms: constant gradient -> W_k = W_0 - lr GQ sum_j (1-m^j)/(1-m);
+    zero gradient with decay only -> W_k = (1 - lr wd)^k W_0."""
+    S, M, lr, m = 3, 5, 0.1, 0.9
+    W0, G = rng0.standard_normal((S, M)), rng0.standard_normal((S, M))
+    T = np.eye(M) + 0.2 * rng0.standard_normal((M, M))
+    Q = T.T @ T
+    W1, V1 = ora.sgd_update(W0, None, G, Q, lr)
+    assert np.allclose(W1, W0 - lr * G @ T.T @ T, atol=1e-14) and np.allclose(V1, G @ Q)
+    W, V = W0, None
+    for k in range(1, 8):
+        W, V = ora.sgd_update(W, V, G, Q, lr, momentum=m)
+        geo = sum((1 - m ** j) / (1 - m) for j in range(1, k + 1))
+        assert np.allclose(W, W0 - lr * geo * (G @ Q), atol=1e-12)
+    W, V = W0, None
+    for k in range(1, 6):
+        W, V = ora.sgd_update(W, V, np.zeros((S, M)), Q, lr, weight_decay=0.05)
+        assert np.allclose(W, (1 - lr * 0.05) ** k * W0, atol=1e-14)
+    # decay acts on the stored parameter, not through Q
+    W2, _ = ora.sgd_update(W0, None, G, Q, lr, weight_decay=0.5)
+    assert np.allclose(W2, W0 - lr * (G @ Q) - lr * 0.5 * W0, atol=1e-14)
+
+
+def test_per_tap_transform_equals_direct_whitening_of_a_convolution():
+    """Per-channel form (eq. (vzrp3) with one weight matrix per kernel tap): a 3x3 valid convolution on channel-whitened
+    input y = T(x - mu), updated by plain SGD, equals the convolution with W~[:, :, ky, kx] = W[:, :, ky, kx] T on the
+    centred input updated with every tap's gradient times Q = T^T T.  Convolutions by explicit loops."""
+    B, C, H, Wd, S, k, eta = 2, 3, 5, 4, 2, 3, 0.07
+    x = rng0.standard_normal((B, C, H, Wd)) + 0.5
+    mu = x.mean(axis=(0, 2, 3))
+    T = np.eye(C) + 0.3 * rng0.standard_normal((C, C))
+    Wc = rng0.standard_normal((S, C, k, k))
+    Ho, Wo = H - k + 1, Wd - k + 1
+    tgt = rng0.standard_normal((B, S, Ho, Wo))
+
+    def conv(inp, Wt):
+        out = np.zeros((B, S, Ho, Wo))
+        for b_ in range(B):
+            for s_ in range(S):
+                for oy in range(Ho):
+                    for ox in range(Wo):
+                        out[b_, s_, oy, ox] = sum(Wt[s_, c, ky, kx] * inp[b_, c, oy + ky, ox + kx]
+                                                   for c in range(C) for ky in range(k) for kx in range(k))
+        return out
+
+    def wgrad(inp, D):
+        g = np.zeros((S, C, k, k))
+        for s_ in range(S):
+            for c in range(C):
+                for ky in range(k):
+                    for kx in range(k):
+                        g[s_, c, ky, kx] = sum(D[b_, s_, oy, ox] * inp[b_, c, oy + ky, ox + kx]
+                                               for b_ in range(B) for oy in range(Ho) for ox in range(Wo))
+        return g
+
+    xc = x - mu[None, :, None, None]
+    y = np.einsum("dc,bchw->bdhw", T, xc)
+    Z = conv(y, Wc)
+    W_direct = Wc - eta * wgrad(y, Z - tgt)
+    Wt = np.einsum("sdkl,dc->sckl", Wc, T)            # W~ = W T, tap by tap
+    Zt = conv(xc, Wt)
+    assert np.allclose(Z, Zt)
+    G4 = wgrad(xc, Zt - tgt)
+    Wt_new = Wt - eta * ora.grad_transform_taps(G4, ora.Q_from_T(T))
+    assert np.allclose(Wt_new, np.einsum("sdkl,dc->sckl", W_direct, T), atol=1e-12)
+    wrong = Wt - eta * ora.grad_transform_taps(G4, T @ T.T)
+    assert not np.allclose(wrong, np.einsum("sdkl,dc->sckl", W_direct, T), atol=1e-6)
+
+
 # ----------------------------------------------------------------------------- recursive whitening
 def _rank1_plus_noise(M, snr, seed):
     r = np.random.default_rng(seed)
