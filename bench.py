@@ -120,11 +120,18 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False):
             fn()
         e1.record(); torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
+    # the companions outside the step: fused weight update (momentum 0.9, decay 5e-4: Sec. 6) and the whiteness figure
+    Wt, Vt = torch.randn(S, M, device=dev), torch.zeros(S, M, device=dev)
+    sgd = b.sgd_params(0.1, 0.9, 5e-4)
+    diag_out = torch.zeros(4, device=dev)
+    ws_diag = torch.empty(b.fw_workspace_bytes(b.FW_OP_DIAGNOSTICS, M), dtype=torch.uint8, device=dev)
     out = {"M": M, "S": S, "n_rows": n_rows, "bf16": bf16, "ms_per_step": ms_per_step, "cov_ms": cov_ms,
            "cond_ms": time_call(lambda: b.fw_cond_reduce_step(st, prm, info, ws_cond)),
            "grad_ms": time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)),
            "fin_ms": time_call(lambda: b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar)),
            "refresh_ms": time_call(lambda: b.fw_cond_state_refresh(st), reps=5),
+           "sgd_ms": time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt)),
+           "diag_ms": time_call(lambda: b.fw_diagnostics(Py, None, M, diag_out, ws_diag)),
            "gamma": prm.gamma, "act_bytes": float(X.numel() * X.element_size()), "step": step}
     if evd:   # the EVD / ZCA reference construction replaces the recursive step; timed once, outside the headline
         ws_evd = torch.empty(b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, M), dtype=torch.uint8, device=dev)
@@ -230,6 +237,8 @@ def main():
     # once per block when the data (hence Phi_x) changes between blocks; the timed step feeds the same batch again, so
     # Phi_x is stationary there and the call is not part of the step
     out["breakdown_ms"]["cond_state_refresh_per_block"] = r["refresh_ms"]
+    out["breakdown_ms"]["sgd_update_fused"] = r["sgd_ms"]
+    out["breakdown_ms"]["diagnostics_whiteness"] = r["diag_ms"]
     out["cond_state_refresh_TFLOPs"] = 4.0 * M * M * M / (r["refresh_ms"] * 1e-3) / 1e12
     if "evd_ms" in r:
         out["breakdown_ms"]["whiten_evd"] = r["evd_ms"]

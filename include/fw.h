@@ -61,7 +61,8 @@ typedef struct { int B, Cin, H, W, kh, kw, stride, pad; } fw_conv_desc;
 
 /* Operations for fw_workspace_bytes. */
 typedef enum {
-    FW_OP_COV_ACCUMULATE = 0, FW_OP_GRAD_TRANSFORM = 1, FW_OP_COND_REDUCE_STEP = 2, FW_OP_WHITEN_EVD = 3, FW_OP_COND_STATE_REFRESH = 4
+    FW_OP_COV_ACCUMULATE = 0, FW_OP_GRAD_TRANSFORM = 1, FW_OP_COND_REDUCE_STEP = 2, FW_OP_WHITEN_EVD = 3, FW_OP_COND_STATE_REFRESH = 4,
+    FW_OP_GRAD_TRANSFORM_TAPS = 5, FW_OP_SGD_UPDATE = 6, FW_OP_DIAGNOSTICS = 7
 } fw_op;
 
 /* ------------------------------------------------------------------------------------------------------------
@@ -118,6 +119,44 @@ fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, fl
  */
 fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const float* T, const float* Q,
                             void* G_out, void* ws, size_t ws_bytes, void* stream);
+
+/* Per-tap form of eq. (mod_weight_grad): a layer of eq. (vzrp3) has one S x M weight matrix per spatial offset n, and
+ * each of their gradients is multiplied by the same Q.  For a convolution whitened per input channel (M = Cin, the
+ * whitening placed in front of the convolution, Sec. 6) the offsets are the kernel taps:
+ *   G_out[s][:][t] = G[s][:][t] Q   for every tap t
+ *   G, G_out   [S, M, taps] element type `dt` (the layout of a convolution weight [S, Cin, kh, kw], taps = kh kw);
+ *              must not overlap.  A channels-last weight [S, kh, kw, Cin] is plain [S taps, M] rows: use fw_grad_transform.
+ *   Q          [M, M] float32, symmetric
+ *   ws         scratch, fw_workspace_bytes(FW_OP_GRAD_TRANSFORM_TAPS, M, S * taps, NULL, dt) bytes (the gradient as rows)
+ * Products are float32 on the matrix cores for both element types; bfloat16 results are rounded to nearest even.
+ */
+fw_status fw_grad_transform_taps(const void* G, fw_dtype dt, int S, int M, int taps, const float* Q, void* G_out,
+                                 void* ws, size_t ws_bytes, void* stream);
+
+/* Weight update with the transformed gradient fused into the product -- eqs. (vtWrn_SGD), (mod_weight_grad); momentum
+ * and weight decay as named in Sec. 6 (heavy-ball form; the decay acts on the stored parameter):
+ *   d = G Q + weight_decay W;   V = momentum V + d  (when momentum > 0);   W -= lr (V, or d without momentum)
+ *   G      in      [S, M] (taps = 1) or [S, M, taps], element type `dt`; not overlapping W or V
+ *   W      in/out  stored weights W~, float32, same shape as G
+ *   V      in/out  momentum buffer, float32, same shape, zero before the first update; may be NULL when momentum = 0
+ *   ws     scratch, fw_workspace_bytes(FW_OP_SGD_UPDATE, M, S * taps, NULL, dt) bytes; not needed for FW_F32 with taps = 1
+ * The transformed gradient itself is not written anywhere.
+ */
+typedef struct { float lr, momentum, weight_decay; } fw_sgd_params;
+fw_status fw_sgd_update(const void* G, fw_dtype dt, int S, int M, int taps, const float* Q, const fw_sgd_params* p,
+                        float* W, float* V, void* ws, size_t ws_bytes, void* stream);
+
+/* Bias compensation when the tracked mean moves at a block boundary -- Sec. 3.1, eq. (vtb_corr):
+ *   b[s] += scale * sum_{c,t} W[s][c][t] (mu_new[c] - mu_old[c])
+ * so that sum W~ (x - mu) + b is the same before and after (new mean minus old mean: the sign that keeps that relation;
+ * the printed equation has the two means swapped).
+ *   b        in/out  [S] float32
+ *   W        in      [S, M] (taps = 1) or [S, M, taps] float32
+ *   mu_old, mu_new   [M] float32
+ *   scale    the factor (1/R) sum_r of the equation for weights shared over the R output positions: 1
+ */
+fw_status fw_bias_compensate(float* b, const float* W, int S, int M, int taps, const float* mu_old, const float* mu_new,
+                             float scale, void* stream);
 
 /* ------------------------------------------------------------------------------------------------------------
  * (3) Recursive condition-number reduction -- Sec. 4 (eqs. (lambda)-(vQ_rec), (xim)-(tve)).
@@ -199,7 +238,20 @@ typedef struct {
 fw_status fw_whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float* T, float* Q, float* Qs,
                         float* lambda, void* ws, size_t ws_bytes, void* stream);
 
-/* Scratch bytes an entry point needs for the given sizes (0 if none).  `d` is needed for FW_OP_COV_ACCUMULATE only. */
+/* Monitoring figures of Sec. 6.
+ *   Phi_y   in   [M, M] float32 with positive diagonal, or NULL:  out[0] = rho = M / sum_{m,m'} Phi_y[m'][m]^2 /
+ *                (Phi_y[m][m] Phi_y[m'][m'])   (eq. (rho), summed over all pairs, m = m' included: the reading that has
+ *                both stated extremes, 1 for a diagonal matrix and 1/M for fully correlated features)
+ *   lambda  in   [M] float32 eigenvalues (any order), or NULL:  out[2] = Ms_hat = exp(-sum lb log lb), lb = lambda /
+ *                sum(lambda), non-positive eigenvalues counted as zero (eq. (hMs), read as the exponential of the spectral
+ *                entropy);  out[1] = kappa = Ms_hat / M
+ *   out     out  device float32[3]; entries whose input is NULL are left alone
+ *   ws      scratch, fw_workspace_bytes(FW_OP_DIAGNOSTICS, M, 0, NULL, FW_F32) bytes, needed when Phi_y is given
+ */
+fw_status fw_diagnostics(const float* Phi_y, const float* lambda, int M, float* out, void* ws, size_t ws_bytes, void* stream);
+
+/* Scratch bytes an entry point needs for the given sizes (0 if none).  `d` is needed for FW_OP_COV_ACCUMULATE only;
+ * for the per-tap operations S is the number of gradient rows, S * taps. */
 size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtype dt);
 
 const char* fw_status_string(fw_status st);

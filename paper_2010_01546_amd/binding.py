@@ -21,10 +21,13 @@ lib = C.CDLL(LIB_PATH)
 FW_OK, FW_ERR_INVALID_ARG, FW_ERR_UNSUPPORTED, FW_ERR_ALIGNMENT, FW_ERR_WORKSPACE, FW_ERR_HIP, FW_ERR_NOT_CONVERGED = range(7)
 FW_F32, FW_BF16 = 0, 1
 FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
-FW_OP_COV_ACCUMULATE, FW_OP_GRAD_TRANSFORM, FW_OP_COND_REDUCE_STEP, FW_OP_WHITEN_EVD, FW_OP_COND_STATE_REFRESH = range(5)
+(FW_OP_COV_ACCUMULATE, FW_OP_GRAD_TRANSFORM, FW_OP_COND_REDUCE_STEP, FW_OP_WHITEN_EVD, FW_OP_COND_STATE_REFRESH,
+ FW_OP_GRAD_TRANSFORM_TAPS, FW_OP_SGD_UPDATE, FW_OP_DIAGNOSTICS) = range(8)
 
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",
-           "fw_whiten_evd", "fw_cond_state_refresh", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+           "fw_whiten_evd", "fw_cond_state_refresh", "fw_grad_transform_taps", "fw_sgd_update", "fw_bias_compensate",
+           "fw_diagnostics", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+N_STATUS_EXPORTS = 11   # the leading entries of EXPORTS return fw_status
 
 
 class fw_conv_desc(C.Structure):
@@ -46,6 +49,10 @@ class fw_cond_info(C.Structure):
                 ("m_prime", C.c_int), ("set_size", C.c_int), ("applied", C.c_int), ("flags", C.c_int)]
 
 
+class fw_sgd_params(C.Structure):
+    _fields_ = [("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float)]
+
+
 class fw_evd_params(C.Structure):
     _fields_ = [("eps", C.c_float), ("g_max", C.c_float), ("beta", C.c_float), ("tol", C.c_float),
                 ("gain_mode", C.c_int), ("max_sweeps", C.c_int)]
@@ -59,12 +66,16 @@ lib.fw_cond_state_init.argtypes = [C.POINTER(fw_cond_state), _P]
 lib.fw_cond_state_refresh.argtypes = [C.POINTER(fw_cond_state), _P, C.c_size_t, _P]
 lib.fw_cond_reduce_step.argtypes = [C.POINTER(fw_cond_state), C.POINTER(fw_cond_params), _P, _P, C.c_size_t, _P]
 lib.fw_whiten_evd.argtypes = [_P, C.c_int, C.POINTER(fw_evd_params), _P, _P, _P, _P, _P, C.c_size_t, _P]
+lib.fw_grad_transform_taps.argtypes = [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, _P, C.c_size_t, _P]
+lib.fw_sgd_update.argtypes = [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.POINTER(fw_sgd_params), _P, _P, _P, C.c_size_t, _P]
+lib.fw_bias_compensate.argtypes = [_P, _P, C.c_int, C.c_int, C.c_int, _P, _P, C.c_float, _P]
+lib.fw_diagnostics.argtypes = [_P, _P, C.c_int, _P, _P, C.c_size_t, _P]
 lib.fw_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.c_int]
 lib.fw_workspace_bytes.restype = C.c_size_t
 lib.fw_status_string.argtypes = [C.c_int]
 lib.fw_status_string.restype = C.c_char_p
 lib.fw_version.restype = C.c_int
-for _n in EXPORTS[:7]:
+for _n in EXPORTS[:N_STATUS_EXPORTS]:
     getattr(lib, _n).restype = C.c_int
 
 
@@ -131,6 +142,32 @@ def fw_cov_finalize(A, s, n, M, alpha, first_block, mu, Phi_x, phi_x, lambda_bar
 def fw_grad_transform(G, dt, S, M, T, Q, G_out, ws=None, stream=None):
     p, n = _ws(ws)
     return _check(lib.fw_grad_transform(_ptr(G), dt, S, M, _ptr(T), _ptr(Q), _ptr(G_out), p, n, _stream(stream)), "fw_grad_transform")
+
+
+def fw_grad_transform_taps(G, dt, S, M, taps, Q, G_out, ws, stream=None):
+    p, n = _ws(ws)
+    return _check(lib.fw_grad_transform_taps(_ptr(G), dt, S, M, taps, _ptr(Q), _ptr(G_out), p, n, _stream(stream)),
+                  "fw_grad_transform_taps")
+
+
+def sgd_params(lr, momentum=0.0, weight_decay=0.0) -> fw_sgd_params:
+    return fw_sgd_params(lr, momentum, weight_decay)
+
+
+def fw_sgd_update(G, dt, S, M, taps, Q, p, W, V=None, ws=None, stream=None):
+    wp, n = _ws(ws)
+    return _check(lib.fw_sgd_update(_ptr(G), dt, S, M, taps, _ptr(Q), C.byref(p), _ptr(W), _ptr(V), wp, n, _stream(stream)),
+                  "fw_sgd_update")
+
+
+def fw_bias_compensate(b, W, S, M, taps, mu_old, mu_new, scale=1.0, stream=None):
+    return _check(lib.fw_bias_compensate(_ptr(b), _ptr(W), S, M, taps, _ptr(mu_old), _ptr(mu_new), float(scale), _stream(stream)),
+                  "fw_bias_compensate")
+
+
+def fw_diagnostics(Phi_y, lam, M, out, ws=None, stream=None):
+    wp, n = _ws(ws)
+    return _check(lib.fw_diagnostics(_ptr(Phi_y), _ptr(lam), M, _ptr(out), wp, n, _stream(stream)), "fw_diagnostics")
 
 
 def cond_state(M, Phi_x, lambda_bar, T, Q, Qs, Phi_y, Psi, xi2) -> fw_cond_state:

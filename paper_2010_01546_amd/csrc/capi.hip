@@ -23,8 +23,8 @@ size_t grad_ws_bytes(int M) {
            cov_workspace_bytes(M, &d, FW_F32, FW_LAYOUT_ROWS);
 }
 
-// bfloat16 gradients: two [S, M] float32 copies behind the area of the Q build
-size_t grad_wide_bytes(int S, int M) { return 2 * align_up((size_t)S * M * sizeof(float), 256); }
+// bfloat16 (or per-tap) gradients: a float32 copy of the gradient as [rows, M]
+size_t grad_wide_bytes(long long rows, int M) { return align_up((size_t)rows * M * sizeof(float), 256); }
 
 }  // namespace
 
@@ -75,11 +75,66 @@ fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const floa
         Q = Qb;
     }
     if (dt == FW_BF16 && ws && ws_bytes >= grad_ws_bytes(M) + grad_wide_bytes(S, M)) {
+        // widened to float32 in the workspace, multiplied in float32, rounded to bfloat16 as the results are stored
         float* G32 = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + grad_ws_bytes(M));
-        float* O32 = reinterpret_cast<float*>(reinterpret_cast<char*>(G32) + grad_wide_bytes(S, M) / 2);
-        return grad_gemm_bf16_widened(G, S, M, Q, G_out, G32, O32, st);
+        const fw_status rc = grad_stage_rows(G, FW_BF16, S, M, 1, G32, st);
+        if (rc != FW_OK) return rc;
+        GemmEpilogue e = {};
+        e.out = G_out; e.out_bf16 = 1; e.taps = 1;
+        return grad_gemm_f32(G32, S, M, Q, e, st);
     }
     return grad_gemm(G, dt, S, M, Q, G_out, st);
+}
+
+fw_status fw_grad_transform_taps(const void* G, fw_dtype dt, int S, int M, int taps, const float* Q, void* G_out, void* ws,
+                                 size_t ws_bytes, void* stream) {
+    if (!G || !G_out || !Q || S <= 0 || M <= 0 || taps <= 0 || !dtype_ok(dt) || G == G_out) return FW_ERR_INVALID_ARG;
+    if (M > 16384 || (long long)S * taps >= (1ll << 31) / 64) return FW_ERR_UNSUPPORTED;
+    if (!aligned16(G) || !aligned16(G_out) || !aligned16(Q) || (ws && !aligned16(ws))) return FW_ERR_ALIGNMENT;
+    if (!ws || ws_bytes < grad_wide_bytes((long long)S * taps, M)) return FW_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    float* rows = reinterpret_cast<float*>(ws);
+    const fw_status rc = grad_stage_rows(G, dt, S, M, taps, rows, st);
+    if (rc != FW_OK) return rc;
+    GemmEpilogue e = {};
+    e.out = G_out; e.out_bf16 = dt == FW_BF16 ? 1 : 0; e.taps = taps;
+    return grad_gemm_f32(rows, S * taps, M, Q, e, st);
+}
+
+fw_status fw_sgd_update(const void* G, fw_dtype dt, int S, int M, int taps, const float* Q, const fw_sgd_params* p, float* W, float* V,
+                        void* ws, size_t ws_bytes, void* stream) {
+    if (!G || !Q || !p || !W || S <= 0 || M <= 0 || taps <= 0 || !dtype_ok(dt) || G == (const void*)W || G == (const void*)V || W == V)
+        return FW_ERR_INVALID_ARG;
+    if (!(p->lr >= 0.f) || !(p->momentum >= 0.f && p->momentum < 1.f) || !(p->weight_decay >= 0.f)) return FW_ERR_INVALID_ARG;
+    if (p->momentum > 0.f && !V) return FW_ERR_INVALID_ARG;
+    if (M > 16384 || (long long)S * taps >= (1ll << 31) / 64) return FW_ERR_UNSUPPORTED;
+    if (!aligned16(G) || !aligned16(Q) || !aligned16(W) || (V && !aligned16(V)) || (ws && !aligned16(ws))) return FW_ERR_ALIGNMENT;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const float* rows = reinterpret_cast<const float*>(G);
+    if (dt == FW_BF16 || taps > 1) {
+        if (!ws || ws_bytes < grad_wide_bytes((long long)S * taps, M)) return FW_ERR_WORKSPACE;
+        const fw_status rc = grad_stage_rows(G, dt, S, M, taps, reinterpret_cast<float*>(ws), st);
+        if (rc != FW_OK) return rc;
+        rows = reinterpret_cast<const float*>(ws);
+    }
+    GemmEpilogue e = {};
+    e.taps = taps; e.W = W; e.V = p->momentum > 0.f ? V : nullptr;
+    e.lr = p->lr; e.momentum = p->momentum; e.wd = p->weight_decay;
+    return grad_gemm_f32(rows, S * taps, M, Q, e, st);
+}
+
+fw_status fw_bias_compensate(float* b, const float* W, int S, int M, int taps, const float* mu_old, const float* mu_new, float scale,
+                             void* stream) {
+    if (!b || !W || !mu_old || !mu_new || S <= 0 || M <= 0 || taps <= 0) return FW_ERR_INVALID_ARG;
+    return bias_compensate(b, W, S, M, taps, mu_old, mu_new, scale, reinterpret_cast<hipStream_t>(stream));
+}
+
+fw_status fw_diagnostics(const float* Phi_y, const float* lambda, int M, float* out, void* ws, size_t ws_bytes, void* stream) {
+    if ((!Phi_y && !lambda) || !out || M <= 0) return FW_ERR_INVALID_ARG;
+    if (M > 16384) return FW_ERR_UNSUPPORTED;
+    if ((Phi_y && !aligned16(Phi_y)) || (ws && !aligned16(ws))) return FW_ERR_ALIGNMENT;
+    if (Phi_y && (!ws || ws_bytes < diagnostics_workspace_bytes(M))) return FW_ERR_WORKSPACE;
+    return diagnostics(Phi_y, lambda, M, out, ws, reinterpret_cast<hipStream_t>(stream));
 }
 
 fw_status fw_cond_state_init(const fw_cond_state* st, void* stream) {
@@ -148,6 +203,9 @@ size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtyp
         case FW_OP_COND_REDUCE_STEP: return M > 0 && M <= 16384 ? cond_workspace_bytes(M) : 0;
         case FW_OP_WHITEN_EVD: return M > 0 && M <= 16384 ? evd_workspace_bytes(M) : 0;
         case FW_OP_COND_STATE_REFRESH: return M > 0 && M <= 16384 ? align_up((size_t)M * M * sizeof(float), 256) : 0;
+        case FW_OP_GRAD_TRANSFORM_TAPS:
+        case FW_OP_SGD_UPDATE: return (M > 0 && M <= 16384 && S > 0) ? grad_wide_bytes(S, M) : 0;
+        case FW_OP_DIAGNOSTICS: return M > 0 && M <= 16384 ? diagnostics_workspace_bytes(M) : 0;
     }
     return 0;
 }
@@ -165,6 +223,6 @@ const char* fw_status_string(fw_status st) {
     return "unknown status";
 }
 
-int fw_version(void) { return 100; }
+int fw_version(void) { return 101; }
 
 }  // extern "C"

@@ -80,8 +80,24 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
                               size_t ws_bytes, hipStream_t st);
 
 // ---- gemm.hip
+// what the float32 product does with its result (see emit() in gemm.hip)
+struct GemmEpilogue {
+    void* out;        // transformed gradient, float32 or bfloat16 bits, or null
+    int out_bf16;
+    int taps;         // 1: [S, M]; > 1: the product ran on [S * taps, M] rows and results go to [S, M, taps]
+    float* W;         // stored weights to update in place, or null
+    float* V;         // momentum buffer, or null
+    float lr, momentum, wd;
+};
 fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st);
-fw_status grad_gemm_bf16_widened(const void* G, int S, int M, const float* Q, void* G_out, float* G32, float* O32, hipStream_t st);
+fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const GemmEpilogue& e, hipStream_t st);
+fw_status grad_stage_rows(const void* G, fw_dtype dt, int S, int M, int taps, float* dst, hipStream_t st);
+
+// ---- extras.hip
+fw_status bias_compensate(float* b, const float* W, int S, int M, int taps, const float* mu_old, const float* mu_new, float scale,
+                          hipStream_t st);
+size_t diagnostics_workspace_bytes(int M);
+fw_status diagnostics(const float* Phi_y, const float* lambda, int M, float* out, void* ws, hipStream_t st);
 
 // ---- cond.hip
 size_t cond_workspace_bytes(int M);

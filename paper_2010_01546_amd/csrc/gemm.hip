@@ -42,6 +42,34 @@ struct Mfma<16> {
     static __device__ __forceinline__ int row(int i, int lk) { return 4 * lk + i; }
 };
 
+// What the float32 kernels do with a finished element (row, col) of G Q, value v:
+//   taps == 1: element index row * M + col.  taps > 1 (per-tap form): the product ran on rows (s, tap) of the permuted
+//   gradient, and the element belongs at [s][col][tap] of an [S, M, taps] array (the layout of a convolution weight).
+//   out (float32, or bfloat16 bits when out_bf16): the transformed gradient, written when non-null.
+//   W (and V): the update  d = v + wd W;  V = momentum V + d (if V);  W -= lr (V or d)   (eq. (vtWrn_SGD)).
+__device__ __forceinline__ void emit(const GemmEpilogue& e, int row, int col, int M, float v) {
+    size_t idx;
+    if (e.taps > 1) {
+        const int s = row / e.taps, t = row - s * e.taps;
+        idx = ((size_t)s * M + col) * e.taps + t;
+    } else {
+        idx = (size_t)row * M + col;
+    }
+    if (e.out) {
+        if (e.out_bf16) reinterpret_cast<unsigned short*>(e.out)[idx] = f32_to_bf16_rne(v);
+        else reinterpret_cast<float*>(e.out)[idx] = v;
+    }
+    if (e.W) {
+        const float w = e.W[idx];
+        float d = v + e.wd * w;
+        if (e.V) {
+            d = e.momentum * e.V[idx] + d;
+            e.V[idx] = d;
+        }
+        e.W[idx] = w - e.lr * d;
+    }
+}
+
 // float4 per lane, panel and chunk: enough for about 2000 cycles of MFMAs per chunk and wavefront, within an LDS stage
 // of at most 80 KB
 __host__ __device__ constexpr int strip_u(int mf, int c) {
@@ -68,9 +96,11 @@ struct StripCfg {
     static __device__ __forceinline__ int swz(int r) { return QR == 8 ? (r >> 1) & 7 : r & 15; }
 };
 
-template <int MF, int C>
+// PLAIN: the result is a float32 [S, M] array and nothing else happens to it (the epilogue's other fields are ignored);
+// kept as an instantiation of its own so that the general epilogue costs the plain product no registers.
+template <int MF, int C, bool PLAIN>
 __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* __restrict__ G, const float* __restrict__ Q,
-                                                                  float* __restrict__ Out, int S, int M) {
+                                                                  GemmEpilogue Out, int S, int M) {
     typedef StripCfg<MF, C> K;
     typedef typename Mfma<MF>::acc_t acc_t;
     __shared__ __attribute__((aligned(16))) float sm[K::SMEM];
@@ -218,7 +248,10 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
 #pragma unroll
                     for (int w = 0; w < 4; ++w) v += (w == q) ? acc[(4 * g + q) % C][i] : red[((q * 4 + w) * K::NACC + i) * 64 + lane];
                     const int row = row0 + Mfma<MF>::row(i, lk);
-                    if (row < S && col < M) Out[(size_t)row * M + col] = v;
+                    if (row < S && col < M) {
+                        if (PLAIN) reinterpret_cast<float*>(Out.out)[(size_t)row * M + col] = v;
+                        else emit(Out, row, col, M, v);
+                    }
                 }
             }
         }
@@ -249,23 +282,28 @@ inline StripChoice pick_strip(int S, int M) {
 }
 
 template <int MF>
-void launch_strip(int c, const float* G, const float* Q, float* Out, int S, int M, hipStream_t st) {
+void launch_strip(int c, const float* G, const float* Q, const GemmEpilogue& Out, int S, int M, hipStream_t st) {
     const dim3 grid(((M + MF - 1) / MF + c - 1) / c, (S + MF - 1) / MF);
+    const bool plain = Out.out && !Out.out_bf16 && Out.taps == 1 && !Out.W;
+#define FW_STRIP_LAUNCH(CC)                                                                                                \
+    if (plain) hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, CC, true>), grid, dim3(256), 0, st, G, Q, Out, S, M);   \
+    else hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, CC, false>), grid, dim3(256), 0, st, G, Q, Out, S, M)
     switch (c) {
-        case 9: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 9>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
-        case 6: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 6>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
-        case 4: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 4>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
-        case 3: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 3>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
-        case 2: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 2>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
-        default: hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, 1>), grid, dim3(256), 0, st, G, Q, Out, S, M); break;
+        case 9: FW_STRIP_LAUNCH(9); break;
+        case 6: FW_STRIP_LAUNCH(6); break;
+        case 4: FW_STRIP_LAUNCH(4); break;
+        case 3: FW_STRIP_LAUNCH(3); break;
+        case 2: FW_STRIP_LAUNCH(2); break;
+        default: FW_STRIP_LAUNCH(1); break;
     }
+#undef FW_STRIP_LAUNCH
 }
 
 // M not a multiple of 4 (rows of G and Q not 16-byte aligned): a workgroup owns a 32x32 tile of G_out and its four
 // wavefronts split the contraction index four ways; operands come straight from global memory / L2 with scalar
 // loads (Q along its rows, like the other kernels), partial tiles are combined through LDS.
 __global__ __launch_bounds__(256) void grad_gemm_f32_small_kernel(const float* __restrict__ G, const float* __restrict__ Q,
-                                                                  float* __restrict__ Out, int S, int M) {
+                                                                  GemmEpilogue Out, int S, int M) {
     __shared__ float red[3][32 * 32];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -309,7 +347,7 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_small_kernel(const float* _
         for (int i = 0; i < 16; ++i) {
             const int rr = 8 * (i >> 2) + 4 * half + (i & 3);
             const float v = acc[i] + red[0][rr * 32 + l32] + red[1][rr * 32 + l32] + red[2][rr * 32 + l32];
-            if (row0 + rr < S && c_ok) Out[(size_t)(row0 + rr) * M + c] = v;
+            if (row0 + rr < S && c_ok) emit(Out, row0 + rr, c, M, v);
         }
     }
 }
@@ -365,7 +403,7 @@ __global__ __launch_bounds__(256) void grad_gemm_bf16_kernel(const unsigned shor
         }
 }
 
-// bfloat16 <-> float32 copies of G and G_out for the widened path of the bfloat16 gradient transform
+// bfloat16 -> float32 copy of G for the widened path of the bfloat16 gradient transform
 __global__ __launch_bounds__(256) void widen_bf16_kernel(const unsigned short* __restrict__ src, float* __restrict__ dst, size_t n) {
     for (size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8; e < n; e += (size_t)gridDim.x * 256 * 8) {
         if (e + 8 <= n) {
@@ -382,53 +420,63 @@ __global__ __launch_bounds__(256) void widen_bf16_kernel(const unsigned short* _
         }
     }
 }
-__global__ __launch_bounds__(256) void narrow_bf16_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst, size_t n) {
-    for (size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8; e < n; e += (size_t)gridDim.x * 256 * 8) {
-        if (e + 8 <= n) {
-            const float4 lo = *reinterpret_cast<const float4*>(src + e), hi = *reinterpret_cast<const float4*>(src + e + 4);
-            uint4 v;
-            v.x = (unsigned)f32_to_bf16_rne(lo.x) | ((unsigned)f32_to_bf16_rne(lo.y) << 16);
-            v.y = (unsigned)f32_to_bf16_rne(lo.z) | ((unsigned)f32_to_bf16_rne(lo.w) << 16);
-            v.z = (unsigned)f32_to_bf16_rne(hi.x) | ((unsigned)f32_to_bf16_rne(hi.y) << 16);
-            v.w = (unsigned)f32_to_bf16_rne(hi.z) | ((unsigned)f32_to_bf16_rne(hi.w) << 16);
-            *reinterpret_cast<uint4*>(dst + e) = v;
-        } else {
-            for (size_t k = e; k < n; ++k) dst[k] = f32_to_bf16_rne(src[k]);
-        }
+
+// [S, M, taps] (float32 or bfloat16 bits) -> [S * taps, M] float32; one thread per element of the destination, so the
+// writes are contiguous and the strided reads of a wavefront fall into taps-times as many cache lines
+__global__ __launch_bounds__(256) void taps_to_rows_kernel(const void* __restrict__ src, int is_bf16, int S, int M, int taps,
+                                                           float* __restrict__ dst) {
+    const size_t n = (size_t)S * M * taps;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256) {
+        const size_t row = e / M;
+        const int c = (int)(e - row * M);
+        const size_t s = row / taps;
+        const int t = (int)(row - s * taps);
+        const size_t i = (s * M + c) * taps + t;
+        dst[e] = is_bf16 ? bf16_to_f32(reinterpret_cast<const unsigned short*>(src)[i]) : reinterpret_cast<const float*>(src)[i];
     }
 }
 
 }  // namespace
 
-fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st) {
-    const dim3 grid((M + TN - 1) / TN, (S + TM - 1) / TM);
-    if (dt == FW_BF16)
-        hipLaunchKernelGGL(grad_gemm_bf16_kernel, grid, dim3(256), 0, st, reinterpret_cast<const unsigned short*>(G), Q,
-                           reinterpret_cast<unsigned short*>(G_out), S, M);
-    else if ((M & 3) != 0)
-        hipLaunchKernelGGL(grad_gemm_f32_small_kernel, dim3((M + 31) / 32, (S + 31) / 32), dim3(256), 0, st,
-                           reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M);
+fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const GemmEpilogue& e, hipStream_t st) {
+    if ((M & 3) != 0)
+        hipLaunchKernelGGL(grad_gemm_f32_small_kernel, dim3((M + 31) / 32, (S + 31) / 32), dim3(256), 0, st, G, Q, e, S, M);
     else {
         const StripChoice ch = pick_strip(S, M);
-        if (ch.mf == 32) launch_strip<32>(ch.c, reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M, st);
-        else launch_strip<16>(ch.c, reinterpret_cast<const float*>(G), Q, reinterpret_cast<float*>(G_out), S, M, st);
+        if (ch.mf == 32) launch_strip<32>(ch.c, G, Q, e, S, M, st);
+        else launch_strip<16>(ch.c, G, Q, e, S, M, st);
     }
     FW_LAUNCH_CHECK();
     return FW_OK;
 }
 
-// G (bfloat16) widened to float32, multiplied by Q in float32 on the matrix cores, rounded back to bfloat16:
-// G32 and O32 are [S, M] float32 scratch.  S*M is a multiple of 8 elements apart from a scalar tail.
-fw_status grad_gemm_bf16_widened(const void* G, int S, int M, const float* Q, void* G_out, float* G32, float* O32, hipStream_t st) {
-    const size_t n = (size_t)S * M;
-    size_t blocks = (n / 8 + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    if (blocks == 0) blocks = 1;
-    hipLaunchKernelGGL(widen_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<const unsigned short*>(G), G32, n);
-    FW_LAUNCH_CHECK();
-    const fw_status rc = grad_gemm(G32, FW_F32, S, M, Q, O32, st);
-    if (rc != FW_OK) return rc;
-    hipLaunchKernelGGL(narrow_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, O32, reinterpret_cast<unsigned short*>(G_out), n);
+fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st) {
+    if (dt == FW_BF16) {
+        const dim3 grid((M + TN - 1) / TN, (S + TM - 1) / TM);
+        hipLaunchKernelGGL(grad_gemm_bf16_kernel, grid, dim3(256), 0, st, reinterpret_cast<const unsigned short*>(G), Q,
+                           reinterpret_cast<unsigned short*>(G_out), S, M);
+        FW_LAUNCH_CHECK();
+        return FW_OK;
+    }
+    GemmEpilogue e = {};
+    e.out = G_out; e.taps = 1;
+    return grad_gemm_f32(reinterpret_cast<const float*>(G), S, M, Q, e, st);
+}
+
+// bfloat16 (or per-tap) gradient -> float32 rows in scratch.  src is [S, M] (taps == 1) or [S, M, taps]; dst is
+// [S * taps, M] float32 with row s * taps + t holding src[s][:][t].
+fw_status grad_stage_rows(const void* G, fw_dtype dt, int S, int M, int taps, float* dst, hipStream_t st) {
+    const size_t n = (size_t)S * M * taps;
+    if (taps == 1 && dt == FW_BF16) {
+        size_t blocks = (n / 8 + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        if (blocks == 0) blocks = 1;
+        hipLaunchKernelGGL(widen_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<const unsigned short*>(G), dst, n);
+    } else {
+        size_t blocks = (n + 255) / 256;
+        if (blocks > 8192) blocks = 8192;
+        hipLaunchKernelGGL(taps_to_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, G, dt == FW_BF16 ? 1 : 0, S, M, taps, dst);
+    }
     FW_LAUNCH_CHECK();
     return FW_OK;
 }

@@ -1,0 +1,141 @@
+"""GPU parity of the companions of the gradient transform: per-tap transform, fused weight update, bias compensation
+(Sec. 3.1, eqs. (vtWrn_SGD), (mod_weight_grad), (vtb_corr)) and the monitoring figures of Sec. 6 (eq. (rho), kappa)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_common import b, dev, ora, relF, workspace, DEV
+
+pytestmark = pytest.mark.gpu
+
+
+def sym_q(M, seed):
+    rng = np.random.default_rng(seed)
+    T = np.eye(M) + 0.2 * rng.standard_normal((M, M)) / np.sqrt(M)
+    return (T.T @ T).astype(np.float32)
+
+
+def host(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("S,M,taps,dtype", [(5, 8, 9, "f32"), (33, 64, 9, "f32"), (64, 130, 9, "bf16"), (17, 67, 4, "f32"),
+                                            (40, 256, 9, "bf16"), (3, 5, 1, "f32"), (128, 512, 9, "f32"), (12, 96, 49, "bf16")])
+def test_per_tap_transform(S, M, taps, dtype):
+    rng = np.random.default_rng(S * 1000 + M)
+    G = (0.03 * rng.standard_normal((S, M, taps))).astype(np.float32)
+    if dtype == "bf16":
+        G = wl.round_to_bf16(G)
+    Q = sym_q(M, M)
+    tdt, dt = (torch.bfloat16, b.FW_BF16) if dtype == "bf16" else (torch.float32, b.FW_F32)
+    Gd = dev(G, tdt)
+    out = torch.full_like(Gd, float("nan"))
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM_TAPS, M, S * taps, None, dt))
+    b.fw_grad_transform_taps(Gd, dt, S, M, taps, dev(Q), out, ws)
+    torch.cuda.synchronize()
+    k = int(round(np.sqrt(taps)))
+    if k * k == taps:
+        want = ora.grad_transform_taps(G.reshape(S, M, k, k), Q).reshape(S, M, taps)
+    else:
+        want = np.stack([ora.grad_transform(G[:, :, t], Q) for t in range(taps)], axis=2)
+    assert relF(host(out), want) < (1e-4 if dtype == "f32" else 2e-2)
+    if dtype == "bf16":   # float32 products, one rounding at the end: each element within half a bfloat16 ulp
+        assert np.all(np.abs(host(out) - want) <= np.abs(want) * 2.0 ** -8 + 1e-6)   # + float32 error of the sum
+
+
+@pytest.mark.parametrize("S,M,taps,dtype,mom,wd", [(32, 64, 1, "f32", 0.0, 0.0), (64, 576, 1, "f32", 0.9, 5e-4), (19, 67, 1, "f32", 0.9, 1e-4),
+                                                   (48, 128, 9, "f32", 0.9, 5e-4), (40, 256, 1, "bf16", 0.9, 5e-4),
+                                                   (33, 96, 9, "bf16", 0.5, 0.0), (512, 2304, 1, "f32", 0.9, 1e-4)])
+def test_fused_weight_update(S, M, taps, dtype, mom, wd):
+    rng = np.random.default_rng(S + 7 * M + taps)
+    shape = (S, M) if taps == 1 else (S, M, taps)
+    W0 = rng.standard_normal(shape).astype(np.float32)
+    Q = sym_q(M, M + 1)
+    tdt, dt = (torch.bfloat16, b.FW_BF16) if dtype == "bf16" else (torch.float32, b.FW_F32)
+    Wd = dev(W0)
+    Vd = torch.zeros_like(Wd) if mom > 0 else None
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_SGD_UPDATE, M, S * taps, None, dt))
+    prm = b.sgd_params(0.1, mom, wd)
+    W_o, V_o = W0.astype(np.float64), None
+    for step in range(3):
+        G = (0.05 * rng.standard_normal(shape)).astype(np.float32)
+        if dtype == "bf16":
+            G = wl.round_to_bf16(G)
+        b.fw_sgd_update(dev(G, tdt), dt, S, M, taps, dev(Q), prm, Wd, Vd, ws if (dtype == "bf16" or taps > 1) else None)
+        torch.cuda.synchronize()
+        # teacher-forced: the oracle starts every update from the GPU's previous float32 state
+        W_prev = W_o
+        if taps == 1:
+            W_o, V_o = ora.sgd_update(W_prev, V_o, G, Q, 0.1, mom, wd)
+        else:
+            cols = [ora.sgd_update(W_prev[:, :, t], None if V_o is None else V_o[:, :, t], G[:, :, t], Q, 0.1, mom, wd) for t in range(taps)]
+            W_o, V_o = np.stack([c[0] for c in cols], axis=2), np.stack([c[1] for c in cols], axis=2)
+        assert relF(host(Wd) - W_prev, W_o - W_prev) < 1e-4, f"step {step}"     # the change itself, not W (it is tiny against W)
+        if Vd is not None:
+            assert relF(host(Vd), V_o) < 1e-4
+            V_o = host(Vd)
+        else:
+            V_o = None
+        W_o = host(Wd)
+
+
+def test_update_rejects_bad_arguments():
+    S, M = 8, 16
+    G, W, Q = torch.zeros(S, M, device=DEV), torch.zeros(S, M, device=DEV), torch.eye(M, device=DEV)
+    with pytest.raises(RuntimeError):
+        b.fw_sgd_update(G, b.FW_F32, S, M, 1, Q, b.sgd_params(0.1, 0.9), W, None)          # momentum without a buffer
+    with pytest.raises(RuntimeError):
+        b.fw_sgd_update(G, b.FW_F32, S, M, 9, Q, b.sgd_params(0.1), W, None)                # per-tap without workspace
+    with pytest.raises(RuntimeError):
+        b.fw_sgd_update(W, b.FW_F32, S, M, 1, Q, b.sgd_params(0.1), W, None)                # gradient aliases the weights
+    with pytest.raises(RuntimeError):
+        b.fw_grad_transform_taps(G, b.FW_F32, S, M, 1, Q, G, workspace(1 << 16))           # in place
+    torch.cuda.synchronize()
+    assert float(W.abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("S,M,taps", [(3, 5, 1), (64, 576, 1), (33, 64, 9), (1000, 512, 1)])
+def test_bias_compensation(S, M, taps):
+    rng = np.random.default_rng(S + M)
+    shape = (S, M) if taps == 1 else (S, M, taps)
+    W = rng.standard_normal(shape).astype(np.float32)
+    b0 = rng.standard_normal(S).astype(np.float32)
+    mu0, mu1 = rng.standard_normal(M).astype(np.float32), rng.standard_normal(M).astype(np.float32)
+    bd = dev(b0)
+    b.fw_bias_compensate(bd, dev(W), S, M, taps, dev(mu0), dev(mu1))
+    torch.cuda.synchronize()
+    Wsum = W.astype(np.float64) if taps == 1 else W.astype(np.float64).sum(axis=2)
+    want = ora.bias_compensation(b0, Wsum, 1, mu0, mu1)
+    assert np.allclose(host(bd), want, rtol=1e-5, atol=1e-5)
+    # the property the rule exists for: the layer output does not move with the mean
+    x = rng.standard_normal(M)
+    assert np.allclose(Wsum @ (x - mu0) + b0, Wsum @ (x - mu1) + host(bd), atol=1e-3)
+
+
+@pytest.mark.parametrize("M", [5, 64, 577, 2304])
+def test_diagnostics(M):
+    rng = np.random.default_rng(M)
+    lam = np.sort(rng.uniform(0.0, 1.0, M) ** 4)[::-1].astype(np.float32)
+    lam[-1] = -1e-7                                     # a rounding-negative eigenvalue counts as zero
+    A = rng.standard_normal((M, M)) / np.sqrt(M)
+    P = (A @ A.T + np.diag(rng.uniform(0.5, 1.5, M))).astype(np.float32)
+    P = ((P + P.T) / 2).astype(np.float32)
+    out = torch.full((4,), float("nan"), device=DEV)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_DIAGNOSTICS, M))
+    b.fw_diagnostics(dev(P), dev(lam), M, out, ws)
+    torch.cuda.synchronize()
+    rho, kappa, ms = (float(v) for v in out[:3])
+    assert rho == pytest.approx(ora.whiteness(P.astype(np.float64)), rel=1e-5)
+    assert kappa == pytest.approx(ora.normalized_rank(lam.astype(np.float64)), rel=1e-5)
+    assert ms == pytest.approx(ora.aic_signal_rank(lam.astype(np.float64)), rel=1e-5)
+    # the stated extremes: a diagonal matrix is perfectly white, equal eigenvalues have full rank
+    out.fill_(float("nan"))
+    b.fw_diagnostics(dev(np.diag(rng.uniform(0.5, 2.0, M))), None, M, out, ws)
+    b.fw_diagnostics(None, dev(np.full(M, 0.3)), M, out)
+    torch.cuda.synchronize()
+    assert float(out[0]) == pytest.approx(1.0, rel=1e-6) and float(out[1]) == pytest.approx(1.0, rel=1e-5)
+    u = rng.uniform(0.5, 2.0, M)
+    b.fw_diagnostics(dev(np.outer(u, u)), None, M, out, ws)
+    torch.cuda.synchronize()
+    assert float(out[0]) == pytest.approx(1.0 / M, rel=1e-4)
