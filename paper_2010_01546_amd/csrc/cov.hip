@@ -618,6 +618,8 @@ size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_lay
     if (dt == FW_BF16) return cov_bf16_workspace_bytes(d, lay);
     if (!d) return 0;
     const bool copy = nchw_through_copy(d, dt, lay);
+    if (cov_shift_applies(d, copy ? FW_LAYOUT_NHWC : lay))
+        return cov_shift_workspace_bytes(d, copy ? FW_LAYOUT_NHWC : lay) + (copy ? act_copy_bytes(d) : 0);
     CovGeom g;
     if (!make_geom(d, dt, copy ? FW_LAYOUT_NHWC : lay, &g)) return 0;
     const size_t part = (size_t)g.nsplit * g.nitems * 4 * BLK * BLK * sizeof(float);
@@ -630,6 +632,20 @@ fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_con
     if (dt == FW_BF16) return cov_bf16_accumulate(X, lay, d, A, s, ws, ws_bytes, st);
     const bool copy = nchw_through_copy(d, dt, lay);
     if (copy) lay = FW_LAYOUT_NHWC;
+    if (cov_shift_applies(d, lay)) {
+        // stride-1 window: tap pairs with the same offset share their products (cov_shift.hip)
+        const size_t need = cov_shift_workspace_bytes(d, lay) + (copy ? act_copy_bytes(d) : 0);
+        if (!ws || ws_bytes < need) return FW_ERR_WORKSPACE;
+        if (copy) {
+            float* Xc = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + cov_shift_workspace_bytes(d, lay));
+            const int HW = d->H * d->W;
+            hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3((HW + 31) / 32, (d->Cin + 31) / 32, d->B), dim3(256), 0, st,
+                               reinterpret_cast<const float*>(X), Xc, d->Cin, HW);
+            FW_LAUNCH_CHECK();
+            X = Xc;
+        }
+        return cov_shift_accumulate(reinterpret_cast<const float*>(X), lay, d, A, s, ws, ws_bytes, st);
+    }
     CovGeom g;
     if (!make_geom(d, dt, lay, &g)) return FW_ERR_UNSUPPORTED;
     const size_t part_bytes = align_up((size_t)g.nsplit * g.nitems * 4 * BLK * BLK * sizeof(float), 256);

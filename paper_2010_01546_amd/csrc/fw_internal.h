@@ -74,6 +74,12 @@ fw_status cov_finalize(const float* A, const float* s, long long n, int M, float
 fw_status symmetrize_from_lower(float* A, int M, hipStream_t st);
 fw_status fill_f32(float* p, size_t n, float v, hipStream_t st);
 
+// ---- cov_shift.hip
+bool cov_shift_applies(const fw_conv_desc* d, fw_layout lay);
+size_t cov_shift_workspace_bytes(const fw_conv_desc* d, fw_layout lay);
+fw_status cov_shift_accumulate(const float* X, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws, size_t ws_bytes,
+                               hipStream_t st);
+
 // ---- cov_bf16.hip
 size_t cov_bf16_workspace_bytes(const fw_conv_desc* d, fw_layout lay);
 fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,

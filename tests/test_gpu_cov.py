@@ -54,6 +54,23 @@ def test_conv_layouts(B, Cin, H, W, k, stride, pad, dtype, layout):
     check_layer(wl.small_conv(B * 100 + Cin, B, Cin, H, W, k, stride, pad, 8, dtype=dtype), layout)
 
 
+SHIFT_CASES = [  # stride-1 windows (B, Cin, H, W, kh, kw, pad): every border shape of the shift-correlation path
+    (3, 64, 9, 7, 3, 3, 1), (2, 64, 8, 8, 3, 3, 0), (2, 64, 5, 6, 3, 3, 2), (2, 32, 9, 9, 5, 5, 2), (5, 128, 2, 2, 3, 3, 1),
+    (2, 64, 6, 5, 3, 1, 0), (2, 64, 5, 7, 1, 3, 0), (3, 96, 7, 7, 2, 2, 1), (1, 64, 3, 8, 4, 4, 3), (2, 200, 6, 6, 3, 3, 1),
+    (40, 64, 12, 11, 3, 3, 1), (1, 256, 1, 1, 3, 3, 1), (2, 64, 3, 3, 3, 3, 0),
+]
+
+
+@pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NCHW, b.FW_LAYOUT_NHWC_KKC])
+@pytest.mark.parametrize("B,Cin,H,W,kh,kw,pad", SHIFT_CASES)
+def test_stride_one_windows(B, Cin, H, W, kh, kw, pad, layout):
+    rng = np.random.default_rng(B + 10 * Cin + H)
+    act = np.abs(rng.standard_normal((B, H, W, Cin)) @ (np.eye(Cin) + 0.3 * rng.standard_normal((Cin, Cin)) / np.sqrt(Cin)))
+    d = wl.ConvDesc(B=B, Cin=Cin, H=H, W=W, kh=kh, kw=kw, stride=1, pad=pad)
+    G = np.zeros((4, d.M), dtype=np.float32)
+    check_layer(wl.Layer("shift", d, 4, "f32", act.astype(np.float32), G), layout)
+
+
 def test_accumulates_over_batches_and_two_block_recursion():
     """Two batches added into one block equal the block of their union; the second block follows eqs. (vmuxi), (vPhixi)."""
     L0 = wl.small_conv(1, 3, 8, 6, 6, 3, 1, 1, 8)
