@@ -16,9 +16,9 @@
 // float32 inside a range of pixels, float64 across ranges and regions.  The column sums follow from per-region channel
 // sums in the same way.
 //
-// Work decomposition of the product: as in the direct kernel, a wavefront owns a 64x64 block (2x2 MFMA 32x32x2 tiles);
-// a workgroup stages one row panel (64 channels at q) and up to four column panels (64 of the nd*Cin shifted features)
-// and its four wavefronts take one column block each; the pixel axis is split into ranges that never cross a region.
+// Work decomposition of the product: a workgroup stages one row panel (64 channels at q) and up to 14 column panels
+// (64 of the nd*Cin shifted features each) per chunk of 16 pixels; its eight wavefronts share out the 32x32 output
+// tiles (v_mfma_f32_32x32x2_f32) evenly; the pixel axis is split into ranges that never cross a region.
 #include "fw_internal.h"
 #include <type_traits>
 
@@ -27,7 +27,10 @@ namespace {
 
 constexpr int BLK = 64;
 constexpr int KT = 16;         // pixels per staged chunk
-constexpr int NSLOT = 5;       // one row panel + four column panels
+constexpr int NCP = 14;        // column panels per workgroup item
+constexpr int NPAN = 2 + NCP;  // staged panels: the row panel, the column panels, one never read (keeps the staging uniform)
+constexpr int NLD = NPAN / 2;   // panels one thread stages = pixel pairs of a chunk
+constexpr int MAXT = 7;        // 32x32 output tiles per wavefront
 constexpr int MAXREG = 32;
 
 struct ShiftRegion {
@@ -42,7 +45,7 @@ struct ShiftGeom {
     int nd;                    // tap differences kept: (0, 0..kw-1), then (dy, -(kw-1)..kw-1) for dy = 1..kh-1
     int F;                     // nd * Cin column features
     int nbr, nbc;              // 64-blocks of the Cin rows and of the F columns
-    int ipr;                   // workgroup items per row block = ceil(nbc / 4)
+    int ipr;                   // workgroup items per row block = ceil(nbc / NCP)
     int nitems;
     int nreg, nsplit;
     int rps;                   // pixels per range (multiple of KT); the last range of a region may be shorter
@@ -59,10 +62,15 @@ __device__ __host__ inline void diff_of(int di, int kw, int* dy, int* dx) {
 __device__ __host__ inline int diff_index(int dy, int dx, int kw) { return dy == 0 ? dx : kw + (dy - 1) * (2 * kw - 1) + dx + kw - 1; }
 
 struct SmemShift {
-    alignas(16) float tile[2][NSLOT][KT][BLK];   // [buffer][panel][pixel][feature], feature position rotated by 32 on odd pixels
+    alignas(16) float tile[2][NPAN][KT][BLK];   // [buffer][panel][pixel][feature], feature position rotated by 32 on odd pixels
 };
 
-__global__ __launch_bounds__(256) void shift_partial_f32_kernel(const float* __restrict__ X, ShiftGeom g, float* __restrict__ part,
+// A workgroup of eight wavefronts owns one row panel (64 channels, two row tiles of 32) and up to NCP column panels
+// (28 column tiles of 32 features).  Wavefront w takes row tile w & 1 and one of four runs of column tiles, at most
+// seven, whose lengths differ by at most one; runs 0 and 2, and 1 and 3, add up to the same length, so the two
+// wavefronts that share a SIMD carry the same load.  For a 3x3 window on 64 channels that is 52 tiles on 8 wavefronts,
+// 6 or 7 each, nothing idle.  Two wavefronts per SIMD hide each other's staging and barriers.
+__global__ __launch_bounds__(512) void shift_partial_f32_kernel(const float* __restrict__ X, ShiftGeom g, float* __restrict__ part,
                                                                 float* __restrict__ spart) {
     __shared__ SmemShift sm;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -72,7 +80,9 @@ __global__ __launch_bounds__(256) void shift_partial_f32_kernel(const float* __r
     const int split = (blockIdx.x & 7) + 8 * ((blockIdx.x >> 3) / g.nitems);
     if (split >= g.nsplit) return;
     const int rb = item_idx / g.ipr, ci = item_idx - rb * g.ipr;
-    const int k = tid >> 4, q = tid & 15;
+    const int cb0 = ci * NCP;                              // first column block of the item
+    const int ncp = min(NCP, g.nbc - cb0);                 // its column panels
+    const int k = (tid >> 4) & 15, q = tid & 15, ph = wave >> 2;
 
     // region of this range
     int ri = 0;
@@ -83,45 +93,55 @@ __global__ __launch_bounds__(256) void shift_partial_f32_kernel(const float* __r
     const int r_begin = (split - g.reg[ri].split_begin) * g.rps;
     const int r_end = min(npix, r_begin + g.rps);
 
-    // what this thread stages per panel: 4 consecutive channels of one shifted pixel
-    int f_off[NSLOT], f_dy[NSLOT], f_dx[NSLOT];
-    bool slot_on[NSLOT], f_ok[NSLOT];
+    // what this thread stages: 4 consecutive channels of one (shifted) pixel for the panels ph, ph + 2, ph + 4, ...
+    int f_off[NLD], f_dy[NLD], f_dx[NLD];
+    bool f_ok[NLD];
 #pragma unroll
-    for (int s = 0; s < NSLOT; ++s) {
-        int dy = 0, dx = 0, c;
+    for (int j = 0; j < NLD; ++j) {
+        const int pan = 2 * j + ph;
+        int dy = 0, dx = 0, c = 0;
         bool ok;
-        if (s == 0) {
+        if (pan == 0) {
             c = rb * BLK + 4 * q;
             ok = c < g.Cin;
-            slot_on[s] = true;
         } else {
-            const int cb = 4 * ci + (s - 1);
-            const int f = cb * BLK + 4 * q;
-            slot_on[s] = cb < g.nbc;
-            ok = slot_on[s] && f < g.F;
+            const int f = (cb0 + pan - 1) * BLK + 4 * q;
+            ok = pan <= ncp && f < g.F;
             const int di = ok ? f / g.Cin : 0;
             c = ok ? f - di * g.Cin : 0;
             diff_of(di, g.kw, &dy, &dx);
         }
-        f_off[s] = (dy * g.W + dx) * g.Cin + (ok ? c : 0);
-        f_dy[s] = dy; f_dx[s] = dx; f_ok[s] = ok;
+        f_off[j] = (dy * g.W + dx) * g.Cin + (ok ? c : 0);
+        f_dy[j] = dy; f_dx[j] = dx; f_ok[j] = ok;
     }
-    const bool sums = ci == 0;
+    const bool sums = ci == 0 && ph == 0;
     float4 ssum = make_float4(0.f, 0.f, 0.f, 0.f);
 
-    floatx16 acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-    const bool active = 4 * ci + wave < g.nbc;
-    const int sb = 1 + wave;
+    // this wavefront's tiles: row tile rt, column tiles ct0 .. ct0 + nt - 1 of the item
+    const int rt = wave & 1, cg = wave >> 1;
+    const int nct = min(2 * ncp, (g.F - cb0 * BLK + 31) / 32);   // column tiles of the item that hold features
+    const int tbase = nct >> 2, textra = nct & 3;
+    const int nt = tbase + (cg < textra ? 1 : 0);
+    const int ct0 = cg * tbase + min(cg, textra);
     const int half = lane >> 5, l32 = lane & 31;
+    floatx16 acc[MAXT];
+#pragma unroll
+    for (int j = 0; j < MAXT; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+    // LDS float offsets (inside a buffer) of the fragments this lane reads at pixel pair 0; a pixel pair further is
+    // 2 * BLK floats further.  Lanes 32..63 read the odd pixel, whose features are rotated by 32.
+    const int rot = half << 5;
+    const int a_off = (0 * KT + half) * BLK + ((32 * rt + l32 + rot) & 63);
+    int b_off[MAXT];
+#pragma unroll
+    for (int j = 0; j < MAXT; ++j) {
+        const int ct = ct0 + (j < nt ? j : 0);
+        b_off[j] = ((1 + (ct >> 1)) * KT + half) * BLK + ((32 * (ct & 1) + l32 + rot) & 63);
+    }
 
     // Position of this thread's pixel in the first chunk, and the step from chunk to chunk.  `base` is the element index
-    // of the pixel's first channel (the whole activation has fewer than 2^31 elements) and moves by precomputed steps,
+    // of the pixel's first channel (the whole activation has fewer than 2^30 elements) and moves by precomputed steps,
     // so a chunk costs no multiplications.
     const int area = rh * rw;
     int r = r_begin + k;
@@ -139,21 +159,19 @@ __global__ __launch_bounds__(256) void shift_partial_f32_kernel(const float* __r
     const int wrap_y = (g.H - rh) * g.W * g.Cin;      // first row of the next image instead of rh rows down
 
     // Loads are issued unconditionally (a masked-out lane reads element 0 instead) and masked when they are stored:
-    // no divergent branches around the loads.
-    float4 pre[NSLOT];
+    // no branches around the loads.  pre[j] holds this thread's 16 bytes of panel 2 j + ph of the chunk after the one
+    // being multiplied; bit j of okmask says whether they are real.
+    static_assert(NLD == KT / 2, "one staged panel per pixel pair");
+    float4 pre[NLD];
     unsigned okmask = 0;
-    auto load_chunk = [&]() {
-        const int y = y0 + yy, x = x0 + xx;
-        const bool row_ok = r < r_end;
-        okmask = 0;
-#pragma unroll
-        for (int s = 0; s < NSLOT; ++s) {
-            if (!slot_on[s]) continue;
-            const bool ok = row_ok && f_ok[s] && (unsigned)(y + f_dy[s]) < (unsigned)g.H && (unsigned)(x + f_dx[s]) < (unsigned)g.W;
-            const int idx = ok ? base + f_off[s] : 0;
-            pre[s] = *reinterpret_cast<const float4*>(X + idx);
-            okmask |= (ok ? 1u : 0u) << s;
-        }
+    int cy = 0, cx = 0;
+    bool row_ok = false;
+    auto locate = [&]() { cy = y0 + yy; cx = x0 + xx; row_ok = r < r_end; };
+    auto load_slot = [&](int j) {
+        const bool ok = row_ok && f_ok[j] && (unsigned)(cy + f_dy[j]) < (unsigned)g.H && (unsigned)(cx + f_dx[j]) < (unsigned)g.W;
+        const int idx = ok ? base + f_off[j] : 0;
+        pre[j] = *reinterpret_cast<const float4*>(X + idx);
+        okmask = (okmask & ~(1u << j)) | ((ok ? 1u : 0u) << j);
     };
     auto advance = [&]() {
         r += KT;
@@ -161,75 +179,83 @@ __global__ __launch_bounds__(256) void shift_partial_f32_kernel(const float* __r
         if (xx >= rw) { xx -= rw; ++yy; base += wrap_x; }
         if (yy >= rh) { yy -= rh; base += wrap_y; }
     };
-    auto store_chunk = [&](int buf) {
-        const int pos = (4 * q + ((k & 1) << 5)) & 63;
-#pragma unroll
-        for (int s = 0; s < NSLOT; ++s) {
-            if (!slot_on[s]) continue;
-            const bool ok = (okmask >> s) & 1u;
-            float4 v;
-            v.x = ok ? pre[s].x : 0.f; v.y = ok ? pre[s].y : 0.f; v.z = ok ? pre[s].z : 0.f; v.w = ok ? pre[s].w : 0.f;
-            *reinterpret_cast<float4*>(&sm.tile[buf][s][k][pos]) = v;
-            if (s == 0 && sums) { ssum.x += v.x; ssum.y += v.y; ssum.z += v.z; ssum.w += v.w; }
-        }
+    const int pos = (4 * q + ((k & 1) << 5)) & 63;
+    auto store_slot = [&](int j, int buf) {
+        const bool ok = (okmask >> j) & 1u;
+        float4 v;
+        v.x = ok ? pre[j].x : 0.f; v.y = ok ? pre[j].y : 0.f; v.z = ok ? pre[j].z : 0.f; v.w = ok ? pre[j].w : 0.f;
+        *reinterpret_cast<float4*>(&sm.tile[buf][2 * j + ph][k][pos]) = v;
+        if (j == 0 && sums) { ssum.x += v.x; ssum.y += v.y; ssum.z += v.z; ssum.w += v.w; }
     };
 
     const int nchunks = (r_end - r_begin + KT - 1) / KT;
-    if (nchunks > 0) {
-        load_chunk();
-        store_chunk(0);
-    }
+    // chunk 0 into buffer 0, chunk 1 into the registers
+    locate();
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) load_slot(j);
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) store_slot(j, 0);
+    advance();
+    locate();
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) load_slot(j);
     __syncthreads();
-    // the loop exists with and without the matrix instructions: a wavefront without a block keeps staging and meeting
-    // the barriers, and the accumulators of the others never sit behind a branch
-    auto run = [&](auto with_mfma) {
+    // While chunk c is multiplied out of one buffer, chunk c + 1 moves from the registers into the other buffer and the
+    // loads of chunk c + 2 are issued, one panel per pixel pair, between the matrix instructions (past the end of the
+    // range the loads read element 0 and what is stored is never read).  One copy of the loop per tile count, so that
+    // no matrix instruction sits behind a branch; a wavefront without tiles (NT = 0) only stages.
+    auto run = [&](auto nt_const) {
+        constexpr int NT = decltype(nt_const)::value;
         for (int c = 0; c < nchunks; ++c) {
             const int buf = c & 1;
-            const bool more = c + 1 < nchunks;
-            if (more) { advance(); load_chunk(); }
-            if constexpr (decltype(with_mfma)::value) {
-                const float* ta_base = &sm.tile[buf][0][0][0];
-                const float* tb_base = &sm.tile[buf][sb][0][0];
+            const float* tb = &sm.tile[buf][0][0][0];
+            advance();
+            locate();
 #pragma unroll
-                for (int k0 = 0; k0 < KT; k0 += 2) {
-                    const int kk = k0 + half;
-                    const int rot = half << 5;
-                    float a[2], b[2];
+            for (int k0 = 0; k0 < KT; k0 += 2) {
+                if constexpr (NT > 0) {
+                    const float a = tb[a_off + k0 * BLK];
+                    float b[NT];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        a[t] = ta_base[kk * BLK + ((32 * t + l32 + rot) & 63)];
-                        b[t] = tb_base[kk * BLK + ((32 * t + l32 + rot) & 63)];
-                    }
+                    for (int j = 0; j < NT; ++j) b[j] = tb[b_off[j] + k0 * BLK];
 #pragma unroll
-                    for (int ta = 0; ta < 2; ++ta)
-#pragma unroll
-                        for (int tb = 0; tb < 2; ++tb)
-                            acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
+                    for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j], acc[j], 0, 0, 0);
                 }
+                store_slot(k0 >> 1, buf ^ 1);
+                load_slot(k0 >> 1);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (more) store_chunk(buf ^ 1);
             __syncthreads();
         }
     };
-    if (active) run(std::true_type{}); else run(std::false_type{});
-
-    if (active) {
-        float* dst = part + (((size_t)split * g.nitems + item_idx) * 4 + wave) * (BLK * BLK);
-#pragma unroll
-        for (int ta = 0; ta < 2; ++ta)
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int row = 32 * ta + 8 * (i >> 2) + 4 * half + (i & 3);
-                    const int col = 32 * tb + l32;
-                    dst[row * BLK + col] = acc[ta][tb][i];
-                }
+    switch (nt) {
+        case 7: run(std::integral_constant<int, 7>{}); break;
+        case 6: run(std::integral_constant<int, 6>{}); break;
+        case 5: run(std::integral_constant<int, 5>{}); break;
+        case 4: run(std::integral_constant<int, 4>{}); break;
+        case 3: run(std::integral_constant<int, 3>{}); break;
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 1: run(std::integral_constant<int, 1>{}); break;
+        default: run(std::integral_constant<int, 0>{}); break;
     }
-    if (sums) {
+
+    // partial blocks: [range][row block * nbc + column block][64 x 64]
+#pragma unroll
+    for (int j = 0; j < MAXT; ++j) {
+        if (j >= nt) continue;
+        const int ct = ct0 + j;
+        float* dst = part + ((size_t)split * g.nbr * g.nbc + (size_t)rb * g.nbc + cb0 + (ct >> 1)) * (BLK * BLK);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = 32 * rt + 8 * (i >> 2) + 4 * half + (i & 3);
+            const int col = 32 * (ct & 1) + l32;
+            dst[row * BLK + col] = acc[j][i];
+        }
+    }
+    if (ci == 0) {
         // channel sums of the row panel: 16 pixel-threads share a channel quad; combine through LDS (the tiles are dead)
         float* red = &sm.tile[0][0][0][0];
-        *reinterpret_cast<float4*>(&red[k * 64 + 4 * q]) = ssum;
+        if (ph == 0) *reinterpret_cast<float4*>(&red[k * 64 + 4 * q]) = ssum;
         __syncthreads();
         if (wave == 0) {
             float v = 0.f;
@@ -240,17 +266,18 @@ __global__ __launch_bounds__(256) void shift_partial_f32_kernel(const float* __r
     }
 }
 
-// R_r = sum of the partial blocks over the ranges of region r, float64; the last nreg * nbr workgroups do the same for
-// the channel sums
+// R_r = sum of the partial blocks over the ranges of region r, float64.  A workgroup sums 256 consecutive elements of a
+// block, 16 bytes per lane: its four wavefronts take every fourth range (four loads in flight each) and combine through
+// LDS in a fixed order.  The last nreg * nbr workgroups do the same for the channel sums.
 __global__ __launch_bounds__(256) void shift_region_reduce_kernel(ShiftGeom g, const float* __restrict__ part, const float* __restrict__ spart,
                                                                   double* __restrict__ Rr, double* __restrict__ Sr) {
-    __shared__ double red[4][64];
-    const int per_reg = g.nitems * 4 * 16;
+    __shared__ double red[4][256];
+    const int ln = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int per_reg = g.nbr * g.nbc * 16;
     const int nblk = g.nreg * per_reg;
     if ((int)blockIdx.x >= nblk) {
         const int idx = (int)blockIdx.x - nblk;
         const int ri = idx / g.nbr, rb = idx - ri * g.nbr;
-        const int ln = threadIdx.x & 63, grp = threadIdx.x >> 6;
         const int s0 = g.reg[ri].split_begin, s1 = s0 + g.reg[ri].nsplit;
         double v = 0.0;
         for (int sp = s0 + grp; sp < s1; sp += 4) v += (double)spart[((size_t)sp * g.nbr + rb) * BLK + ln];
@@ -261,25 +288,27 @@ __global__ __launch_bounds__(256) void shift_region_reduce_kernel(ShiftGeom g, c
     }
     const int ri = blockIdx.x / per_reg;
     const int rem = blockIdx.x - ri * per_reg;
-    const int blk = rem >> 4;                         // (item, wavefront)
-    const int e = ((rem & 15) << 8) + threadIdx.x;    // element of the 64x64 block
-    const int item_idx = blk >> 2, wave = blk & 3;
-    const int ci = item_idx % g.ipr;
-    if (4 * ci + wave >= g.nbc) return;
+    const size_t e = (size_t)rem * 256 + 4 * ln;      // first of this lane's four elements of [block][64 x 64]
     const int s0 = g.reg[ri].split_begin, s1 = s0 + g.reg[ri].nsplit;
-    const size_t stride = (size_t)g.nitems * 4 * BLK * BLK;
-    const float* src = part + (size_t)blk * (BLK * BLK) + e;
-    double v = 0.0;
-    int sp = s0;
-    for (; sp + 8 <= s1; sp += 8) {
-        float x[8];
+    const size_t stride = (size_t)g.nbr * g.nbc * BLK * BLK;
+    const float* src = part + e;
+    double v0 = 0.0, v1 = 0.0, v2 = 0.0, v3 = 0.0;
+    int sp = s0 + grp;
+    for (; sp + 12 < s1; sp += 16) {
+        float4 x[4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) x[j] = src[(size_t)(sp + j) * stride];
+        for (int j = 0; j < 4; ++j) x[j] = *reinterpret_cast<const float4*>(src + (size_t)(sp + 4 * j) * stride);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v += (double)x[j];
+        for (int j = 0; j < 4; ++j) { v0 += (double)x[j].x; v1 += (double)x[j].y; v2 += (double)x[j].z; v3 += (double)x[j].w; }
     }
-    for (; sp < s1; ++sp) v += (double)src[(size_t)sp * stride];
-    Rr[(size_t)ri * stride + (size_t)blk * (BLK * BLK) + e] = v;
+    for (; sp < s1; sp += 4) {
+        const float4 x = *reinterpret_cast<const float4*>(src + (size_t)sp * stride);
+        v0 += (double)x.x; v1 += (double)x.y; v2 += (double)x.z; v3 += (double)x.w;
+    }
+    red[grp][4 * ln] = v0; red[grp][4 * ln + 1] = v1; red[grp][4 * ln + 2] = v2; red[grp][4 * ln + 3] = v3;
+    __syncthreads();
+    const int t = threadIdx.x;
+    Rr[(size_t)ri * stride + (size_t)rem * 256 + t] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
 }
 
 __device__ __forceinline__ void tap_channel(int e, const ShiftGeom& g, int* ty, int* tx, int* c) {
@@ -319,9 +348,8 @@ __global__ __launch_bounds__(256) void shift_assemble_kernel(ShiftGeom g, const 
     }
     const int f = diff_index(dy, dx, g.kw) * g.Cin + c2;
     const int rb = c1 >> 6, cb = f >> 6;
-    const int item_idx = rb * g.ipr + (cb >> 2), wave = cb & 3;
-    const size_t stride = (size_t)g.nitems * 4 * BLK * BLK;
-    const size_t idx = ((size_t)item_idx * 4 + wave) * (BLK * BLK) + (size_t)(c1 & 63) * BLK + (f & 63);
+    const size_t stride = (size_t)g.nbr * g.nbc * BLK * BLK;
+    const size_t idx = ((size_t)rb * g.nbc + cb) * (BLK * BLK) + (size_t)(c1 & 63) * BLK + (f & 63);
     double v = 0.0;
     for (int r = 0; r < g.nreg; ++r)
         if (((g.reg[r].rowmask >> t1y) & 1) && ((g.reg[r].colmask >> t1x) & 1)) v += Rr[(size_t)r * stride + idx];
@@ -361,7 +389,7 @@ ShiftWs shift_ws_layout(const ShiftGeom& g) {
     ShiftWs L;
     size_t o = 0;
     auto take = [&](size_t bytes) { const size_t at = o; o += align_up(bytes, 256); return at; };
-    const size_t blocks = (size_t)g.nitems * 4 * BLK * BLK;
+    const size_t blocks = (size_t)g.nbr * g.nbc * BLK * BLK;
     L.part = take((size_t)g.nsplit * blocks * sizeof(float));
     L.spart = take((size_t)g.nsplit * g.nbr * BLK * sizeof(float));
     L.Rr = take((size_t)g.nreg * blocks * sizeof(double));
@@ -388,23 +416,22 @@ static bool make_shift_geom(const fw_conv_desc* d, fw_layout lay, ShiftGeom* g) 
     g->F = g->nd * d->Cin;
     g->nbr = (d->Cin + BLK - 1) / BLK;
     g->nbc = (g->F + BLK - 1) / BLK;
-    g->ipr = (g->nbc + 3) / 4;
+    g->ipr = (g->nbc + NCP - 1) / NCP;
     g->nitems = g->nbr * g->ipr;
     g->kkc = lay == FW_LAYOUT_NHWC_KKC ? 1 : 0;
-    // fewer 64x64 block products than the lower triangle of the direct form (idle wavefronts of a ragged last item
-    // counted at half weight)
+    // fewer 64x64 block products than the lower triangle of the direct form
     const long long nb = (M + BLK - 1) / BLK;
     const double direct = 0.5 * (double)nb * (double)(nb + 1);
-    const double shifted = (double)g->nbr * (0.5 * g->nbc + 0.5 * 4 * g->ipr);
+    const double shifted = (double)g->nbr * (double)g->nbc;
     if (shifted * 1.1 >= direct) return false;
     Band rows[8 * 2], cols[8 * 2];
     const int nr = make_bands(d->H, d->kh, d->pad, g->Ho, rows, 16), nc = make_bands(d->W, d->kw, d->pad, g->Wo, cols, 16);
     if (nr <= 0 || nc <= 0 || nr * nc > MAXREG) return false;
     g->nreg = nr * nc;
-    // pixel ranges: three workgroups are resident per compute unit, and the grid should fit in ONE such round (a
-    // workgroup that starts late runs almost alone and is bound by latency).  Ranges never cross a region, so the count
+    // pixel ranges: one workgroup is resident per compute unit, and the grid should fit in ONE such round (a
+    // workgroup that starts late holds up the end).  Ranges never cross a region, so the count
     // is found by shrinking the target until the rounded-up ranges of all regions fit; at least four chunks per range.
-    const long long capacity = (256 * 3) / g->nitems;
+    const long long capacity = 256 / g->nitems > 0 ? 256 / g->nitems : 1;
     const long long max_split = (npix + 4 * KT - 1) / (4 * KT);
     int nsplit = 0;
     for (long long want = capacity > 1 ? capacity : 1;; --want) {
@@ -453,9 +480,9 @@ fw_status cov_shift_accumulate(const float* X, fw_layout lay, const fw_conv_desc
     float* spart = reinterpret_cast<float*>(base + L.spart);
     double* Rr = reinterpret_cast<double*>(base + L.Rr);
     double* Sr = reinterpret_cast<double*>(base + L.Sr);
-    hipLaunchKernelGGL(shift_partial_f32_kernel, dim3(8 * g.nitems * ((g.nsplit + 7) / 8)), dim3(256), 0, st, X, g, part, spart);
+    hipLaunchKernelGGL(shift_partial_f32_kernel, dim3(8 * g.nitems * ((g.nsplit + 7) / 8)), dim3(512), 0, st, X, g, part, spart);
     FW_LAUNCH_CHECK();
-    hipLaunchKernelGGL(shift_region_reduce_kernel, dim3(g.nreg * g.nitems * 4 * 16 + g.nreg * g.nbr), dim3(256), 0, st, g, part, spart, Rr, Sr);
+    hipLaunchKernelGGL(shift_region_reduce_kernel, dim3(g.nreg * g.nbr * g.nbc * 16 + g.nreg * g.nbr), dim3(256), 0, st, g, part, spart, Rr, Sr);
     FW_LAUNCH_CHECK();
     hipLaunchKernelGGL(shift_assemble_kernel, dim3((g.M + 255) / 256, g.M + 1), dim3(256), 0, st, g, Rr, Sr, A, s);
     FW_LAUNCH_CHECK();
