@@ -25,11 +25,25 @@
 // tiles go to the workspace and are summed in float64 (and permuted to the caller's feature order).
 #include "fw_internal.h"
 #include <math.h>
+#include <string.h>
+#include <algorithm>
+#include <queue>
+#include <vector>
 
 namespace fw {
 namespace {
 
 constexpr int KU = 4;    // units per staged chunk (32 reduction entries) = wavefronts of a workgroup
+
+constexpr int MAXREG = 32;
+
+// region of the image whose pixels serve the same set of taps (shift-correlation mode, see below)
+struct TileRegion {
+    int y0, x0, rh, rw;          // rectangle of pixels
+    int rowmask, colmask;        // bit ty / tx: its pixels serve taps of row ty / column tx
+    int chunk_begin, nchunks;    // its units in the unit table, padded to whole chunks
+    int split_begin, nsplit;     // its unit ranges
+};
 
 struct TileGeom {
     int M, ntiles;
@@ -40,6 +54,11 @@ struct TileGeom {
     int direct;   // one range per tile and external order == internal order: tiles are added straight into A
     int bg_chunks, bg_per_chunk;   // the pre-pass deals the image groups to this many thread groups
     int zero_off;                  // 16-byte element of P that is always zero (target of masked-off loads)
+    int py, px;                    // zero rows above / columns left of the image in P (Hp, Wp count the border on all sides)
+    int sum_shift;                 // offset of the tap (0,0) of output position (0,0) in P
+    // shift-correlation mode (stride-1 windows): rows = Cin channels of a pixel, columns = nd tap differences x Cin
+    int shift, nd, F, nreg;
+    TileRegion reg[MAXREG];
 };
 
 // column blocks of row block I that touch the lower triangle
@@ -61,7 +80,7 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
     const int e = blockIdx.x * 256 + threadIdx.x;
     const int chunk = blockIdx.y;
     if (blockIdx.x == 0 && chunk == 0 && threadIdx.x < 16) P[g.zero_off + threadIdx.x] = make_uint4(0, 0, 0, 0);
-    if (chunk == 0) {
+    if (chunk == 0 && !g.shift) {
         const int npos = g.Ho * g.Wo;
         for (int u = e; u < g.nchunks * KU; u += gridDim.x * 256) {
             int v = -1;
@@ -69,6 +88,23 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
                 const int bg = u / npos, p = u - bg * npos;
                 const int oy = p / g.Wo, ox = p - oy * g.Wo;
                 v = ((bg * g.Hp + oy * g.stride) * g.Wp + ox * g.stride) * g.Cin;
+            }
+            utab[u] = v;
+        }
+    }
+    if (chunk == 0 && g.shift) {
+        // units are pixels (of an image group), listed region by region, every region padded to whole chunks
+        for (int u = e; u < g.nchunks * KU; u += gridDim.x * 256) {
+            int ri = 0;
+            for (int r = 0; r < g.nreg; ++r)
+                if (u >= g.reg[r].chunk_begin * KU) ri = r;
+            const int l = u - g.reg[ri].chunk_begin * KU;
+            const int area = g.reg[ri].rh * g.reg[ri].rw;
+            int v = -1;
+            if (l < g.Bg * area) {
+                const int bg = l / area, p = l - bg * area;
+                const int yy = p / g.reg[ri].rw, xx = p - yy * g.reg[ri].rw;
+                v = ((bg * g.Hp + g.reg[ri].y0 + yy + g.py) * g.Wp + g.reg[ri].x0 + xx + g.px) * g.Cin;
             }
             utab[u] = v;
         }
@@ -89,7 +125,7 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
         for (int kx = 0; kx < g.kw; ++kx) { const int o = xp - kx; rx |= o >= 0 && o % g.stride == 0 && o / g.stride < g.Wo; }
         if (!(ry && rx)) return;
     }
-    const int y = yp - g.pad, x = xp - g.pad;
+    const int y = yp - g.py, x = xp - g.px;
     const bool inside = (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
     const long long img_stride = (long long)g.Cin * g.H * g.W;
     const long long src0 = g.layout == FW_LAYOUT_NCHW ? ((long long)c * g.H + y) * g.W + x : ((long long)y * g.W + x) * g.Cin + c;
@@ -151,15 +187,32 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
     const int total = g.ntiles * g.nsplit;
     const int per_xcd = (total + 7) / 8;
     int tile, split;
-    {
+    int I, J, c_begin, nchunks;
+    if (!g.shift) {
         const int w = blockIdx.x;
         const int n = (w & 7) * per_xcd + (w >> 3);
         if (n >= total || (w >> 3) >= per_xcd) return;   // padding of the last run
         split = n / g.ntiles;
         tile = n - split * g.ntiles;
+        tile_coords(tile, g, &I, &J);
+        c_begin = split * g.chunks_per_split;
+        nchunks = min(g.nchunks, c_begin + g.chunks_per_split) - c_begin;
+    } else {
+        // shift-correlation mode: rectangular grid of tiles; the ranges differ in length (they never cross a region), so
+        // XCD x takes the ranges x, x + 8, ... with all their tiles rather than one contiguous run
+        const int w = blockIdx.x;
+        tile = (w >> 3) % g.ntiles;
+        split = (w & 7) + 8 * ((w >> 3) / g.ntiles);
+        if (split >= g.nsplit) return;
+        I = tile / g.ncb;
+        J = tile - I * g.ncb;
+        int ri = 0;
+        for (int r = 0; r < g.nreg; ++r)
+            if (split >= g.reg[r].split_begin) ri = r;
+        const int first = (split - g.reg[ri].split_begin) * g.chunks_per_split;
+        c_begin = g.reg[ri].chunk_begin + first;
+        nchunks = min(g.chunks_per_split, g.reg[ri].nchunks - first);
     }
-    int I, J;
-    tile_coords(tile, g, &I, &J);
 
     // Staging: a wavefront-wide 16-byte load fills 64 consecutive features of one unit (1 KB of LDS); wavefront w
     // brings unit w of every chunk, NF loads.  Lanes whose feature lies beyond M, and units beyond the range, read the
@@ -169,9 +222,21 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
 #pragma unroll
     for (int k = 0; k < NF; ++k) {
         const int f = k < NRT ? I * TR + 64 * k + lane : J * TC + 64 * (k - NRT) + lane;
-        const bool ok = f < g.M;
-        int ext_unused;
-        feat_map(ok ? f : 0, g, &off[k], &ext_unused);
+        bool ok;
+        if (!g.shift) {
+            ok = f < g.M;
+            int ext_unused;
+            feat_map(ok ? f : 0, g, &off[k], &ext_unused);
+        } else if (k < NRT) {           // channel f of the pixel itself
+            ok = f < g.Cin;
+            off[k] = ok ? f : 0;
+        } else {                        // channel c of the pixel shifted back by tap difference di
+            ok = f < g.F;
+            const int di = ok ? f / g.Cin : 0, c = ok ? f - di * g.Cin : 0;
+            int dy, dx;
+            shift_diff_of(di, g.kw, &dy, &dx);
+            off[k] = -(dy * g.Wp + dx) * g.Cin + c;
+        }
         okmask |= (ok ? 1u : 0u) << k;
     }
 
@@ -182,9 +247,6 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
         for (int b = 0; b < NCT; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-
-    const int c_begin = split * g.chunks_per_split;
-    const int nchunks = min(g.nchunks, c_begin + g.chunks_per_split) - c_begin;
 
     // offset of the unit this wavefront loads next (wavefront-uniform; -1 past the end of the range)
     int nb = -1;
@@ -312,7 +374,7 @@ __global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const flo
     auto at = [&](int idx) {
         const int k = idx / npos, p = idx - k * npos;
         const int oy = p / g.Wo, ox = p - oy * g.Wo;
-        return S8[(size_t)k * per_img + ((oy * g.stride) * g.Wp + ox * g.stride) * g.Cin + off];
+        return S8[(size_t)k * per_img + ((oy * g.stride) * g.Wp + ox * g.stride) * g.Cin + g.sum_shift + off];
     };
     double v = 0.0;
     if (ok) {
@@ -355,13 +417,174 @@ __global__ __launch_bounds__(256) void tile_reduce_kernel(TileGeom g, const floa
     *dst = (float)((double)*dst + v);
 }
 
-bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
+// Shift-correlation mode: the block of A that pairs row tap t1 with column tap t2 <= t1 (in tap order) is the sum, over
+// the regions whose pixels serve t1 and over their unit ranges, of the partial tiles' entries R(t1 - t2)[c1][c2].  A
+// workgroup takes 16 channels c1 x 64 channels c2 of one pair of taps, so the window and the ranges are uniform and the
+// loads (16 bytes per lane along c2, four in flight) and the writes run along rows; float64 sums.
+__global__ __launch_bounds__(256) void shift_tile_assemble_kernel(TileGeom g, const float* __restrict__ part, float* __restrict__ A) {
+    const int kk = g.kh * g.kw;
+    int t1 = 0;
+    {
+        int pr = blockIdx.z;                          // pair index: t1 (t1 + 1) / 2 + t2
+        while ((t1 + 1) * (t1 + 2) / 2 <= pr) ++t1;
+        pr -= t1 * (t1 + 1) / 2;
+        const int t2 = pr;
+        const int t1y = t1 / g.kw, t1x = t1 - t1y * g.kw, t2y = t2 / g.kw, t2x = t2 - t2y * g.kw;
+        int dy = t1y - t2y, dx = t1x - t2x;           // >= 0 in lexicographic order because t1 >= t2
+        const int di = shift_diff_index(dy, dx, g.kw);
+        const int c1 = blockIdx.y * 16 + (threadIdx.x >> 4);
+        const int c2 = blockIdx.x * 64 + 4 * (threadIdx.x & 15);
+        if (c1 >= g.Cin || c2 >= g.Cin) return;
+        if (t1 == t2 && c2 > c1 + 3) return;          // diagonal block: entries right of the diagonal are not kept
+        const int f = di * g.Cin + c2;                // four consecutive columns f .. f+3 lie in one tile (Cin % 4 == 0)
+        const int I = c1 / g.tr, J = f / g.tc;
+        const size_t tsz = (size_t)g.tr * g.tc;
+        const float* src = part + (size_t)(I * g.ncb + J) * tsz + (size_t)(c1 - I * g.tr) * g.tc + (f - J * g.tc);
+        const size_t stride = (size_t)g.ntiles * tsz;
+        double v0 = 0.0, v1 = 0.0, v2 = 0.0, v3 = 0.0;
+        for (int r = 0; r < g.nreg; ++r) {
+            if (!(((g.reg[r].rowmask >> t1y) & 1) && ((g.reg[r].colmask >> t1x) & 1))) continue;
+            const int s1 = g.reg[r].split_begin + g.reg[r].nsplit;
+            int sp = g.reg[r].split_begin;
+            for (; sp + 4 <= s1; sp += 4) {
+                float4 x[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) x[q] = *reinterpret_cast<const float4*>(src + (size_t)(sp + q) * stride);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) { v0 += (double)x[q].x; v1 += (double)x[q].y; v2 += (double)x[q].z; v3 += (double)x[q].w; }
+            }
+            for (; sp < s1; ++sp) {
+                const float4 x = *reinterpret_cast<const float4*>(src + (size_t)sp * stride);
+                v0 += (double)x.x; v1 += (double)x.y; v2 += (double)x.z; v3 += (double)x.w;
+            }
+        }
+        const double v[4] = {v0, v1, v2, v3};
+        const bool kkc = g.layout == FW_LAYOUT_NHWC_KKC;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int cc = c2 + q;
+            if (t1 == t2 && cc > c1) continue;
+            const int ei = kkc ? t1 * g.Cin + c1 : c1 * kk + t1;
+            const int ej = kkc ? t2 * g.Cin + cc : cc * kk + t2;
+            float* dst = A + (size_t)max(ei, ej) * g.M + min(ei, ej);
+            *dst = (float)((double)*dst + v[q]);
+        }
+    }
+}
+
+// Geometry of the shift-correlation mode; false when it does not apply.  *cost is an estimate of its run time in the
+// same terms as the direct form's (see make_tile_geom).
+bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
+    if (d->stride != 1 || d->kh * d->kw <= 1 || d->kh > 8 || d->kw > 8 || (d->Cin & 3) != 0) return false;
+    const int Cin = d->Cin;
+    g->nd = d->kw + (d->kh - 1) * (2 * d->kw - 1);
+    const long long F = (long long)g->nd * Cin;
+    if (F > (1 << 20)) return false;
+    g->F = (int)F;
+    g->shift = 1;
+    // border of zeros: what the tap differences reach above and to both sides, the windows' own padding below
+    const int hy = d->kh - 1 > d->pad ? d->kh - 1 : d->pad, hx = d->kw - 1 > d->pad ? d->kw - 1 : d->pad;
+    g->py = hy; g->px = hx;
+    g->Hp = d->H + hy + d->pad; g->Wp = d->W + 2 * hx;
+    g->sum_shift = ((g->py - d->pad) * g->Wp + (g->px - d->pad)) * Cin;
+    const long long packed = (long long)g->Bg * g->Hp * g->Wp * Cin;
+    if (packed + 16 >= (1ll << 31)) return false;
+    ShiftBand rows[16], cols[16];
+    const int nr = shift_bands(d->H, d->kh, d->pad, g->Ho, rows, 16), nc = shift_bands(d->W, d->kw, d->pad, g->Wo, cols, 16);
+    if (nr <= 0 || nc <= 0 || nr * nc > MAXREG) return false;
+    g->nreg = nr * nc;
+    g->nrt = Cin > 192 ? 4 : Cin > 128 ? 3 : 2;
+    g->nct = 4;
+    g->tr = 64 * g->nrt; g->tc = 64 * g->nct;
+    g->nrb = (Cin + g->tr - 1) / g->tr; g->ncb = (g->F + g->tc - 1) / g->tc;
+    g->ntiles = g->nrb * g->ncb;
+    // regions, largest first: their ranges are dispatched in this order, so the short ones fill the end
+    int nregs = 0;
+    for (int a = 0; a < nr; ++a)
+        for (int b = 0; b < nc; ++b) {
+            TileRegion& R = g->reg[nregs++];
+            R.y0 = rows[a].begin; R.rh = rows[a].len; R.rowmask = rows[a].mask;
+            R.x0 = cols[b].begin; R.rw = cols[b].len; R.colmask = cols[b].mask;
+            R.nchunks = (int)(((long long)g->Bg * R.rh * R.rw + KU - 1) / KU);
+        }
+    std::stable_sort(g->reg, g->reg + nregs, [](const TileRegion& x, const TileRegion& y) { return x.nchunks > y.nchunks; });
+    long long total_chunks = 0;
+    for (int r = 0; r < nregs; ++r) {
+        g->reg[r].chunk_begin = (int)total_chunks;
+        total_chunks += g->reg[r].nchunks;
+    }
+    if (total_chunks * KU >= (1ll << 31) - KU) return false;
+    for (int r = g->nreg; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0};
+    g->nchunks = (int)total_chunks;
+    g->n_units = (int)(total_chunks * KU);
+    g->direct = 0;
+    g->zero_off = (int)packed;
+    // Length of a unit range (ranges never cross a region): simulate the dispatch of the workgroups, in launch order, onto
+    // the 256 compute units for a ladder of lengths and keep the cheapest: time of the longest compute unit plus the
+    // traffic of the partial tiles (written once, read back by the assembly about 0.6 times per tap pair of a window).
+    const double clk = 2.0e9, bw = 4.0e12, lds_load_rate = 23.0;
+    const double t_mfma = 64.0 * g->nrt * g->nct + 150.0, t_load = (double)(g->tr + g->tc) * KU * 16.0 / lds_load_rate;
+    const double t_chunk = (t_mfma > t_load ? t_mfma : t_load) / clk;
+    const double ideal = (double)total_chunks * g->ntiles / 256.0;
+    const int kk = d->kh * d->kw;
+    double best = 1e300;
+    long long best_cps = 8;
+    for (int step = -8; step <= 8; ++step) {
+        long long cps = (long long)(ideal * pow(2.0, step / 4.0) + 0.5);
+        if (cps < 8) cps = 8;
+        if (cps > total_chunks) cps = total_chunks;
+        int nsplit = 0;
+        int len[MAXREG], cnt[MAXREG];
+        for (int r = 0; r < nregs; ++r) {
+            cnt[r] = (int)((g->reg[r].nchunks + cps - 1) / cps);
+            len[r] = g->reg[r].nchunks - (cnt[r] - 1) * (int)cps;   // the last range of a region
+            nsplit += cnt[r];
+        }
+        if ((long long)nsplit * g->ntiles > 65536) continue;
+        // launch order: groups of 8 ranges x all tiles; a min-heap of the compute units' finish times
+        std::priority_queue<double, std::vector<double>, std::greater<double>> cu;
+        for (int i = 0; i < 256; ++i) cu.push(0.0);
+        double makespan = 0.0;
+        int r = 0, within = 0;
+        std::vector<int> range_len(nsplit);
+        for (int sp = 0; sp < nsplit; ++sp) {
+            range_len[sp] = within == cnt[r] - 1 ? len[r] : (int)cps;
+            if (++within == cnt[r]) { within = 0; ++r; }
+        }
+        for (int g8 = 0; g8 < nsplit; g8 += 8)
+            for (int t = 0; t < g->ntiles; ++t)
+                for (int sp = g8; sp < g8 + 8 && sp < nsplit; ++sp) {
+                    const double f = cu.top() + range_len[sp] + 6.0;   // fill of the ring and write-out of the tile
+                    cu.pop(); cu.push(f);
+                    if (f > makespan) makespan = f;
+                }
+        const double wgs = (double)g->ntiles * nsplit;
+        const double c = makespan * t_chunk + wgs * g->tr * g->tc * 4.0 / bw +
+                         0.5 * kk * (kk + 1) * (double)Cin * Cin * 4.0 * 0.6 * nsplit / bw + 0.5 * (double)g->M * g->M * 8.0 / bw;
+        if (c < best) { best = c; best_cps = cps; }
+    }
+    g->chunks_per_split = (int)best_cps;
+    int nsplit = 0;
+    for (int r = 0; r < nregs; ++r) {
+        g->reg[r].split_begin = nsplit;
+        g->reg[r].nsplit = (int)((g->reg[r].nchunks + best_cps - 1) / best_cps);
+        nsplit += g->reg[r].nsplit;
+    }
+    g->nsplit = nsplit;
+    *cost = best;
+    return true;
+}
+
+bool build_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     g->B = d->B; g->Cin = d->Cin; g->H = d->H; g->W = d->W;
     g->kh = d->kh; g->kw = d->kw; g->stride = d->stride; g->pad = d->pad;
     g->layout = (int)lay;
     g->Ho = (d->H + 2 * d->pad - d->kh) / d->stride + 1;
     g->Wo = (d->W + 2 * d->pad - d->kw) / d->stride + 1;
     g->Hp = d->H + 2 * d->pad; g->Wp = d->W + 2 * d->pad;
+    g->py = g->px = d->pad; g->sum_shift = 0;
+    g->shift = 0; g->nd = 0; g->F = 0; g->nreg = 0;
+    for (int r = 0; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0};
     g->Bg = (d->B + 7) / 8;
     const long long M = (long long)d->Cin * d->kh * d->kw;
     const long long n_units = (long long)g->Bg * g->Ho * g->Wo;
@@ -396,6 +619,21 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
                 if (cost < best * 0.999) { best = cost; best_nrt = nrt; best_nct = nct; best_ns = ns; }
             }
         }
+    {
+        // stride-1 windows: tap pairs with the same difference share their products (shift-correlation mode)
+        TileGeom gs = *g;
+        double cs = 0.0;
+        if (lay != FW_LAYOUT_ROWS && make_shift_tile_geom(d, &gs, &cs) && cs < best) {
+            const long long per_img = (long long)gs.Hp * gs.Wp * d->Cin;
+            long long ch = (524288 + per_img - 1) / per_img;
+            if (ch > gs.Bg) ch = gs.Bg;
+            if (ch < 1) ch = 1;
+            gs.bg_per_chunk = (int)((gs.Bg + ch - 1) / ch);
+            gs.bg_chunks = (gs.Bg + gs.bg_per_chunk - 1) / gs.bg_per_chunk;
+            *g = gs;
+            return true;
+        }
+    }
     g->nrt = best_nrt; g->nct = best_nct; g->tr = 64 * best_nrt; g->tc = 64 * best_nct;
     g->ncb = (int)((M + g->tc - 1) / g->tc); g->nrb = (int)((M + g->tr - 1) / g->tr);
     g->ntiles = 0;
@@ -414,6 +652,21 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     }
     g->direct = (g->nsplit == 1 && ident) ? 1 : 0;
     return true;
+}
+
+// The geometry of the last layer asked for is kept per host thread: a call computes it for the workspace check and for
+// the launches, and a training loop asks for the same few layers over and over.
+bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
+    struct Last { bool valid = false, ok = false; fw_conv_desc d; fw_layout lay; TileGeom g; };
+    static thread_local Last last;
+    if (last.valid && last.lay == lay && memcmp(&last.d, d, sizeof(*d)) == 0) {
+        if (last.ok) *g = last.g;
+        return last.ok;
+    }
+    last.ok = build_tile_geom(d, lay, &last.g);
+    last.d = *d; last.lay = lay; last.valid = true;
+    if (last.ok) *g = last.g;
+    return last.ok;
 }
 
 struct Bf16Ws { size_t packed, utab, part, s8, total; };
@@ -452,7 +705,7 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     hipLaunchKernelGGL(pack_images_kernel, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st, reinterpret_cast<const u16*>(X),
                        g, P, S8, utab);
     FW_LAUNCH_CHECK();
-    const dim3 grid((g.ntiles * g.nsplit + 7) / 8 * 8);
+    const dim3 grid(g.shift ? 8 * g.ntiles * ((g.nsplit + 7) / 8) : (g.ntiles * g.nsplit + 7) / 8 * 8);
 #define FW_TILE_LAUNCH(R, C) hipLaunchKernelGGL((cov_bf16_tile_kernel<R, C>), grid, dim3(256), 0, st, P, utab, g, part, A)
     switch (g.nrt * 10 + g.nct) {
         case 44: FW_TILE_LAUNCH(4, 4); break;
@@ -460,11 +713,15 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
         case 42: FW_TILE_LAUNCH(4, 2); break;
         case 33: FW_TILE_LAUNCH(3, 3); break;
         case 32: FW_TILE_LAUNCH(3, 2); break;
+        case 34: FW_TILE_LAUNCH(3, 4); break;
+        case 24: FW_TILE_LAUNCH(2, 4); break;
         default: FW_TILE_LAUNCH(2, 2); break;
     }
 #undef FW_TILE_LAUNCH
     FW_LAUNCH_CHECK();
-    if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * (g.tr * g.tc / 256)), dim3(256), 0, st, g, part, A);
+    if (g.shift) hipLaunchKernelGGL(shift_tile_assemble_kernel, dim3((g.Cin + 63) / 64, (g.Cin + 15) / 16, g.kh * g.kw * (g.kh * g.kw + 1) / 2),
+                                    dim3(256), 0, st, g, part, A);
+    else if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * (g.tr * g.tc / 256)), dim3(256), 0, st, g, part, A);
     hipLaunchKernelGGL(column_sums_kernel, dim3((g.M + 15) / 16), dim3(1024), 0, st, g, S8, s);
     FW_LAUNCH_CHECK();
     return FW_OK;

@@ -53,14 +53,6 @@ struct ShiftGeom {
     ShiftRegion reg[MAXREG];
 };
 
-__device__ __host__ inline void diff_of(int di, int kw, int* dy, int* dx) {
-    if (di < kw) { *dy = 0; *dx = di; return; }
-    const int e = di - kw, w2 = 2 * kw - 1;
-    *dy = 1 + e / w2;
-    *dx = e % w2 - (kw - 1);
-}
-__device__ __host__ inline int diff_index(int dy, int dx, int kw) { return dy == 0 ? dx : kw + (dy - 1) * (2 * kw - 1) + dx + kw - 1; }
-
 struct SmemShift {
     alignas(16) float tile[2][NPAN][KT][BLK];   // [buffer][panel][pixel][feature], feature position rotated by 32 on odd pixels
 };
@@ -109,7 +101,7 @@ __global__ __launch_bounds__(512) void shift_partial_f32_kernel(const float* __r
             ok = pan <= ncp && f < g.F;
             const int di = ok ? f / g.Cin : 0;
             c = ok ? f - di * g.Cin : 0;
-            diff_of(di, g.kw, &dy, &dx);
+            shift_diff_of(di, g.kw, &dy, &dx);
         }
         f_off[j] = (dy * g.W + dx) * g.Cin + (ok ? c : 0);
         f_dy[j] = dy; f_dx[j] = dx; f_ok[j] = ok;
@@ -346,7 +338,7 @@ __global__ __launch_bounds__(256) void shift_assemble_kernel(ShiftGeom g, const 
         t = t1x; t1x = t2x; t2x = t;
         t = c1; c1 = c2; c2 = t;
     }
-    const int f = diff_index(dy, dx, g.kw) * g.Cin + c2;
+    const int f = shift_diff_index(dy, dx, g.kw) * g.Cin + c2;
     const int rb = c1 >> 6, cb = f >> 6;
     const size_t stride = (size_t)g.nbr * g.nbc * BLK * BLK;
     const size_t idx = ((size_t)rb * g.nbc + cb) * (BLK * BLK) + (size_t)(c1 & 63) * BLK + (f & 63);
@@ -355,33 +347,6 @@ __global__ __launch_bounds__(256) void shift_assemble_kernel(ShiftGeom g, const 
         if (((g.reg[r].rowmask >> t1y) & 1) && ((g.reg[r].colmask >> t1x) & 1)) v += Rr[(size_t)r * stride + idx];
     float* dst = A + (size_t)i * g.M + j;
     *dst = (float)((double)*dst + v);
-}
-
-// bands of one axis: maximal runs of coordinates that serve the same set of taps
-struct Band { int begin, len, mask; };
-int make_bands(int H, int k, int pad, int Ho, Band* out, int cap) {
-    int n = 0;
-    int y = 0;
-    auto mask_of = [&](int yy) {
-        int m = 0;
-        for (int t = 0; t < k; ++t) {
-            const int p = yy - t + pad;
-            if (p >= 0 && p <= Ho - 1) m |= 1 << t;
-        }
-        return m;
-    };
-    while (y < H) {
-        const int m = mask_of(y);
-        int y1 = y;
-        while (y1 + 1 < H && mask_of(y1 + 1) == m) ++y1;
-        if (m) {
-            if (n == cap) return -1;
-            out[n].begin = y; out[n].len = y1 - y + 1; out[n].mask = m;
-            ++n;
-        }
-        y = y1 + 1;
-    }
-    return n;
 }
 
 struct ShiftWs { size_t part, spart, Rr, Sr, total; };
@@ -424,8 +389,8 @@ static bool make_shift_geom(const fw_conv_desc* d, fw_layout lay, ShiftGeom* g) 
     const double direct = 0.5 * (double)nb * (double)(nb + 1);
     const double shifted = (double)g->nbr * (double)g->nbc;
     if (shifted * 1.1 >= direct) return false;
-    Band rows[8 * 2], cols[8 * 2];
-    const int nr = make_bands(d->H, d->kh, d->pad, g->Ho, rows, 16), nc = make_bands(d->W, d->kw, d->pad, g->Wo, cols, 16);
+    ShiftBand rows[8 * 2], cols[8 * 2];
+    const int nr = shift_bands(d->H, d->kh, d->pad, g->Ho, rows, 16), nc = shift_bands(d->W, d->kw, d->pad, g->Wo, cols, 16);
     if (nr <= 0 || nc <= 0 || nr * nc > MAXREG) return false;
     g->nreg = nr * nc;
     // pixel ranges: one workgroup is resident per compute unit, and the grid should fit in ONE such round (a

@@ -74,6 +74,42 @@ fw_status cov_finalize(const float* A, const float* s, long long n, int M, float
 fw_status symmetrize_from_lower(float* A, int M, hipStream_t st);
 fw_status fill_f32(float* p, size_t n, float v, hipStream_t st);
 
+// ---- shift correlations of stride-1 windows (cov_shift.hip, cov_bf16.hip)
+// tap differences kept, in order: (0, 0..kw-1), then (dy, -(kw-1)..kw-1) for dy = 1..kh-1
+__device__ __host__ inline void shift_diff_of(int di, int kw, int* dy, int* dx) {
+    if (di < kw) { *dy = 0; *dx = di; return; }
+    const int e = di - kw, w2 = 2 * kw - 1;
+    *dy = 1 + e / w2;
+    *dx = e % w2 - (kw - 1);
+}
+__device__ __host__ inline int shift_diff_index(int dy, int dx, int kw) { return dy == 0 ? dx : kw + (dy - 1) * (2 * kw - 1) + dx + kw - 1; }
+// bands of one image axis: maximal runs of coordinates y that serve the same set of taps t (bit t of mask: the output
+// coordinate y - t + pad lies in [0, Ho)); returns the number of bands, -1 if more than cap
+struct ShiftBand { int begin, len, mask; };
+inline int shift_bands(int H, int k, int pad, int Ho, ShiftBand* out, int cap) {
+    auto mask_of = [&](int yy) {
+        int m = 0;
+        for (int t = 0; t < k; ++t) {
+            const int p = yy - t + pad;
+            if (p >= 0 && p <= Ho - 1) m |= 1 << t;
+        }
+        return m;
+    };
+    int n = 0, y = 0;
+    while (y < H) {
+        const int m = mask_of(y);
+        int y1 = y;
+        while (y1 + 1 < H && mask_of(y1 + 1) == m) ++y1;
+        if (m) {
+            if (n == cap) return -1;
+            out[n].begin = y; out[n].len = y1 - y + 1; out[n].mask = m;
+            ++n;
+        }
+        y = y1 + 1;
+    }
+    return n;
+}
+
 // ---- cov_shift.hip
 bool cov_shift_applies(const fw_conv_desc* d, fw_layout lay);
 size_t cov_shift_workspace_bytes(const fw_conv_desc* d, fw_layout lay);

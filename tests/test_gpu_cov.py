@@ -61,14 +61,18 @@ SHIFT_CASES = [  # stride-1 windows (B, Cin, H, W, kh, kw, pad): every border sh
 ]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NCHW, b.FW_LAYOUT_NHWC_KKC])
 @pytest.mark.parametrize("B,Cin,H,W,kh,kw,pad", SHIFT_CASES)
-def test_stride_one_windows(B, Cin, H, W, kh, kw, pad, layout):
+def test_stride_one_windows(B, Cin, H, W, kh, kw, pad, layout, dtype):
     rng = np.random.default_rng(B + 10 * Cin + H)
     act = np.abs(rng.standard_normal((B, H, W, Cin)) @ (np.eye(Cin) + 0.3 * rng.standard_normal((Cin, Cin)) / np.sqrt(Cin)))
+    act = act.astype(np.float32)
+    if dtype == "bf16":
+        act = wl.round_to_bf16(act)
     d = wl.ConvDesc(B=B, Cin=Cin, H=H, W=W, kh=kh, kw=kw, stride=1, pad=pad)
     G = np.zeros((4, d.M), dtype=np.float32)
-    check_layer(wl.Layer("shift", d, 4, "f32", act.astype(np.float32), G), layout)
+    check_layer(wl.Layer("shift", d, 4, dtype, act, G), layout)
 
 
 def test_accumulates_over_batches_and_two_block_recursion():
