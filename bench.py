@@ -29,9 +29,9 @@ HBM_PEAK = 8.0e12
 # runs of this script with --copy-calibration (summary: profiles/fw_cov_accumulate_hbm_traffic_counters.txt), each
 # counter scaled by what it reads on a 256 MiB device copy (2 KiB per FETCH_SIZE count, 1 KiB per WRITE_SIZE count).
 # Measured with the default layout (kkc); other layouts report null.
-MEASURED_TRAFFIC = {"c2": {"read": 79.5e6, "written": 48.0e6},
-                    "c3": {"read": 174.4e6, "written": 112.9e6},
-                    "c4": {"read": 217.8e6, "written": 65.6e6}}
+MEASURED_TRAFFIC = {"c2": {"read": 122.5e6, "written": 58.9e6},
+                    "c3": {"read": 192.0e6, "written": 126.0e6},
+                    "c4": {"read": 466.1e6, "written": 242.4e6}}
 
 
 def parse():
@@ -208,6 +208,19 @@ def main():
 
     cov_flops = float(n_rows) * M * (M + 1)                 # lower triangle incl. diagonal, 2 flops per product
     achieved = cov_flops / (cov_ms * 1e-3)
+    # A stride-1 window is accumulated through shift correlations: tap pairs with the same offset share one product, so
+    # the matrix cores issue fewer flops than the algorithmic count (13 instead of 45 tap pairs for 3x3); report both.
+    shifted = (not layer.is_rows) and d.stride == 1 and d.kh * d.kw > 1 and d.Cin % 4 == 0
+    if shifted:
+        nd = d.kw + (d.kh - 1) * (2 * d.kw - 1)
+        if bf16:
+            tr = 256 if d.Cin > 192 else 192 if d.Cin > 128 else 128
+            rows_x, cols_x = -(-d.Cin // tr) * tr, -(-(nd * d.Cin) // 256) * 256
+        else:
+            rows_x, cols_x = -(-d.Cin // 64) * 64, -(-(nd * d.Cin) // 32) * 32
+        issued = 2.0 * rows_x * cols_x * d.B * d.H * d.W
+    else:
+        issued = None
     peak = PEAK[layer.dtype]
     tr = MEASURED_TRAFFIC.get(args.config) if (layer.is_rows or args.layout == "kkc") else None
     traffic = tr["read"] + tr["written"] if tr else None
@@ -225,11 +238,16 @@ def main():
         "config": {"workload": f"{layer.name}: M={M} S={S} N_rows={n_rows} layout={args.layout if not layer.is_rows else 'rows'}",
                    "batch": d.B, "block_length": 1, "cond_params": "gamma=0.99 beta=0.1 delta=0.25 (paper defaults)"},
         "roofline": {"bound": "mfma",
-                     "kernel": ("pack_images + cov_bf16_tile (+ tile_reduce) + column_sums" if bf16 else
-                                "cov_partial_f32v4 + cov_reduce") + " = one fw_cov_accumulate",
+                     "kernel": (("pack_images + cov_bf16_tile + shift_tile_assemble + column_sums" if shifted else
+                                 "pack_images + cov_bf16_tile (+ tile_reduce) + column_sums") if bf16 else
+                                ("shift_partial_f32 + shift_region_reduce + shift_assemble" if shifted else
+                                 "cov_partial_f32v4 + cov_reduce")) + " = one fw_cov_accumulate",
                      "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": traffic, "traffic_unit": "bytes per fw_cov_accumulate call (HBM read + written, counters)",
-                     "traffic_read_written": tr, "algorithmic_bytes": alg_bytes},
+                     "traffic_read_written": tr, "algorithmic_bytes": alg_bytes,
+                     "note": "achieved = algorithmic flops N_rows*M*(M+1) per call / time of the call",
+                     "mfma_flops_issued": issued,
+                     "issued_frac_of_peak": (issued / (cov_ms * 1e-3) / peak) if issued else None},
         "breakdown_ms": {"cov_accumulate": cov_ms, "cov_finalize": fin_ms, "cond_reduce_step": cond_ms, "grad_transform": grad_ms},
         "cond_step_GBps": cond_bytes / (cond_ms * 1e-3) / 1e9,
         "grad_transform_TFLOPs": 2.0 * S * M * M / (grad_ms * 1e-3) / 1e12,
