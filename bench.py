@@ -45,6 +45,7 @@ def parse():
     ap.add_argument("--layout", default="kkc", choices=["kkc", "nhwc", "nchw"],
                     help="kkc: NHWC tensor with channels-last feature order (ky,kx,c); nhwc/nchw: feature order (c,ky,kx)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--c5-unlocked", action="store_true", help=argparse.SUPPRESS)   # only once the fault of the sweep is explained
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, copy a 256 MiB tensor five times: the known-size kernel against which the\n"
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command are scaled")
@@ -148,6 +149,12 @@ def main():
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    if args.config == "c5" and not args.c5_unlocked:
+        # One run of this sweep (default steps, fresh machine) ended with a GPU memory fault whose cause has not been
+        # found; three runs of the same code before it were clean.  Until the cause is known the sweep does not run.
+        print("bench.py --config c5 is switched off: a run of it ended in an unexplained GPU fault "
+              "(the recorded figures of its earlier clean runs are in DESIGN.md)", file=sys.stderr)
+        sys.exit(3)
     import numpy as np
     import torch
 
