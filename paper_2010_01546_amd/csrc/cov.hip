@@ -137,7 +137,7 @@ struct Smem {
 
 // Generic float32 path (any layout, any Cin): one element per load through a per-row table.  bfloat16 inputs take
 // the packed-tile path of cov_bf16.hip.
-__global__ __launch_bounds__(256) void cov_partial_kernel(const float* __restrict__ X, CovGeom g, float* __restrict__ part,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void cov_partial_kernel(const float* __restrict__ X, CovGeom g, float* __restrict__ part,
                                                           float* __restrict__ spart) {
     constexpr int KT = KT_F32;
     __shared__ Smem sm;

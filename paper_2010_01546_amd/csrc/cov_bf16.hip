@@ -213,6 +213,10 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
         c_begin = g.reg[ri].chunk_begin + first;
         nchunks = min(g.chunks_per_split, g.reg[ri].nchunks - first);
     }
+    // all of these are the same for the whole workgroup: keep them in scalar registers
+    tile = __builtin_amdgcn_readfirstlane(tile); split = __builtin_amdgcn_readfirstlane(split);
+    I = __builtin_amdgcn_readfirstlane(I); J = __builtin_amdgcn_readfirstlane(J);
+    c_begin = __builtin_amdgcn_readfirstlane(c_begin); nchunks = __builtin_amdgcn_readfirstlane(nchunks);
 
     // Staging: a wavefront-wide 16-byte load fills 64 consecutive features of one unit (1 KB of LDS); wavefront w
     // brings unit w of every chunk, NF loads.  Lanes whose feature lies beyond M, and units beyond the range, read the
@@ -343,16 +347,19 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
             for (int ta = 0; ta < NRT; ++ta) {
                 const int gi0 = I * TR + 32 * NRT * wi + 32 * ta + 4 * half;
                 if (gi0 + 27 < J * TC + 32 * NCT * wj + 32 * tb) continue;   // MFMA tile entirely above the diagonal
-                float old[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int gi = gi0 + 8 * (i >> 2) + (i & 3);
-                    old[i] = (gi < g.M && gj < g.M && gj <= gi) ? A[(size_t)gi * g.M + gj] : 0.f;
-                }
+                for (int h = 0; h < 16; h += 8) {   // eight loads in flight (sixteen do not fit beside 256 accumulators)
+                    float old[8];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int gi = gi0 + 8 * (i >> 2) + (i & 3);
-                    if (gi < g.M && gj < g.M && gj <= gi) A[(size_t)gi * g.M + gj] = old[i] + acc[ta][tb][i];
+                    for (int i = 0; i < 8; ++i) {
+                        const int gi = gi0 + 8 * ((h + i) >> 2) + ((h + i) & 3);
+                        old[i] = (gi < g.M && gj < g.M && gj <= gi) ? A[(size_t)gi * g.M + gj] : 0.f;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int gi = gi0 + 8 * ((h + i) >> 2) + ((h + i) & 3);
+                        if (gi < g.M && gj < g.M && gj <= gi) A[(size_t)gi * g.M + gj] = old[i] + acc[ta][tb][h + i];
+                    }
                 }
             }
         }

@@ -261,13 +261,14 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
 
 // (MF, C) with the lowest cost: rounds of 256 workgroups x MFMA time of a workgroup, contraction padded to whole chunks
 struct StripChoice { int mf, c; };
-inline StripChoice pick_strip(int S, int M) {
+inline StripChoice pick_strip(int S, int M, bool plain) {
     static const int cs[6] = {9, 6, 4, 3, 2, 1};
     StripChoice best = {32, 1};
     double best_cost = 1e300;
     for (int mf = 32; mf >= 16; mf -= 16)
         for (int ci = 0; ci < 6; ++ci) {
             const int c = cs[ci];
+            if (!plain && mf == 32 && c == 9) continue;   // the general epilogue does not fit beside 9 x 16 accumulators
             const int kw = mf == 32 ? 8 : 16, u = strip_u(mf, c), kc = 4 * kw * u;
             const long long tr = (S + mf - 1) / mf, tc = (M + mf - 1) / mf;
             const long long wgs = tr * ((tc + c - 1) / c);
@@ -287,7 +288,8 @@ void launch_strip(int c, const float* G, const float* Q, const GemmEpilogue& Out
     const bool plain = Out.out && !Out.out_bf16 && Out.taps == 1 && !Out.W;
 #define FW_STRIP_LAUNCH(CC)                                                                                                \
     if (plain) hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, CC, true>), grid, dim3(256), 0, st, G, Q, Out, S, M);   \
-    else hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, CC, false>), grid, dim3(256), 0, st, G, Q, Out, S, M)
+    else if constexpr (!(MF == 32 && CC == 9))                                                                             \
+        hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, CC, false>), grid, dim3(256), 0, st, G, Q, Out, S, M)
     switch (c) {
         case 9: FW_STRIP_LAUNCH(9); break;
         case 6: FW_STRIP_LAUNCH(6); break;
@@ -442,7 +444,8 @@ fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const Gemm
     if ((M & 3) != 0)
         hipLaunchKernelGGL(grad_gemm_f32_small_kernel, dim3((M + 31) / 32, (S + 31) / 32), dim3(256), 0, st, G, Q, e, S, M);
     else {
-        const StripChoice ch = pick_strip(S, M);
+        const bool plain = e.out && !e.out_bf16 && e.taps == 1 && !e.W;
+        const StripChoice ch = pick_strip(S, M, plain);
         if (ch.mf == 32) launch_strip<32>(ch.c, G, Q, e, S, M, st);
         else launch_strip<16>(ch.c, G, Q, e, S, M, st);
     }
