@@ -217,17 +217,9 @@ def main():
     achieved = cov_flops / (cov_ms * 1e-3)
     # A stride-1 window is accumulated through shift correlations: tap pairs with the same offset share one product, so
     # the matrix cores issue fewer flops than the algorithmic count (13 instead of 45 tap pairs for 3x3); report both.
-    shifted = (not layer.is_rows) and d.stride == 1 and d.kh * d.kw > 1 and d.Cin % 4 == 0
-    if shifted:
-        nd = d.kw + (d.kh - 1) * (2 * d.kw - 1)
-        if bf16:
-            tr = 256 if d.Cin > 192 else 192 if d.Cin > 128 else 128
-            rows_x, cols_x = -(-d.Cin // tr) * tr, -(-(nd * d.Cin) // 256) * 256
-        else:
-            rows_x, cols_x = -(-d.Cin // 64) * 64, -(-(nd * d.Cin) // 32) * 32
-        issued = 2.0 * rows_x * cols_x * d.B * d.H * d.W
-    else:
-        issued = None
+    lay_id = b.FW_LAYOUT_ROWS if layer.is_rows else {"kkc": b.FW_LAYOUT_NHWC_KKC, "nhwc": b.FW_LAYOUT_NHWC, "nchw": b.FW_LAYOUT_NCHW}[args.layout]
+    plan = b.fw_cov_plan_query(b.FW_BF16 if bf16 else b.FW_F32, lay_id, b.conv_desc(*d.astuple()))
+    shifted, issued = bool(plan.shift), plan.mfma_flops_issued
     peak = PEAK[layer.dtype]
     tr = MEASURED_TRAFFIC.get(args.config) if (layer.is_rows or args.layout == "kkc") else None
     traffic = tr["read"] + tr["written"] if tr else None
@@ -253,8 +245,9 @@ def main():
                      "traffic": traffic, "traffic_unit": "bytes per fw_cov_accumulate call (HBM read + written, counters)",
                      "traffic_read_written": tr, "algorithmic_bytes": alg_bytes,
                      "note": "achieved = algorithmic flops N_rows*M*(M+1) per call / time of the call",
-                     "mfma_flops_issued": issued,
-                     "issued_frac_of_peak": (issued / (cov_ms * 1e-3) / peak) if issued else None},
+                     "mfma_flops_issued": issued, "issued_frac_of_peak": issued / (cov_ms * 1e-3) / peak,
+                     "plan": {"shift": plan.shift, "regions": plan.regions, "differences": plan.differences,
+                              "workgroups": plan.workgroups, "ranges": plan.ranges}},
         "breakdown_ms": {"cov_accumulate": cov_ms, "cov_finalize": fin_ms, "cond_reduce_step": cond_ms, "grad_transform": grad_ms},
         "cond_step_GBps": cond_bytes / (cond_ms * 1e-3) / 1e9,
         "grad_transform_TFLOPs": 2.0 * S * M * M / (grad_ms * 1e-3) / 1e12,

@@ -250,6 +250,24 @@ fw_status fw_whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float
  */
 fw_status fw_diagnostics(const float* Phi_y, const float* lambda, int M, float* out, void* ws, size_t ws_bytes, void* stream);
 
+/* How fw_cov_accumulate would run a layer (host arithmetic only, no GPU call): for introspection and tests.
+ *   shift              1: stride-1 window accumulated through shift correlations (tap pairs with the same offset share one
+ *                      product), 0: direct products of the unfolded patch rows
+ *   regions            shift form: image regions whose pixels serve the same set of taps (0 in the direct form)
+ *   covered_pixels     shift form: pixels of all regions together (= B H W when every pixel lies under some window)
+ *   differences        shift form: tap differences kept (13 for a 3x3 window)
+ *   workgroups         workgroups of the contraction kernel
+ *   ranges             pieces the reduction axis (patch rows / pixels) is cut into
+ *   mfma_flops_issued  flops the matrix cores execute per call, padding included (the algorithmic count is
+ *                      N_rows M (M + 1))
+ */
+typedef struct {
+    int shift, regions, differences, workgroups, ranges;
+    long long covered_pixels;
+    double mfma_flops_issued;
+} fw_cov_plan;
+fw_status fw_cov_plan_query(fw_dtype dt, fw_layout lay, const fw_conv_desc* d, fw_cov_plan* plan);
+
 /* Scratch bytes an entry point needs for the given sizes (0 if none).  `d` is needed for FW_OP_COV_ACCUMULATE only;
  * for the per-tap operations S is the number of gradient rows, S * taps. */
 size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtype dt);

@@ -26,8 +26,8 @@ FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
 
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",
            "fw_whiten_evd", "fw_cond_state_refresh", "fw_grad_transform_taps", "fw_sgd_update", "fw_bias_compensate",
-           "fw_diagnostics", "fw_workspace_bytes", "fw_status_string", "fw_version"]
-N_STATUS_EXPORTS = 11   # the leading entries of EXPORTS return fw_status
+           "fw_diagnostics", "fw_cov_plan_query", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+N_STATUS_EXPORTS = 12   # the leading entries of EXPORTS return fw_status
 
 
 class fw_conv_desc(C.Structure):
@@ -53,6 +53,11 @@ class fw_sgd_params(C.Structure):
     _fields_ = [("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float)]
 
 
+class fw_cov_plan(C.Structure):
+    _fields_ = [("shift", C.c_int), ("regions", C.c_int), ("differences", C.c_int), ("workgroups", C.c_int), ("ranges", C.c_int),
+                ("covered_pixels", C.c_longlong), ("mfma_flops_issued", C.c_double)]
+
+
 class fw_evd_params(C.Structure):
     _fields_ = [("eps", C.c_float), ("g_max", C.c_float), ("beta", C.c_float), ("tol", C.c_float),
                 ("gain_mode", C.c_int), ("max_sweeps", C.c_int)]
@@ -70,6 +75,7 @@ lib.fw_grad_transform_taps.argtypes = [_P, C.c_int, C.c_int, C.c_int, C.c_int, _
 lib.fw_sgd_update.argtypes = [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.POINTER(fw_sgd_params), _P, _P, _P, C.c_size_t, _P]
 lib.fw_bias_compensate.argtypes = [_P, _P, C.c_int, C.c_int, C.c_int, _P, _P, C.c_float, _P]
 lib.fw_diagnostics.argtypes = [_P, _P, C.c_int, _P, _P, C.c_size_t, _P]
+lib.fw_cov_plan_query.argtypes = [C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.POINTER(fw_cov_plan)]
 lib.fw_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.c_int]
 lib.fw_workspace_bytes.restype = C.c_size_t
 lib.fw_status_string.argtypes = [C.c_int]
@@ -168,6 +174,13 @@ def fw_bias_compensate(b, W, S, M, taps, mu_old, mu_new, scale=1.0, stream=None)
 def fw_diagnostics(Phi_y, lam, M, out, ws=None, stream=None):
     wp, n = _ws(ws)
     return _check(lib.fw_diagnostics(_ptr(Phi_y), _ptr(lam), M, _ptr(out), wp, n, _stream(stream)), "fw_diagnostics")
+
+
+def fw_cov_plan_query(dt, lay, d) -> fw_cov_plan:
+    """Host arithmetic only: works without a GPU."""
+    plan = fw_cov_plan()
+    _check(lib.fw_cov_plan_query(dt, lay, C.byref(d), C.byref(plan)), "fw_cov_plan_query")
+    return plan
 
 
 def cond_state(M, Phi_x, lambda_bar, T, Q, Qs, Phi_y, Psi, xi2) -> fw_cond_state:

@@ -627,6 +627,19 @@ size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_lay
     return align_up(part, 256) + align_up(sp, 256) + (copy ? act_copy_bytes(d) : 0);
 }
 
+bool cov_plan(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, fw_cov_plan* plan) {
+    *plan = fw_cov_plan{};
+    if (dt == FW_BF16) return cov_bf16_plan(d, lay, plan);
+    if (nchw_through_copy(d, dt, lay)) lay = FW_LAYOUT_NHWC;
+    if (cov_shift_plan(d, lay, plan)) return true;
+    CovGeom g;
+    if (!make_geom(d, dt, lay, &g)) return false;
+    plan->workgroups = g.nitems * g.nsplit; plan->ranges = g.nsplit;
+    // 64x64 blocks of the lower triangle, diagonal blocks in full
+    plan->mfma_flops_issued = 2.0 * 64.0 * 64.0 * (0.5 * g.nb * (g.nb + 1)) * (double)g.n_rows;
+    return true;
+}
+
 fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,
                          size_t ws_bytes, hipStream_t st) {
     if (dt == FW_BF16) return cov_bf16_accumulate(X, lay, d, A, s, ws, ws_bytes, st);

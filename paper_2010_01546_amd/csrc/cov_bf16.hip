@@ -691,6 +691,18 @@ Bf16Ws ws_layout(const TileGeom& g) {
 
 }  // namespace
 
+bool cov_bf16_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan) {
+    TileGeom g;
+    if (!d || !make_tile_geom(d, lay, &g)) return false;
+    plan->shift = g.shift; plan->regions = g.nreg; plan->differences = g.nd;
+    plan->workgroups = g.ntiles * g.nsplit; plan->ranges = g.nsplit;
+    plan->covered_pixels = 0;
+    for (int r = 0; r < g.nreg; ++r) plan->covered_pixels += (long long)g.B * g.reg[r].rh * g.reg[r].rw;
+    // every tile is multiplied over all chunks of its ranges: 32 reduction entries (4 units of 8 images) per chunk
+    plan->mfma_flops_issued = 2.0 * (double)g.ntiles * g.tr * g.tc * 32.0 * (double)g.nchunks;
+    return true;
+}
+
 size_t cov_bf16_workspace_bytes(const fw_conv_desc* d, fw_layout lay) {
     TileGeom g;
     if (!d || !make_tile_geom(d, lay, &g)) return 0;

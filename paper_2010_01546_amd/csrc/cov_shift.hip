@@ -434,6 +434,18 @@ bool cov_shift_applies(const fw_conv_desc* d, fw_layout lay) {
     return d && make_shift_geom(d, lay, &g);
 }
 
+bool cov_shift_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan) {
+    ShiftGeom g;
+    if (!d || !make_shift_geom(d, lay, &g)) return false;
+    plan->shift = 1; plan->regions = g.nreg; plan->differences = g.nd;
+    plan->workgroups = g.nitems * g.nsplit; plan->ranges = g.nsplit;
+    plan->covered_pixels = 0;
+    for (int r = 0; r < g.nreg; ++r) plan->covered_pixels += (long long)g.B * g.reg[r].rh * g.reg[r].rw;
+    // every item multiplies its 64 rows by the 32-feature column tiles that hold features, over all pixels
+    plan->mfma_flops_issued = 2.0 * (g.nbr * 64.0) * (((g.F + 31) / 32) * 32.0) * (double)g.B * g.H * g.W;
+    return true;
+}
+
 fw_status cov_shift_accumulate(const float* X, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws, size_t ws_bytes,
                                hipStream_t st) {
     ShiftGeom g;

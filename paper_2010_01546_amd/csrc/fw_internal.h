@@ -73,6 +73,7 @@ fw_status cov_finalize(const float* A, const float* s, long long n, int M, float
                        float* Phi_x, float* phi_x, float* lambda_bar, hipStream_t st);
 fw_status symmetrize_from_lower(float* A, int M, hipStream_t st);
 fw_status fill_f32(float* p, size_t n, float v, hipStream_t st);
+bool cov_plan(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, fw_cov_plan* plan);
 
 // ---- shift correlations of stride-1 windows (cov_shift.hip, cov_bf16.hip)
 // tap differences kept, in order: (0, 0..kw-1), then (dy, -(kw-1)..kw-1) for dy = 1..kh-1
@@ -116,7 +117,10 @@ size_t cov_shift_workspace_bytes(const fw_conv_desc* d, fw_layout lay);
 fw_status cov_shift_accumulate(const float* X, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws, size_t ws_bytes,
                                hipStream_t st);
 
+bool cov_shift_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan);
+
 // ---- cov_bf16.hip
+bool cov_bf16_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan);
 size_t cov_bf16_workspace_bytes(const fw_conv_desc* d, fw_layout lay);
 fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,
                               size_t ws_bytes, hipStream_t st);

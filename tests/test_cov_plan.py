@@ -1,0 +1,61 @@
+"""Host logic of the covariance planning (no GPU): which form a layer takes, and invariants of the shift-correlation
+decomposition (Sec. 2 sums over unfolded rows, re-grouped by tap difference): the regions partition the pixels, the
+number of kept differences is one of each +/- pair, the grid of the float32 kernel fits one round of the compute units."""
+import pytest
+
+from paper_2010_01546_amd import binding as b
+
+SHAPES = [  # B, Cin, H, W, kh, kw, stride, pad
+    (128, 64, 32, 32, 3, 3, 1, 1), (256, 256, 14, 14, 3, 3, 1, 1), (256, 512, 7, 7, 3, 3, 1, 1), (2, 64, 8, 8, 3, 3, 1, 0),
+    (2, 64, 5, 6, 3, 3, 1, 2), (2, 32, 9, 9, 5, 5, 1, 2), (5, 128, 2, 2, 3, 3, 1, 1), (2, 64, 6, 5, 3, 1, 1, 0), (3, 96, 7, 7, 2, 2, 1, 1),
+    (1, 64, 3, 8, 4, 4, 1, 3), (1, 256, 1, 1, 3, 3, 1, 1), (256, 64, 56, 56, 3, 3, 1, 1), (256, 128, 28, 28, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("dt", [b.FW_F32, b.FW_BF16])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_stride_one_windows_take_the_shift_form(shape, dt):
+    B, Cin, H, W, kh, kw, stride, pad = shape
+    d = b.conv_desc(*shape)
+    for lay in (b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NHWC_KKC, b.FW_LAYOUT_NCHW):
+        p = b.fw_cov_plan_query(dt, lay, d)
+        if dt == b.FW_BF16 and B < 128 and p.shift == 0:
+            continue   # tiny bfloat16 layers: the cost estimate may keep the direct form
+        assert p.shift == 1, (shape, lay)
+        assert p.differences == ((2 * kh - 1) * (2 * kw - 1) + 1) // 2
+        # every pixel of a stride-1 window with pad < k lies under some window; the regions are disjoint
+        assert p.covered_pixels == B * H * W
+        assert 1 <= p.regions <= 32 and p.ranges >= p.regions
+        Ho, Wo = H + 2 * pad - kh + 1, W + 2 * pad - kw + 1
+        M = Cin * kh * kw
+        algorithmic = float(B * Ho * Wo) * M * (M + 1)
+        assert p.mfma_flops_issued > 0
+        if Cin % 64 == 0 and H * W >= 49 and 2 * pad == kh - 1 and dt == b.FW_F32:
+            assert p.mfma_flops_issued < 0.5 * algorithmic      # the point of the form: far fewer multiplications
+        if dt == b.FW_F32:
+            assert p.workgroups <= 256 or p.ranges == p.regions  # one round of the 256 compute units
+
+
+@pytest.mark.parametrize("dt", [b.FW_F32, b.FW_BF16])
+@pytest.mark.parametrize("shape,lay", [((256, 3, 224, 224, 7, 7, 2, 3), b.FW_LAYOUT_NHWC), ((256, 64, 56, 56, 3, 3, 2, 1), b.FW_LAYOUT_NHWC),
+                                       ((256, 64, 56, 56, 1, 1, 2, 0), b.FW_LAYOUT_NHWC), ((256, 512, 1, 1, 1, 1, 1, 0), b.FW_LAYOUT_ROWS),
+                                       ((4, 6, 8, 8, 3, 3, 1, 1), b.FW_LAYOUT_NHWC)])
+def test_other_shapes_keep_the_direct_form(shape, lay, dt):
+    p = b.fw_cov_plan_query(dt, lay, b.conv_desc(*shape))
+    assert p.shift == 0 and p.regions == 0 and p.covered_pixels == 0
+    assert p.workgroups >= 1 and p.mfma_flops_issued > 0
+
+
+def test_headline_workload_numbers():
+    """Config 2: 9 regions, 13 differences, 64 x 832 x 131072 products."""
+    p = b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(128, 64, 32, 32, 3, 3, 1, 1))
+    assert (p.shift, p.regions, p.differences) == (1, 9, 13)
+    assert p.mfma_flops_issued == 2.0 * 64 * 832 * 131072
+    assert p.workgroups <= 256
+
+
+def test_bad_arguments():
+    with pytest.raises(b.FwError):
+        b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(0, 64, 8, 8, 3, 3, 1, 1))
+    with pytest.raises(b.FwError):
+        b.fw_cov_plan_query(7, b.FW_LAYOUT_NHWC, b.conv_desc(2, 64, 8, 8, 3, 3, 1, 1))
