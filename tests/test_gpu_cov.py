@@ -58,6 +58,7 @@ SHIFT_CASES = [  # stride-1 windows (B, Cin, H, W, kh, kw, pad): every border sh
     (3, 64, 9, 7, 3, 3, 1), (2, 64, 8, 8, 3, 3, 0), (2, 64, 5, 6, 3, 3, 2), (2, 32, 9, 9, 5, 5, 2), (5, 128, 2, 2, 3, 3, 1),
     (2, 64, 6, 5, 3, 1, 0), (2, 64, 5, 7, 1, 3, 0), (3, 96, 7, 7, 2, 2, 1), (1, 64, 3, 8, 4, 4, 3), (2, 200, 6, 6, 3, 3, 1),
     (40, 64, 12, 11, 3, 3, 1), (1, 256, 1, 1, 3, 3, 1), (2, 64, 3, 3, 3, 3, 0),
+    (1, 8, 10, 10, 3, 3, 1), (2, 12, 7, 9, 3, 3, 1), (1, 64, 12, 12, 7, 7, 3), (3, 64, 6, 6, 5, 3, 2), (300, 4, 5, 5, 3, 3, 1), (9, 320, 4, 5, 3, 3, 1),
 ]
 
 
