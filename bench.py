@@ -134,6 +134,20 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False):
            "sgd_ms": time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt)),
            "diag_ms": time_call(lambda: b.fw_diagnostics(Py, None, M, diag_out, ws_diag)),
            "gamma": prm.gamma, "act_bytes": float(X.numel() * X.element_size()), "step": step}
+    if not layer.is_rows and d.kh * d.kw > 1:
+        # per-channel variant of the same layer (whitening in front of the convolution, M = Cin): moments of the 1x1
+        # "window" over the input pixels, and every tap's S x Cin gradient times the one Cin x Cin Q
+        taps = d.kh * d.kw
+        d1 = wl.ConvDesc(B=d.B, Cin=d.Cin, H=d.H, W=d.W, kh=1, kw=1, stride=1, pad=0)
+        desc1 = b.conv_desc(*d1.astuple())
+        A1 = torch.zeros(d.Cin, d.Cin, device=dev); s1 = torch.zeros(d.Cin, device=dev)
+        ws1 = torch.empty(b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, d.Cin, 0, desc1, dt), dtype=torch.uint8, device=dev)
+        Q1 = torch.eye(d.Cin, device=dev)
+        G4 = torch.randn(S, d.Cin, taps, device=dev) * 0.03
+        G4o = torch.empty_like(G4)
+        ws4 = torch.empty(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM_TAPS, d.Cin, S * taps), dtype=torch.uint8, device=dev)
+        out["per_channel_cov_ms"] = time_call(lambda: b.fw_cov_accumulate(X, dt, lay, desc1, A1, s1, ws1))
+        out["per_channel_grad_ms"] = time_call(lambda: b.fw_grad_transform_taps(G4, b.FW_F32, S, d.Cin, taps, Q1, G4o, ws4))
     if evd:   # the EVD / ZCA reference construction replaces the recursive step; timed once, outside the headline
         ws_evd = torch.empty(b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, M), dtype=torch.uint8, device=dev)
         lam = torch.empty(M, device=dev)
@@ -257,6 +271,9 @@ def main():
     out["breakdown_ms"]["cond_state_refresh_per_block"] = r["refresh_ms"]
     out["breakdown_ms"]["sgd_update_fused"] = r["sgd_ms"]
     out["breakdown_ms"]["diagnostics_whiteness"] = r["diag_ms"]
+    if "per_channel_cov_ms" in r:
+        out["breakdown_ms"]["per_channel_variant_cov_accumulate"] = r["per_channel_cov_ms"]
+        out["breakdown_ms"]["per_channel_variant_grad_transform_taps"] = r["per_channel_grad_ms"]
     out["cond_state_refresh_TFLOPs"] = 4.0 * M * M * M / (r["refresh_ms"] * 1e-3) / 1e12
     if "evd_ms" in r:
         out["breakdown_ms"]["whiten_evd"] = r["evd_ms"]
