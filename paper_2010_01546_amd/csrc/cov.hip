@@ -615,6 +615,7 @@ static bool nchw_through_copy(const fw_conv_desc* d, fw_dtype dt, fw_layout lay)
 static size_t act_copy_bytes(const fw_conv_desc* d) { return align_up((size_t)d->B * d->Cin * d->H * d->W * sizeof(float), 256); }
 
 size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_layout lay) {
+    if (d && cov_skinny_applies(d, lay)) return cov_skinny_workspace_bytes(d, lay);
     if (dt == FW_BF16) return cov_bf16_workspace_bytes(d, lay);
     if (!d) return 0;
     const bool copy = nchw_through_copy(d, dt, lay);
@@ -629,6 +630,7 @@ size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_lay
 
 bool cov_plan(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, fw_cov_plan* plan) {
     *plan = fw_cov_plan{};
+    if (cov_skinny_plan(d, lay, plan)) return true;
     if (dt == FW_BF16) return cov_bf16_plan(d, lay, plan);
     if (nchw_through_copy(d, dt, lay)) lay = FW_LAYOUT_NHWC;
     if (cov_shift_plan(d, lay, plan)) return true;
@@ -642,6 +644,8 @@ bool cov_plan(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, fw_cov_plan* pl
 
 fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,
                          size_t ws_bytes, hipStream_t st) {
+    // few features, many rows, 1x1 window: streamed once, no staging (cov_skinny.hip)
+    if (cov_skinny_applies(d, lay)) return cov_skinny_accumulate(X, dt, lay, d, A, s, ws, ws_bytes, st);
     if (dt == FW_BF16) return cov_bf16_accumulate(X, lay, d, A, s, ws, ws_bytes, st);
     const bool copy = nchw_through_copy(d, dt, lay);
     if (copy) lay = FW_LAYOUT_NHWC;

@@ -119,6 +119,13 @@ fw_status cov_shift_accumulate(const float* X, fw_layout lay, const fw_conv_desc
 
 bool cov_shift_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan);
 
+// ---- cov_skinny.hip
+bool cov_skinny_applies(const fw_conv_desc* d, fw_layout lay);
+size_t cov_skinny_workspace_bytes(const fw_conv_desc* d, fw_layout lay);
+bool cov_skinny_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan);
+fw_status cov_skinny_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,
+                                size_t ws_bytes, hipStream_t st);
+
 // ---- cov_bf16.hip
 bool cov_bf16_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan);
 size_t cov_bf16_workspace_bytes(const fw_conv_desc* d, fw_layout lay);

@@ -76,6 +76,26 @@ def test_stride_one_windows(B, Cin, H, W, kh, kw, pad, layout, dtype):
     check_layer(wl.Layer("shift", d, 4, dtype, act, G), layout)
 
 
+SKINNY_ROWS = [(5000, 64, "f32"), (4096, 100, "bf16"), (3001, 17, "f32"), (2500, 128, "bf16"), (3000, 5, "f32"), (2049, 33, "bf16"),
+               (70000, 96, "f32")]
+
+
+@pytest.mark.parametrize("n_rows,M,dtype", SKINNY_ROWS)
+def test_few_features_many_rows(n_rows, M, dtype):
+    """Plain rows with M <= 128 and thousands of rows take the streaming kernel (no staging, one partial result per workgroup)."""
+    layer = wl.small_rows(20 + M, n_rows, M, 4, dtype=dtype)
+    assert b.fw_cov_plan_query(b.FW_BF16 if dtype == "bf16" else b.FW_F32, b.FW_LAYOUT_ROWS, b.conv_desc(*layer.desc.astuple())).shift == 0
+    check_layer(layer, b.FW_LAYOUT_ROWS)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NCHW, b.FW_LAYOUT_NHWC_KKC])
+@pytest.mark.parametrize("B,Cin,H,W,stride", [(16, 64, 31, 30, 2), (8, 96, 20, 20, 1), (40, 16, 9, 9, 1), (6, 128, 33, 17, 3)])
+def test_pointwise_windows(B, Cin, H, W, stride, layout, dtype):
+    """1x1 windows (the per-channel variant, shortcut convolutions): strided pixel subsets of a channels-last tensor."""
+    check_layer(wl.small_conv(B + Cin, B, Cin, H, W, 1, stride, 0, 8, dtype=dtype), layout)
+
+
 def test_accumulates_over_batches_and_two_block_recursion():
     """Two batches added into one block equal the block of their union; the second block follows eqs. (vmuxi), (vPhixi)."""
     L0 = wl.small_conv(1, 3, 8, 6, 6, 3, 1, 1, 8)
