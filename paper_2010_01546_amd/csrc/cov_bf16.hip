@@ -133,11 +133,19 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
     const int bg0 = chunk * g.bg_per_chunk, bg1 = min(g.Bg, bg0 + g.bg_per_chunk);
     float acc = 0.f;
     for (int bg = bg0; bg < bg1; ++bg) {
+        // eight loads in flight: issued unconditionally (a masked one reads element 0) and masked afterwards; the empty
+        // asm statement keeps the compiler from moving them into branches, where each would be waited for on the spot
         unsigned v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int b = bg * 8 + i;
-            v[i] = (inside && b < g.B) ? X[(long long)b * img_stride + src0] : 0u;
+            const long long idx = (inside && b < g.B) ? (long long)b * img_stride + src0 : 0;
+            v[i] = X[idx];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            asm volatile("" : "+v"(v[i]));
+            if (!(inside && bg * 8 + i < g.B)) v[i] = 0u;
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc += __uint_as_float(v[i] << 16);
