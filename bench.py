@@ -167,7 +167,7 @@ def main():
         # One run of this sweep (default steps, fresh machine) ended with a GPU memory fault whose cause has not been
         # found; three runs of the same code before it were clean.  Until the cause is known the sweep does not run.
         print("bench.py --config c5 is switched off: a run of it ended in an unexplained GPU fault "
-              "(the recorded figures of its earlier clean runs are in DESIGN.md)", file=sys.stderr)
+              "(the figures of its earlier clean runs are recorded in the design notes)", file=sys.stderr)
         sys.exit(3)
     import numpy as np
     import torch
