@@ -30,8 +30,8 @@ HBM_PEAK = 8.0e12
 # counter scaled by what it reads on a 256 MiB device copy (2 KiB per FETCH_SIZE count, 1 KiB per WRITE_SIZE count).
 # Measured with the default layout (kkc); other layouts report null.
 MEASURED_TRAFFIC = {"c2": {"read": 122.5e6, "written": 58.9e6},
-                    "c3": {"read": 192.0e6, "written": 126.0e6},
-                    "c4": {"read": 466.1e6, "written": 242.4e6}}
+                    "c3": {"read": 192.4e6, "written": 120.2e6},
+                    "c4": {"read": 467.2e6, "written": 228.9e6}}
 
 
 def parse():
@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--layout", default="kkc", choices=["kkc", "nhwc", "nchw"],
                     help="kkc: NHWC tensor with channels-last feature order (ky,kx,c); nhwc/nchw: feature order (c,ky,kx)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the timing of the companion exports (refresh, fused update, diagnostics, per-channel variant): "
+                         "a profile of such a run holds the kernels of the step only")
     ap.add_argument("--c5-unlocked", action="store_true", help=argparse.SUPPRESS)   # only once the fault of the sweep is explained
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, copy a 256 MiB tensor five times: the known-size kernel against which the\n"
@@ -52,7 +55,7 @@ def parse():
     return ap.parse_args()
 
 
-def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False):
+def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extras=True):
     """One whitened layer: K timed steps of the whole hot path plus a per-export breakdown.  Returns a dict of timings."""
     dev = "cuda:0"
     d = layer.desc
@@ -130,11 +133,11 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False):
            "cond_ms": time_call(lambda: b.fw_cond_reduce_step(st, prm, info, ws_cond)),
            "grad_ms": time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)),
            "fin_ms": time_call(lambda: b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar)),
-           "refresh_ms": time_call(lambda: b.fw_cond_state_refresh(st), reps=5),
-           "sgd_ms": time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt)),
-           "diag_ms": time_call(lambda: b.fw_diagnostics(Py, None, M, diag_out, ws_diag)),
+           "refresh_ms": time_call(lambda: b.fw_cond_state_refresh(st), reps=5) if extras else None,
+           "sgd_ms": time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt)) if extras else None,
+           "diag_ms": time_call(lambda: b.fw_diagnostics(Py, None, M, diag_out, ws_diag)) if extras else None,
            "gamma": prm.gamma, "act_bytes": float(X.numel() * X.element_size()), "step": step}
-    if not layer.is_rows and d.kh * d.kw > 1:
+    if extras and not layer.is_rows and d.kh * d.kw > 1:
         # per-channel variant of the same layer (whitening in front of the convolution, M = Cin): moments of the 1x1
         # "window" over the input pixels, and every tap's S x Cin gradient times the one Cin x Cin Q
         taps = d.kh * d.kw
@@ -223,7 +226,7 @@ def main():
 
     layer = {"c1": wl.config1, "c2": wl.config2, "c3": wl.config3, "c4": wl.config4}[args.config]()
     d = layer.desc
-    r = time_layer(layer, args.layout, args.steps, args.warmup, torch, b, wl, evd=args.evd)
+    r = time_layer(layer, args.layout, args.steps, args.warmup, torch, b, wl, evd=args.evd, extras=not args.no_extras)
     M, S, n_rows, bf16 = r["M"], r["S"], r["n_rows"], r["bf16"]
     ms_per_step, cov_ms, cond_ms, grad_ms, fin_ms = r["ms_per_step"], r["cov_ms"], r["cond_ms"], r["grad_ms"], r["fin_ms"]
 
@@ -268,13 +271,14 @@ def main():
     }
     # once per block when the data (hence Phi_x) changes between blocks; the timed step feeds the same batch again, so
     # Phi_x is stationary there and the call is not part of the step
-    out["breakdown_ms"]["cond_state_refresh_per_block"] = r["refresh_ms"]
-    out["breakdown_ms"]["sgd_update_fused"] = r["sgd_ms"]
-    out["breakdown_ms"]["diagnostics_whiteness"] = r["diag_ms"]
+    if r["refresh_ms"] is not None:
+        out["breakdown_ms"]["cond_state_refresh_per_block"] = r["refresh_ms"]
+        out["breakdown_ms"]["sgd_update_fused"] = r["sgd_ms"]
+        out["breakdown_ms"]["diagnostics_whiteness"] = r["diag_ms"]
+        out["cond_state_refresh_TFLOPs"] = 4.0 * M * M * M / (r["refresh_ms"] * 1e-3) / 1e12
     if "per_channel_cov_ms" in r:
         out["breakdown_ms"]["per_channel_variant_cov_accumulate"] = r["per_channel_cov_ms"]
         out["breakdown_ms"]["per_channel_variant_grad_transform_taps"] = r["per_channel_grad_ms"]
-    out["cond_state_refresh_TFLOPs"] = 4.0 * M * M * M / (r["refresh_ms"] * 1e-3) / 1e12
     if "evd_ms" in r:
         out["breakdown_ms"]["whiten_evd"] = r["evd_ms"]
     alpha = 0.1
