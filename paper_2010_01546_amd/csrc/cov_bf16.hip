@@ -43,7 +43,18 @@ struct TileRegion {
     int rowmask, colmask;        // bit ty / tx: its pixels serve taps of row ty / column tx
     int chunk_begin, nchunks;    // its units in the unit table, padded to whole chunks
     int split_begin, nsplit;     // its unit ranges
+    unsigned dmask[4];           // bit di: some pair of taps (t1 >= t2, t1 served by this region) has the difference di
 };
+
+// does column tile J (features J*tc .. J*tc + tc - 1 of the nd*Cin shifted features) hold a difference the region uses?
+__host__ __device__ inline bool region_needs_tile(const TileRegion& R, int J, int tc, int Cin, int nd) {
+    const int d0 = (J * tc) / Cin;
+    int d1 = (J * tc + tc - 1) / Cin;
+    if (d1 > nd - 1) d1 = nd - 1;
+    for (int di = d0; di <= d1; ++di)
+        if ((R.dmask[di >> 5] >> (di & 31)) & 1u) return true;
+    return false;
+}
 
 struct TileGeom {
     int M, ntiles;
@@ -220,6 +231,8 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
         const int first = (split - g.reg[ri].split_begin) * g.chunks_per_split;
         c_begin = g.reg[ri].chunk_begin + first;
         nchunks = min(g.chunks_per_split, g.reg[ri].nchunks - first);
+        // a border region serves few taps, and so only some of the differences: its other tiles are never read
+        if (!region_needs_tile(g.reg[ri], J, g.tc, g.Cin, g.nd)) return;
     }
     // all of these are the same for the whole workgroup: keep them in scalar registers
     tile = __builtin_amdgcn_readfirstlane(tile); split = __builtin_amdgcn_readfirstlane(split);
@@ -521,6 +534,15 @@ bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
             R.y0 = rows[a].begin; R.rh = rows[a].len; R.rowmask = rows[a].mask;
             R.x0 = cols[b].begin; R.rw = cols[b].len; R.colmask = cols[b].mask;
             R.nchunks = (int)(((long long)g->Bg * R.rh * R.rw + KU - 1) / KU);
+            for (int q = 0; q < 4; ++q) R.dmask[q] = 0;
+            for (int t1 = 0; t1 < d->kh * d->kw; ++t1) {
+                const int t1y = t1 / d->kw, t1x = t1 - t1y * d->kw;
+                if (!(((R.rowmask >> t1y) & 1) && ((R.colmask >> t1x) & 1))) continue;
+                for (int t2 = 0; t2 <= t1; ++t2) {
+                    const int di = shift_diff_index(t1y - t2 / d->kw, t1x - t2 % d->kw, d->kw);
+                    R.dmask[di >> 5] |= 1u << (di & 31);
+                }
+            }
         }
     std::stable_sort(g->reg, g->reg + nregs, [](const TileRegion& x, const TileRegion& y) { return x.nchunks > y.nchunks; });
     long long total_chunks = 0;
@@ -529,7 +551,7 @@ bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
         total_chunks += g->reg[r].nchunks;
     }
     if (total_chunks * KU >= (1ll << 31) - KU) return false;
-    for (int r = g->nreg; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0};
+    for (int r = g->nreg; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0, {0, 0, 0, 0}};
     g->nchunks = (int)total_chunks;
     g->n_units = (int)(total_chunks * KU);
     g->direct = 0;
@@ -561,19 +583,22 @@ bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
         for (int i = 0; i < 256; ++i) cu.push(0.0);
         double makespan = 0.0;
         int r = 0, within = 0;
-        std::vector<int> range_len(nsplit);
+        std::vector<int> range_len(nsplit), range_reg(nsplit);
         for (int sp = 0; sp < nsplit; ++sp) {
             range_len[sp] = within == cnt[r] - 1 ? len[r] : (int)cps;
+            range_reg[sp] = r;
             if (++within == cnt[r]) { within = 0; ++r; }
         }
+        double wgs = 0.0;
         for (int g8 = 0; g8 < nsplit; g8 += 8)
             for (int t = 0; t < g->ntiles; ++t)
                 for (int sp = g8; sp < g8 + 8 && sp < nsplit; ++sp) {
+                    if (!region_needs_tile(g->reg[range_reg[sp]], t % g->ncb, g->tc, Cin, g->nd)) continue;   // leaves at once
                     const double f = cu.top() + range_len[sp] + 6.0;   // fill of the ring and write-out of the tile
                     cu.pop(); cu.push(f);
                     if (f > makespan) makespan = f;
+                    wgs += 1.0;
                 }
-        const double wgs = (double)g->ntiles * nsplit;
         const double c = makespan * t_chunk + wgs * g->tr * g->tc * 4.0 / bw +
                          0.5 * kk * (kk + 1) * (double)Cin * Cin * 4.0 * 0.6 * nsplit / bw + 0.5 * (double)g->M * g->M * 8.0 / bw;
         if (c < best) { best = c; best_cps = cps; }
@@ -599,7 +624,7 @@ bool build_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     g->Hp = d->H + 2 * d->pad; g->Wp = d->W + 2 * d->pad;
     g->py = g->px = d->pad; g->sum_shift = 0;
     g->shift = 0; g->nd = 0; g->F = 0; g->nreg = 0;
-    for (int r = 0; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0};
+    for (int r = 0; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0, {0, 0, 0, 0}};
     g->Bg = (d->B + 7) / 8;
     const long long M = (long long)d->Cin * d->kh * d->kw;
     const long long n_units = (long long)g->Bg * g->Ho * g->Wo;
@@ -708,6 +733,13 @@ bool cov_bf16_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan) {
     for (int r = 0; r < g.nreg; ++r) plan->covered_pixels += (long long)g.B * g.reg[r].rh * g.reg[r].rw;
     // every tile is multiplied over all chunks of its ranges: 32 reduction entries (4 units of 8 images) per chunk
     plan->mfma_flops_issued = 2.0 * (double)g.ntiles * g.tr * g.tc * 32.0 * (double)g.nchunks;
+    if (g.shift) {   // border regions skip the column tiles whose differences they never use
+        double chunk_tiles = 0.0;
+        for (int r = 0; r < g.nreg; ++r)
+            for (int t = 0; t < g.ntiles; ++t)
+                if (region_needs_tile(g.reg[r], t % g.ncb, g.tc, g.Cin, g.nd)) chunk_tiles += g.reg[r].nchunks;
+        plan->mfma_flops_issued = 2.0 * chunk_tiles * g.tr * g.tc * 32.0;
+    }
     return true;
 }
 
