@@ -387,18 +387,24 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
     }
 }
 
-// s[m] += sum over the output positions of the per-pixel sums under the tap of feature m: 16 features per workgroup
-// of 1024 threads, 64 lanes per feature over (position, image-group chunk), four loads in flight, float64
-__global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const float* __restrict__ S8, float* __restrict__ s) {
-    __shared__ double red[64][16];
-    const int fl = threadIdx.x & 15, pl = threadIdx.x >> 4;
-    const int fi = blockIdx.x * 16 + fl;
+// Column sums from the per-pixel sums: s[m] += sum over the output positions of S8 under the tap of feature m, in two
+// steps.  First: 64 consecutive features (consecutive channels of a tap lie next to each other in S8: a wavefront reads
+// 256 contiguous bytes) x one of CS_SLICES slices of the positions per workgroup of 1024 threads, the slice dealt to its
+// 16 wavefronts, four loads in flight, float64.  Second: the slices are added in a fixed order.
+constexpr int CS_SLICES = 16;
+__global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const float* __restrict__ S8, double* __restrict__ cpart,
+                                                           float* __restrict__ s) {
+    __shared__ double red[16][64];
+    const int fl = threadIdx.x & 63, pl = threadIdx.x >> 6;
+    const int fi = blockIdx.x * 64 + fl;
     const bool ok = fi < g.M;
     int off = 0, ext = 0;
     if (ok) feat_map(fi, g, &off, &ext);
     const int per_img = g.Hp * g.Wp * g.Cin;
     const int npos = g.Ho * g.Wo;
     const int total = npos * g.bg_chunks;
+    const int per_slice = (total + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int i0 = blockIdx.y * per_slice, i1 = min(total, i0 + per_slice);
     auto at = [&](int idx) {
         const int k = idx / npos, p = idx - k * npos;
         const int oy = p / g.Wo, ox = p - oy * g.Wo;
@@ -406,21 +412,30 @@ __global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const flo
     };
     double v = 0.0;
     if (ok) {
-        int idx = pl;
-        for (; idx + 192 < total; idx += 256) {
-            const float x0 = at(idx), x1 = at(idx + 64), x2 = at(idx + 128), x3 = at(idx + 192);
+        int idx = i0 + pl;
+        for (; idx + 48 < i1; idx += 64) {
+            const float x0 = at(idx), x1 = at(idx + 16), x2 = at(idx + 32), x3 = at(idx + 48);
             v += ((double)x0 + (double)x1) + ((double)x2 + (double)x3);
         }
-        for (; idx < total; idx += 64) v += (double)at(idx);
+        for (; idx < i1; idx += 16) v += (double)at(idx);
     }
     red[pl][fl] = v;
     __syncthreads();
     if (pl == 0 && ok) {
         double t = 0.0;
-#pragma unroll 8
-        for (int q = 0; q < 64; ++q) t += red[q][fl];
-        s[ext] = (float)((double)s[ext] + t);
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t += red[q][fl];
+        if (gridDim.y == 1) s[ext] = (float)((double)s[ext] + t);   // few positions: one slice, no second step
+        else cpart[(size_t)blockIdx.y * g.M + ext] = t;
     }
+}
+
+__global__ __launch_bounds__(256) void column_sums_final_kernel(int M, int nslices, const double* __restrict__ cpart, float* __restrict__ s) {
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= M) return;
+    double t = 0.0;
+    for (int q = 0; q < nslices; ++q) t += cpart[(size_t)q * M + m];
+    s[m] = (float)((double)s[m] + t);
 }
 
 // partial tiles -> A (float64 sum over the ranges), one thread per tile element
@@ -709,7 +724,7 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     return last.ok;
 }
 
-struct Bf16Ws { size_t packed, utab, part, s8, total; };
+struct Bf16Ws { size_t packed, utab, part, s8, cpart, total; };
 Bf16Ws ws_layout(const TileGeom& g) {
     Bf16Ws L;
     size_t o = 0;
@@ -718,6 +733,7 @@ Bf16Ws ws_layout(const TileGeom& g) {
     L.utab = take((size_t)g.nchunks * KU * 4);
     L.part = take(g.direct ? 0 : (size_t)g.nsplit * g.ntiles * g.tr * g.tc * 4);
     L.s8 = take((size_t)g.bg_chunks * g.Hp * g.Wp * g.Cin * 4);
+    L.cpart = take((size_t)CS_SLICES * g.M * sizeof(double));
     L.total = o;
     return L;
 }
@@ -760,6 +776,7 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     int* utab = reinterpret_cast<int*>(base + L.utab);
     float* part = reinterpret_cast<float*>(base + L.part);
     float* S8 = reinterpret_cast<float*>(base + L.s8);
+    double* cpart = reinterpret_cast<double*>(base + L.cpart);
     const int per_img = g.Hp * g.Wp * g.Cin;
     hipLaunchKernelGGL(pack_images_kernel, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st, reinterpret_cast<const u16*>(X),
                        g, P, S8, utab);
@@ -781,7 +798,17 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     if (g.shift) hipLaunchKernelGGL(shift_tile_assemble_kernel, dim3((g.Cin + 63) / 64, (g.Cin + 15) / 16, g.kh * g.kw * (g.kh * g.kw + 1) / 2),
                                     dim3(256), 0, st, g, part, A);
     else if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * (g.tr * g.tc / 256)), dim3(256), 0, st, g, part, A);
-    hipLaunchKernelGGL(column_sums_kernel, dim3((g.M + 15) / 16), dim3(1024), 0, st, g, S8, s);
+    {
+        // slices of the positions: enough workgroups to fill the chip, none when a workgroup per 64 features already does
+        const long long total = (long long)g.Ho * g.Wo * g.bg_chunks;
+        const int nfb = (g.M + 63) / 64;
+        int ns = (int)((256 + nfb - 1) / nfb);
+        if ((long long)ns * 256 > total) ns = (int)(total / 256);
+        if (ns > CS_SLICES) ns = CS_SLICES;
+        if (ns < 1) ns = 1;
+        hipLaunchKernelGGL(column_sums_kernel, dim3(nfb, ns), dim3(1024), 0, st, g, S8, cpart, s);
+        if (ns > 1) hipLaunchKernelGGL(column_sums_final_kernel, dim3((g.M + 255) / 256), dim3(256), 0, st, g.M, ns, cpart, s);
+    }
     FW_LAUNCH_CHECK();
     return FW_OK;
 }
