@@ -268,6 +268,14 @@ typedef struct {
 } fw_cov_plan;
 fw_status fw_cov_plan_query(fw_dtype dt, fw_layout lay, const fw_conv_desc* d, fw_cov_plan* plan);
 
+/* Which form fw_cov_accumulate takes where both the direct product and the shift form (stride-1 windows, see above)
+ * apply.  Both compute the same sums of Sec. 2; the default picks by an estimate of the run time.  The setting is
+ * process-wide, read at every call (also by fw_cov_plan_query and fw_workspace_bytes, so set it before sizing the
+ * workspace), and meant for tuning and for tests that must reach one form at sizes where the estimate prefers the other.
+ * Returns FW_ERR_INVALID_ARG for any other value. */
+typedef enum { FW_COV_FORM_AUTO = 0, FW_COV_FORM_SHIFT = 1, FW_COV_FORM_DIRECT = 2 } fw_cov_form;
+fw_status fw_cov_set_form(fw_cov_form form);
+
 /* Scratch bytes an entry point needs for the given sizes (0 if none).  `d` is needed for FW_OP_COV_ACCUMULATE only;
  * for the per-tap operations S is the number of gradient rows, S * taps. */
 size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtype dt);

@@ -184,6 +184,12 @@ fw_status fw_whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float
     return whiten_evd(Phi_x, M, p, T, Q, Qs, lambda, ws, ws_bytes, reinterpret_cast<hipStream_t>(stream));
 }
 
+fw_status fw_cov_set_form(fw_cov_form form) {
+    if (form != FW_COV_FORM_AUTO && form != FW_COV_FORM_SHIFT && form != FW_COV_FORM_DIRECT) return FW_ERR_INVALID_ARG;
+    cov_set_form((int)form);
+    return FW_OK;
+}
+
 fw_status fw_cov_plan_query(fw_dtype dt, fw_layout lay, const fw_conv_desc* d, fw_cov_plan* plan) {
     if (!plan || !d || !dtype_ok(dt) || !layout_ok(lay) || !desc_ok(d, lay)) return FW_ERR_INVALID_ARG;
     return cov_plan(d, dt, lay, plan) ? FW_OK : FW_ERR_UNSUPPORTED;
@@ -228,6 +234,6 @@ const char* fw_status_string(fw_status st) {
     return "unknown status";
 }
 
-int fw_version(void) { return 102; }
+int fw_version(void) { return 103; }
 
 }  // extern "C"

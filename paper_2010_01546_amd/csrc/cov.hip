@@ -12,6 +12,7 @@
 // read consecutive channels; the reduce kernel maps back to the external order m = (c*kh + ky)*kw + kx, or keeps the
 // internal order when the caller asked for it (FW_LAYOUT_NHWC_KKC).
 #include "fw_internal.h"
+#include <atomic>
 #include <type_traits>
 
 namespace fw {
@@ -627,6 +628,10 @@ size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_lay
     const size_t sp = (size_t)g.nsplit * g.nb * BLK * sizeof(float);
     return align_up(part, 256) + align_up(sp, 256) + (copy ? act_copy_bytes(d) : 0);
 }
+
+static std::atomic<int> g_cov_form{FW_COV_FORM_AUTO};
+int cov_form() { return g_cov_form.load(std::memory_order_relaxed); }
+void cov_set_form(int form) { g_cov_form.store(form, std::memory_order_relaxed); }
 
 bool cov_plan(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, fw_cov_plan* plan) {
     *plan = fw_cov_plan{};

@@ -41,6 +41,7 @@ constexpr int MAXREG = 32;
 struct TileRegion {
     int y0, x0, rh, rw;          // rectangle of pixels
     int rowmask, colmask;        // bit ty / tx: its pixels serve taps of row ty / column tx
+    int colmask2;                // pixel pairs (gx = 2): the column taps served by the odd pixel of a pair
     int chunk_begin, nchunks;    // its units in the unit table, padded to whole chunks
     int split_begin, nsplit;     // its unit ranges
     unsigned dmask[4];           // bit di: some pair of taps (t1 >= t2, t1 served by this region) has the difference di
@@ -69,6 +70,13 @@ struct TileGeom {
     int sum_shift;                 // offset of the tap (0,0) of output position (0,0) in P
     // shift-correlation mode (stride-1 windows): rows = Cin channels of a pixel, columns = nd tap differences x Cin
     int shift, nd, F, nreg;
+    // Few channels (Cin <= 64): a unit of the shift mode is a PAIR of horizontally neighbouring pixels, i.e. the image is
+    // read as W/2 pixels of 2 Cin channels (the packed layout is the same memory either way).  Row features: both pixels'
+    // channels (a full 128-row tile); kept differences: those of a window half as wide, (dy, e) with e counted in pairs.
+    // A product of pixel 2X+a with pixel 2X+a-dx of the original differences is the entry (a, c1) x (a', c2) of the pair
+    // difference e = -floor((a - dx) / 2), a' = (a - dx) mod 2.
+    int gx;                      // pixels per unit along x: 1 or 2
+    int t_cin, t_wp, t_kw;       // the contraction's view: channels per unit, units per packed row, width of the difference window
     TileRegion reg[MAXREG];
 };
 
@@ -115,7 +123,7 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
             if (l < g.Bg * area) {
                 const int bg = l / area, p = l - bg * area;
                 const int yy = p / g.reg[ri].rw, xx = p - yy * g.reg[ri].rw;
-                v = ((bg * g.Hp + g.reg[ri].y0 + yy + g.py) * g.Wp + g.reg[ri].x0 + xx + g.px) * g.Cin;
+                v = ((bg * g.Hp + g.reg[ri].y0 + yy + g.py) * g.Wp + g.gx * (g.reg[ri].x0 + xx) + g.px) * g.Cin;
             }
             utab[u] = v;
         }
@@ -232,7 +240,7 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
         c_begin = g.reg[ri].chunk_begin + first;
         nchunks = min(g.chunks_per_split, g.reg[ri].nchunks - first);
         // a border region serves few taps, and so only some of the differences: its other tiles are never read
-        if (!region_needs_tile(g.reg[ri], J, g.tc, g.Cin, g.nd)) return;
+        if (!region_needs_tile(g.reg[ri], J, g.tc, g.t_cin, g.nd)) return;
     }
     // all of these are the same for the whole workgroup: keep them in scalar registers
     tile = __builtin_amdgcn_readfirstlane(tile); split = __builtin_amdgcn_readfirstlane(split);
@@ -252,15 +260,15 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
             ok = f < g.M;
             int ext_unused;
             feat_map(ok ? f : 0, g, &off[k], &ext_unused);
-        } else if (k < NRT) {           // channel f of the pixel itself
-            ok = f < g.Cin;
+        } else if (k < NRT) {           // channel f of the unit (pixel, or pixel pair) itself
+            ok = f < g.t_cin;
             off[k] = ok ? f : 0;
-        } else {                        // channel c of the pixel shifted back by tap difference di
+        } else {                        // channel c of the unit shifted back by difference di
             ok = f < g.F;
-            const int di = ok ? f / g.Cin : 0, c = ok ? f - di * g.Cin : 0;
+            const int di = ok ? f / g.t_cin : 0, c = ok ? f - di * g.t_cin : 0;
             int dy, dx;
-            shift_diff_of(di, g.kw, &dy, &dx);
-            off[k] = -(dy * g.Wp + dx) * g.Cin + c;
+            shift_diff_of(di, g.t_kw, &dy, &dx);
+            off[k] = -(dy * g.t_wp + dx) * g.t_cin + c;
         }
         okmask |= (ok ? 1u : 0u) << k;
     }
@@ -389,9 +397,10 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
 
 // Column sums from the per-pixel sums: s[m] += sum over the output positions of S8 under the tap of feature m, in two
 // steps.  First: 64 consecutive features (consecutive channels of a tap lie next to each other in S8: a wavefront reads
-// 256 contiguous bytes) x one of CS_SLICES slices of the positions per workgroup of 1024 threads, the slice dealt to its
-// 16 wavefronts, four loads in flight, float64.  Second: the slices are added in a fixed order.
-constexpr int CS_SLICES = 16;
+// 256 contiguous bytes) x one of up to CS_SLICES slices of the positions per workgroup of 1024 threads, the slice dealt
+// to its 16 wavefronts in runs of eight positions along an output row: eight loads in flight and no index arithmetic
+// between them, float64 (the loop is a chain of load latencies: many short slices beat few long ones).  Second: the slices are added in a fixed order, 16 lanes per feature.
+constexpr int CS_SLICES = 64;
 __global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const float* __restrict__ S8, double* __restrict__ cpart,
                                                            float* __restrict__ s) {
     __shared__ double red[16][64];
@@ -401,24 +410,29 @@ __global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const flo
     int off = 0, ext = 0;
     if (ok) feat_map(fi, g, &off, &ext);
     const int per_img = g.Hp * g.Wp * g.Cin;
-    const int npos = g.Ho * g.Wo;
-    const int total = npos * g.bg_chunks;
+    // items: runs of eight positions along an output row (one batch of loads, no index arithmetic inside)
+    const int nseg = (g.Wo + 7) >> 3;
+    const int total = g.Ho * g.bg_chunks * nseg;
     const int per_slice = (total + (int)gridDim.y - 1) / (int)gridDim.y;
     const int i0 = blockIdx.y * per_slice, i1 = min(total, i0 + per_slice);
-    auto at = [&](int idx) {
-        const int k = idx / npos, p = idx - k * npos;
-        const int oy = p / g.Wo, ox = p - oy * g.Wo;
-        return S8[(size_t)k * per_img + ((oy * g.stride) * g.Wp + ox * g.stride) * g.Cin + g.sum_shift + off];
-    };
+    const int step = g.stride * g.Cin;
     double v = 0.0;
-    if (ok) {
-        int idx = i0 + pl;
-        for (; idx + 48 < i1; idx += 64) {
-            const float x0 = at(idx), x1 = at(idx + 16), x2 = at(idx + 32), x3 = at(idx + 48);
-            v += ((double)x0 + (double)x1) + ((double)x2 + (double)x3);
+    if (ok)
+        for (int it = i0 + pl; it < i1; it += 16) {
+            const int row = it / nseg, seg = it - row * nseg;
+            const int k = row / g.Ho, oy = row - k * g.Ho;
+            const float* src = S8 + (size_t)k * per_img + ((oy * g.stride) * g.Wp + seg * 8 * g.stride) * g.Cin + g.sum_shift + off;
+            const int n = min(8, g.Wo - seg * 8);
+            float x[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) x[q] = src[(q < n ? q : 0) * step];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                asm volatile("" : "+v"(x[q]));      // all eight loads are issued before the first is used
+                if (q >= n) x[q] = 0.f;
+            }
+            v += (((double)x[0] + (double)x[1]) + ((double)x[2] + (double)x[3])) + (((double)x[4] + (double)x[5]) + ((double)x[6] + (double)x[7]));
         }
-        for (; idx < i1; idx += 16) v += (double)at(idx);
-    }
     red[pl][fl] = v;
     __syncthreads();
     if (pl == 0 && ok) {
@@ -431,11 +445,19 @@ __global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const flo
 }
 
 __global__ __launch_bounds__(256) void column_sums_final_kernel(int M, int nslices, const double* __restrict__ cpart, float* __restrict__ s) {
-    const int m = blockIdx.x * 256 + threadIdx.x;
-    if (m >= M) return;
+    const int m = blockIdx.x * 16 + (threadIdx.x & 15), part = threadIdx.x >> 4;   // 16 features x 16 lanes
     double t = 0.0;
-    for (int q = 0; q < nslices; ++q) t += cpart[(size_t)q * M + m];
-    s[m] = (float)((double)s[m] + t);
+    if (m < M)
+        for (int q = part; q < nslices; q += 16) t += cpart[(size_t)q * M + m];
+    __shared__ double red[16][17];
+    red[part][threadIdx.x & 15] = t;
+    __syncthreads();
+    if (part == 0 && m < M) {
+        double v = 0.0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) v += red[q][threadIdx.x];
+        s[m] = (float)((double)s[m] + v);
+    }
 }
 
 // partial tiles -> A (float64 sum over the ranges), one thread per tile element
@@ -474,31 +496,44 @@ __global__ __launch_bounds__(256) void shift_tile_assemble_kernel(TileGeom g, co
         const int t2 = pr;
         const int t1y = t1 / g.kw, t1x = t1 - t1y * g.kw, t2y = t2 / g.kw, t2x = t2 - t2y * g.kw;
         int dy = t1y - t2y, dx = t1x - t2x;           // >= 0 in lexicographic order because t1 >= t2
-        const int di = shift_diff_index(dy, dx, g.kw);
         const int c1 = blockIdx.y * 16 + (threadIdx.x >> 4);
         const int c2 = blockIdx.x * 64 + 4 * (threadIdx.x & 15);
         if (c1 >= g.Cin || c2 >= g.Cin) return;
         if (t1 == t2 && c2 > c1 + 3) return;          // diagonal block: entries right of the diagonal are not kept
-        const int f = di * g.Cin + c2;                // four consecutive columns f .. f+3 lie in one tile (Cin % 4 == 0)
-        const int I = c1 / g.tr, J = f / g.tc;
         const size_t tsz = (size_t)g.tr * g.tc;
-        const float* src = part + (size_t)(I * g.ncb + J) * tsz + (size_t)(c1 - I * g.tr) * g.tc + (f - J * g.tc);
         const size_t stride = (size_t)g.ntiles * tsz;
         double v0 = 0.0, v1 = 0.0, v2 = 0.0, v3 = 0.0;
-        for (int r = 0; r < g.nreg; ++r) {
-            if (!(((g.reg[r].rowmask >> t1y) & 1) && ((g.reg[r].colmask >> t1x) & 1))) continue;
-            const int s1 = g.reg[r].split_begin + g.reg[r].nsplit;
-            int sp = g.reg[r].split_begin;
-            for (; sp + 4 <= s1; sp += 4) {
-                float4 x[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) x[q] = *reinterpret_cast<const float4*>(src + (size_t)(sp + q) * stride);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) { v0 += (double)x[q].x; v1 += (double)x[q].y; v2 += (double)x[q].z; v3 += (double)x[q].w; }
+        for (int a = 0; a < g.gx; ++a) {              // the pixel of a pair that plays the row tap (one pass without pairs)
+            int row, f;
+            if (g.gx == 1) {
+                row = c1;
+                f = shift_diff_index(dy, dx, g.kw) * g.Cin + c2;
+            } else {
+                const int sft = a - dx;               // the column pixel is 2X + a - dx: pair X + floor(sft / 2), parity sft mod 2
+                const int fl = sft >= 0 ? sft / 2 : -((1 - sft) / 2);
+                const int ap = sft - 2 * fl;
+                row = a * g.Cin + c1;
+                f = shift_diff_index(dy, -fl, g.t_kw) * g.t_cin + ap * g.Cin + c2;
             }
-            for (; sp < s1; ++sp) {
-                const float4 x = *reinterpret_cast<const float4*>(src + (size_t)sp * stride);
-                v0 += (double)x.x; v1 += (double)x.y; v2 += (double)x.z; v3 += (double)x.w;
+            // four consecutive columns f .. f+3 lie in one tile (Cin % 4 == 0)
+            const int I = row / g.tr, J = f / g.tc;
+            const float* src = part + (size_t)(I * g.ncb + J) * tsz + (size_t)(row - I * g.tr) * g.tc + (f - J * g.tc);
+            for (int r = 0; r < g.nreg; ++r) {
+                const int cm = a == 0 ? g.reg[r].colmask : g.reg[r].colmask2;
+                if (!(((g.reg[r].rowmask >> t1y) & 1) && ((cm >> t1x) & 1))) continue;
+                const int s1 = g.reg[r].split_begin + g.reg[r].nsplit;
+                int sp = g.reg[r].split_begin;
+                for (; sp + 4 <= s1; sp += 4) {
+                    float4 x[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) x[q] = *reinterpret_cast<const float4*>(src + (size_t)(sp + q) * stride);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) { v0 += (double)x[q].x; v1 += (double)x[q].y; v2 += (double)x[q].z; v3 += (double)x[q].w; }
+                }
+                for (; sp < s1; ++sp) {
+                    const float4 x = *reinterpret_cast<const float4*>(src + (size_t)sp * stride);
+                    v0 += (double)x.x; v1 += (double)x.y; v2 += (double)x.z; v3 += (double)x.w;
+                }
             }
         }
         const double v[4] = {v0, v1, v2, v3};
@@ -519,27 +554,63 @@ __global__ __launch_bounds__(256) void shift_tile_assemble_kernel(TileGeom g, co
 // same terms as the direct form's (see make_tile_geom).
 bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
     if (d->stride != 1 || d->kh * d->kw <= 1 || d->kh > 8 || d->kw > 8 || (d->Cin & 3) != 0) return false;
+    if (cov_form() == FW_COV_FORM_DIRECT) return false;
     const int Cin = d->Cin;
-    g->nd = d->kw + (d->kh - 1) * (2 * d->kw - 1);
-    const long long F = (long long)g->nd * Cin;
+    const int gx = Cin <= 128 && d->W >= 4 ? 2 : 1;    // few channels: pairs of pixels fill the rows of a larger tile
+    g->gx = gx;
+    g->t_cin = gx * Cin;
+    g->t_kw = gx == 1 ? d->kw : d->kw / 2 + 1;        // pairs back: 0 .. kw / 2 (and as many forward under dy > 0)
+    g->nd = g->t_kw + (d->kh - 1) * (2 * g->t_kw - 1);
+    const long long F = (long long)g->nd * g->t_cin;
     if (F > (1 << 20)) return false;
     g->F = (int)F;
     g->shift = 1;
-    // border of zeros: what the tap differences reach above and to both sides, the windows' own padding below
-    const int hy = d->kh - 1 > d->pad ? d->kh - 1 : d->pad, hx = d->kw - 1 > d->pad ? d->kw - 1 : d->pad;
+    // border of zeros: what the differences reach above and to both sides, the windows' own padding below
+    const int reach = gx * (g->t_kw - 1);
+    const int hy = d->kh - 1 > d->pad ? d->kh - 1 : d->pad, hx = reach > d->pad ? reach : d->pad;
+    const int wu = (d->W + gx - 1) / gx;               // units per image row; an odd last pixel pairs with the border
     g->py = hy; g->px = hx;
-    g->Hp = d->H + hy + d->pad; g->Wp = d->W + 2 * hx;
+    g->Hp = d->H + hy + d->pad; g->Wp = hx + gx * wu + hx;
+    if (g->Wp % gx) ++g->Wp;
+    g->t_wp = g->Wp / gx;
     g->sum_shift = ((g->py - d->pad) * g->Wp + (g->px - d->pad)) * Cin;
     const long long packed = (long long)g->Bg * g->Hp * g->Wp * Cin;
     if (packed + 16 >= (1ll << 31)) return false;
     ShiftBand rows[16], cols[16];
-    const int nr = shift_bands(d->H, d->kh, d->pad, g->Ho, rows, 16), nc = shift_bands(d->W, d->kw, d->pad, g->Wo, cols, 16);
-    if (nr <= 0 || nc <= 0 || nr * nc > MAXREG) return false;
+    const int nr = shift_bands(d->H, d->kh, d->pad, g->Ho, rows, 16);
+    int nc = shift_bands(d->W, d->kw, d->pad, g->Wo, cols, 16);
+    if (nr <= 0 || nc <= 0) return false;
+    int colmask2[16] = {0};
+    if (gx == 2) {
+        // bands of pairs: runs of pairs X whose pixels 2X and 2X + 1 serve the same two sets of column taps
+        auto mask_at = [&](int x) {
+            for (int b = 0; b < nc; ++b)
+                if (x >= cols[b].begin && x < cols[b].begin + cols[b].len) return cols[b].mask;
+            return 0;                                  // beyond the image, or a pixel that serves no tap
+        };
+        ShiftBand pc[16];
+        int np = 0, X = 0;
+        while (X < wu) {
+            const int m0 = mask_at(2 * X), m1 = mask_at(2 * X + 1);
+            int X1 = X;
+            while (X1 + 1 < wu && mask_at(2 * X1 + 2) == m0 && mask_at(2 * X1 + 3) == m1) ++X1;
+            if (m0 | m1) {
+                if (np == 16) return false;
+                pc[np] = ShiftBand{X, X1 - X + 1, m0};
+                colmask2[np++] = m1;
+            }
+            X = X1 + 1;
+        }
+        nc = np;
+        for (int b = 0; b < nc; ++b) cols[b] = pc[b];
+        if (nc <= 0) return false;
+    }
+    if (nr * nc > MAXREG) return false;
     g->nreg = nr * nc;
-    g->nrt = Cin > 192 ? 4 : Cin > 128 ? 3 : 2;
+    g->nrt = g->t_cin > 192 ? 4 : g->t_cin > 128 ? 3 : 2;
     g->nct = 4;
     g->tr = 64 * g->nrt; g->tc = 64 * g->nct;
-    g->nrb = (Cin + g->tr - 1) / g->tr; g->ncb = (g->F + g->tc - 1) / g->tc;
+    g->nrb = (g->t_cin + g->tr - 1) / g->tr; g->ncb = (g->F + g->tc - 1) / g->tc;
     g->ntiles = g->nrb * g->ncb;
     // regions, largest first: their ranges are dispatched in this order, so the short ones fill the end
     int nregs = 0;
@@ -547,17 +618,24 @@ bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
         for (int b = 0; b < nc; ++b) {
             TileRegion& R = g->reg[nregs++];
             R.y0 = rows[a].begin; R.rh = rows[a].len; R.rowmask = rows[a].mask;
-            R.x0 = cols[b].begin; R.rw = cols[b].len; R.colmask = cols[b].mask;
+            R.x0 = cols[b].begin; R.rw = cols[b].len; R.colmask = cols[b].mask; R.colmask2 = colmask2[b];
             R.nchunks = (int)(((long long)g->Bg * R.rh * R.rw + KU - 1) / KU);
             for (int q = 0; q < 4; ++q) R.dmask[q] = 0;
-            for (int t1 = 0; t1 < d->kh * d->kw; ++t1) {
-                const int t1y = t1 / d->kw, t1x = t1 - t1y * d->kw;
-                if (!(((R.rowmask >> t1y) & 1) && ((R.colmask >> t1x) & 1))) continue;
-                for (int t2 = 0; t2 <= t1; ++t2) {
-                    const int di = shift_diff_index(t1y - t2 / d->kw, t1x - t2 % d->kw, d->kw);
-                    R.dmask[di >> 5] |= 1u << (di & 31);
+            for (int pa = 0; pa < gx; ++pa)
+                for (int t1 = 0; t1 < d->kh * d->kw; ++t1) {
+                    const int t1y = t1 / d->kw, t1x = t1 - t1y * d->kw;
+                    if (!(((R.rowmask >> t1y) & 1) && (((pa ? R.colmask2 : R.colmask) >> t1x) & 1))) continue;
+                    for (int t2 = 0; t2 <= t1; ++t2) {
+                        const int dy = t1y - t2 / d->kw, dx = t1x - t2 % d->kw;
+                        int di;
+                        if (gx == 1) di = shift_diff_index(dy, dx, d->kw);
+                        else {
+                            const int sft = pa - dx;
+                            di = shift_diff_index(dy, sft >= 0 ? -(sft / 2) : (1 - sft) / 2, g->t_kw);
+                        }
+                        R.dmask[di >> 5] |= 1u << (di & 31);
+                    }
                 }
-            }
         }
     std::stable_sort(g->reg, g->reg + nregs, [](const TileRegion& x, const TileRegion& y) { return x.nchunks > y.nchunks; });
     long long total_chunks = 0;
@@ -566,7 +644,7 @@ bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
         total_chunks += g->reg[r].nchunks;
     }
     if (total_chunks * KU >= (1ll << 31) - KU) return false;
-    for (int r = g->nreg; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0, {0, 0, 0, 0}};
+    for (int r = g->nreg; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0, 0, {0, 0, 0, 0}};
     g->nchunks = (int)total_chunks;
     g->n_units = (int)(total_chunks * KU);
     g->direct = 0;
@@ -608,14 +686,14 @@ bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
         for (int g8 = 0; g8 < nsplit; g8 += 8)
             for (int t = 0; t < g->ntiles; ++t)
                 for (int sp = g8; sp < g8 + 8 && sp < nsplit; ++sp) {
-                    if (!region_needs_tile(g->reg[range_reg[sp]], t % g->ncb, g->tc, Cin, g->nd)) continue;   // leaves at once
+                    if (!region_needs_tile(g->reg[range_reg[sp]], t % g->ncb, g->tc, g->t_cin, g->nd)) continue;   // leaves at once
                     const double f = cu.top() + range_len[sp] + 6.0;   // fill of the ring and write-out of the tile
                     cu.pop(); cu.push(f);
                     if (f > makespan) makespan = f;
                     wgs += 1.0;
                 }
         const double c = makespan * t_chunk + wgs * g->tr * g->tc * 4.0 / bw +
-                         0.5 * kk * (kk + 1) * (double)Cin * Cin * 4.0 * 0.6 * nsplit / bw + 0.5 * (double)g->M * g->M * 8.0 / bw;
+                         0.5 * kk * (kk + 1) * (double)Cin * Cin * 4.0 * 0.6 * gx * nsplit / bw + 0.5 * (double)g->M * g->M * 8.0 / bw;
         if (c < best) { best = c; best_cps = cps; }
     }
     g->chunks_per_split = (int)best_cps;
@@ -639,7 +717,8 @@ bool build_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     g->Hp = d->H + 2 * d->pad; g->Wp = d->W + 2 * d->pad;
     g->py = g->px = d->pad; g->sum_shift = 0;
     g->shift = 0; g->nd = 0; g->F = 0; g->nreg = 0;
-    for (int r = 0; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0, {0, 0, 0, 0}};
+    for (int r = 0; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0, 0, {0, 0, 0, 0}};
+    g->gx = 1; g->t_cin = d->Cin; g->t_wp = g->Wp; g->t_kw = d->kw;
     g->Bg = (d->B + 7) / 8;
     const long long M = (long long)d->Cin * d->kh * d->kw;
     const long long n_units = (long long)g->Bg * g->Ho * g->Wo;
@@ -678,7 +757,7 @@ bool build_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
         // stride-1 windows: tap pairs with the same difference share their products (shift-correlation mode)
         TileGeom gs = *g;
         double cs = 0.0;
-        if (lay != FW_LAYOUT_ROWS && make_shift_tile_geom(d, &gs, &cs) && cs < best) {
+        if (lay != FW_LAYOUT_ROWS && make_shift_tile_geom(d, &gs, &cs) && (cs < best || cov_form() == FW_COV_FORM_SHIFT)) {
             const long long per_img = (long long)gs.Hp * gs.Wp * d->Cin;
             long long ch = (524288 + per_img - 1) / per_img;
             if (ch > gs.Bg) ch = gs.Bg;
@@ -712,14 +791,15 @@ bool build_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
 // The geometry of the last layer asked for is kept per host thread: a call computes it for the workspace check and for
 // the launches, and a training loop asks for the same few layers over and over.
 bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
-    struct Last { bool valid = false, ok = false; fw_conv_desc d; fw_layout lay; TileGeom g; };
+    struct Last { bool valid = false, ok = false; fw_conv_desc d; fw_layout lay; int form; TileGeom g; };
     static thread_local Last last;
-    if (last.valid && last.lay == lay && memcmp(&last.d, d, sizeof(*d)) == 0) {
+    const int form = cov_form();
+    if (last.valid && last.lay == lay && last.form == form && memcmp(&last.d, d, sizeof(*d)) == 0) {
         if (last.ok) *g = last.g;
         return last.ok;
     }
     last.ok = build_tile_geom(d, lay, &last.g);
-    last.d = *d; last.lay = lay; last.valid = true;
+    last.d = *d; last.lay = lay; last.form = form; last.valid = true;
     if (last.ok) *g = last.g;
     return last.ok;
 }
@@ -746,14 +826,15 @@ bool cov_bf16_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan) {
     plan->shift = g.shift; plan->regions = g.nreg; plan->differences = g.nd;
     plan->workgroups = g.ntiles * g.nsplit; plan->ranges = g.nsplit;
     plan->covered_pixels = 0;
-    for (int r = 0; r < g.nreg; ++r) plan->covered_pixels += (long long)g.B * g.reg[r].rh * g.reg[r].rw;
+    for (int r = 0; r < g.nreg; ++r)
+        plan->covered_pixels += (long long)g.B * g.reg[r].rh * g.reg[r].rw * ((g.reg[r].colmask != 0) + (g.gx == 2 && g.reg[r].colmask2 != 0));
     // every tile is multiplied over all chunks of its ranges: 32 reduction entries (4 units of 8 images) per chunk
     plan->mfma_flops_issued = 2.0 * (double)g.ntiles * g.tr * g.tc * 32.0 * (double)g.nchunks;
     if (g.shift) {   // border regions skip the column tiles whose differences they never use
         double chunk_tiles = 0.0;
         for (int r = 0; r < g.nreg; ++r)
             for (int t = 0; t < g.ntiles; ++t)
-                if (region_needs_tile(g.reg[r], t % g.ncb, g.tc, g.Cin, g.nd)) chunk_tiles += g.reg[r].nchunks;
+                if (region_needs_tile(g.reg[r], t % g.ncb, g.tc, g.t_cin, g.nd)) chunk_tiles += g.reg[r].nchunks;
         plan->mfma_flops_issued = 2.0 * chunk_tiles * g.tr * g.tc * 32.0;
     }
     return true;
@@ -800,14 +881,14 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     else if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * (g.tr * g.tc / 256)), dim3(256), 0, st, g, part, A);
     {
         // slices of the positions: enough workgroups to fill the chip, none when a workgroup per 64 features already does
-        const long long total = (long long)g.Ho * g.Wo * g.bg_chunks;
+        const long long total = (long long)g.Ho * g.bg_chunks * ((g.Wo + 7) / 8);   // runs of eight positions
         const int nfb = (g.M + 63) / 64;
-        int ns = (int)((256 + nfb - 1) / nfb);
-        if ((long long)ns * 256 > total) ns = (int)(total / 256);
+        int ns = (int)((1024 + nfb - 1) / nfb);
+        if ((long long)ns * 32 > total) ns = (int)(total / 32);                     // two runs per wavefront at least
         if (ns > CS_SLICES) ns = CS_SLICES;
         if (ns < 1) ns = 1;
         hipLaunchKernelGGL(column_sums_kernel, dim3(nfb, ns), dim3(1024), 0, st, g, S8, cpart, s);
-        if (ns > 1) hipLaunchKernelGGL(column_sums_final_kernel, dim3((g.M + 255) / 256), dim3(256), 0, st, g.M, ns, cpart, s);
+        if (ns > 1) hipLaunchKernelGGL(column_sums_final_kernel, dim3((g.M + 15) / 16), dim3(256), 0, st, g.M, ns, cpart, s);
     }
     FW_LAUNCH_CHECK();
     return FW_OK;

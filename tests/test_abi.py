@@ -35,7 +35,7 @@ def test_binding_names_match_header():
     from paper_2010_01546_amd import binding
     for n in declared_symbols():
         assert hasattr(binding, n), n
-    assert binding.fw_version() == 102
+    assert binding.fw_version() == 103
     assert binding.fw_status_string(0) == "ok" and "workspace" in binding.fw_status_string(4)
     assert C.sizeof(binding.fw_cond_info) == 32 and C.sizeof(binding.fw_conv_desc) == 32
 

@@ -22,7 +22,9 @@ def test_stride_one_windows_take_the_shift_form(shape, dt):
         if dt == b.FW_BF16 and B < 128 and p.shift == 0:
             continue   # tiny bfloat16 layers: the cost estimate may keep the direct form
         assert p.shift == 1, (shape, lay)
-        assert p.differences == ((2 * kh - 1) * (2 * kw - 1) + 1) // 2
+        pairs = dt == b.FW_BF16 and Cin <= 128 and W >= 4   # bfloat16 with few channels: units are pairs of pixels
+        kwu = kw // 2 + 1 if pairs else kw
+        assert p.differences == ((2 * kh - 1) * (2 * kwu - 1) + 1) // 2
         # every pixel of a stride-1 window with pad < k lies under some window; the regions are disjoint
         assert p.covered_pixels == B * H * W
         assert 1 <= p.regions <= 32 and p.ranges >= p.regions
@@ -59,3 +61,22 @@ def test_bad_arguments():
         b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(0, 64, 8, 8, 3, 3, 1, 1))
     with pytest.raises(b.FwError):
         b.fw_cov_plan_query(7, b.FW_LAYOUT_NHWC, b.conv_desc(2, 64, 8, 8, 3, 3, 1, 1))
+
+
+def test_form_preference():
+    """The process-wide preference overrides the estimate where both forms apply, and nothing else."""
+    small = b.conv_desc(2, 64, 9, 7, 3, 3, 1, 1)
+    strided = b.conv_desc(2, 64, 9, 7, 3, 3, 2, 1)
+    try:
+        assert b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, small).shift == 0
+        b.fw_cov_set_form(b.FW_COV_FORM_SHIFT)
+        p = b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, small)
+        assert p.shift == 1 and p.covered_pixels == 2 * 9 * 7
+        assert b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, strided).shift == 0   # does not apply: stays direct
+        b.fw_cov_set_form(b.FW_COV_FORM_DIRECT)
+        assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(128, 64, 32, 32, 3, 3, 1, 1)).shift == 0
+        with pytest.raises(b.FwError):
+            b.fw_cov_set_form(3)
+    finally:
+        b.fw_cov_set_form(b.FW_COV_FORM_AUTO)
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(128, 64, 32, 32, 3, 3, 1, 1)).shift == 1

@@ -76,6 +76,41 @@ def test_stride_one_windows(B, Cin, H, W, kh, kw, pad, layout, dtype):
     check_layer(wl.Layer("shift", d, 4, dtype, act, G), layout)
 
 
+@pytest.fixture
+def forced_form(request):
+    """The form named by the parameter for one test; the estimate's own choice afterwards."""
+    b.fw_cov_set_form(request.param)
+    yield request.param
+    b.fw_cov_set_form(b.FW_COV_FORM_AUTO)
+
+
+# the same border shapes, plus pair-unit specials (odd widths, width 4, even and 1-wide windows, few channels), at sizes
+# where the run-time estimate would keep the other form: both forms must give the sums of Sec. 2
+FORCED_CASES = SHIFT_CASES + [(9, 64, 4, 4, 3, 3, 1), (3, 16, 13, 4, 3, 2, 0), (5, 60, 9, 5, 3, 3, 1), (2, 36, 15, 15, 3, 3, 1),
+                              (17, 48, 7, 7, 2, 2, 1), (2, 128, 6, 7, 3, 3, 1), (3, 100, 5, 8, 3, 3, 1), (3, 64, 5, 9, 3, 4, 2), (2, 64, 7, 5, 2, 5, 0), (8, 24, 6, 10, 5, 5, 4)]
+
+
+@pytest.mark.parametrize("forced_form", [b.FW_COV_FORM_SHIFT, b.FW_COV_FORM_DIRECT], indirect=True)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NCHW, b.FW_LAYOUT_NHWC_KKC])
+@pytest.mark.parametrize("B,Cin,H,W,kh,kw,pad", FORCED_CASES)
+def test_stride_one_windows_in_either_form(B, Cin, H, W, kh, kw, pad, layout, dtype, forced_form):
+    d = wl.ConvDesc(B=B, Cin=Cin, H=H, W=W, kh=kh, kw=kw, stride=1, pad=pad)
+    cd = b.conv_desc(B, Cin, H, W, kh, kw, 1, pad)
+    plan = b.fw_cov_plan_query(b.FW_BF16 if dtype == "bf16" else b.FW_F32, layout, cd)
+    if forced_form == b.FW_COV_FORM_DIRECT:
+        assert plan.shift == 0
+    elif Cin % 4 == 0 and 1 < kh * kw <= 25 and (dtype == "bf16" or layout != b.FW_LAYOUT_NCHW):   # 7 x 7: too many regions
+        assert plan.shift == 1, "the shift form applies to this layer and was asked for"
+    rng = np.random.default_rng(7 * B + 10 * Cin + H + W)
+    act = np.abs(rng.standard_normal((B, H, W, Cin)) @ (np.eye(Cin) + 0.3 * rng.standard_normal((Cin, Cin)) / np.sqrt(Cin)))
+    act = act.astype(np.float32)
+    if dtype == "bf16":
+        act = wl.round_to_bf16(act)
+    G = np.zeros((4, d.M), dtype=np.float32)
+    check_layer(wl.Layer("forced", d, 4, dtype, act, G), layout)
+
+
 SKINNY_ROWS = [(5000, 64, "f32"), (4096, 100, "bf16"), (3001, 17, "f32"), (2500, 128, "bf16"), (3000, 5, "f32"), (2049, 33, "bf16"),
                (70000, 96, "f32")]
 
