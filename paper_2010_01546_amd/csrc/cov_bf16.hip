@@ -484,8 +484,10 @@ __global__ __launch_bounds__(256) void tile_reduce_kernel(TileGeom g, const floa
 
 // Shift-correlation mode: the block of A that pairs row tap t1 with column tap t2 <= t1 (in tap order) is the sum, over
 // the regions whose pixels serve t1 and over their unit ranges, of the partial tiles' entries R(t1 - t2)[c1][c2].  A
-// workgroup takes 16 channels c1 x 64 channels c2 of one pair of taps, so the window and the ranges are uniform and the
-// loads (16 bytes per lane along c2, four in flight) and the writes run along rows; float64 sums.
+// workgroup takes 16 / NG channels c1 x 64 channels c2 of one pair of taps, so the window and the ranges are uniform
+// and the loads (16 bytes per lane along c2, four in flight) and the writes run along rows; its NG groups of threads
+// share the ranges and are added in a fixed order; float64 sums.
+template <int NG>
 __global__ __launch_bounds__(256) void shift_tile_assemble_kernel(TileGeom g, const float* __restrict__ part, float* __restrict__ A) {
     const int kk = g.kh * g.kw;
     int t1 = 0;
@@ -496,14 +498,16 @@ __global__ __launch_bounds__(256) void shift_tile_assemble_kernel(TileGeom g, co
         const int t2 = pr;
         const int t1y = t1 / g.kw, t1x = t1 - t1y * g.kw, t2y = t2 / g.kw, t2x = t2 - t2y * g.kw;
         int dy = t1y - t2y, dx = t1x - t2x;           // >= 0 in lexicographic order because t1 >= t2
-        const int c1 = blockIdx.y * 16 + (threadIdx.x >> 4);
-        const int c2 = blockIdx.x * 64 + 4 * (threadIdx.x & 15);
-        if (c1 >= g.Cin || c2 >= g.Cin) return;
-        if (t1 == t2 && c2 > c1 + 3) return;          // diagonal block: entries right of the diagonal are not kept
+        constexpr int R = 16 / NG;                     // channels c1 per workgroup; NG groups of 16 R threads share the ranges
+        const int lane = threadIdx.x % (16 * R), grp = threadIdx.x / (16 * R);
+        const int c1 = blockIdx.y * R + (lane >> 4);
+        const int c2 = blockIdx.x * 64 + 4 * (lane & 15);
+        // entries right of the diagonal of a diagonal block are not kept
+        const bool active = c1 < g.Cin && c2 < g.Cin && !(t1 == t2 && c2 > c1 + 3);
         const size_t tsz = (size_t)g.tr * g.tc;
         const size_t stride = (size_t)g.ntiles * tsz;
         double v0 = 0.0, v1 = 0.0, v2 = 0.0, v3 = 0.0;
-        for (int a = 0; a < g.gx; ++a) {              // the pixel of a pair that plays the row tap (one pass without pairs)
+        for (int a = 0; a < g.gx && active; ++a) {    // the pixel of a pair that plays the row tap (one pass without pairs)
             int row, f;
             if (g.gx == 1) {
                 row = c1;
@@ -521,21 +525,28 @@ __global__ __launch_bounds__(256) void shift_tile_assemble_kernel(TileGeom g, co
             for (int r = 0; r < g.nreg; ++r) {
                 const int cm = a == 0 ? g.reg[r].colmask : g.reg[r].colmask2;
                 if (!(((g.reg[r].rowmask >> t1y) & 1) && ((cm >> t1x) & 1))) continue;
-                const int s1 = g.reg[r].split_begin + g.reg[r].nsplit;
-                int sp = g.reg[r].split_begin;
-                for (; sp + 4 <= s1; sp += 4) {
+                const int s0 = g.reg[r].split_begin, s1 = s0 + g.reg[r].nsplit;
+                for (int sp = s0 + 4 * grp; sp < s1; sp += 4 * NG) {   // group grp: every NG-th batch of four ranges
                     float4 x[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) x[q] = *reinterpret_cast<const float4*>(src + (size_t)(sp + q) * stride);
+                    for (int q = 0; q < 4; ++q) x[q] = *reinterpret_cast<const float4*>(src + (size_t)(sp + q < s1 ? sp + q : s0) * stride);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) { v0 += (double)x[q].x; v1 += (double)x[q].y; v2 += (double)x[q].z; v3 += (double)x[q].w; }
-                }
-                for (; sp < s1; ++sp) {
-                    const float4 x = *reinterpret_cast<const float4*>(src + (size_t)sp * stride);
-                    v0 += (double)x.x; v1 += (double)x.y; v2 += (double)x.z; v3 += (double)x.w;
+                    for (int q = 0; q < 4; ++q) {
+                        asm volatile("" : "+v"(x[q].x), "+v"(x[q].y), "+v"(x[q].z), "+v"(x[q].w));
+                        if (sp + q < s1) { v0 += (double)x[q].x; v1 += (double)x[q].y; v2 += (double)x[q].z; v3 += (double)x[q].w; }
+                    }
                 }
             }
         }
+        if (NG > 1) {
+            __shared__ double red[NG > 1 ? NG - 1 : 1][4][16 * R];
+            if (grp > 0) { red[grp - 1][0][lane] = v0; red[grp - 1][1][lane] = v1; red[grp - 1][2][lane] = v2; red[grp - 1][3][lane] = v3; }
+            __syncthreads();
+            if (grp > 0) return;
+#pragma unroll
+            for (int q = 0; q < NG - 1; ++q) { v0 += red[q][0][lane]; v1 += red[q][1][lane]; v2 += red[q][2][lane]; v3 += red[q][3][lane]; }
+        }
+        if (!active) return;
         const double v[4] = {v0, v1, v2, v3};
         const bool kkc = g.layout == FW_LAYOUT_NHWC_KKC;
 #pragma unroll
@@ -876,8 +887,14 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     }
 #undef FW_TILE_LAUNCH
     FW_LAUNCH_CHECK();
-    if (g.shift) hipLaunchKernelGGL(shift_tile_assemble_kernel, dim3((g.Cin + 63) / 64, (g.Cin + 15) / 16, g.kh * g.kw * (g.kh * g.kw + 1) / 2),
-                                    dim3(256), 0, st, g, part, A);
+    if (g.shift) {
+        // few channels: too few workgroups of 16 x 64 entries to hide the chain of loads over the ranges; share them
+        const int pairs = g.kh * g.kw * (g.kh * g.kw + 1) / 2, cb = (g.Cin + 63) / 64;
+        if ((long long)cb * ((g.Cin + 15) / 16) * pairs < 512)
+            hipLaunchKernelGGL(shift_tile_assemble_kernel<4>, dim3(cb, (g.Cin + 3) / 4, pairs), dim3(256), 0, st, g, part, A);
+        else
+            hipLaunchKernelGGL(shift_tile_assemble_kernel<1>, dim3(cb, (g.Cin + 15) / 16, pairs), dim3(256), 0, st, g, part, A);
+    }
     else if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * (g.tr * g.tc / 256)), dim3(256), 0, st, g, part, A);
     {
         // slices of the positions: enough workgroups to fill the chip, none when a workgroup per 64 features already does
