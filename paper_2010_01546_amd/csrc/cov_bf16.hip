@@ -70,7 +70,8 @@ struct TileGeom {
     int sum_shift;                 // offset of the tap (0,0) of output position (0,0) in P
     // shift-correlation mode (stride-1 windows): rows = Cin channels of a pixel, columns = nd tap differences x Cin
     int shift, nd, F, nreg;
-    // Few channels (Cin <= 64): a unit of the shift mode is a PAIR of horizontally neighbouring pixels, i.e. the image is
+    int spread;                  // shift mode: how workgroups map to (tile, range), see the tile kernel
+    // Few channels (Cin <= 128): a unit of the shift mode is a PAIR of horizontally neighbouring pixels, i.e. the image is
     // read as W/2 pixels of 2 Cin channels (the packed layout is the same memory either way).  Row features: both pixels'
     // channels (a full 128-row tile); kept differences: those of a window half as wide, (dy, e) with e counted in pairs.
     // A product of pixel 2X+a with pixel 2X+a-dx of the original differences is the entry (a, c1) x (a', c2) of the pair
@@ -225,11 +226,18 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
         c_begin = split * g.chunks_per_split;
         nchunks = min(g.nchunks, c_begin + g.chunks_per_split) - c_begin;
     } else {
-        // shift-correlation mode: rectangular grid of tiles; the ranges differ in length (they never cross a region), so
-        // XCD x takes the ranges x, x + 8, ... with all their tiles rather than one contiguous run
+        // shift-correlation mode: rectangular grid of tiles; the ranges differ in length (they never cross a region).
+        // Many ranges: XCD x takes the ranges x, x + 8, ... with all their tiles (each XCD reads its own units only).
+        // Few ranges cannot be dealt evenly to 8 XCDs: then the tiles of every range are spread over the XCDs (workgroup
+        // index = range-major, tile-minor; every XCD reads all units, which are few in that case).
         const int w = blockIdx.x;
-        tile = (w >> 3) % g.ntiles;
-        split = (w & 7) + 8 * ((w >> 3) / g.ntiles);
+        if (g.spread) {
+            split = w / g.ntiles;
+            tile = w - split * g.ntiles;
+        } else {
+            tile = (w >> 3) % g.ntiles;
+            split = (w & 7) + 8 * ((w >> 3) / g.ntiles);
+        }
         if (split >= g.nsplit) return;
         I = tile / g.ncb;
         J = tile - I * g.ncb;
@@ -670,10 +678,16 @@ bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
     const int kk = d->kh * d->kw;
     double best = 1e300;
     long long best_cps = 8;
-    for (int step = -8; step <= 8; ++step) {
-        long long cps = (long long)(ideal * pow(2.0, step / 4.0) + 0.5);
+    int best_spread = 0;
+    // what the spread mapping costs: seven more XCDs pull the packed units into their L2 (from the shared last-level cache)
+    const double spread_penalty = 7.0 * (double)packed * 16.0 / 8.0e12;
+    long long last_cps = -1;
+    for (int step = -24; step <= 24; ++step) {
+        long long cps = (long long)(ideal * pow(2.0, step / 12.0) + 0.5);
         if (cps < 8) cps = 8;
         if (cps > total_chunks) cps = total_chunks;
+        if (cps == last_cps) continue;
+        last_cps = cps;
         int nsplit = 0;
         int len[MAXREG], cnt[MAXREG];
         for (int r = 0; r < nregs; ++r) {
@@ -681,11 +695,7 @@ bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
             len[r] = g->reg[r].nchunks - (cnt[r] - 1) * (int)cps;   // the last range of a region
             nsplit += cnt[r];
         }
-        if ((long long)nsplit * g->ntiles > 65536) continue;
-        // launch order: groups of 8 ranges x all tiles; a min-heap of the compute units' finish times
-        std::priority_queue<double, std::vector<double>, std::greater<double>> cu;
-        for (int i = 0; i < 256; ++i) cu.push(0.0);
-        double makespan = 0.0;
+        if ((long long)nsplit * g->ntiles > 8192) continue;
         int r = 0, within = 0;
         std::vector<int> range_len(nsplit), range_reg(nsplit);
         for (int sp = 0; sp < nsplit; ++sp) {
@@ -693,20 +703,36 @@ bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
             range_reg[sp] = r;
             if (++within == cnt[r]) { within = 0; ++r; }
         }
-        double wgs = 0.0;
-        for (int g8 = 0; g8 < nsplit; g8 += 8)
-            for (int t = 0; t < g->ntiles; ++t)
-                for (int sp = g8; sp < g8 + 8 && sp < nsplit; ++sp) {
-                    if (!region_needs_tile(g->reg[range_reg[sp]], t % g->ncb, g->tc, g->t_cin, g->nd)) continue;   // leaves at once
-                    const double f = cu.top() + range_len[sp] + 6.0;   // fill of the ring and write-out of the tile
-                    cu.pop(); cu.push(f);
-                    if (f > makespan) makespan = f;
-                    wgs += 1.0;
-                }
-        const double c = makespan * t_chunk + wgs * g->tr * g->tc * 4.0 / bw +
-                         0.5 * kk * (kk + 1) * (double)Cin * Cin * 4.0 * 0.6 * gx * nsplit / bw + 0.5 * (double)g->M * g->M * 8.0 / bw;
-        if (c < best) { best = c; best_cps = cps; }
+        for (int spread = 0; spread < 2; ++spread) {
+            // workgroup w goes to XCD w % 8, which hands its workgroups, in launch order, to its 32 compute units
+            // (one workgroup each): a min-heap of finish times per XCD
+            std::priority_queue<double, std::vector<double>, std::greater<double>> cu[8];
+            for (int x = 0; x < 8; ++x)
+                for (int i = 0; i < 32; ++i) cu[x].push(0.0);
+            double makespan = 0.0, wgs = 0.0;
+            auto place = [&](int w, int sp, int t) {
+                if (!region_needs_tile(g->reg[range_reg[sp]], t % g->ncb, g->tc, g->t_cin, g->nd)) return;   // leaves at once
+                auto& q = cu[w & 7];
+                const double f = q.top() + range_len[sp] + 6.0;   // fill of the ring and write-out of the tile
+                q.pop(); q.push(f);
+                if (f > makespan) makespan = f;
+                wgs += 1.0;
+            };
+            if (spread) {
+                for (int w = 0; w < nsplit * g->ntiles; ++w) place(w, w / g->ntiles, w % g->ntiles);
+            } else {
+                int w = 0;
+                for (int g8 = 0; g8 < nsplit; g8 += 8)
+                    for (int t = 0; t < g->ntiles; ++t)
+                        for (int sp = g8; sp < g8 + 8; ++sp, ++w)
+                            if (sp < nsplit) place(w, sp, t);
+            }
+            const double c = makespan * t_chunk + wgs * g->tr * g->tc * 4.0 / bw + (spread ? spread_penalty : 0.0) +
+                             0.5 * kk * (kk + 1) * (double)Cin * Cin * 4.0 * 0.6 * gx * nsplit / bw + 0.5 * (double)g->M * g->M * 8.0 / bw;
+            if (c < best) { best = c; best_cps = cps; best_spread = spread; }
+        }
     }
+    g->spread = best_spread;
     g->chunks_per_split = (int)best_cps;
     int nsplit = 0;
     for (int r = 0; r < nregs; ++r) {
@@ -727,7 +753,7 @@ bool build_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     g->Wo = (d->W + 2 * d->pad - d->kw) / d->stride + 1;
     g->Hp = d->H + 2 * d->pad; g->Wp = d->W + 2 * d->pad;
     g->py = g->px = d->pad; g->sum_shift = 0;
-    g->shift = 0; g->nd = 0; g->F = 0; g->nreg = 0;
+    g->shift = 0; g->nd = 0; g->F = 0; g->nreg = 0; g->spread = 0;
     for (int r = 0; r < MAXREG; ++r) g->reg[r] = TileRegion{0, 0, 1, 1, 0, 0, 0, 0, 0, 0, 0, {0, 0, 0, 0}};
     g->gx = 1; g->t_cin = d->Cin; g->t_wp = g->Wp; g->t_kw = d->kw;
     g->Bg = (d->B + 7) / 8;
@@ -799,20 +825,27 @@ bool build_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     return true;
 }
 
-// The geometry of the last layer asked for is kept per host thread: a call computes it for the workspace check and for
-// the launches, and a training loop asks for the same few layers over and over.
+// The geometries of the layers asked for most recently (64 of them) are kept per host thread: a call computes one for the
+// workspace check and for the launches, the dispatch simulation behind it takes milliseconds, and a training loop asks for
+// the same layers over and over.
 bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
-    struct Last { bool valid = false, ok = false; fw_conv_desc d; fw_layout lay; int form; TileGeom g; };
-    static thread_local Last last;
+    struct Entry { bool ok; fw_conv_desc d; fw_layout lay; int form; TileGeom g; };
+    static thread_local std::vector<Entry> cache;     // most recent first
     const int form = cov_form();
-    if (last.valid && last.lay == lay && last.form == form && memcmp(&last.d, d, sizeof(*d)) == 0) {
-        if (last.ok) *g = last.g;
-        return last.ok;
-    }
-    last.ok = build_tile_geom(d, lay, &last.g);
-    last.d = *d; last.lay = lay; last.form = form; last.valid = true;
-    if (last.ok) *g = last.g;
-    return last.ok;
+    for (size_t i = 0; i < cache.size(); ++i)
+        if (cache[i].lay == lay && cache[i].form == form && memcmp(&cache[i].d, d, sizeof(*d)) == 0) {
+            if (i) std::swap(cache[i], cache[0]);
+            if (cache[0].ok) *g = cache[0].g;
+            return cache[0].ok;
+        }
+    Entry e;
+    memset(&e, 0, sizeof(e));
+    e.ok = build_tile_geom(d, lay, &e.g);
+    e.d = *d; e.lay = lay; e.form = form;
+    if (cache.size() >= 64) cache.pop_back();
+    cache.insert(cache.begin(), e);
+    if (e.ok) *g = e.g;
+    return e.ok;
 }
 
 struct Bf16Ws { size_t packed, utab, part, s8, cpart, total; };
@@ -873,7 +906,7 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     hipLaunchKernelGGL(pack_images_kernel, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st, reinterpret_cast<const u16*>(X),
                        g, P, S8, utab);
     FW_LAUNCH_CHECK();
-    const dim3 grid(g.shift ? 8 * g.ntiles * ((g.nsplit + 7) / 8) : (g.ntiles * g.nsplit + 7) / 8 * 8);
+    const dim3 grid(g.shift && !g.spread ? 8 * g.ntiles * ((g.nsplit + 7) / 8) : (g.ntiles * g.nsplit + 7) / 8 * 8);
 #define FW_TILE_LAUNCH(R, C) hipLaunchKernelGGL((cov_bf16_tile_kernel<R, C>), grid, dim3(256), 0, st, P, utab, g, part, A)
     switch (g.nrt * 10 + g.nct) {
         case 44: FW_TILE_LAUNCH(4, 4); break;
