@@ -80,3 +80,46 @@ def test_form_preference():
     finally:
         b.fw_cov_set_form(b.FW_COV_FORM_AUTO)
     assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(128, 64, 32, 32, 3, 3, 1, 1)).shift == 1
+
+
+def test_plan_invariants_on_random_layers():
+    """Seeded sweep of stride-1 layers in both precisions, the shift form asked for: wherever it is taken the regions
+    partition the pixels that lie under some window, one of each +/- pair of differences is kept (of pixel pairs for
+    bfloat16 up to 128 channels), the matrix cores are not asked for more than the direct form's work on a chip-filling
+    layer, and the query is repeatable (cached geometry == fresh geometry)."""
+    import random
+    rnd = random.Random(20101546)
+    b.fw_cov_set_form(b.FW_COV_FORM_SHIFT)
+    try:
+        taken = 0
+        for _ in range(300):
+            kh, kw = rnd.choice([(3, 3), (3, 3), (5, 5), (2, 2), (1, 3), (3, 1), (4, 2), (7, 7), (2, 5)])
+            Cin = 4 * rnd.randint(1, 80)
+            H, W = rnd.randint(1, 40), rnd.randint(1, 40)
+            pad = rnd.randint(0, min(kh, kw) - 1)   # a window may not lie wholly in the padding
+            B = rnd.choice([1, 3, 8, 64, 256])
+            if H + 2 * pad < kh or W + 2 * pad < kw:
+                continue
+            d = b.conv_desc(B, Cin, H, W, kh, kw, 1, pad)
+            Ho, Wo = H + 2 * pad - kh + 1, W + 2 * pad - kw + 1
+            # pixels under some window: rows y with an output row oy = y - ty + pad in [0, Ho) for some tap row ty
+            rows = sum(1 for y in range(H) if any(0 <= y - t + pad < Ho for t in range(kh)))
+            cols = sum(1 for x in range(W) if any(0 <= x - t + pad < Wo for t in range(kw)))
+            for dt in (b.FW_F32, b.FW_BF16):
+                lay = rnd.choice([b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NHWC_KKC])
+                p = b.fw_cov_plan_query(dt, lay, d)
+                again = b.fw_cov_plan_query(dt, lay, d)
+                assert (p.shift, p.regions, p.differences, p.workgroups, p.ranges, p.covered_pixels, p.mfma_flops_issued) == \
+                       (again.shift, again.regions, again.differences, again.workgroups, again.ranges, again.covered_pixels,
+                        again.mfma_flops_issued)
+                if not p.shift:
+                    continue
+                taken += 1
+                assert p.covered_pixels == B * rows * cols, (B, Cin, H, W, kh, kw, pad, dt)
+                kwu = kw // 2 + 1 if (dt == b.FW_BF16 and Cin <= 128 and W >= 4) else kw
+                assert p.differences == ((2 * kh - 1) * (2 * kwu - 1) + 1) // 2
+                assert 1 <= p.regions <= 32 and p.ranges >= p.regions and p.workgroups >= 1
+                assert p.mfma_flops_issued > 0
+        assert taken > 200
+    finally:
+        b.fw_cov_set_form(b.FW_COV_FORM_AUTO)

@@ -189,3 +189,40 @@ def test_run_to_run_determinism():
     A1, s1 = run_cov(L, b.FW_LAYOUT_NHWC)
     A2, s2 = run_cov(L, b.FW_LAYOUT_NHWC)
     assert torch.equal(A1, A2) and torch.equal(s1, s2)
+
+
+@pytest.mark.parametrize("forced_form", [b.FW_COV_FORM_AUTO, b.FW_COV_FORM_SHIFT], indirect=True)
+def test_seeded_sweep_of_window_shapes(forced_form):
+    """Eighty seeded random layers (windows 1..5 squared or not, strides 1..3, every layout, both precisions, odd sizes):
+    raw sums against the oracle's, once with the estimate's own choice of form and once with the shift form wherever it
+    applies."""
+    rng = np.random.default_rng(1546 + forced_form)
+    done = 0
+    while done < 80:
+        kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        stride = int(rng.choice([1, 1, 1, 2, 3]))
+        pad = int(rng.integers(0, min(kh, kw)))
+        H, W = int(rng.integers(1, 14)), int(rng.integers(1, 14))
+        Cin = int(rng.choice([1, 3, 4, 8, 12, 16, 20, 32, 64, 68, 96, 128, 132, 200, 256]))
+        if Cin * kh * kw > 2400:
+            Cin = max(4, 2400 // (kh * kw) // 4 * 4)
+        B = int(rng.choice([1, 2, 3, 5, 8, 9, 17, 40, 130]))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        layout = int(rng.choice([b.FW_LAYOUT_NCHW, b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NHWC_KKC]))
+        if H + 2 * pad < kh or W + 2 * pad < kw:
+            continue
+        d = wl.ConvDesc(B=B, Cin=Cin, H=H, W=W, kh=kh, kw=kw, stride=stride, pad=pad)
+        if d.n_rows * d.M * d.M > 1.5e9 or d.n_rows * d.M > 3e7:
+            continue
+        act = np.abs(rng.standard_normal((B, H, W, Cin))).astype(np.float32)
+        if dtype == "bf16":
+            act = wl.round_to_bf16(act)
+        layer = wl.Layer("sweep", d, 4, dtype, act, np.zeros((4, d.M), np.float32))
+        case = (B, Cin, H, W, kh, kw, stride, pad, dtype, layout)
+        A_o, s_o, n = ora.raw_sums(oracle_rows(layer, layout))
+        A, s = run_cov(layer, layout)
+        A_h = A.cpu().numpy()
+        assert relF(lower(A_h), lower(A_o)) < RAW_TOL[dtype], case
+        assert relF(s.cpu().numpy(), s_o) < RAW_TOL[dtype], case
+        assert np.array_equal(np.triu(A_h, 1), np.zeros_like(A_h)), case
+        done += 1
