@@ -18,8 +18,9 @@
  *     (P = Ho*Wo output positions), M = Cin*kh*kw features in the order m = (c*kh + ky)*kw + kx (the order of a
  *     contiguous weight tensor [S, Cin, kh, kw] viewed as [S, M]) unless the layout says otherwise, zero padding
  *     counts as data.  N_rows = B*P.  Whatever order is chosen, G, T, Q and Phi_x of a layer must all use it.
- *   - The library allocates no device memory, keeps no state between calls and never frees.  Scratch comes
- *     from the caller through (ws, ws_bytes); fw_workspace_bytes gives the size an entry point needs.
+ *   - The library allocates no device memory, keeps no device state between calls and never frees (host side it
+ *     keeps the setting of fw_cov_set_form and, per calling thread, the launch geometry of recently seen layers).
+ *     Scratch comes from the caller through (ws, ws_bytes); fw_workspace_bytes gives the size an entry point needs.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on it and the
  *     call returns without waiting, except fw_whiten_evd, which waits on its own convergence flag.
  *   - Errors are return codes.  Arguments are validated before anything is enqueued; on a non-OK return
