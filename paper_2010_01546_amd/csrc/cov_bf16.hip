@@ -468,21 +468,45 @@ __global__ __launch_bounds__(256) void column_sums_final_kernel(int M, int nslic
     }
 }
 
-// partial tiles -> A (float64 sum over the ranges), one thread per tile element
+// partial tiles -> A (float64 sum over the ranges).  A workgroup takes 256 / NG consecutive tile elements; its NG groups
+// of threads share the ranges (group q takes the ranges q, q + NG, ..., eight loads in flight) and are added in a fixed
+// order, so that many ranges do not become a long chain of loads in few threads.
+template <int NG>
 __global__ __launch_bounds__(256) void tile_reduce_kernel(TileGeom g, const float* __restrict__ part, float* __restrict__ A) {
-    const int bpt = g.tr * g.tc / 256;             // blocks of 256 threads per tile of tr x tc
+    constexpr int EPB = 256 / NG;                  // elements per workgroup
+    const int bpt = g.tr * g.tc / EPB;             // workgroups per tile of tr x tc
     const int tile = blockIdx.x / bpt;
-    const int e = (blockIdx.x - tile * bpt) * 256 + threadIdx.x;
+    const int le = threadIdx.x % EPB, grp = threadIdx.x / EPB;
+    const int e = (blockIdx.x - tile * bpt) * EPB + le;
     int I, J;
     tile_coords(tile, g, &I, &J);
     const int row = e / g.tc, col = e - row * g.tc;
     const int fi = I * g.tr + row, fj = J * g.tc + col;
-    if (fi >= g.M || fj >= g.M || fj > fi) return;
+    const bool active = fi < g.M && fj < g.M && fj <= fi;
     const size_t tsz = (size_t)g.tr * g.tc;
     const size_t stride = (size_t)g.ntiles * tsz;
     const float* src = part + (size_t)tile * tsz + e;
     double v = 0.0;
-    for (int sp = 0; sp < g.nsplit; ++sp) v += (double)src[sp * stride];
+    if (active) {
+        int sp = grp;
+        for (; sp + 7 * NG < g.nsplit; sp += 8 * NG) {
+            float x[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) x[q] = src[(size_t)(sp + q * NG) * stride];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v += (double)x[q];
+        }
+        for (; sp < g.nsplit; sp += NG) v += (double)src[(size_t)sp * stride];
+    }
+    if (NG > 1) {
+        __shared__ double red[NG > 1 ? NG - 1 : 1][EPB];
+        if (grp > 0) red[grp - 1][le] = v;
+        __syncthreads();
+        if (grp > 0) return;
+#pragma unroll
+        for (int q = 0; q < NG - 1; ++q) v += red[q][le];
+    }
+    if (!active) return;
     int o, ei, ej;
     feat_map(fi, g, &o, &ei);
     feat_map(fj, g, &o, &ej);
@@ -928,7 +952,16 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
         else
             hipLaunchKernelGGL(shift_tile_assemble_kernel<1>, dim3(cb, (g.Cin + 15) / 16, pairs), dim3(256), 0, st, g, part, A);
     }
-    else if (!g.direct) hipLaunchKernelGGL(tile_reduce_kernel, dim3(g.ntiles * (g.tr * g.tc / 256)), dim3(256), 0, st, g, part, A);
+    else if (!g.direct) {
+        // many ranges and few tiles: share the ranges inside a workgroup
+        const int elems = g.ntiles * g.tr * g.tc;
+        if (g.nsplit >= 64 && elems / 16 <= 65536 * 4)
+            hipLaunchKernelGGL(tile_reduce_kernel<16>, dim3(elems / 16), dim3(256), 0, st, g, part, A);
+        else if (g.nsplit >= 24)
+            hipLaunchKernelGGL(tile_reduce_kernel<4>, dim3(elems / 64), dim3(256), 0, st, g, part, A);
+        else
+            hipLaunchKernelGGL(tile_reduce_kernel<1>, dim3(elems / 256), dim3(256), 0, st, g, part, A);
+    }
     {
         // slices of the positions: enough workgroups to fill the chip, none when a workgroup per 64 features already does
         const long long total = (long long)g.Ho * g.bg_chunks * ((g.Wo + 7) / 8);   // runs of eight positions
