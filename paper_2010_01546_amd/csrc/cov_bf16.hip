@@ -28,6 +28,7 @@
 #include <string.h>
 #include <algorithm>
 #include <queue>
+#include <type_traits>
 #include <vector>
 
 namespace fw {
@@ -57,7 +58,9 @@ __host__ __device__ inline bool region_needs_tile(const TileRegion& R, int J, in
     return false;
 }
 
-struct TileGeom {
+// everything about a layer's launch geometry except the regions (kernels that do not need those take this part only:
+// a kernel argument of 2 KB makes a launch noticeably slower on the host)
+struct TileCore {
     int M, ntiles;
     int nrt, nct, tr, tc, ncb, nrb;  // MFMA row / column tiles per wavefront, tile = 64 nrt x 64 nct, column / row blocks of A
     int B, Bg, Cin, H, W, Hp, Wp, kh, kw, stride, pad, Ho, Wo;
@@ -78,6 +81,8 @@ struct TileGeom {
     // difference e = -floor((a - dx) / 2), a' = (a - dx) mod 2.
     int gx;                      // pixels per unit along x: 1 or 2
     int t_cin, t_wp, t_kw;       // the contraction's view: channels per unit, units per packed row, width of the difference window
+};
+struct TileGeom : TileCore {
     TileRegion reg[MAXREG];
 };
 
@@ -94,13 +99,15 @@ typedef unsigned short u16;
 // S8[chunk][yp][xp][c] has a fixed order of additions.
 // The first row of workgroups also writes the unit table: offset (in 16-byte elements) of the top-left tap of every
 // unit, -1 for the padding up to a whole number of chunks.
-__global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict__ X, TileGeom g, uint4* __restrict__ P,
+template <bool SHIFT>
+__global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict__ X, std::conditional_t<SHIFT, TileGeom, TileCore> g,
+                                                          uint4* __restrict__ P,
                                                           float* __restrict__ S8, int* __restrict__ utab) {
     const int per_img = g.Hp * g.Wp * g.Cin;
     const int e = blockIdx.x * 256 + threadIdx.x;
     const int chunk = blockIdx.y;
     if (blockIdx.x == 0 && chunk == 0 && threadIdx.x < 16) P[g.zero_off + threadIdx.x] = make_uint4(0, 0, 0, 0);
-    if (chunk == 0 && !g.shift) {
+    if (chunk == 0 && !SHIFT) {
         const int npos = g.Ho * g.Wo;
         for (int u = e; u < g.nchunks * KU; u += gridDim.x * 256) {
             int v = -1;
@@ -112,7 +119,7 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
             utab[u] = v;
         }
     }
-    if (chunk == 0 && g.shift) {
+    if constexpr (SHIFT) if (chunk == 0) {
         // units are pixels (of an image group), listed region by region, every region padded to whole chunks
         for (int u = e; u < g.nchunks * KU; u += gridDim.x * 256) {
             int ri = 0;
@@ -178,14 +185,14 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
 
 // internal feature (tap-major, channel-minor) -> offset inside a unit, external index m = (c*kh + ky)*kw + kx
 // (or the internal index itself when the caller works in channels-last feature order)
-__device__ __forceinline__ void feat_map(int fi, const TileGeom& g, int* off, int* ext) {
+__device__ __forceinline__ void feat_map(int fi, const TileCore& g, int* off, int* ext) {
     const int t = fi / g.Cin, c = fi - t * g.Cin;
     const int ky = t / g.kw, kx = t - ky * g.kw;
     *off = (ky * g.Wp + kx) * g.Cin + c;
     *ext = g.layout == FW_LAYOUT_NHWC_KKC ? fi : c * (g.kh * g.kw) + t;
 }
 
-__device__ __forceinline__ void tile_coords(int tile, const TileGeom& g, int* I, int* J) {
+__device__ __forceinline__ void tile_coords(int tile, const TileCore& g, int* I, int* J) {
     int i = 0;
     for (;;) {
         const int n = cols_of_row(i, g.tr, g.tc, g.ncb);
@@ -195,8 +202,9 @@ __device__ __forceinline__ void tile_coords(int tile, const TileGeom& g, int* I,
     *I = i; *J = tile;
 }
 
-template <int NRT, int NCT>
-__global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restrict__ P, const int* __restrict__ utab, TileGeom g,
+template <int NRT, int NCT, bool SHIFT>
+__global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restrict__ P, const int* __restrict__ utab,
+                                                            std::conditional_t<SHIFT, TileGeom, TileCore> g,
                                                             float* __restrict__ part, float* __restrict__ A) {
     constexpr int TR = 64 * NRT;      // tile rows
     constexpr int TC = 64 * NCT;      // tile columns
@@ -216,7 +224,7 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
     const int per_xcd = (total + 7) / 8;
     int tile, split;
     int I, J, c_begin, nchunks;
-    if (!g.shift) {
+    if constexpr (!SHIFT) {
         const int w = blockIdx.x;
         const int n = (w & 7) * per_xcd + (w >> 3);
         if (n >= total || (w >> 3) >= per_xcd) return;   // padding of the last run
@@ -264,7 +272,7 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
     for (int k = 0; k < NF; ++k) {
         const int f = k < NRT ? I * TR + 64 * k + lane : J * TC + 64 * (k - NRT) + lane;
         bool ok;
-        if (!g.shift) {
+        if (!SHIFT) {
             ok = f < g.M;
             int ext_unused;
             feat_map(ok ? f : 0, g, &off[k], &ext_unused);
@@ -409,7 +417,7 @@ __global__ __launch_bounds__(256) void cov_bf16_tile_kernel(const uint4* __restr
 // to its 16 wavefronts in runs of eight positions along an output row: eight loads in flight and no index arithmetic
 // between them, float64 (the loop is a chain of load latencies: many short slices beat few long ones).  Second: the slices are added in a fixed order, 16 lanes per feature.
 constexpr int CS_SLICES = 64;
-__global__ __launch_bounds__(1024) void column_sums_kernel(TileGeom g, const float* __restrict__ S8, double* __restrict__ cpart,
+__global__ __launch_bounds__(1024) void column_sums_kernel(TileCore g, const float* __restrict__ S8, double* __restrict__ cpart,
                                                            float* __restrict__ s) {
     __shared__ double red[16][64];
     const int fl = threadIdx.x & 63, pl = threadIdx.x >> 6;
@@ -472,7 +480,7 @@ __global__ __launch_bounds__(256) void column_sums_final_kernel(int M, int nslic
 // of threads share the ranges (group q takes the ranges q, q + NG, ..., eight loads in flight) and are added in a fixed
 // order, so that many ranges do not become a long chain of loads in few threads.
 template <int NG>
-__global__ __launch_bounds__(256) void tile_reduce_kernel(TileGeom g, const float* __restrict__ part, float* __restrict__ A) {
+__global__ __launch_bounds__(256) void tile_reduce_kernel(TileCore g, const float* __restrict__ part, float* __restrict__ A) {
     constexpr int EPB = 256 / NG;                  // elements per workgroup
     const int bpt = g.tr * g.tc / EPB;             // workgroups per tile of tr x tc
     const int tile = blockIdx.x / bpt;
@@ -927,20 +935,28 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     float* S8 = reinterpret_cast<float*>(base + L.s8);
     double* cpart = reinterpret_cast<double*>(base + L.cpart);
     const int per_img = g.Hp * g.Wp * g.Cin;
-    hipLaunchKernelGGL(pack_images_kernel, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st, reinterpret_cast<const u16*>(X),
-                       g, P, S8, utab);
+    const TileCore& core = g;   // the direct form's kernels take the geometry without the regions
+    if (g.shift)
+        hipLaunchKernelGGL(pack_images_kernel<true>, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st,
+                           reinterpret_cast<const u16*>(X), g, P, S8, utab);
+    else
+        hipLaunchKernelGGL(pack_images_kernel<false>, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st,
+                           reinterpret_cast<const u16*>(X), core, P, S8, utab);
     FW_LAUNCH_CHECK();
     const dim3 grid(g.shift && !g.spread ? 8 * g.ntiles * ((g.nsplit + 7) / 8) : (g.ntiles * g.nsplit + 7) / 8 * 8);
-#define FW_TILE_LAUNCH(R, C) hipLaunchKernelGGL((cov_bf16_tile_kernel<R, C>), grid, dim3(256), 0, st, P, utab, g, part, A)
-    switch (g.nrt * 10 + g.nct) {
-        case 44: FW_TILE_LAUNCH(4, 4); break;
-        case 43: FW_TILE_LAUNCH(4, 3); break;
-        case 42: FW_TILE_LAUNCH(4, 2); break;
-        case 33: FW_TILE_LAUNCH(3, 3); break;
-        case 32: FW_TILE_LAUNCH(3, 2); break;
-        case 34: FW_TILE_LAUNCH(3, 4); break;
-        case 24: FW_TILE_LAUNCH(2, 4); break;
-        default: FW_TILE_LAUNCH(2, 2); break;
+#define FW_TILE_LAUNCH(R, C, S, G) hipLaunchKernelGGL((cov_bf16_tile_kernel<R, C, S>), grid, dim3(256), 0, st, P, utab, G, part, A)
+    if (g.shift) switch (g.nrt) {      // the shift form's tiles are 64 nrt x 256
+        case 4: FW_TILE_LAUNCH(4, 4, true, g); break;
+        case 3: FW_TILE_LAUNCH(3, 4, true, g); break;
+        default: FW_TILE_LAUNCH(2, 4, true, g); break;
+    }
+    else switch (g.nrt * 10 + g.nct) {
+        case 44: FW_TILE_LAUNCH(4, 4, false, core); break;
+        case 43: FW_TILE_LAUNCH(4, 3, false, core); break;
+        case 42: FW_TILE_LAUNCH(4, 2, false, core); break;
+        case 33: FW_TILE_LAUNCH(3, 3, false, core); break;
+        case 32: FW_TILE_LAUNCH(3, 2, false, core); break;
+        default: FW_TILE_LAUNCH(2, 2, false, core); break;
     }
 #undef FW_TILE_LAUNCH
     FW_LAUNCH_CHECK();
