@@ -230,9 +230,11 @@ bool make_skinny_geom(const fw_conv_desc* d, fw_layout lay, SkinnyGeom* g) {
     if (n_rows < 2048 || n_rows >= (1ll << 31) - 64 || (long long)d->B * d->H * d->W * d->Cin >= (1ll << 30)) return false;   // element indices stay far inside int
     g->n_rows = (int)n_rows; g->M = d->Cin; g->H = d->H; g->W = d->W; g->Ho = Ho; g->Wo = Wo; g->stride = d->stride;
     // as many workgroups as the registers let a compute unit hold (4, 2 or 1), each wavefront with at least 128 rows: what
-    // hides the latency of the loads is wavefronts x batches in flight
+    // hides the latency of the loads is wavefronts x batches in flight.  With 3 or 4 blocks of 32 features a row pair
+    // costs 6 or 10 matrix instructions, and it is those that want to be spread over all SIMDs: 64 and 32 rows then.
     long long nwg = d->Cin <= 64 ? 1024 : d->Cin <= 96 ? 512 : 256;
-    while (nwg > 1 && n_rows / (nwg * 4) < 128) nwg >>= 1;
+    const int min_rows = d->Cin <= 64 ? 128 : d->Cin <= 96 ? 64 : 32;
+    while (nwg > 1 && n_rows / (nwg * 4) < min_rows) nwg >>= 1;
     long long rpw = (n_rows + nwg * 4 - 1) / (nwg * 4);
     rpw = (rpw + 2 * SK_UMAX - 1) / (2 * SK_UMAX) * (2 * SK_UMAX);
     g->rows_per_wave = (int)rpw;
