@@ -60,10 +60,16 @@ __device__ __forceinline__ double wave_sum(double v) {
 // wavefront-uniform and travels in M0).  Written as assembly so that the compiler does not track it as a pending LDS
 // store (it would then wait for ALL outstanding loads before every LDS read): completion is awaited by hand with
 // FW_WAIT_VM, counting these loads in issue order, followed by a workgroup barrier.
+// M0 is named as clobbered; the compiler warns that it does not save reserved registers around assembly, which is what
+// is wanted here: it never keeps a value in M0 (it writes M0 itself right before each instruction of its own that
+// reads it), so nothing is lost.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(const void* src, void* lds_dst) {
     const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds_dst;
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // ---- cov.hip
 size_t cov_workspace_bytes(int M, const fw_conv_desc* d, fw_dtype dt, fw_layout lay);
