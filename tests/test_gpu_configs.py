@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_common import (CondRunner, b, dev, desc_of, dt_of, lower, ora, oracle_rows, relF, run_cov, run_finalize, workspace, DEV)
+from gpu_common import (CondRunner, b, dev, ora, oracle_rows, relF, run_cov, run_finalize, workspace, DEV)
 
 pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-4, "bf16": 2e-2}

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_common import (b, dev, lower, oracle_rows, ora, relF, run_cov, run_finalize, upload_act, desc_of, dt_of, workspace, DEV)
+from gpu_common import (b, lower, oracle_rows, ora, relF, run_cov, run_finalize, workspace, DEV)
 
 pytestmark = pytest.mark.gpu
 
