@@ -23,6 +23,13 @@
 // current step, so that the matrix pipe stays busy while a single wavefront per SIMD does all the issuing.
 // With one range per tile and the feature order kept, the result is added straight into A; otherwise partial
 // tiles go to the workspace and are summed in float64 (and permuted to the caller's feature order).
+//
+// Stride-1 windows take the shift-correlation form instead (same sums, see cov_shift.hip for the derivation): the same
+// kernel runs on a rectangular grid of tiles whose rows are the channels of a pixel and whose columns are (tap
+// difference, channel) of the pixel shifted back by that difference; units are pixels listed region by region, ranges
+// never cross a region, and an assembly kernel adds, per pair of taps, the partial tiles of the regions that serve the
+// row tap.  Up to 128 channels a unit is a pair of horizontally neighbouring pixels (2 Cin "channels"), which fills the
+// row tiles and halves the units.
 #include "fw_internal.h"
 #include <math.h>
 #include <string.h>
