@@ -567,6 +567,75 @@ __global__ __launch_bounds__(256) void finalize_phi_kernel(const float* __restri
     }
 }
 
+// The same for M a multiple of 4, on 64x64 tiles with 16-byte accesses: thread (ty, tx) takes rows ty, ty + 16, ty + 32,
+// ty + 48 and columns 4 tx .. 4 tx + 3; all its loads are issued before the first is used.  Off the diagonal the tile is
+// stored from registers and its mirror image from a transposed read of LDS; a diagonal tile is stored once, made
+// symmetric from its lower half (A holds nothing above the diagonal).
+__global__ __launch_bounds__(256) void finalize_phi64_kernel(const float* __restrict__ A, const float* __restrict__ s,
+                                                             const float* __restrict__ mu_old, double inv_n, int M, float alpha,
+                                                             int first, float* __restrict__ Phi) {
+    const int I = blockIdx.y, J = blockIdx.x;
+    if (J > I) return;
+    __shared__ float tr[64][65];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int j0 = J * 64 + 4 * tx;
+    const bool col_ok = j0 < M;
+    float4 a[4], ph[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = I * 64 + ty + 16 * r;
+        const size_t e = (col_ok && i < M) ? (size_t)i * M + j0 : 0;
+        a[r] = *reinterpret_cast<const float4*>(A + e);
+        ph[r] = first ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4*>(Phi + e);
+    }
+    double mhj[4], mj[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int j = j0 + q;
+        mhj[q] = j < M ? (double)s[j] * inv_n : 0.0;
+        mj[q] = j < M ? (first ? mhj[q] : (double)alpha * (double)mu_old[j] + (1.0 - (double)alpha) * mhj[q]) : 0.0;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int yy = ty + 16 * r;
+        const int i = I * 64 + yy;
+        asm volatile("" : "+v"(a[r].x), "+v"(a[r].y), "+v"(a[r].z), "+v"(a[r].w));
+        const bool row_ok = col_ok && i < M;
+        const double mhi = row_ok ? (double)s[i] * inv_n : 0.0;
+        const double mi = first ? mhi : (double)alpha * (double)(row_ok ? mu_old[i] : 0.f) + (1.0 - (double)alpha) * mhi;
+        const float av[4] = {a[r].x, a[r].y, a[r].z, a[r].w}, pv[4] = {ph[r].x, ph[r].y, ph[r].z, ph[r].w};
+        float o[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            double c = (double)av[q] * inv_n - mhi * mj[q] - mi * mhj[q] + mi * mj[q];
+            if (!first) c = (double)alpha * (double)pv[q] + (1.0 - (double)alpha) * c;
+            o[q] = (row_ok && j0 + q <= i) ? (float)c : 0.f;     // nothing is taken from above the diagonal
+            tr[yy][4 * tx + q] = o[q];
+        }
+        if (I != J && row_ok) *reinterpret_cast<float4*>(Phi + (size_t)i * M + j0) = make_float4(o[0], o[1], o[2], o[3]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int yy = ty + 16 * r;
+        if (I != J) {
+            // mirror image: element (J*64 + yy, I*64 + x) = tile element (x, yy)
+            const int row = J * 64 + yy, c0 = I * 64 + 4 * tx;
+            if (row < M && c0 < M)
+                *reinterpret_cast<float4*>(Phi + (size_t)row * M + c0) =
+                    make_float4(tr[4 * tx][yy], tr[4 * tx + 1][yy], tr[4 * tx + 2][yy], tr[4 * tx + 3][yy]);
+        } else {
+            const int row = I * 64 + yy, c0 = I * 64 + 4 * tx;
+            if (row < M && c0 < M) {
+                float v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) { const int x = 4 * tx + q; v[q] = x <= yy ? tr[yy][x] : tr[x][yy]; }
+                *reinterpret_cast<float4*>(Phi + (size_t)row * M + c0) = make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void mirror_lower_kernel(float* __restrict__ A, int M) {
     const int i = blockIdx.y * 16 + threadIdx.y, j = blockIdx.x * 16 + threadIdx.x;
     if (i >= M || j >= M || j >= i) return;
@@ -700,8 +769,13 @@ fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_con
 fw_status cov_finalize(const float* A, const float* s, long long n, int M, float alpha, int first_block, float* mu, float* Phi_x,
                        float* phi_x, float* lambda_bar, hipStream_t st) {
     const double inv_n = 1.0 / (double)n;
-    const int tb = (M + 31) / 32;
-    hipLaunchKernelGGL(finalize_phi_kernel, dim3(tb, tb), dim3(256), 0, st, A, s, mu, inv_n, M, alpha, first_block, Phi_x);
+    if ((M & 3) == 0) {
+        const int tb = (M + 63) / 64;
+        hipLaunchKernelGGL(finalize_phi64_kernel, dim3(tb, tb), dim3(256), 0, st, A, s, mu, inv_n, M, alpha, first_block, Phi_x);
+    } else {
+        const int tb = (M + 31) / 32;
+        hipLaunchKernelGGL(finalize_phi_kernel, dim3(tb, tb), dim3(256), 0, st, A, s, mu, inv_n, M, alpha, first_block, Phi_x);
+    }
     FW_LAUNCH_CHECK();
     hipLaunchKernelGGL(finalize_vec_kernel, dim3(1), dim3(1024), 0, st, A, s, inv_n, M, alpha, first_block, mu, phi_x, lambda_bar);
     FW_LAUNCH_CHECK();
