@@ -371,6 +371,24 @@ __global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const floa
     const float g1 = 1.f - gamma, g2 = gamma * gamma, gg1 = gamma * g1, g1sq = g1 * g1, b1 = 1.f - beta;
     const float aa2 = a * (a + 2.f), a2lam = a * a * lam;
 
+    // Everything this workgroup reads is asked for before anything is stored (the state pointers may not be told apart
+    // by the compiler, so a load behind a store would wait for it: a chain of round trips that dominates small M).
+    const int npos = (I == J) ? 1 : 2;
+    float Qv[2][4], Yv[2][4], Sv[2][4], Xv[2][4], Tv[2][4];
+#pragma unroll
+    for (int pos = 0; pos < 2; ++pos) {
+        const int rowblk = pos == 0 ? I : J, colblk = pos == 0 ? J : I;
+        const int j = colblk * TILE + tx;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = rowblk * TILE + ty + 8 * r;
+            const bool ok = pos < npos && i < M && j < M;
+            const size_t e = ok ? (size_t)i * M + j : 0;
+            Qv[pos][r] = s.Q[e]; Yv[pos][r] = s.Phi_y[e]; Sv[pos][r] = s.Qs[e];
+            Xv[pos][r] = leak ? s.Phi_x[e] : 0.f;
+            Tv[pos][r] = leak ? 0.f : s.T[e];
+        }
+    }
     // stage the old T and Psi tiles of both positions (only needed for the transposed terms)
     if (leak) {
 #pragma unroll
@@ -387,8 +405,9 @@ __global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const floa
         __syncthreads();
     }
 
-    const int npos = (I == J) ? 1 : 2;
-    for (int pos = 0; pos < npos; ++pos) {
+#pragma unroll
+    for (int pos = 0; pos < 2; ++pos) {
+        if (pos >= npos) break;
         const int rowblk = pos == 0 ? I : J, colblk = pos == 0 ? J : I;
         const int j = colblk * TILE + tx;
         const float vj = j < M ? v[j] : 0.f, uj = j < M ? u[j] : 0.f, tj = j < M ? t[j] : 0.f;
@@ -409,14 +428,14 @@ __global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const floa
                     Psiold = pos == 0 ? Pa[yy][tx] : Pb[yy][tx];
                     if (I == J) { Tt = Ta[tx][yy]; Psit = Pa[tx][yy]; }
                     else { Tt = pos == 0 ? Tb[tx][yy] : Ta[tx][yy]; Psit = pos == 0 ? Pb[tx][yy] : Pa[tx][yy]; }
-                    phix = s.Phi_x[e];
+                    phix = Xv[pos][r];
                     pi = p[i];
                 } else {
-                    Told = s.T[e];
+                    Told = Tv[pos][r];
                 }
                 const float Tn = gamma * (Told + a * vi * tj) + g1 * dij;
-                float Qn = g2 * (s.Q[e] + aa2 * (ti * tj)) + g1sq * dij;
-                float Yn = g2 * (s.Phi_y[e] + a * (vi * uj + ui * vj) + a2lam * (vi * vj));
+                float Qn = g2 * (Qv[pos][r] + aa2 * (ti * tj)) + g1sq * dij;
+                float Yn = g2 * (Yv[pos][r] + a * (vi * uj + ui * vj) + a2lam * (vi * vj));
                 if (leak) {
                     Qn += gg1 * (a * (vi * tj + ti * vj) + Told + Tt);
                     Yn += gg1 * (Psiold + Psit + a * (vi * pj + pi * vj)) + g1sq * phix;
@@ -424,7 +443,7 @@ __global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const floa
                 }
                 s.T[e] = Tn;
                 s.Q[e] = Qn;
-                s.Qs[e] = beta * s.Qs[e] + b1 * Qn;
+                s.Qs[e] = beta * Sv[pos][r] + b1 * Qn;
                 s.Phi_y[e] = Yn;
                 sq = Yn * Yn;
             }
