@@ -596,15 +596,22 @@ __global__ __launch_bounds__(256) void shift_tile_assemble_kernel(TileGeom g, co
         if (!active) return;
         const double v[4] = {v0, v1, v2, v3};
         const bool kkc = g.layout == FW_LAYOUT_NHWC_KKC;
+        // the four old values are read before the first new one is written (a read behind a write would wait for it)
+        float* dst[4];
+        float old[4];
+        bool keep[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int cc = c2 + q;
-            if (t1 == t2 && cc > c1) continue;
+            keep[q] = !(t1 == t2 && cc > c1);
             const int ei = kkc ? t1 * g.Cin + c1 : c1 * kk + t1;
             const int ej = kkc ? t2 * g.Cin + cc : cc * kk + t2;
-            float* dst = A + (size_t)max(ei, ej) * g.M + min(ei, ej);
-            *dst = (float)((double)*dst + v[q]);
+            dst[q] = A + (keep[q] ? (size_t)max(ei, ej) * g.M + min(ei, ej) : 0);
+            old[q] = *dst[q];
         }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (keep[q]) *dst[q] = (float)((double)old[q] + v[q]);
     }
 }
 
