@@ -30,8 +30,8 @@ HBM_PEAK = 8.0e12
 # counter scaled by what it reads on a 256 MiB device copy (2 KiB per FETCH_SIZE count, 1 KiB per WRITE_SIZE count).
 # Measured with the default layout (kkc); other layouts report null.
 MEASURED_TRAFFIC = {"c2": {"read": 122.5e6, "written": 58.9e6},
-                    "c3": {"read": 195.3e6, "written": 116.4e6},
-                    "c4": {"read": 499.2e6, "written": 184.3e6}}
+                    "c3": {"read": 195.6e6, "written": 116.2e6},
+                    "c4": {"read": 499.9e6, "written": 184.1e6}}
 
 
 def parse():
