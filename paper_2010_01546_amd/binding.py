@@ -193,7 +193,12 @@ def fw_cov_set_form(form):
 
 
 def cond_state(M, Phi_x, lambda_bar, T, Q, Qs, Phi_y, Psi, xi2) -> fw_cond_state:
-    return fw_cond_state(M, _ptr(Phi_x), _ptr(lambda_bar), _ptr(T), _ptr(Q), _ptr(Qs), _ptr(Phi_y), _ptr(Psi), _ptr(xi2))
+    """The struct holds raw device addresses; the tensors behind them are attached to it (``tensors``) so that the
+    memory lives as long as the struct does: a caller that keeps only the struct would otherwise hand the library
+    addresses that the allocator has already given to somebody else."""
+    st = fw_cond_state(M, _ptr(Phi_x), _ptr(lambda_bar), _ptr(T), _ptr(Q), _ptr(Qs), _ptr(Phi_y), _ptr(Psi), _ptr(xi2))
+    st.tensors = (Phi_x, lambda_bar, T, Q, Qs, Phi_y, Psi, xi2)
+    return st
 
 
 def cond_params(gamma=0.99, delta=0.25, eps=1e-5, c_rel=0.025, c_abs=1e-6, beta=0.1, n_power_iters=0, guard=1) -> fw_cond_params:

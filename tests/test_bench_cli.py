@@ -23,3 +23,26 @@ def test_default_workload_is_config2():
     finally:
         sys.argv = old
     assert a.gpus == 1 and a.config == "c2" and a.steps > 0 and a.warmup >= 0
+
+
+def test_cond_state_keeps_its_tensors_alive():
+    """The struct carries raw addresses only; the binding attaches the tensors so that a caller holding just the struct
+    (a closure over it, say) does not hand the library memory that the allocator has already given away."""
+    import gc
+    import weakref
+
+    import torch
+    from paper_2010_01546_amd import binding as b
+    M = 8
+    ts = [torch.zeros(M, M) for _ in range(7)] + [torch.zeros(M)]
+    Phi, T, Q, Qs, Py, Psi, lbar, xi2 = ts[0], ts[1], ts[2], ts[3], ts[4], ts[5], ts[6], ts[7]
+    refs = [weakref.ref(t) for t in ts]
+    ptrs = [t.data_ptr() for t in ts]
+    st = b.cond_state(M, Phi, lbar, T, Q, Qs, Py, Psi, xi2)
+    del ts, Phi, T, Q, Qs, Py, Psi, lbar, xi2
+    gc.collect()
+    assert all(r() is not None for r in refs)
+    assert [st.Phi_x, st.T, st.Q, st.Qs, st.Phi_y, st.Psi, st.lambda_bar, st.xi2] == ptrs
+    del st
+    gc.collect()
+    assert all(r() is None for r in refs)
