@@ -216,6 +216,19 @@ fw_status fw_cond_state_refresh(const fw_cond_state* st, void* ws, size_t ws_byt
 fw_status fw_cond_reduce_step(const fw_cond_state* st, const fw_cond_params* p, fw_cond_info* info_dev,
                               void* ws, size_t ws_bytes, void* stream);
 
+/* The same step for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Identical arithmetic and kernels; the scratch is a fixed array
+ * of 4 MiB in the library's device image (one copy per GPU, held until the process ends), so
+ *   - M is limited to FW_COND_STATIC_MAX_M (FW_ERR_UNSUPPORTED beyond it, nothing enqueued),
+ *   - the call allocates and frees nothing (its only set-up is one symbol-address lookup per device, on the first call
+ *     made with that device current),
+ *   - all calls on one GPU share the array: calls that overlap in time on one GPU (different streams, different
+ *     threads) race on it and must be serialised by the caller.  Nothing in the array has to survive between calls and
+ *     every entry is written before it is read, so a call is not affected by what the previous one left.
+ * Other arguments, validation and error codes as fw_cond_reduce_step. */
+#define FW_COND_STATIC_MAX_M 4608
+fw_status fw_cond_reduce_step_static(const fw_cond_state* st, const fw_cond_params* p, fw_cond_info* info_dev, void* stream);
+
 /* ------------------------------------------------------------------------------------------------------------
  * (4) EVD / ZCA reference -- eqs. (vPhix_evd), (vT_EVD), (vg) of Sec. 2; gain variant eqs. (hMs), (g_mod) of Sec. 3.2.
  */

@@ -26,8 +26,8 @@ FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
 
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",
            "fw_whiten_evd", "fw_cond_state_refresh", "fw_grad_transform_taps", "fw_sgd_update", "fw_bias_compensate",
-           "fw_diagnostics", "fw_cov_plan_query", "fw_cov_set_form", "fw_workspace_bytes", "fw_status_string", "fw_version"]
-N_STATUS_EXPORTS = 13   # the leading entries of EXPORTS return fw_status
+           "fw_diagnostics", "fw_cov_plan_query", "fw_cov_set_form", "fw_cond_reduce_step_static", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+N_STATUS_EXPORTS = 14   # the leading entries of EXPORTS return fw_status
 
 
 class fw_conv_desc(C.Structure):
@@ -70,6 +70,7 @@ lib.fw_grad_transform.argtypes = [_P, C.c_int, C.c_int, C.c_int, _P, _P, _P, _P,
 lib.fw_cond_state_init.argtypes = [C.POINTER(fw_cond_state), _P]
 lib.fw_cond_state_refresh.argtypes = [C.POINTER(fw_cond_state), _P, C.c_size_t, _P]
 lib.fw_cond_reduce_step.argtypes = [C.POINTER(fw_cond_state), C.POINTER(fw_cond_params), _P, _P, C.c_size_t, _P]
+lib.fw_cond_reduce_step_static.argtypes = [C.POINTER(fw_cond_state), C.POINTER(fw_cond_params), _P, _P]
 lib.fw_whiten_evd.argtypes = [_P, C.c_int, C.POINTER(fw_evd_params), _P, _P, _P, _P, _P, C.c_size_t, _P]
 lib.fw_grad_transform_taps.argtypes = [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, _P, C.c_size_t, _P]
 lib.fw_sgd_update.argtypes = [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.POINTER(fw_sgd_params), _P, _P, _P, C.c_size_t, _P]
@@ -223,6 +224,13 @@ def fw_cond_state_refresh(st, ws=None, stream=None):
 def fw_cond_reduce_step(st, p, info_dev, ws, stream=None):
     wp, n = _ws(ws)
     return _check(lib.fw_cond_reduce_step(C.byref(st), C.byref(p), _ptr(info_dev), wp, n, _stream(stream)), "fw_cond_reduce_step")
+
+
+FW_COND_STATIC_MAX_M = 4608
+
+
+def fw_cond_reduce_step_static(st, p, info_dev, stream=None):
+    return _check(lib.fw_cond_reduce_step_static(C.byref(st), C.byref(p), _ptr(info_dev), _stream(stream)), "fw_cond_reduce_step_static")
 
 
 def fw_whiten_evd(Phi_x, M, p, T, Q, Qs, lam, ws, stream=None, allow_not_converged=False):

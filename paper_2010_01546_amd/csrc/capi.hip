@@ -155,8 +155,8 @@ fw_status fw_cond_state_refresh(const fw_cond_state* st, void* ws, size_t ws_byt
     return cond_state_refresh(st, reinterpret_cast<float*>(ws), reinterpret_cast<hipStream_t>(stream));
 }
 
-fw_status fw_cond_reduce_step(const fw_cond_state* st, const fw_cond_params* p, fw_cond_info* info_dev, void* ws, size_t ws_bytes,
-                              void* stream) {
+// argument checks shared by the two forms of the recursive step (everything except the workspace)
+static fw_status cond_step_check(const fw_cond_state* st, const fw_cond_params* p) {
     if (!st || !p || st->M <= 0 || !st->Phi_x || !st->lambda_bar || !st->T || !st->Q || !st->Qs || !st->Phi_y || !st->xi2)
         return FW_ERR_INVALID_ARG;
     if (!(p->gamma > 0.f && p->gamma <= 1.f) || !(p->delta > 0.f) || !(p->eps > 0.f) || !(p->beta >= 0.f && p->beta < 1.f) ||
@@ -165,9 +165,29 @@ fw_status fw_cond_reduce_step(const fw_cond_state* st, const fw_cond_params* p, 
     if (p->gamma < 1.f && !st->Psi) return FW_ERR_INVALID_ARG;
     if (st->M > 16384) return FW_ERR_UNSUPPORTED;
     if (!aligned16(st->Phi_x) || !aligned16(st->T) || !aligned16(st->Q) || !aligned16(st->Qs) || !aligned16(st->Phi_y) ||
-        !aligned16(st->xi2) || (st->Psi && !aligned16(st->Psi)) || (ws && !aligned16(ws)))
+        !aligned16(st->xi2) || (st->Psi && !aligned16(st->Psi)))
         return FW_ERR_ALIGNMENT;
+    return FW_OK;
+}
+
+fw_status fw_cond_reduce_step(const fw_cond_state* st, const fw_cond_params* p, fw_cond_info* info_dev, void* ws, size_t ws_bytes,
+                              void* stream) {
+    const fw_status rc = cond_step_check(st, p);
+    if (rc != FW_OK) return rc;
+    if (ws && !aligned16(ws)) return FW_ERR_ALIGNMENT;
     if (!ws || ws_bytes < cond_workspace_bytes(st->M)) return FW_ERR_WORKSPACE;
+    return cond_reduce_step(st, p, info_dev, ws, reinterpret_cast<hipStream_t>(stream));
+}
+
+fw_status fw_cond_reduce_step_static(const fw_cond_state* st, const fw_cond_params* p, fw_cond_info* info_dev, void* stream) {
+    fw_status rc = cond_step_check(st, p);
+    if (rc != FW_OK) return rc;
+    if (st->M > FW_COND_STATIC_MAX_M) return FW_ERR_UNSUPPORTED;
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    rc = cond_static_scratch(&ws, &ws_bytes);   // no allocation: the address of a static device array
+    if (rc != FW_OK) return rc;
+    if (cond_workspace_bytes(st->M) > ws_bytes) return FW_ERR_UNSUPPORTED;
     return cond_reduce_step(st, p, info_dev, ws, reinterpret_cast<hipStream_t>(stream));
 }
 

@@ -19,6 +19,12 @@
 // t = T^T v (the transposed reading of eq. (vtve)) is what makes T' equal gamma T~ T + (1-gamma) I.
 // Matrix-vector products use one wavefront per row with a 64-lane shuffle reduction.
 #include "fw_internal.h"
+#include <mutex>
+
+// Scratch of the allocation-free variant of the step (fw_cond_reduce_step_static): the workspace of one step for
+// M <= 4608, held by every GPU the library runs on until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress; the address kernels are given comes from static_scratch() below.
+static __device__ __align__(256) unsigned char scratch[4u << 20];
 
 namespace fw {
 namespace {
@@ -507,6 +513,27 @@ fw_status cond_state_refresh(const fw_cond_state* s, float* psi_scratch, hipStre
     if (rc != FW_OK) return rc;
     hipLaunchKernelGGL(rownorm2_kernel, dim3((M + 3) / 4), dim3(256), 0, st, s->Phi_y, M, s->xi2);
     FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
+// Device address of `scratch` on the current device, looked up once per device (every GPU holds its own copy of the
+// array at its own address).
+fw_status cond_static_scratch(void** ptr, size_t* bytes) {
+    constexpr int kMaxDevices = 64;
+    static void* table[kMaxDevices] = {};
+    static std::mutex mu;
+    int dev = -1;
+    FW_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return FW_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!table[dev]) {
+        void* p = nullptr;
+        FW_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return FW_ERR_HIP;
+        table[dev] = p;
+    }
+    *ptr = table[dev];
+    *bytes = sizeof(scratch);
     return FW_OK;
 }
 

@@ -166,6 +166,7 @@ size_t cond_workspace_bytes(int M);
 fw_status cond_state_init(const fw_cond_state* s, hipStream_t st);
 fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_cond_info* info, void* ws, hipStream_t st);
 fw_status cond_state_refresh(const fw_cond_state* s, float* psi_scratch, hipStream_t st);
+fw_status cond_static_scratch(void** ptr, size_t* bytes);
 
 // ---- evd.hip
 size_t evd_workspace_bytes(int M);

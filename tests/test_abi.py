@@ -90,6 +90,11 @@ def test_argument_validation_without_a_device():
         pb = b.cond_params(**kw)
         assert L.fw_cond_reduce_step(C.byref(st), C.byref(pb), None, fake, 1 << 20, None) == b.FW_ERR_INVALID_ARG, kw
     assert L.fw_cond_state_init(None, None) == b.FW_ERR_INVALID_ARG
+    # the allocation-free form: same checks, and its own size limit, all before any device call
+    assert L.fw_cond_reduce_step_static(C.byref(st), C.byref(p), None, None) == b.FW_ERR_INVALID_ARG
+    assert L.fw_cond_reduce_step_static(None, C.byref(p1), None, None) == b.FW_ERR_INVALID_ARG
+    big = b.fw_cond_state(b.FW_COND_STATIC_MAX_M + 1, fake, fake, fake, fake, fake, fake, fake, fake)
+    assert L.fw_cond_reduce_step_static(C.byref(big), C.byref(p), None, None) == b.FW_ERR_UNSUPPORTED
     # EVD
     e = b.evd_params()
     assert L.fw_whiten_evd(None, 8, C.byref(e), fake, fake, None, fake, fake, 1 << 20, None) == b.FW_ERR_INVALID_ARG
