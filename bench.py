@@ -1,14 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the feature-whitening hot path on one MI355X.
 
-One "step" is one whitened gradient update of one layer: fw_cov_accumulate (+ fw_cov_finalize) on a batch, one
-fw_cond_reduce_step, and fw_grad_transform of the layer's weight gradient -- block length L = 1, the worst case
-(the paper amortises the recursive step over L batches).  Inputs are seeded synthetic activations and gradients,
-resident in HBM before the timed region starts.
+One "step" is one whitened gradient update of one layer with block length L = 1 (the worst case: the paper amortises
+everything but the moments and the gradient product over L batches): zero the block sums, fw_cov_accumulate on the
+batch, fw_cov_finalize (alpha = 0.1), fw_cond_state_refresh (the block's new Phi_x invalidates Phi_y = T Phi_x T^T
+and Psi = T Phi_x, which the recursive step keeps up to date only while Phi_x stands still), one fw_cond_reduce_step
+with the paper's hyper-parameters, and fw_grad_transform of the layer's weight gradient.  Two different batches are
+fed in turn, so Phi_x really moves from step to step.  Inputs are seeded synthetic activations and gradients, resident
+in HBM before the timed region starts.
 
-Prints ONE JSON line.  `roofline` describes the dominant kernel pair (the split-K covariance kernel and its reduce,
-i.e. one fw_cov_accumulate call) timed with events on the launch stream inside the timed region; `cpu_baseline`
-times the float64 numpy oracle on the host cores for one update of the same workload.
+With no --config the three single-layer configurations C2, C3, C4 run one after the other in this process; the
+top-level fields of the ONE JSON line are C4's (the largest state: all three roofs bind there), C2 and C3 sit under
+"configs".  Every export of the step is bracketed by HIP events on the launch stream inside the timed region;
+"rooflines" holds one entry per export, "roofline" repeats the entry of the export that takes the largest share of
+the step.  `cpu_baseline` times the float64 numpy oracle on the host cores for updates of the same workload.
 """
 from __future__ import annotations
 
@@ -25,38 +30,41 @@ if ROOT not in sys.path:
 PEAK = {"f32": 157.3e12, "bf16": 2.5e15}   # dense MFMA peaks of MI355X, flop/s
 HBM_PEAK = 8.0e12
 
-# HBM bytes (read + written) per fw_cov_accumulate call, all its kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this script with --copy-calibration (summary: profiles/fw_cov_accumulate_hbm_traffic_counters.txt), each
-# counter scaled by what it reads on a 256 MiB device copy (2 KiB per FETCH_SIZE count, 1 KiB per WRITE_SIZE count).
-# Measured with the default layout (kkc); other layouts report null.
-MEASURED_TRAFFIC = {"c2": {"read": 122.5e6, "written": 58.9e6},
+# HBM bytes (read + written) per fw_cov_accumulate call, all its kernels.  NOT measured by this script: copied from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --config cN --no-extras --copy-calibration` whose summary is
+# profiles/fw_cov_accumulate_hbm_traffic_counters.txt, each counter scaled by what it reads on a 256 MiB device copy
+# (2 KiB per FETCH_SIZE count, 1 KiB per WRITE_SIZE count).  Default layout (kkc) only.
+PROFILED_TRAFFIC = {"c2": {"read": 122.5e6, "written": 58.9e6},
                     "c3": {"read": 195.6e6, "written": 116.2e6},
                     "c4": {"read": 499.9e6, "written": 184.1e6}}
 
+EXPORTS = ("cov_accumulate", "cov_finalize", "cond_state_refresh", "cond_reduce_step", "grad_transform")
 
-def parse():
+
+def parse(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"],
-                    help="c2 is the headline workload; c5 sweeps the 21 ResNet-18 layers and reports the aggregate")
+    ap.add_argument("--config", default="all", choices=["all", "c1", "c2", "c3", "c4", "c5"],
+                    help="all (default): C2, C3 and C4 in one process, C4 on top; c5 sweeps the 21 ResNet-18 layers and "
+                         "reports the aggregate")
     ap.add_argument("--evd", action="store_true", help="also time one fw_whiten_evd call (outside the headline)")
     ap.add_argument("--layout", default="kkc", choices=["kkc", "nhwc", "nchw"],
                     help="kkc: NHWC tensor with channels-last feature order (ky,kx,c); nhwc/nchw: feature order (c,ky,kx)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the timing of the companion exports (refresh, fused update, diagnostics, per-channel variant): "
-                         "a profile of such a run holds the kernels of the step only")
-    ap.add_argument("--c5-unlocked", action="store_true", help=argparse.SUPPRESS)   # only once the fault of the sweep is explained
+                    help="skip the second timed loop (stationary Phi_x) and the companion exports (fused update, diagnostics, "
+                         "per-channel variant): a profile of such a run holds the kernels of the step only")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, copy a 256 MiB tensor five times: the known-size kernel against which the\n"
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command are scaled")
-    return ap.parse_args()
+    return ap.parse_args(argv)
 
 
 def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extras=True):
-    """One whitened layer: K timed steps of the whole hot path plus a per-export breakdown.  Returns a dict of timings."""
+    """One whitened layer: `steps` timed steps of the whole hot path, every export bracketed by events.  Returns a dict
+    of timings and the step function (which keeps the layer's device state alive)."""
     dev = "cuda:0"
     d = layer.desc
     M, S, n_rows = d.M, layer.S, d.n_rows
@@ -65,10 +73,13 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
     tdt = torch.bfloat16 if bf16 else torch.float32
     if layer.is_rows:
         lay = b.FW_LAYOUT_ROWS
-        X = torch.as_tensor(layer.act).to(dev).to(tdt).contiguous()
+        X0 = torch.as_tensor(layer.act).to(dev).to(tdt).contiguous()
+        X1 = X0.flip(1).contiguous()            # a second batch: the same rows with the features in reverse order
     else:
         lay = {"kkc": b.FW_LAYOUT_NHWC_KKC, "nhwc": b.FW_LAYOUT_NHWC, "nchw": b.FW_LAYOUT_NCHW}[layout_name]
-        X = torch.as_tensor(wl.to_layout(layer.act, lay)).to(dev).to(tdt).contiguous()
+        X0 = torch.as_tensor(wl.to_layout(layer.act, lay)).to(dev).to(tdt).contiguous()
+        X1 = X0.flip(3 if lay == b.FW_LAYOUT_NCHW else 2).contiguous()   # a second batch: the images mirrored left-right
+    Xs = (X0, X1)
     desc = b.conv_desc(*d.astuple())
     G = torch.as_tensor(layer.G).to(dev)          # float32 gradient
     Gout = torch.empty_like(G)
@@ -86,15 +97,18 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
     ws_cond = torch.empty(b.fw_workspace_bytes(b.FW_OP_COND_REDUCE_STEP, M), dtype=torch.uint8, device=dev)
     prm = b.cond_params()                          # the paper's hyper-parameters (Sec. 6)
     alpha = 0.1
-    st = b.cond_state(M, Phi, lbar, T, Q, Qs, Py, Psi, xi2)
+    st = b.cond_state(M, Phi, lbar, T, Q, Qs, Py, Psi, xi2)   # holds the nine tensors
 
     # first block: moments and initial state
-    b.fw_cov_accumulate(X, dt, lay, desc, A, s, ws_cov)
+    b.fw_cov_accumulate(X0, dt, lay, desc, A, s, ws_cov)
     b.fw_cov_finalize(A, s, n_rows, M, alpha, 1, mu, Phi, phi, lbar)
     b.fw_cond_state_init(st)
     torch.cuda.synchronize()
+    counter = [0]
 
-    def step(ev=None):
+    def step(ev=None, refresh=True):
+        X = Xs[counter[0] & 1] if refresh else X0   # without the refresh the same batch comes again: Phi_x stands still
+        counter[0] += 1
         As.zero_()
         if ev is not None:
             ev[0].record()
@@ -102,66 +116,272 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
         if ev is not None:
             ev[1].record()
         b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar)
+        if ev is not None:
+            ev[2].record()
+        if refresh:
+            b.fw_cond_state_refresh(st)      # Psi is part of the state: no scratch needed
+        if ev is not None:
+            ev[3].record()
         b.fw_cond_reduce_step(st, prm, info, ws_cond)
+        if ev is not None:
+            ev[4].record()
         b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)
+        if ev is not None:
+            ev[5].record()
 
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    t0 = time.perf_counter()
-    for k in range(steps):
-        step(events[k])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / steps
-    cov_ms = sum(e0.elapsed_time(e1) for e0, e1 in events) / steps
-    assert torch.isfinite(Gout).all() and torch.isfinite(T).all()
+    def timed(refresh):
+        for _ in range(warmup):
+            step(None, refresh)
+        torch.cuda.synchronize()
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(steps)]
+        t0 = time.perf_counter()
+        for k in range(steps):
+            step(events[k], refresh)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        per = [sum(e[i].elapsed_time(e[i + 1]) for e in events) / steps for i in range(5)]
+        return (t1 - t0) * 1e3 / steps, dict(zip(EXPORTS, per))
 
-    # separate, untimed-for-the-headline breakdown of the other exports
-    def time_call(fn, reps=20):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        fn(); torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record(); torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
-    # the companions outside the step: fused weight update (momentum 0.9, decay 5e-4: Sec. 6) and the whiteness figure
-    Wt, Vt = torch.randn(S, M, device=dev), torch.zeros(S, M, device=dev)
-    sgd = b.sgd_params(0.1, 0.9, 5e-4)
-    diag_out = torch.zeros(4, device=dev)
-    ws_diag = torch.empty(b.fw_workspace_bytes(b.FW_OP_DIAGNOSTICS, M), dtype=torch.uint8, device=dev)
-    out = {"M": M, "S": S, "n_rows": n_rows, "bf16": bf16, "ms_per_step": ms_per_step, "cov_ms": cov_ms,
-           "cond_ms": time_call(lambda: b.fw_cond_reduce_step(st, prm, info, ws_cond)),
-           "grad_ms": time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)),
-           "fin_ms": time_call(lambda: b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar)),
-           "refresh_ms": time_call(lambda: b.fw_cond_state_refresh(st), reps=5) if extras else None,
-           "sgd_ms": time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt)) if extras else None,
-           "diag_ms": time_call(lambda: b.fw_diagnostics(Py, None, M, diag_out, ws_diag)) if extras else None,
-           "gamma": prm.gamma, "act_bytes": float(X.numel() * X.element_size()), "step": step}
-    if extras and not layer.is_rows and d.kh * d.kw > 1:
-        # per-channel variant of the same layer (whitening in front of the convolution, M = Cin): moments of the 1x1
-        # "window" over the input pixels, and every tap's S x Cin gradient times the one Cin x Cin Q
-        taps = d.kh * d.kw
-        d1 = wl.ConvDesc(B=d.B, Cin=d.Cin, H=d.H, W=d.W, kh=1, kw=1, stride=1, pad=0)
-        desc1 = b.conv_desc(*d1.astuple())
-        A1 = torch.zeros(d.Cin, d.Cin, device=dev); s1 = torch.zeros(d.Cin, device=dev)
-        ws1 = torch.empty(b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, d.Cin, 0, desc1, dt), dtype=torch.uint8, device=dev)
-        Q1 = torch.eye(d.Cin, device=dev)
-        G4 = torch.randn(S, d.Cin, taps, device=dev) * 0.03
-        G4o = torch.empty_like(G4)
-        ws4 = torch.empty(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM_TAPS, d.Cin, S * taps), dtype=torch.uint8, device=dev)
-        out["per_channel_cov_ms"] = time_call(lambda: b.fw_cov_accumulate(X, dt, lay, desc1, A1, s1, ws1))
-        out["per_channel_grad_ms"] = time_call(lambda: b.fw_grad_transform_taps(G4, b.FW_F32, S, d.Cin, taps, Q1, G4o, ws4))
+    ms_per_step, ex_ms = timed(True)
+    assert torch.isfinite(Gout).all() and torch.isfinite(T).all() and torch.isfinite(Py).all()
+    out = {"M": M, "S": S, "n_rows": n_rows, "bf16": bf16, "ms_per_step": ms_per_step, "export_ms": ex_ms,
+           "gamma": prm.gamma, "act_bytes": float(X0.numel() * X0.element_size()), "step": step, "lay": lay, "extra_ms": {}}
+    if extras:
+        # Phi_x standing still (what a block of L > 1 batches sees between its boundaries, and the step as it was timed
+        # before the refresh joined it): the same loop without fw_cond_state_refresh
+        out["ms_per_step_stationary"], st_ms = timed(False)
+        out["export_ms_stationary"] = st_ms
+
+        def time_call(fn, reps=20):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn(); torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        # the companions outside the step: fused weight update (momentum 0.9, decay 5e-4: Sec. 6) and the whiteness figure
+        Wt, Vt = torch.randn(S, M, device=dev), torch.zeros(S, M, device=dev)
+        sgd = b.sgd_params(0.1, 0.9, 5e-4)
+        diag_out = torch.zeros(4, device=dev)
+        ws_diag = torch.empty(b.fw_workspace_bytes(b.FW_OP_DIAGNOSTICS, M), dtype=torch.uint8, device=dev)
+        xm = out["extra_ms"]
+        xm["sgd_update_fused"] = time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt))
+        xm["diagnostics_whiteness"] = time_call(lambda: b.fw_diagnostics(Py, None, M, diag_out, ws_diag))
+        if not layer.is_rows and d.kh * d.kw > 1:
+            # per-channel variant of the same layer (whitening in front of the convolution, M = Cin): moments of the 1x1
+            # "window" over the input pixels, and every tap's S x Cin gradient times the one Cin x Cin Q
+            taps = d.kh * d.kw
+            d1 = wl.ConvDesc(B=d.B, Cin=d.Cin, H=d.H, W=d.W, kh=1, kw=1, stride=1, pad=0)
+            desc1 = b.conv_desc(*d1.astuple())
+            A1 = torch.zeros(d.Cin, d.Cin, device=dev); s1 = torch.zeros(d.Cin, device=dev)
+            ws1 = torch.empty(b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, d.Cin, 0, desc1, dt), dtype=torch.uint8, device=dev)
+            Q1 = torch.eye(d.Cin, device=dev)
+            G4 = torch.randn(S, d.Cin, taps, device=dev) * 0.03
+            G4o = torch.empty_like(G4)
+            ws4 = torch.empty(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM_TAPS, d.Cin, S * taps), dtype=torch.uint8, device=dev)
+            xm["per_channel_variant_cov_accumulate"] = time_call(lambda: b.fw_cov_accumulate(X0, dt, lay, desc1, A1, s1, ws1))
+            xm["per_channel_variant_grad_transform_taps"] = time_call(
+                lambda: b.fw_grad_transform_taps(G4, b.FW_F32, S, d.Cin, taps, Q1, G4o, ws4))
     if evd:   # the EVD / ZCA reference construction replaces the recursive step; timed once, outside the headline
         ws_evd = torch.empty(b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, M), dtype=torch.uint8, device=dev)
         lam = torch.empty(M, device=dev)
-        b.fw_whiten_evd(Phi, M, b.evd_params(), T, Q, None, lam, ws_evd); torch.cuda.synchronize()
+        Te, Qe = torch.empty(M, M, device=dev), torch.empty(M, M, device=dev)
+        b.fw_whiten_evd(Phi, M, b.evd_params(), Te, Qe, None, lam, ws_evd); torch.cuda.synchronize()
         te = time.perf_counter()
-        b.fw_whiten_evd(Phi, M, b.evd_params(), T, Q, None, lam, ws_evd); torch.cuda.synchronize()
-        out["evd_ms"] = (time.perf_counter() - te) * 1e3
+        b.fw_whiten_evd(Phi, M, b.evd_params(), Te, Qe, None, lam, ws_evd); torch.cuda.synchronize()
+        out["extra_ms"]["whiten_evd"] = (time.perf_counter() - te) * 1e3
     return out
+
+
+def rooflines_of(r, layer, b, cfg_key, layout_name):
+    """One roofline entry per export of the step, from the event times of the timed region.
+
+    a1: issued matrix-core flops / time against the MFMA peak of the input type (the shift-correlation form issues fewer
+    flops than the dense lower triangle N_rows M (M+1); that dense-equivalent rate is reported beside it, it is a speed-up
+    over the direct form, not a utilisation).  a2, refresh: 2 S M^2 and 4 M^3 float32 flops against the float32 MFMA
+    peak.  a3: 16 M^2 (10 M^2 without leak) float32 words against the HBM peak; finalize: lower triangle of A and of the
+    old Phi_x read, Phi_x written."""
+    M, S, n_rows, bf16 = r["M"], r["S"], r["n_rows"], r["bf16"]
+    d = layer.desc
+    ex = r["export_ms"]
+    plan = b.fw_cov_plan_query(b.FW_BF16 if bf16 else b.FW_F32, r["lay"], b.conv_desc(*d.astuple()))
+    issued = plan.mfma_flops_issued
+    dense = float(n_rows) * M * (M + 1)
+    peak = PEAK["bf16" if bf16 else "f32"]
+    t = ex["cov_accumulate"] * 1e-3
+    tr = PROFILED_TRAFFIC.get(cfg_key) if (layer.is_rows or layout_name == "kkc") else None
+    shifted = bool(plan.shift)
+    a1 = {"bound": "mfma", "export": "fw_cov_accumulate",
+          "kernel": (("pack_images + cov_bf16_tile + shift_tile_assemble + column_sums" if shifted else
+                      "pack_images + cov_bf16_tile (+ tile_reduce) + column_sums") if bf16 else
+                     ("shift_partial_f32 + shift_region_reduce + shift_assemble" if shifted else
+                      "cov_partial_f32v4 + cov_reduce")) + " = one fw_cov_accumulate",
+          "achieved": issued / t / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": issued / t / peak,
+          "ms": ex["cov_accumulate"], "mfma_flops_issued": issued,
+          "note": "achieved = flops the matrix cores issue per call (padding included) / time of the call",
+          "dense_equivalent_flops": dense, "dense_equivalent_rate_TFLOPs": dense / t / 1e12,
+          "speedup_vs_direct_form_flops": dense / issued,
+          "traffic": (tr["read"] + tr["written"]) if tr else None,
+          "traffic_source": "profiles/fw_cov_accumulate_hbm_traffic_counters.txt (rocprofv3 counters of an earlier run of this "
+                            "command, not measured by this run)" if tr else None,
+          "traffic_read_written": tr, "algorithmic_bytes": r["act_bytes"] + 4.0 * M * M,
+          "plan": {"shift": plan.shift, "regions": plan.regions, "differences": plan.differences,
+                   "workgroups": plan.workgroups, "ranges": plan.ranges}}
+    t2 = ex["grad_transform"] * 1e-3
+    a2 = {"bound": "mfma", "export": "fw_grad_transform", "kernel": "grad_gemm_f32_strip", "achieved": 2.0 * S * M * M / t2 / 1e12,
+          "peak": PEAK["f32"] / 1e12, "unit": "TFLOP/s", "frac": 2.0 * S * M * M / t2 / PEAK["f32"], "ms": ex["grad_transform"],
+          "traffic": None}
+    words = 16 if r["gamma"] < 1.0 else 10
+    t3 = ex["cond_reduce_step"] * 1e-3
+    a3 = {"bound": "hbm", "export": "fw_cond_reduce_step", "kernel": "matvec_c + matvec_vt + matvec_u_vecmat + t_reduce_scalars + "
+          "matvec + update + partial_sum", "achieved": words * 4.0 * M * M / t3 / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+          "frac": words * 4.0 * M * M / t3 / HBM_PEAK, "ms": ex["cond_reduce_step"], "algorithmic_bytes": words * 4.0 * M * M,
+          "traffic": None,
+          "note": None if M > 1152 else "state of this size stays in the caches: launch- and latency-bound, no HBM fraction claimed"}
+    t4 = ex["cond_state_refresh"] * 1e-3
+    rf = {"bound": "mfma", "export": "fw_cond_state_refresh", "kernel": "two M x M x M products + mirror + row norms",
+          "achieved": 4.0 * M ** 3 / t4 / 1e12, "peak": PEAK["f32"] / 1e12, "unit": "TFLOP/s", "frac": 4.0 * M ** 3 / t4 / PEAK["f32"],
+          "ms": ex["cond_state_refresh"], "traffic": None}
+    t5 = ex["cov_finalize"] * 1e-3
+    fin_bytes = 4.0 * (M * (M + 1) + M * M)
+    fn = {"bound": "hbm", "export": "fw_cov_finalize", "kernel": "finalize_phi64 + finalize_vec", "achieved": fin_bytes / t5 / 1e9,
+          "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": fin_bytes / t5 / HBM_PEAK, "ms": ex["cov_finalize"], "traffic": None}
+    return {"a1_cov_accumulate": a1, "a1_cov_finalize": fn, "a2_grad_transform": a2, "a3_cond_reduce_step": a3,
+            "a3_cond_state_refresh": rf}
+
+
+def cpu_baseline_of(layer, np):
+    """The oracle as it stands (float64 numpy) on a bounded sample: whole updates of the same workload, repeated until
+    about 8 s have passed (at least one, at most 64); images beyond a memory bound are dropped and the moment terms,
+    which are linear in the rows, scaled."""
+    from oracle import fw_oracle as ora
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    d = layer.desc
+    M = d.M
+    alpha = 0.1
+    Bs = d.B if layer.is_rows else max(1, min(d.B, int(4e9 // max(1, 8 * d.P * M))))
+    scale = d.B / Bs
+    reps, spent, secs = 0, 0.0, {"unfold": 0.0, "moments": 0.0, "cond_step": 0.0, "grad_transform": 0.0}
+    while reps < 64 and spent < 8.0:
+        tc0 = time.perf_counter()
+        if layer.is_rows:
+            Xr = np.asarray(layer.act[:Bs], dtype=np.float64)
+        else:
+            Xr = ora.patch_rows(layer.act[:Bs], Bs, d.Cin, d.H, d.W, d.kh, d.kw, d.stride, d.pad)
+        tc1 = time.perf_counter()
+        mu_o, Phi_o, phi_o, lb_o = ora.block_moments(Xr, alpha, True)
+        del Xr
+        tc2 = time.perf_counter()
+        st_o, _ = ora.cond_reduce_step(ora.CondState.initial(Phi_o), lb_o, ora.CondParams())   # forms T Phi_x T^T explicitly
+        tc3 = time.perf_counter()
+        ora.grad_transform(layer.G, st_o.Qs)
+        tc4 = time.perf_counter()
+        for k, v in zip(secs, (tc1 - tc0, tc2 - tc1, tc3 - tc2, tc4 - tc3)):
+            secs[k] += v
+        reps += 1
+        spent += tc4 - tc0
+    secs = {k: v / reps for k, v in secs.items()}
+    t_update = (secs["unfold"] + secs["moments"]) * scale + secs["cond_step"] + secs["grad_transform"]
+    return {"value": 1.0 / t_update, "unit": "updates/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{reps} update(s) on {Bs} of {d.B} images (moment terms scaled by {scale:g}), "
+                      f"float64 numpy, {spent:.1f} s of CPU work",
+            "seconds_per_update": secs}
+
+
+def config_record(cfg_key, args, torch, b, wl, np):
+    """Everything reported for one single-layer configuration."""
+    layer = {"c1": wl.config1, "c2": wl.config2, "c3": wl.config3, "c4": wl.config4}[cfg_key]()
+    d = layer.desc
+    r = time_layer(layer, args.layout, args.steps, args.warmup, torch, b, wl, evd=args.evd, extras=not args.no_extras)
+    M, S, n_rows, bf16 = r["M"], r["S"], r["n_rows"], r["bf16"]
+    roofs = rooflines_of(r, layer, b, cfg_key, args.layout)
+    dominant = max(roofs.values(), key=lambda e: e["ms"])
+    rec = {
+        "metric": "whitened grad-updates/s per layer",
+        "value": 1e3 / r["ms_per_step"],
+        "unit": "updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if not bf16 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{layer.name}: M={M} S={S} N_rows={n_rows} layout={args.layout if not layer.is_rows else 'rows'}",
+                   "batch": d.B, "block_length": 1,
+                   "step": "zero sums, cov_accumulate, cov_finalize, cond_state_refresh, cond_reduce_step, grad_transform; "
+                           "two batches fed in turn",
+                   "cond_params": "gamma=0.99 beta=0.1 delta=0.25 alpha=0.1 (paper defaults, recursive variant)"},
+        "roofline": dict(dominant, share_of_step=dominant["ms"] / r["ms_per_step"]),
+        "rooflines": roofs,
+        "breakdown_ms": dict(r["export_ms"]),
+    }
+    if "ms_per_step_stationary" in r:
+        rec["ms_per_step_stationary_phi_x"] = r["ms_per_step_stationary"]
+        rec["updates_per_s_stationary_phi_x"] = 1e3 / r["ms_per_step_stationary"]
+        rec["breakdown_ms_stationary_phi_x"] = r["export_ms_stationary"]
+    if r["extra_ms"]:
+        rec["companion_exports_ms"] = r["extra_ms"]
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline_of(layer, np)
+    return rec
+
+
+def run_c5(args, torch, b, wl):
+    """ResNet-18 sweep: one whitened update of every layer per batch; aggregate = layers x steps / total time."""
+    rows, total_ms, step_fns = [], 0.0, []
+    for index in range(len(wl.RESNET18_LAYERS)):
+        layer = wl.config5_layer(index)
+        r = time_layer(layer, args.layout, args.steps, args.warmup, torch, b, wl, extras=False)
+        total_ms += r["ms_per_step"]
+        step_fns.append(r["step"])   # the closure holds every device tensor of the layer (the state struct holds its own)
+        flops = float(r["n_rows"]) * r["M"] * (r["M"] + 1)
+        plan = b.fw_cov_plan_query(b.FW_BF16, r["lay"], b.conv_desc(*layer.desc.astuple()))
+        ex = r["export_ms"]
+        rows.append({"layer": layer.name, "M": r["M"], "S": r["S"], "n_rows": r["n_rows"], "ms_per_step": round(r["ms_per_step"], 4),
+                     "cov_ms": round(ex["cov_accumulate"], 4), "fin_ms": round(ex["cov_finalize"], 4),
+                     "refresh_ms": round(ex["cond_state_refresh"], 4), "cond_ms": round(ex["cond_reduce_step"], 4),
+                     "grad_ms": round(ex["grad_transform"], 4), "shift_form": int(plan.shift),
+                     "cov_issued_frac_of_bf16_peak": round(plan.mfma_flops_issued / (ex["cov_accumulate"] * 1e-3) / PEAK["bf16"], 4),
+                     "cov_dense_equivalent_TFLOPs": round(flops / (ex["cov_accumulate"] * 1e-3) / 1e12, 1),
+                     "issued": plan.mfma_flops_issued, "dense": flops})
+        print(f"[c5] {layer.name}: {r['ms_per_step']:.3f} ms", file=sys.stderr, flush=True)
+        del layer
+    # The layers are independent: the same updates issued round-robin on four streams (default priority), so that
+    # the launch- and latency-bound small layers run under the large ones.
+    streams = [torch.cuda.Stream() for _ in range(4)]
+
+    def sweep():
+        for i, fn in enumerate(step_fns):
+            with torch.cuda.stream(streams[i % 4]):
+                fn()
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        sweep()
+    torch.cuda.synchronize()
+    tc0 = time.perf_counter()
+    for _ in range(args.steps):
+        sweep()
+    torch.cuda.synchronize()
+    conc_ms = (time.perf_counter() - tc0) * 1e3 / args.steps
+    issued = sum(x.pop("issued") for x in rows)
+    dense = sum(x.pop("dense") for x in rows)
+    cov_s = sum(x["cov_ms"] for x in rows) * 1e-3
+    return {"metric": "whitened grad-updates/s per layer", "value": len(rows) * 1e3 / conc_ms, "unit": "updates/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": conc_ms,
+            "ms_per_step_one_layer_at_a_time": total_ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "C5: ResNet-18 sweep, 21 layers at batch 256, one update of every layer per step",
+                       "streams": 4, "block_length": 1,
+                       "step": "zero sums, cov_accumulate, cov_finalize, cond_state_refresh, cond_reduce_step, grad_transform",
+                       "cond_params": "gamma=0.99 beta=0.1 delta=0.25 alpha=0.1 (paper defaults, recursive variant)"},
+            "roofline": {"bound": "mfma", "kernel": "fw_cov_accumulate over the 21 layers, one at a time",
+                         "achieved": issued / cov_s / 1e12, "peak": PEAK["bf16"] / 1e12, "unit": "TFLOP/s",
+                         "frac": issued / cov_s / PEAK["bf16"], "traffic": None,
+                         "dense_equivalent_rate_TFLOPs": dense / cov_s / 1e12},
+            "layers": rows}
 
 
 def main():
@@ -169,12 +389,6 @@ def main():
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
-    if args.config == "c5" and not args.c5_unlocked:
-        # One run of this sweep (default steps, fresh machine) ended with a GPU memory fault whose cause has not been
-        # found; three runs of the same code before it were clean.  Until the cause is known the sweep does not run.
-        print("bench.py --config c5 is switched off: a run of it ended in an unexplained GPU fault "
-              "(the figures of its earlier clean runs are recorded in the design notes)", file=sys.stderr)
-        sys.exit(3)
     import numpy as np
     import torch
 
@@ -184,153 +398,24 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
     if args.config == "c5":
-        # ResNet-18 sweep: one whitened update of every layer per batch; aggregate = layers x steps / total time
-        rows, total_ms, step_fns = [], 0.0, []
-        for index in range(len(wl.RESNET18_LAYERS)):
-            layer = wl.config5_layer(index)
-            r = time_layer(layer, args.layout, args.steps, args.warmup, torch, b, wl)
-            total_ms += r["ms_per_step"]
-            step_fns.append(r["step"])   # keeps the layer's device state alive for the concurrent pass below
-            flops = float(r["n_rows"]) * r["M"] * (r["M"] + 1)
-            rows.append({"layer": layer.name, "M": r["M"], "S": r["S"], "n_rows": r["n_rows"], "ms_per_step": round(r["ms_per_step"], 4),
-                         "cov_ms": round(r["cov_ms"], 4), "cov_frac_of_bf16_peak": round(flops / (r["cov_ms"] * 1e-3) / PEAK["bf16"], 4),
-                         "cond_ms": round(r["cond_ms"], 4), "grad_ms": round(r["grad_ms"], 4)})
-            del layer
-        # The layers are independent: the same updates issued round-robin on four streams (default priority), so that
-        # the launch- and latency-bound small layers run under the large ones.
-        streams = [torch.cuda.Stream() for _ in range(4)]
-
-        def sweep():
-            for i, fn in enumerate(step_fns):
-                with torch.cuda.stream(streams[i % 4]):
-                    fn()
-        for _ in range(args.warmup):
-            sweep()
-        torch.cuda.synchronize()
-        tc0 = time.perf_counter()
-        for _ in range(args.steps):
-            sweep()
-        torch.cuda.synchronize()
-        conc_ms = (time.perf_counter() - tc0) * 1e3 / args.steps
-        cov_flops = sum(float(x["n_rows"]) * x["M"] * (x["M"] + 1) for x in rows)
-        cov_s = sum(x["cov_ms"] for x in rows) * 1e-3
-        out = {"metric": "whitened grad-updates/s per layer", "value": len(rows) * 1e3 / conc_ms, "unit": "updates/s",
-               "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": conc_ms,
-               "ms_per_step_one_layer_at_a_time": total_ms,
-               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-               "config": {"workload": "C5: ResNet-18 sweep, 21 layers at batch 256, one update of every layer per step",
-                          "streams": 4,
-                          "block_length": 1, "cond_params": "gamma=0.99 beta=0.1 delta=0.25 (paper defaults)"},
-               "roofline": {"bound": "mfma", "kernel": "fw_cov_accumulate over the 21 layers", "achieved": cov_flops / cov_s / 1e12,
-                            "peak": PEAK["bf16"] / 1e12, "unit": "TFLOP/s", "frac": cov_flops / cov_s / PEAK["bf16"], "traffic": None},
-               "layers": rows}
-        print(json.dumps(out))
+        print(json.dumps(run_c5(args, torch, b, wl)))
         return
-
-    layer = {"c1": wl.config1, "c2": wl.config2, "c3": wl.config3, "c4": wl.config4}[args.config]()
-    d = layer.desc
-    r = time_layer(layer, args.layout, args.steps, args.warmup, torch, b, wl, evd=args.evd, extras=not args.no_extras)
-    M, S, n_rows, bf16 = r["M"], r["S"], r["n_rows"], r["bf16"]
-    ms_per_step, cov_ms, cond_ms, grad_ms, fin_ms = r["ms_per_step"], r["cov_ms"], r["cond_ms"], r["grad_ms"], r["fin_ms"]
-
-    cov_flops = float(n_rows) * M * (M + 1)                 # lower triangle incl. diagonal, 2 flops per product
-    achieved = cov_flops / (cov_ms * 1e-3)
-    # A stride-1 window is accumulated through shift correlations: tap pairs with the same offset share one product, so
-    # the matrix cores issue fewer flops than the algorithmic count (13 instead of 45 tap pairs for 3x3); report both.
-    lay_id = b.FW_LAYOUT_ROWS if layer.is_rows else {"kkc": b.FW_LAYOUT_NHWC_KKC, "nhwc": b.FW_LAYOUT_NHWC, "nchw": b.FW_LAYOUT_NCHW}[args.layout]
-    plan = b.fw_cov_plan_query(b.FW_BF16 if bf16 else b.FW_F32, lay_id, b.conv_desc(*d.astuple()))
-    shifted, issued = bool(plan.shift), plan.mfma_flops_issued
-    peak = PEAK[layer.dtype]
-    tr = MEASURED_TRAFFIC.get(args.config) if (layer.is_rows or args.layout == "kkc") else None
-    traffic = tr["read"] + tr["written"] if tr else None
-    alg_bytes = r["act_bytes"] + 4.0 * M * M   # activation once + A once
-    cond_words = 16 if r["gamma"] < 1.0 else 10
-    cond_bytes = cond_words * M * M * 4.0
-    out = {
-        "metric": "whitened grad-updates/s per layer",
-        "value": 1e3 / ms_per_step,
-        "unit": "updates/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if not bf16 else "bf16",
-        "data": "synthetic",
-        "config": {"workload": f"{layer.name}: M={M} S={S} N_rows={n_rows} layout={args.layout if not layer.is_rows else 'rows'}",
-                   "batch": d.B, "block_length": 1, "cond_params": "gamma=0.99 beta=0.1 delta=0.25 (paper defaults)"},
-        "roofline": {"bound": "mfma",
-                     "kernel": (("pack_images + cov_bf16_tile + shift_tile_assemble + column_sums" if shifted else
-                                 "pack_images + cov_bf16_tile (+ tile_reduce) + column_sums") if bf16 else
-                                ("shift_partial_f32 + shift_region_reduce + shift_assemble" if shifted else
-                                 "cov_partial_f32v4 + cov_reduce")) + " = one fw_cov_accumulate",
-                     "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": traffic, "traffic_unit": "bytes per fw_cov_accumulate call (HBM read + written, counters)",
-                     "traffic_read_written": tr, "algorithmic_bytes": alg_bytes,
-                     "note": "achieved = algorithmic flops N_rows*M*(M+1) per call / time of the call",
-                     "mfma_flops_issued": issued, "issued_frac_of_peak": issued / (cov_ms * 1e-3) / peak,
-                     "plan": {"shift": plan.shift, "regions": plan.regions, "differences": plan.differences,
-                              "workgroups": plan.workgroups, "ranges": plan.ranges}},
-        "breakdown_ms": {"cov_accumulate": cov_ms, "cov_finalize": fin_ms, "cond_reduce_step": cond_ms, "grad_transform": grad_ms},
-        "cond_step_GBps": cond_bytes / (cond_ms * 1e-3) / 1e9,
-        "grad_transform_TFLOPs": 2.0 * S * M * M / (grad_ms * 1e-3) / 1e12,
-    }
-    # once per block when the data (hence Phi_x) changes between blocks; the timed step feeds the same batch again, so
-    # Phi_x is stationary there and the call is not part of the step
-    if r["refresh_ms"] is not None:
-        out["breakdown_ms"]["cond_state_refresh_per_block"] = r["refresh_ms"]
-        out["breakdown_ms"]["sgd_update_fused"] = r["sgd_ms"]
-        out["breakdown_ms"]["diagnostics_whiteness"] = r["diag_ms"]
-        out["cond_state_refresh_TFLOPs"] = 4.0 * M * M * M / (r["refresh_ms"] * 1e-3) / 1e12
-    if "per_channel_cov_ms" in r:
-        out["breakdown_ms"]["per_channel_variant_cov_accumulate"] = r["per_channel_cov_ms"]
-        out["breakdown_ms"]["per_channel_variant_grad_transform_taps"] = r["per_channel_grad_ms"]
-    if "evd_ms" in r:
-        out["breakdown_ms"]["whiten_evd"] = r["evd_ms"]
-    alpha = 0.1
-    dev = "cuda:0"
+    if args.config == "all":
+        recs = {}
+        for key in ("c2", "c3", "c4"):
+            recs[key] = config_record(key, args, torch, b, wl, np)
+            print(f"[bench] {key}: {recs[key]['ms_per_step']:.3f} ms/step", file=sys.stderr, flush=True)
+        out = recs.pop("c4")
+        out["configs"] = recs
+    else:
+        out = config_record(args.config, args, torch, b, wl, np)
 
     if args.copy_calibration:
-        src = torch.ones(64 * 1024 * 1024, device=dev)      # 256 MiB read + 256 MiB written per copy
+        src = torch.ones(64 * 1024 * 1024, device="cuda:0")      # 256 MiB read + 256 MiB written per copy
         dst = torch.empty_like(src)
         for _ in range(5):
             dst.copy_(src)
         torch.cuda.synchronize()
-
-    if not args.no_cpu_baseline:
-        from oracle import fw_oracle as ora
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
-        except Exception:
-            cores = os.cpu_count() or 1
-        # bounded sample: whole updates of the same workload by the oracle, repeated until about 10 s have passed
-        # (at least one, at most 64 updates); images beyond a memory bound are dropped and the moment terms scaled,
-        # which are linear in the rows
-        Bs = d.B if layer.is_rows else max(1, min(d.B, int(4e9 // max(1, 8 * d.P * M))))
-        scale = d.B / Bs
-        reps, spent, secs = 0, 0.0, {"unfold": 0.0, "moments": 0.0, "cond_step": 0.0, "grad_transform": 0.0}
-        while reps < 64 and spent < 10.0:
-            tc0 = time.perf_counter()
-            if layer.is_rows:
-                Xr = np.asarray(layer.act[:Bs], dtype=np.float64)
-            else:
-                Xr = ora.patch_rows(layer.act[:Bs], Bs, d.Cin, d.H, d.W, d.kh, d.kw, d.stride, d.pad)
-            tc1 = time.perf_counter()
-            mu_o, Phi_o, phi_o, lb_o = ora.block_moments(Xr, alpha, True)
-            del Xr
-            tc2 = time.perf_counter()
-            st_o, _ = ora.cond_reduce_step(ora.CondState.initial(Phi_o), lb_o, ora.CondParams())
-            tc3 = time.perf_counter()
-            ora.grad_transform(layer.G, st_o.Qs)
-            tc4 = time.perf_counter()
-            for k, v in zip(secs, (tc1 - tc0, tc2 - tc1, tc3 - tc2, tc4 - tc3)):
-                secs[k] += v
-            reps += 1
-            spent += tc4 - tc0
-        secs = {k: v / reps for k, v in secs.items()}
-        t_update = (secs["unfold"] + secs["moments"]) * scale + secs["cond_step"] + secs["grad_transform"]
-        out["cpu_baseline"] = {"value": 1.0 / t_update, "unit": "updates/s", "cores": int(cores), "kind": "oracle",
-                               "sample": f"{reps} update(s) on {Bs} of {d.B} images (moment terms scaled by {scale:g}), "
-                                         f"float64 numpy, {spent:.1f} s of CPU work",
-                               "seconds_per_update": secs}
     print(json.dumps(out))
 
 

@@ -13,16 +13,14 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert r.stdout.strip() == ""
 
 
-def test_default_workload_is_config2():
+def test_default_run_covers_c2_c3_c4_and_the_sweep_is_selectable():
     sys.path.insert(0, ROOT)
     import bench
-    old = sys.argv
-    try:
-        sys.argv = ["bench.py"]
-        a = bench.parse()
-    finally:
-        sys.argv = old
-    assert a.gpus == 1 and a.config == "c2" and a.steps > 0 and a.warmup >= 0
+    a = bench.parse([])
+    assert a.gpus == 1 and a.config == "all" and a.steps > 0 and a.warmup >= 0
+    assert bench.parse(["--config", "c5"]).config == "c5"
+    # the step the bench times names every export of the path, the refresh included
+    assert bench.EXPORTS == ("cov_accumulate", "cov_finalize", "cond_state_refresh", "cond_reduce_step", "grad_transform")
 
 
 def test_cond_state_keeps_its_tensors_alive():
