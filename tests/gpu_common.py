@@ -101,3 +101,73 @@ class CondRunner:
 
     def host(self, name):
         return getattr(self, name).cpu().numpy().astype(np.float64)
+
+
+BAND = 2e-5   # relative guard band of a decision taken in float32 on the GPU and in float64 by the oracle
+
+
+def oracle_params(gp):
+    return ora.CondParams(gamma=gp.gamma, delta=gp.delta, eps=gp.eps, c_rel=gp.c_rel, c_abs=gp.c_abs, beta=gp.beta,
+                          n_power_iters=gp.n_power_iters, guard=bool(gp.guard))
+
+
+def forced_step(run: CondRunner, P64, lbar32, gp, op, tol=1e-4, label=""):
+    """One teacher-forced step: the oracle starts from the GPU's own state (up-cast), both take one step.
+
+    Returns (compared, info, oracle_info, new_oracle_state).  The integer decisions (arg-max m', membership in the
+    coherence set) must agree unless the deciding margin lies inside the guard band: then `compared` is False (marginal
+    members cannot be told apart from outside) and the caller resynchronises from the GPU state at the next step.
+    Otherwise T, Q, Qs, Phi_y (and Psi) are compared element by element and lambda_e, g_e as scalars."""
+    st = ora.CondState(P64, run.host("T"), run.host("Q"), run.host("Qs"))
+    info = run.step(gp)
+    new, oi = ora.cond_reduce_step(st, lbar32, op)
+    forced = False
+    if info.m_prime != oi.m_prime:
+        assert oi.xi[info.m_prime] >= oi.xi[oi.m_prime] * (1 - BAND), f"{label}: arg-max differs beyond rounding"
+        forced = True
+    if forced or info.set_size != oi.set_size:
+        xi, c = oi.xi, ora.high_power_subspace(oi.Phi_y, op.c_rel, op.c_abs, 0, forced_m_prime=info.m_prime)[4]
+        thr = np.maximum(op.c_rel * xi[info.m_prime] * xi, op.c_abs)
+        sure_in = np.abs(c) >= thr * (1 + BAND)
+        sure_out = np.abs(c) < thr * (1 - BAND)
+        n_marg = int((~sure_in & ~sure_out).sum())
+        assert sure_in.sum() <= info.set_size <= sure_in.sum() + n_marg, f"{label}: set size differs beyond rounding"
+        return False, info, oi, new
+    assert bool(info.applied) == oi.applied, label
+    if oi.applied:
+        assert abs(info.lambda_e - oi.lambda_e) <= 2e-4 * abs(oi.lambda_e), label
+        assert abs(info.g_e - oi.g_e) <= 2e-4 * abs(oi.g_e), label
+    errs = [relF(run.host("T"), new.T), relF(run.host("Q"), new.Q), relF(run.host("Qs"), new.Qs),
+            relF(run.host("Phi_y"), ora.transformed_covariance(new.T, P64))]
+    if run.Psi is not None:
+        errs.append(relF(run.host("Psi"), new.T @ P64))
+    assert max(errs) < tol, f"{label}: {errs}"
+    # carried column norms belong to the new Phi_y
+    assert relF(run.host("xi2"), np.sum(run.host("Phi_y") ** 2, axis=0)) < 1e-5, label
+    return True, info, oi, new
+
+
+def oracle_first_block_moments_chunked(layer: wl.Layer, layout: int, images_per_chunk: int):
+    """First-block moments of a layer too large to unfold at once: mean over image chunks, then the centred products
+    sum (x - mu)(x - mu)^T over the same chunks (the centred form of eqs. (vmuxnz), (vPhixnz), raw squares for eq.
+    (phixmi)), all through the oracle's own unfolding and sums."""
+    d = layer.desc
+    order = "kkc" if layout == b.FW_LAYOUT_NHWC_KKC else "ckk"
+    if layer.is_rows:
+        return ora.block_moments(np.asarray(layer.act, dtype=np.float64), 0.0, True)
+    M = d.M
+    geo = (d.Cin, d.H, d.W, d.kh, d.kw, d.stride, d.pad)
+    s = np.zeros(M); sq = np.zeros(M); n = 0
+    for lo in range(0, d.B, images_per_chunk):
+        hi = min(d.B, lo + images_per_chunk)
+        X = ora.patch_rows(layer.act[lo:hi], hi - lo, *geo, order=order)
+        s += X.sum(axis=0); sq += (X * X).sum(axis=0); n += X.shape[0]
+    mu = s / n
+    C = np.zeros((M, M))
+    for lo in range(0, d.B, images_per_chunk):
+        hi = min(d.B, lo + images_per_chunk)
+        X = ora.patch_rows(layer.act[lo:hi], hi - lo, *geo, order=order)
+        X -= mu[None, :]
+        C += ora.raw_sums(X)[0]
+    phi = sq / n
+    return mu, C / n, phi, float(phi.mean())
