@@ -454,3 +454,49 @@ def whiteness(Phi_y: np.ndarray) -> float:
     P = np.asarray(Phi_y, F64)
     d = np.diag(P)
     return float(P.shape[0] / np.sum(P * P / np.outer(d, d)))
+
+
+# =============================================================================
+# Condition-number probe -- Sec. 4, opening paragraphs: the quantity the recursion is built to reduce is the condition
+# number of Phi_y (convergence time is proportional to it; 1 means white).  A monitoring companion to kappa and rho of
+# Sec. 6.  The paper gives no procedure for it; the estimate taken here is the classical one: the extreme Ritz values
+# of Phi_y on a Krylov subspace of small dimension k.
+# =============================================================================
+def krylov_ritz_values(A: np.ndarray, b0: np.ndarray, k: int, breakdown: float = 1e-7):
+    """Ritz values of the symmetric matrix A on span{b0, A b0, ..., A^(k-1) b0}, by the definition: an orthonormal basis
+    Q of that space (Gram-Schmidt on the successive images, each orthogonalised twice against all earlier vectors),
+    H = Q^T A Q, eigenvalues of H in decreasing order.
+
+    The basis stops early when the next image lies in the span already built (its remainder is below ``breakdown``
+    times its own length): the space is then invariant and its Ritz values are eigenvalues of A.  Returns (ritz, steps).
+    Every Ritz value lies between the extreme eigenvalues of A, so max/min of them never overestimates the condition
+    number.
+    """
+    A = np.asarray(A, F64)
+    q = np.asarray(b0, F64).copy()
+    q /= np.linalg.norm(q)
+    Q = [q]
+    for _ in range(1, k):
+        w = A @ Q[-1]
+        n0 = np.linalg.norm(w)
+        for _rep in range(2):
+            for qi in Q:
+                w = w - (qi @ w) * qi
+        nw = np.linalg.norm(w)
+        if not nw > breakdown * n0:
+            break
+        Q.append(w / nw)
+    Qm = np.stack(Q, axis=1)
+    H = Qm.T @ A @ Qm
+    H = 0.5 * (H + H.T)
+    return np.linalg.eigvalsh(H)[::-1], Qm.shape[1]
+
+
+def condition_probe(Phi_y: np.ndarray, b0: np.ndarray, k: int):
+    """(lambda_max estimate, lambda_min estimate, their ratio, Krylov dimension reached) of Phi_y from ``k`` Krylov steps
+    started at b0.  A non-positive lower estimate gives an infinite ratio (parity unpinned: the paper defines no probe;
+    the arithmetic is pinned against LAPACK, the Rayleigh quotient, the textbook three-term recurrence and exactness on an
+    invariant subspace)."""
+    ritz, steps = krylov_ritz_values(Phi_y, b0, k)
+    hi, lo = float(ritz[0]), float(ritz[-1])
+    return hi, lo, (hi / lo if lo > 0.0 else float("inf")), steps

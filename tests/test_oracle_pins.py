@@ -457,3 +457,75 @@ def test_workload_recipes_shapes_and_bf16():
     assert len(wl.RESNET18_LAYERS) == 21
     L5 = wl.config5_layer(6, B=2, scale=0.25)
     assert L5.desc.kh == 1 and L5.desc.stride == 2 and L5.desc.M == 64
+
+
+# ----------------------------------------------------------------------------- condition-number probe (Sec. 4, purpose of the recursion)
+def _three_term_lanczos(A, b0, k):
+    """Textbook Lanczos recurrence, written independently of the oracle's projection form: alpha_j = q_j^T A q_j,
+    r = A q_j - alpha_j q_j - beta_(j-1) q_(j-1), beta_j = |r|; Ritz values = eigenvalues of tridiag(alpha, beta)."""
+    q_prev = np.zeros_like(b0)
+    q = b0 / np.linalg.norm(b0)
+    alpha, beta = [], []
+    b_prev = 0.0
+    for j in range(k):
+        w = A @ q
+        a = float(q @ w)
+        alpha.append(a)
+        r = w - a * q - b_prev * q_prev
+        b_prev = float(np.linalg.norm(r))
+        if j + 1 < k:
+            beta.append(b_prev)
+            q_prev, q = q, r / b_prev
+    Tk = np.diag(alpha) + np.diag(beta, 1) + np.diag(beta, -1)
+    return np.linalg.eigvalsh(Tk)[::-1]
+
+
+def test_probe_single_step_is_the_rayleigh_quotient():
+    A = np.array([[4.0, 1.0], [1.0, 3.0]])
+    b0 = np.array([1.0, 2.0])
+    ritz, steps = ora.krylov_ritz_values(A, b0, 1)
+    assert steps == 1 and abs(ritz[0] - (b0 @ A @ b0) / (b0 @ b0)) < 1e-14      # (4 + 4 + 12) / 5 = 4
+    assert abs(ritz[0] - 4.0) < 1e-14
+
+
+def test_probe_full_dimension_gives_the_spectrum():
+    M = 12
+    lam = np.linspace(5.0, 0.5, M)
+    A = wl.spd_matrix(3, M, lam)
+    b0 = np.random.default_rng(0).standard_normal(M)
+    ritz, steps = ora.krylov_ritz_values(A, b0, M)
+    assert steps == M and np.allclose(ritz, lam, rtol=0, atol=1e-9)
+    hi, lo, cond, _ = ora.condition_probe(A, b0, M)
+    assert abs(cond - 10.0) < 1e-7
+
+
+def test_probe_stops_on_an_invariant_subspace_and_is_exact_there():
+    A = np.diag([7.0, 3.0, 2.0, 1.0])
+    b0 = np.array([1.0, 0.0, 1.0, 0.0])        # lives in the span of two eigenvectors
+    ritz, steps = ora.krylov_ritz_values(A, b0, 4)
+    assert steps == 2 and np.allclose(ritz, [7.0, 2.0], atol=1e-12)
+
+
+def test_probe_ritz_values_stay_inside_the_spectrum_and_improve_with_k():
+    M = 60
+    A = wl.spd_matrix(8, M, np.logspace(1.0, -2.0, M))
+    w = np.linalg.eigvalsh(A)
+    b0 = np.random.default_rng(1).standard_normal(M)
+    last_hi, last_lo = -np.inf, np.inf
+    for k in (1, 2, 4, 8, 16, 32):
+        hi, lo, cond, steps = ora.condition_probe(A, b0, k)
+        assert w[0] - 1e-12 <= lo <= hi <= w[-1] + 1e-12
+        assert hi >= last_hi - 1e-12 and lo <= last_lo + 1e-12          # nested Krylov spaces: the extremes can only widen
+        assert cond <= w[-1] / w[0] * (1 + 1e-9)                        # never an overestimate
+        last_hi, last_lo = hi, lo
+    assert abs(last_hi / w[-1] - 1) < 1e-6                              # the top converges fast
+
+
+def test_probe_matches_the_three_term_recurrence():
+    M = 40
+    A = wl.spd_matrix(9, M, np.logspace(0.5, -1.5, M))
+    b0 = np.random.default_rng(2).standard_normal(M)
+    for k in (2, 5, 9):
+        ritz, steps = ora.krylov_ritz_values(A, b0, k)
+        assert steps == k
+        assert np.allclose(ritz, _three_term_lanczos(A, b0, k), rtol=1e-9, atol=1e-12)
