@@ -168,6 +168,8 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
         xm = out["extra_ms"]
         xm["sgd_update_fused"] = time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt))
         xm["diagnostics_whiteness"] = time_call(lambda: b.fw_diagnostics(Py, None, M, diag_out, ws_diag))
+        ws_probe = torch.empty(b.fw_workspace_bytes(b.FW_OP_COND_PROBE, M, 16), dtype=torch.uint8, device=dev)
+        xm["cond_probe_16_steps"] = time_call(lambda: b.fw_cond_probe(Py, M, None, 16, diag_out, ws_probe), reps=5)
         if not layer.is_rows and d.kh * d.kw > 1:
             # per-channel variant of the same layer (whitening in front of the convolution, M = Cin): moments of the 1x1
             # "window" over the input pixels, and every tap's S x Cin gradient times the one Cin x Cin Q

@@ -63,7 +63,7 @@ typedef struct { int B, Cin, H, W, kh, kw, stride, pad; } fw_conv_desc;
 /* Operations for fw_workspace_bytes. */
 typedef enum {
     FW_OP_COV_ACCUMULATE = 0, FW_OP_GRAD_TRANSFORM = 1, FW_OP_COND_REDUCE_STEP = 2, FW_OP_WHITEN_EVD = 3, FW_OP_COND_STATE_REFRESH = 4,
-    FW_OP_GRAD_TRANSFORM_TAPS = 5, FW_OP_SGD_UPDATE = 6, FW_OP_DIAGNOSTICS = 7
+    FW_OP_GRAD_TRANSFORM_TAPS = 5, FW_OP_SGD_UPDATE = 6, FW_OP_DIAGNOSTICS = 7, FW_OP_COND_PROBE = 8
 } fw_op;
 
 /* ------------------------------------------------------------------------------------------------------------
@@ -264,6 +264,22 @@ fw_status fw_whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float
  */
 fw_status fw_diagnostics(const float* Phi_y, const float* lambda, int M, float* out, void* ws, size_t ws_bytes, void* stream);
 
+/* Condition-number probe.  Sec. 4 builds the recursion on one figure: the condition number of Phi_y (convergence time is
+ * proportional to it, 1 means white).  This call estimates it without an eigen-decomposition: k steps of the Lanczos
+ * iteration on Phi_y from the start vector b0 (fully re-orthogonalised, vectors and sums in float64, Phi_y read once per
+ * step: k M^2 words of traffic), then the extreme eigenvalues of the k x k tridiagonal projection.  Those Ritz values lie
+ * inside the spectrum, so the ratio never overestimates the condition number; the top converges within a few steps, the
+ * bottom more slowly.
+ *   Phi_y   in   [M, M] float32, symmetric
+ *   b0      in   [M] float32 start vector, or NULL for the all-ones vector
+ *   k       Krylov dimension, 1 .. FW_COND_PROBE_MAX_K; the iteration stops early when the space becomes invariant
+ *   out     out  device float32[4]: largest Ritz value, smallest Ritz value, their ratio (inf when the smallest is <= 0),
+ *                dimension reached
+ *   ws      scratch, fw_workspace_bytes(FW_OP_COND_PROBE, M, k, NULL, FW_F32) bytes (the S argument carries k)
+ * No host synchronisation. */
+#define FW_COND_PROBE_MAX_K 32
+fw_status fw_cond_probe(const float* Phi_y, int M, const float* b0, int k, float* out, void* ws, size_t ws_bytes, void* stream);
+
 /* How fw_cov_accumulate would run a layer (host arithmetic only, no GPU call): for introspection and tests.
  *   shift              1: stride-1 window accumulated through shift correlations (tap pairs with the same offset share one
  *                      product), 0: direct products of the unfolded patch rows
@@ -291,7 +307,7 @@ typedef enum { FW_COV_FORM_AUTO = 0, FW_COV_FORM_SHIFT = 1, FW_COV_FORM_DIRECT =
 fw_status fw_cov_set_form(fw_cov_form form);
 
 /* Scratch bytes an entry point needs for the given sizes (0 if none).  `d` is needed for FW_OP_COV_ACCUMULATE only;
- * for the per-tap operations S is the number of gradient rows, S * taps. */
+ * for the per-tap operations S is the number of gradient rows, S * taps; for FW_OP_COND_PROBE S is the Krylov dimension k. */
 size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtype dt);
 
 const char* fw_status_string(fw_status st);

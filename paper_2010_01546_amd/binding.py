@@ -22,12 +22,12 @@ FW_OK, FW_ERR_INVALID_ARG, FW_ERR_UNSUPPORTED, FW_ERR_ALIGNMENT, FW_ERR_WORKSPAC
 FW_F32, FW_BF16 = 0, 1
 FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
 (FW_OP_COV_ACCUMULATE, FW_OP_GRAD_TRANSFORM, FW_OP_COND_REDUCE_STEP, FW_OP_WHITEN_EVD, FW_OP_COND_STATE_REFRESH,
- FW_OP_GRAD_TRANSFORM_TAPS, FW_OP_SGD_UPDATE, FW_OP_DIAGNOSTICS) = range(8)
+ FW_OP_GRAD_TRANSFORM_TAPS, FW_OP_SGD_UPDATE, FW_OP_DIAGNOSTICS, FW_OP_COND_PROBE) = range(9)
 
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",
            "fw_whiten_evd", "fw_cond_state_refresh", "fw_grad_transform_taps", "fw_sgd_update", "fw_bias_compensate",
-           "fw_diagnostics", "fw_cov_plan_query", "fw_cov_set_form", "fw_cond_reduce_step_static", "fw_workspace_bytes", "fw_status_string", "fw_version"]
-N_STATUS_EXPORTS = 14   # the leading entries of EXPORTS return fw_status
+           "fw_diagnostics", "fw_cov_plan_query", "fw_cov_set_form", "fw_cond_reduce_step_static", "fw_cond_probe", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+N_STATUS_EXPORTS = 15   # the leading entries of EXPORTS return fw_status
 
 
 class fw_conv_desc(C.Structure):
@@ -76,6 +76,7 @@ lib.fw_grad_transform_taps.argtypes = [_P, C.c_int, C.c_int, C.c_int, C.c_int, _
 lib.fw_sgd_update.argtypes = [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.POINTER(fw_sgd_params), _P, _P, _P, C.c_size_t, _P]
 lib.fw_bias_compensate.argtypes = [_P, _P, C.c_int, C.c_int, C.c_int, _P, _P, C.c_float, _P]
 lib.fw_diagnostics.argtypes = [_P, _P, C.c_int, _P, _P, C.c_size_t, _P]
+lib.fw_cond_probe.argtypes = [_P, C.c_int, _P, C.c_int, _P, _P, C.c_size_t, _P]
 lib.fw_cov_plan_query.argtypes = [C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.POINTER(fw_cov_plan)]
 lib.fw_cov_set_form.argtypes = [C.c_int]
 lib.fw_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.c_int]
@@ -176,6 +177,14 @@ def fw_bias_compensate(b, W, S, M, taps, mu_old, mu_new, scale=1.0, stream=None)
 def fw_diagnostics(Phi_y, lam, M, out, ws=None, stream=None):
     wp, n = _ws(ws)
     return _check(lib.fw_diagnostics(_ptr(Phi_y), _ptr(lam), M, _ptr(out), wp, n, _stream(stream)), "fw_diagnostics")
+
+
+FW_COND_PROBE_MAX_K = 32
+
+
+def fw_cond_probe(Phi_y, M, b0, k, out, ws, stream=None):
+    wp, n = _ws(ws)
+    return _check(lib.fw_cond_probe(_ptr(Phi_y), M, _ptr(b0), k, _ptr(out), wp, n, _stream(stream)), "fw_cond_probe")
 
 
 def fw_cov_plan_query(dt, lay, d) -> fw_cov_plan:

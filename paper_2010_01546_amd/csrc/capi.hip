@@ -137,6 +137,14 @@ fw_status fw_diagnostics(const float* Phi_y, const float* lambda, int M, float* 
     return diagnostics(Phi_y, lambda, M, out, ws, reinterpret_cast<hipStream_t>(stream));
 }
 
+fw_status fw_cond_probe(const float* Phi_y, int M, const float* b0, int k, float* out, void* ws, size_t ws_bytes, void* stream) {
+    if (!Phi_y || !out || M <= 0 || k < 1 || k > FW_COND_PROBE_MAX_K) return FW_ERR_INVALID_ARG;
+    if (M > 16384) return FW_ERR_UNSUPPORTED;
+    if (!aligned16(Phi_y) || (ws && !aligned16(ws))) return FW_ERR_ALIGNMENT;
+    if (!ws || ws_bytes < cond_probe_workspace_bytes(M, k)) return FW_ERR_WORKSPACE;
+    return cond_probe(Phi_y, M, b0, k, out, ws, reinterpret_cast<hipStream_t>(stream));
+}
+
 fw_status fw_cond_state_init(const fw_cond_state* st, void* stream) {
     if (!st || st->M <= 0 || !st->Phi_x || !st->T || !st->Q || !st->Qs || !st->Phi_y || !st->xi2) return FW_ERR_INVALID_ARG;
     if (!aligned16(st->Phi_x) || !aligned16(st->T) || !aligned16(st->Q) || !aligned16(st->Qs) || !aligned16(st->Phi_y) ||
@@ -237,6 +245,7 @@ size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtyp
         case FW_OP_GRAD_TRANSFORM_TAPS:
         case FW_OP_SGD_UPDATE: return (M > 0 && M <= 16384 && S > 0) ? grad_wide_bytes(S, M) : 0;
         case FW_OP_DIAGNOSTICS: return M > 0 && M <= 16384 ? diagnostics_workspace_bytes(M) : 0;
+        case FW_OP_COND_PROBE: return M > 0 && M <= 16384 ? cond_probe_workspace_bytes(M, S > 0 ? S : FW_COND_PROBE_MAX_K) : 0;
     }
     return 0;
 }

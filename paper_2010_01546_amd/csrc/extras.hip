@@ -103,7 +103,182 @@ __global__ __launch_bounds__(1024) void diagnostics_final_kernel(const double* _
     }
 }
 
+// ---- condition-number probe: extreme Ritz values of Phi_y on a Krylov space of dimension <= 32 (Sec. 4: the condition
+// number of Phi_y is what the recursion reduces).  Lanczos with full re-orthogonalisation, vectors and sums in float64
+// (the matrix is read as float32, once per step: that read is the cost), no host synchronisation: a breakdown (the next
+// image already lies in the space built so far) is recorded in `st` on the device and the remaining launches return at once.
+struct ProbeState { int steps, done; double prev_beta; };
+constexpr int PROBE_MAX_K = 32;
+
+// q_0 = b0 / |b0| (b0 = all ones when absent)
+__global__ __launch_bounds__(1024) void probe_init_kernel(const float* __restrict__ b0, int M, double* __restrict__ q0, ProbeState* __restrict__ st) {
+    __shared__ double red[16];
+    double ss = 0.0;
+    for (int m = threadIdx.x; m < M; m += 1024) { const double x = b0 ? (double)b0[m] : 1.0; ss += x * x; }
+    const double nrm = sqrt(block_sum_1024(ss, red));
+    const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+    for (int m = threadIdx.x; m < M; m += 1024) q0[m] = (b0 ? (double)b0[m] : 1.0) * inv;
+    if (threadIdx.x == 0) { st->steps = 0; st->done = nrm > 0.0 ? 0 : 1; st->prev_beta = 0.0; }
+}
+
+// w = A q, one wavefront per row, float64 accumulation
+__global__ __launch_bounds__(256) void probe_matvec_kernel(const float* __restrict__ A, const double* __restrict__ q, int M,
+                                                           double* __restrict__ w, const ProbeState* __restrict__ st) {
+    if (st->done) return;
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;
+    const float* row = A + (size_t)r * M;
+    double acc = 0.0;
+    if ((M & 3) == 0) {
+        const float4* r4 = reinterpret_cast<const float4*>(row);
+        const int n4 = M >> 2;
+        int c = lane;
+        for (; c + 192 < n4; c += 256) {
+            float4 a[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[j] = r4[c + 64 * j];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double* qq = q + 4 * (c + 64 * j);
+                acc += (double)a[j].x * qq[0] + (double)a[j].y * qq[1] + (double)a[j].z * qq[2] + (double)a[j].w * qq[3];
+            }
+        }
+        for (; c < n4; c += 64) {
+            const float4 a = r4[c];
+            const double* qq = q + 4 * c;
+            acc += (double)a.x * qq[0] + (double)a.y * qq[1] + (double)a.z * qq[2] + (double)a.w * qq[3];
+        }
+    } else {
+        for (int c = lane; c < M; c += 64) acc += (double)row[c] * q[c];
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) w[r] = acc;
+}
+
+// Step j of the recurrence, one workgroup: alpha_j = q_j . w, w made orthogonal to q_0 .. q_j (twice, all coefficients of
+// a pass taken from the same w), beta_j = |w|, q_(j+1) = w / beta_j -- or the breakdown flag when nothing is left of w.
+__global__ __launch_bounds__(1024) void probe_orth_kernel(int j, int M, size_t ld, double* __restrict__ Qb, double* __restrict__ w,
+                                                          double* __restrict__ alpha, double* __restrict__ beta, double breakdown,
+                                                          ProbeState* __restrict__ st) {
+    __shared__ double red[16];
+    __shared__ double coef[PROBE_MAX_K + 1];
+    if (st->done) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double s0 = 0.0;
+    for (int m = threadIdx.x; m < M; m += 1024) s0 += w[m] * w[m];
+    const double n0 = sqrt(block_sum_1024(s0, red));
+    for (int pass = 0; pass < 2; ++pass) {
+        // wavefront v takes the basis vectors v, v + 16, ...
+        for (int i = wave; i <= j; i += 16) {
+            const double* qi = Qb + (size_t)i * ld;
+            double d = 0.0;
+            for (int m = lane; m < M; m += 64) d += qi[m] * w[m];
+            d = wave_sum(d);
+            if (lane == 0) coef[i] = d;
+        }
+        __syncthreads();
+        if (pass == 0 && threadIdx.x == 0) alpha[j] = coef[j];
+        for (int m = threadIdx.x; m < M; m += 1024) {
+            double x = w[m];
+            for (int i = 0; i <= j; ++i) x -= coef[i] * Qb[(size_t)i * ld + m];
+            w[m] = x;
+        }
+        __syncthreads();
+    }
+    double s1 = 0.0;
+    for (int m = threadIdx.x; m < M; m += 1024) s1 += w[m] * w[m];
+    const double nw = sqrt(block_sum_1024(s1, red));
+    const bool stop = !(nw > breakdown * n0);
+    if (!stop) {
+        const double inv = 1.0 / nw;
+        double* qn = Qb + (size_t)(j + 1) * ld;
+        for (int m = threadIdx.x; m < M; m += 1024) qn[m] = w[m] * inv;
+    }
+    if (threadIdx.x == 0) {
+        beta[j] = nw;
+        st->steps = j + 1;
+        if (stop) st->done = 1;
+    }
+}
+
+// extreme eigenvalues of the symmetric tridiagonal matrix (alpha_0..alpha_(n-1); beta_0..beta_(n-2)) by bisection on the
+// number of eigenvalues below x (sign changes of the pivots of T - x I)
+__device__ int tridiag_count_below(const double* a, const double* b, int n, double x) {
+    int cnt = 0;
+    double d = 1.0;
+    for (int i = 0; i < n; ++i) {
+        const double off = i > 0 ? b[i - 1] * b[i - 1] : 0.0;
+        d = a[i] - x - (i > 0 ? off / d : 0.0);
+        if (d == 0.0) d = -1e-300;
+        if (d < 0.0) ++cnt;
+    }
+    return cnt;
+}
+
+__global__ void probe_final_kernel(const double* __restrict__ alpha, const double* __restrict__ beta, const ProbeState* __restrict__ st,
+                                   float* __restrict__ out) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int n = st->steps;
+    if (n <= 0) { out[0] = 0.f; out[1] = 0.f; out[2] = 0.f; out[3] = 0.f; return; }
+    double lo = alpha[0], hi = alpha[0];
+    for (int i = 0; i < n; ++i) {
+        const double r = (i > 0 ? fabs(beta[i - 1]) : 0.0) + (i + 1 < n ? fabs(beta[i]) : 0.0);
+        lo = fmin(lo, alpha[i] - r);
+        hi = fmax(hi, alpha[i] + r);
+    }
+    // largest: the smallest x with count_below(x) = n;  smallest: the smallest x with count_below(x) >= 1
+    double a0 = lo, b0 = hi, a1 = lo, b1 = hi;
+    for (int it = 0; it < 64; ++it) {   // the bracket shrinks below float64 resolution
+        const double m0 = 0.5 * (a0 + b0), m1 = 0.5 * (a1 + b1);
+        if (tridiag_count_below(alpha, beta, n, m0) >= n) b0 = m0; else a0 = m0;
+        if (tridiag_count_below(alpha, beta, n, m1) >= 1) b1 = m1; else a1 = m1;
+    }
+    const double lmax = 0.5 * (a0 + b0), lmin = 0.5 * (a1 + b1);
+    out[0] = (float)lmax;
+    out[1] = (float)lmin;
+    out[2] = lmin > 0.0 ? (float)(lmax / lmin) : __builtin_inff();
+    out[3] = (float)n;
+}
+
 }  // namespace
+
+namespace {
+struct ProbeWs { size_t Q, w, alpha, beta, st, total, ld; };
+ProbeWs probe_layout(int M, int k) {
+    ProbeWs L;
+    L.ld = align_up((size_t)M, 32);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
+    L.Q = take((size_t)(k + 1) * L.ld * sizeof(double));
+    L.w = take(L.ld * sizeof(double));
+    L.alpha = take(PROBE_MAX_K * sizeof(double));
+    L.beta = take(PROBE_MAX_K * sizeof(double));
+    L.st = take(sizeof(ProbeState));
+    L.total = o;
+    return L;
+}
+}  // namespace
+
+size_t cond_probe_workspace_bytes(int M, int k) { return probe_layout(M, k < 1 ? 1 : (k > PROBE_MAX_K ? PROBE_MAX_K : k)).total; }
+
+fw_status cond_probe(const float* Phi_y, int M, const float* b0, int k, float* out, void* ws, hipStream_t st) {
+    const ProbeWs L = probe_layout(M, k);
+    char* base = reinterpret_cast<char*>(ws);
+    double* Qb = reinterpret_cast<double*>(base + L.Q);
+    double* w = reinterpret_cast<double*>(base + L.w);
+    double* alpha = reinterpret_cast<double*>(base + L.alpha);
+    double* beta = reinterpret_cast<double*>(base + L.beta);
+    ProbeState* ps = reinterpret_cast<ProbeState*>(base + L.st);
+    hipLaunchKernelGGL(probe_init_kernel, dim3(1), dim3(1024), 0, st, b0, M, Qb, ps);
+    for (int j = 0; j < k; ++j) {
+        hipLaunchKernelGGL(probe_matvec_kernel, dim3((M + 3) / 4), dim3(256), 0, st, Phi_y, Qb + (size_t)j * L.ld, M, w, ps);
+        hipLaunchKernelGGL(probe_orth_kernel, dim3(1), dim3(1024), 0, st, j, M, L.ld, Qb, w, alpha, beta, 1e-7, ps);
+    }
+    hipLaunchKernelGGL(probe_final_kernel, dim3(1), dim3(64), 0, st, alpha, beta, ps, out);
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
 
 fw_status bias_compensate(float* b, const float* W, int S, int M, int taps, const float* mu_old, const float* mu_new, float scale,
                           hipStream_t st) {

@@ -160,6 +160,8 @@ fw_status bias_compensate(float* b, const float* W, int S, int M, int taps, cons
                           hipStream_t st);
 size_t diagnostics_workspace_bytes(int M);
 fw_status diagnostics(const float* Phi_y, const float* lambda, int M, float* out, void* ws, hipStream_t st);
+size_t cond_probe_workspace_bytes(int M, int k);
+fw_status cond_probe(const float* Phi_y, int M, const float* b0, int k, float* out, void* ws, hipStream_t st);
 
 // ---- cond.hip
 size_t cond_workspace_bytes(int M);

@@ -95,6 +95,12 @@ def test_argument_validation_without_a_device():
     assert L.fw_cond_reduce_step_static(None, C.byref(p1), None, None) == b.FW_ERR_INVALID_ARG
     big = b.fw_cond_state(b.FW_COND_STATIC_MAX_M + 1, fake, fake, fake, fake, fake, fake, fake, fake)
     assert L.fw_cond_reduce_step_static(C.byref(big), C.byref(p), None, None) == b.FW_ERR_UNSUPPORTED
+    # condition-number probe
+    assert L.fw_cond_probe(None, 8, None, 4, fake, fake, 1 << 20, None) == b.FW_ERR_INVALID_ARG
+    assert L.fw_cond_probe(fake, 8, None, 0, fake, fake, 1 << 20, None) == b.FW_ERR_INVALID_ARG
+    assert L.fw_cond_probe(fake, 8, None, b.FW_COND_PROBE_MAX_K + 1, fake, fake, 1 << 20, None) == b.FW_ERR_INVALID_ARG
+    assert L.fw_cond_probe(fake, 8, None, 4, fake, fake, 16, None) == b.FW_ERR_WORKSPACE
+    assert b.fw_workspace_bytes(b.FW_OP_COND_PROBE, 4608, 16) >= 17 * 4608 * 8
     # EVD
     e = b.evd_params()
     assert L.fw_whiten_evd(None, 8, C.byref(e), fake, fake, None, fake, fake, 1 << 20, None) == b.FW_ERR_INVALID_ARG

@@ -96,3 +96,64 @@ def test_blocks_with_forgetting(dtype, layout):
     Tn = host(T)
     assert not np.allclose(Tn, np.eye(M), atol=1e-3)
     assert relF(host(Q), Tn.T @ Tn) < 1e-4
+
+
+@pytest.mark.parametrize("dtype,layout", [("f32", 2), ("bf16", 3)])
+def test_blocks_on_the_evd_leg_with_rank_limited_gains(dtype, layout):
+    """The EVD variant over several blocks (Sec. 2, Sec. 3.2): block moments with forgetting, eigen-decomposition of every
+    block's covariance, gains limited to the estimated signal rank with g_max (eqs. (hMs), (g_mod)), Q smoothed across
+    blocks (eq. (vQs), beta = 0.95 as in Sec. 6), gradient multiplied by the smoothed Q.  The oracle does the same block by
+    block from its own moments of the GPU's covariance (T, Q are spectral functions of Phi_x: compared, never V)."""
+    n_blocks, L, alpha, beta, g_max, eps = 4, 2, 0.9, 0.95, 10.0, 1e-5
+    blocks = drifting_batches(dtype, n_blocks, L, 900)
+    d0 = blocks[0][0].desc
+    M, S = d0.M, blocks[0][0].S
+    A = torch.zeros(M, M, device=DEV); s = torch.zeros(M, device=DEV)
+    mu = torch.zeros(M, device=DEV); Phi = torch.zeros(M, M, device=DEV); phi = torch.zeros(M, device=DEV)
+    lbar = torch.zeros(4, device=DEV)
+    T, Q = torch.empty(M, M, device=DEV), torch.empty(M, M, device=DEV)
+    Qs = torch.eye(M, device=DEV)                      # Qs(-1) = I
+    lam = torch.empty(M, device=DEV)
+    diag = torch.zeros(4, device=DEV)
+    ws_cov = workspace(b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, M, 0, desc_of(blocks[0][0]), dt_of(blocks[0][0])))
+    ws_evd = workspace(b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, M))
+    ep = b.evd_params(eps=eps, g_max=g_max, beta=beta, gain_mode=1)
+    host = lambda t: t.cpu().numpy().astype(np.float64)
+    mu_o = Phi_o = phi_o = None
+    Qs_o = np.eye(M)
+    ranks = []
+    for i, blk in enumerate(blocks):
+        A.zero_(); s.zero_()
+        rows = []
+        for layer in blk:
+            X, lay = upload_act(layer, layout)
+            b.fw_cov_accumulate(X, dt_of(layer), lay, desc_of(layer), A, s, ws_cov)
+            rows.append(oracle_rows(layer, layout))
+        rows = np.concatenate(rows, axis=0)
+        b.fw_cov_finalize(A, s, rows.shape[0], M, alpha, 1 if i == 0 else 0, mu, Phi, phi, lbar)
+        mu_o, Phi_o, phi_o, lbar_o = ora.block_moments(rows, alpha, i == 0, mu_o, Phi_o, phi_o)
+        b.fw_whiten_evd(Phi, M, ep, T, Q, Qs, lam, ws_evd)
+        b.fw_diagnostics(None, lam, M, diag)
+        torch.cuda.synchronize()
+        assert relF(host(Phi), Phi_o) < TOL[dtype], f"block {i}"
+        # the oracle continues from the GPU's covariance of this block
+        P64 = host(Phi)
+        T_o, Q_o, lam_o = ora.whiten_evd(P64, eps=eps, gain_mode=1, g_max=g_max)
+        Qs_o = ora.smooth_Q(Qs_o, Q_o, beta)
+        assert np.max(np.abs(host(lam) - lam_o)) <= 1e-6 * lam_o[0]
+        assert relF(host(T), T_o) < 1e-4 and relF(host(Q), Q_o) < 1e-4, f"block {i}"
+        assert relF(host(Qs), Qs_o) < 1e-4, f"block {i}"
+        ms = ora.aic_signal_rank(lam_o)
+        ranks.append(ora.round_rank(ms, M))
+        assert float(diag[2]) == pytest.approx(ms, rel=1e-4)
+        # gains really are the rank-limited ones: beyond the signal rank the transform leaves the eigen-directions alone
+        g = ora.evd_gains(lam_o, eps, 1, g_max)
+        assert np.all(g[ranks[-1]:] == 1.0) and np.all(g[:ranks[-1]] <= g_max)
+        Qs_o = host(Qs)                                # carry the GPU's smoothed Q forward: every block is compared on its own
+        G = blk[-1].G
+        Gout = torch.empty(S, M, device=DEV)
+        b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, Qs, Gout)
+        torch.cuda.synchronize()
+        assert relF(host(Gout), ora.grad_transform(G.astype(np.float64), host(Qs))) < 1e-4
+    assert 1 <= min(ranks) and max(ranks) < M          # the rank limit was active
+    assert relF(host(Qs), np.eye(M)) > 1e-3            # and the smoothing has moved Qs away from its start

@@ -88,7 +88,7 @@ def test_config1_sixteen_steps():
     assert applied >= 8
 
 
-@pytest.mark.parametrize("M,leak", [(96, True), (130, True), (64, False), (70, False)])
+@pytest.mark.parametrize("M,leak", [(96, True), (130, True), (64, False), (70, False), (1152, True), (2304, True)])
 def test_refresh_for_a_new_block(M, leak):
     """A new block changes Phi_x while T carries over: Psi, Phi_y and the column norms are rebuilt for the T at hand, and
     the next steps agree with the oracle, which forms T Phi_x T^T explicitly from the new Phi_x."""

@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_common import (CondRunner, b, dev, forced_step, ora, oracle_first_block_moments_chunked, oracle_params, oracle_rows, relF,
+from gpu_common import (CondRunner, b, dev, forced_step, marginal_decision_ok, membership_band, ora, oracle_first_block_moments_chunked, oracle_params, oracle_rows, relF,
                         run_cov, run_finalize, workspace, DEV)
 
 pytestmark = pytest.mark.gpu
@@ -194,11 +194,16 @@ def cond_number(T, P64):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("cfg,n_steps,checkpoints", [("c2", 32, (1, 2, 4, 8, 16, 32)), ("c3", 24, (2, 8, 24)), ("c4", 8, (2, 8))])
+@pytest.mark.parametrize("cfg,n_steps,checkpoints", [("c2", 32, (1, 2, 4, 8, 16, 32)), ("c3", 24, (2, 8, 16, 24)), ("c4", 8, (2, 8))])
 def test_free_running_condition_number_trajectory(cfg, n_steps, checkpoints):
     """Free running from T = I on the configuration's own covariance: the GPU (float32 state, O(M^2) upkeep of Phi_y) and
     the oracle (float64, T Phi_x T^T formed explicitly every step) each follow their own trajectory; the condition number
-    of T Phi_x T^T, evaluated in float64 for both, must stay within 1e-3 (relative) of the oracle's at every checkpoint."""
+    of T Phi_x T^T, evaluated in float64 for both, must stay within 1e-3 (relative) of the oracle's at every checkpoint.
+
+    The trajectories are comparable only while the integer decisions (arg-max, coherence set) agree.  Where they differ
+    the test requires the difference to be marginal (inside a guard band widened for the drift the two states have
+    gathered by then), lets the oracle continue from the GPU's state, and goes on comparing: every stretch between two
+    such points is a free run of both sides from a common state."""
     layer = {"c2": wl.config2, "c3": wl.config3, "c4": wl.config4}[cfg]()
     M = layer.desc.M
     A, s = run_cov(layer, b.FW_LAYOUT_NHWC_KKC)
@@ -212,18 +217,28 @@ def test_free_running_condition_number_trajectory(cfg, n_steps, checkpoints):
     op = oracle_params(gp)
     st_o = ora.CondState.initial(P64)
     c0 = cond_number(np.eye(M), P64)
-    worst, same_decisions = 0.0, 0
+    band = 5e-5
+    worst, resyncs, longest, since = 0.0, 0, 0, 0
     for k in range(1, n_steps + 1):
         info = run.step(gp)
         st_o, oi = ora.cond_reduce_step(st_o, lbar32, op)
-        same_decisions += int(info.m_prime == oi.m_prime and info.set_size == oi.set_size)
+        if info.m_prime != oi.m_prime or info.set_size != oi.set_size:
+            assert marginal_decision_ok(info, oi, op, band_argmax=band, band_set=2.0 * membership_band(M, op.c_rel)), \
+                f"step {k}: arg-max or coherence set differs beyond rounding and drift"
+            st_o = ora.CondState(P64, run.host("T"), run.host("Q"), run.host("Qs"))
+            resyncs += 1
+            since = 0
+        else:
+            since += 1
+            longest = max(longest, since)
         if k in checkpoints:
             cg, co = cond_number(run.host("T"), P64), cond_number(st_o.T, P64)
             dev_rel = abs(cg / co - 1.0)
             worst = max(worst, dev_rel)
             print(f"{layer.name} step {k}: cond gpu {cg:.6e} oracle {co:.6e} (start {c0:.6e}) rel dev {dev_rel:.2e}, "
-                  f"same decisions so far {same_decisions}/{k}")
+                  f"marginal decisions so far {resyncs}, free run of {since} steps behind this point")
             assert dev_rel < 1e-3
-    # the end states themselves: reported, not gated (free-running trajectories may part ways legitimately)
+    assert longest >= min(8, n_steps), "no stretch of free running long enough to mean anything"
+    # the end states themselves: reported, not gated
     print(f"{layer.name}: end-state rel-F T {relF(run.host('T'), st_o.T):.2e}, Qs {relF(run.host('Qs'), st_o.Qs):.2e}; "
-          f"worst condition-number deviation {worst:.2e}")
+          f"worst condition-number deviation {worst:.2e}, longest free run {longest} steps")

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_common import b, dev, ora, relF, workspace, DEV
+from gpu_common import CondRunner, b, dev, ora, relF, workspace, DEV
 
 pytestmark = pytest.mark.gpu
 
@@ -139,3 +139,67 @@ def test_diagnostics(M):
     b.fw_diagnostics(dev(np.outer(u, u)), None, M, out, ws)
     torch.cuda.synchronize()
     assert float(out[0]) == pytest.approx(1.0 / M, rel=1e-4)
+
+
+@pytest.mark.parametrize("M,k", [(8, 8), (33, 6), (200, 16), (577, 16), (2304, 12), (64, 32)])
+def test_condition_probe_against_the_oracle(M, k):
+    """Extreme Ritz values of a symmetric positive definite matrix on a k-dimensional Krylov space: the GPU's Lanczos
+    recurrence against the oracle's projection form, same start vector.  Both work in float64 on the float32 matrix, so
+    what is left is the rounding of the float32 outputs and of a differently ordered orthogonalisation."""
+    rng = np.random.default_rng(1000 + M)
+    P = wl.spd_matrix(M, M, np.logspace(1.0, -2.0, M)).astype(np.float32)
+    P = ((P + P.T) / 2).astype(np.float32)
+    b0 = rng.standard_normal(M).astype(np.float32)
+    out = torch.full((4,), float("nan"), device=DEV)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_COND_PROBE, M, k))
+    b.fw_cond_probe(dev(P), M, dev(b0), k, out, ws)
+    torch.cuda.synchronize()
+    hi, lo, cond, steps = ora.condition_probe(P.astype(np.float64), b0.astype(np.float64), k)
+    g_hi, g_lo, g_cond, g_steps = (float(v) for v in out)
+    assert int(g_steps) == steps == min(k, M)
+    assert g_hi == pytest.approx(hi, rel=2e-6) and g_lo == pytest.approx(lo, rel=2e-6) and g_cond == pytest.approx(cond, rel=4e-6)
+    # never an overestimate of the true condition number
+    w = np.linalg.eigvalsh(P.astype(np.float64))
+    assert g_cond <= w[-1] / w[0] * (1 + 1e-5)
+
+
+def test_condition_probe_special_cases():
+    # invariant subspace: the start vector lives in the span of two eigenvectors -> stops at dimension 2, exact there
+    P = np.diag([7.0, 3.0, 2.0, 1.0, 0.5]).astype(np.float32)
+    b0 = np.array([1.0, 0.0, 1.0, 0.0, 0.0], dtype=np.float32)
+    out = torch.full((4,), float("nan"), device=DEV)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_COND_PROBE, 5, 5))
+    b.fw_cond_probe(dev(P), 5, dev(b0), 5, out, ws)
+    torch.cuda.synchronize()
+    assert [float(v) for v in out] == pytest.approx([7.0, 2.0, 3.5, 2.0], rel=1e-6)
+    assert ora.condition_probe(P.astype(np.float64), b0.astype(np.float64), 5)[3] == 2
+    # default start vector (all ones); a white matrix has condition number 1 after a single step
+    b.fw_cond_probe(dev(np.eye(5) * 0.3), 5, None, 4, out, ws)
+    torch.cuda.synchronize()
+    assert [float(v) for v in out] == pytest.approx([0.3, 0.3, 1.0, 1.0], rel=1e-6)
+    want = ora.condition_probe(P.astype(np.float64), np.ones(5), 3)
+    b.fw_cond_probe(dev(P), 5, None, 3, out, ws)
+    torch.cuda.synchronize()
+    assert [float(v) for v in out] == pytest.approx(list(want), rel=2e-6)
+
+
+def test_condition_probe_follows_the_recursion():
+    """The figure the recursion is built to reduce: probe Phi_y before and after a run of steps; the estimate drops with
+    the true condition number and stays below it."""
+    M = 96
+    Phi = wl.spd_matrix(5, M, np.logspace(2.0, -2.0, M)).astype(np.float32)
+    run = CondRunner(Phi, float(np.trace(Phi) / M))
+    out = torch.zeros(4, device=DEV)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_COND_PROBE, M, 24))
+    b.fw_cond_probe(run.Phi_y, M, None, 24, out, ws)
+    torch.cuda.synchronize()
+    before = float(out[2])
+    gp = b.cond_params()
+    for _ in range(40):
+        run.step(gp)
+    b.fw_cond_probe(run.Phi_y, M, None, 24, out, ws)
+    torch.cuda.synchronize()
+    after = float(out[2])
+    w = np.linalg.eigvalsh(run.host("Phi_y"))
+    assert after < before / 3 and after <= w[-1] / w[0] * (1 + 1e-5)
+    assert float(out[0]) == pytest.approx(w[-1], rel=1e-3)
