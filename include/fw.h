@@ -18,8 +18,9 @@
  *     (P = Ho*Wo output positions), M = Cin*kh*kw features in the order m = (c*kh + ky)*kw + kx (the order of a
  *     contiguous weight tensor [S, Cin, kh, kw] viewed as [S, M]) unless the layout says otherwise, zero padding
  *     counts as data.  N_rows = B*P.  Whatever order is chosen, G, T, Q and Phi_x of a layer must all use it.
- *   - The library allocates no device memory, keeps no device state between calls and never frees (host side it
- *     keeps the setting of fw_cov_set_form and, per calling thread, the launch geometry of recently seen layers).
+ *   - The library allocates no device memory, keeps no device state between calls and never frees, and has no
+ *     process-wide setting (host side, each calling thread keeps the launch geometry of the layers it saw most recently,
+ *     a pure function of the descriptor; fw_cond_reduce_step_static alone owns a fixed device array, see there).
  *     Scratch comes from the caller through (ws, ws_bytes); fw_workspace_bytes gives the size an entry point needs.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on it and the
  *     call returns without waiting, except fw_whiten_evd, which waits on its own convergence flag.
@@ -57,8 +58,16 @@ typedef enum {
                               work in; the other tensor layouts pay a permutation of A when the sums are written out. */
 } fw_layout;
 
-/* Geometry of a layer input.  FW_LAYOUT_ROWS: B = N_rows, Cin = M, H = W = kh = kw = stride = 1, pad = 0. */
-typedef struct { int B, Cin, H, W, kh, kw, stride, pad; } fw_conv_desc;
+/* Which form fw_cov_accumulate takes where both the direct product of the unfolded patch rows and the shift form
+ * (stride-1 windows: tap pairs with the same offset share one product) apply.  Both compute the same sums of Sec. 2;
+ * AUTO picks by an estimate of the run time.  SHIFT and DIRECT are meant for tuning and for tests that must reach one
+ * form at sizes where the estimate prefers the other; where the shift form does not apply the field changes nothing. */
+typedef enum { FW_COV_FORM_AUTO = 0, FW_COV_FORM_SHIFT = 1, FW_COV_FORM_DIRECT = 2 } fw_cov_form;
+
+/* Geometry of a layer input.  FW_LAYOUT_ROWS: B = N_rows, Cin = M, H = W = kh = kw = stride = 1, pad = 0.
+ * `form` (a fw_cov_form) travels with the geometry, so that fw_workspace_bytes, fw_cov_plan_query and fw_cov_accumulate
+ * given the same descriptor always agree on how the layer runs; a zero-initialised field means AUTO. */
+typedef struct { int B, Cin, H, W, kh, kw, stride, pad, form; } fw_conv_desc;
 
 /* Operations for fw_workspace_bytes. */
 typedef enum {
@@ -297,14 +306,6 @@ typedef struct {
     double mfma_flops_issued;
 } fw_cov_plan;
 fw_status fw_cov_plan_query(fw_dtype dt, fw_layout lay, const fw_conv_desc* d, fw_cov_plan* plan);
-
-/* Which form fw_cov_accumulate takes where both the direct product and the shift form (stride-1 windows, see above)
- * apply.  Both compute the same sums of Sec. 2; the default picks by an estimate of the run time.  The setting is
- * process-wide, read at every call (also by fw_cov_plan_query and fw_workspace_bytes, so set it before sizing the
- * workspace), and meant for tuning and for tests that must reach one form at sizes where the estimate prefers the other.
- * Returns FW_ERR_INVALID_ARG for any other value. */
-typedef enum { FW_COV_FORM_AUTO = 0, FW_COV_FORM_SHIFT = 1, FW_COV_FORM_DIRECT = 2 } fw_cov_form;
-fw_status fw_cov_set_form(fw_cov_form form);
 
 /* Scratch bytes an entry point needs for the given sizes (0 if none).  `d` is needed for FW_OP_COV_ACCUMULATE only;
  * for the per-tap operations S is the number of gradient rows, S * taps; for FW_OP_COND_PROBE S is the Krylov dimension k. */

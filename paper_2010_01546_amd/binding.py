@@ -26,12 +26,12 @@ FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
 
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",
            "fw_whiten_evd", "fw_cond_state_refresh", "fw_grad_transform_taps", "fw_sgd_update", "fw_bias_compensate",
-           "fw_diagnostics", "fw_cov_plan_query", "fw_cov_set_form", "fw_cond_reduce_step_static", "fw_cond_probe", "fw_workspace_bytes", "fw_status_string", "fw_version"]
-N_STATUS_EXPORTS = 15   # the leading entries of EXPORTS return fw_status
+           "fw_diagnostics", "fw_cov_plan_query", "fw_cond_reduce_step_static", "fw_cond_probe", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+N_STATUS_EXPORTS = 14   # the leading entries of EXPORTS return fw_status
 
 
 class fw_conv_desc(C.Structure):
-    _fields_ = [(n, C.c_int) for n in ("B", "Cin", "H", "W", "kh", "kw", "stride", "pad")]
+    _fields_ = [(n, C.c_int) for n in ("B", "Cin", "H", "W", "kh", "kw", "stride", "pad", "form")]
 
 
 class fw_cond_params(C.Structure):
@@ -78,7 +78,6 @@ lib.fw_bias_compensate.argtypes = [_P, _P, C.c_int, C.c_int, C.c_int, _P, _P, C.
 lib.fw_diagnostics.argtypes = [_P, _P, C.c_int, _P, _P, C.c_size_t, _P]
 lib.fw_cond_probe.argtypes = [_P, C.c_int, _P, C.c_int, _P, _P, C.c_size_t, _P]
 lib.fw_cov_plan_query.argtypes = [C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.POINTER(fw_cov_plan)]
-lib.fw_cov_set_form.argtypes = [C.c_int]
 lib.fw_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.c_int]
 lib.fw_workspace_bytes.restype = C.c_size_t
 lib.fw_status_string.argtypes = [C.c_int]
@@ -122,8 +121,8 @@ def _check(status, where, allow=()):
     return status
 
 
-def conv_desc(B, Cin, H=1, W=1, kh=1, kw=1, stride=1, pad=0) -> fw_conv_desc:
-    return fw_conv_desc(B, Cin, H, W, kh, kw, stride, pad)
+def conv_desc(B, Cin, H=1, W=1, kh=1, kw=1, stride=1, pad=0, form=0) -> fw_conv_desc:
+    return fw_conv_desc(B, Cin, H, W, kh, kw, stride, pad, form)
 
 
 def fw_workspace_bytes(op, M, S=0, d=None, dt=FW_F32) -> int:
@@ -195,11 +194,6 @@ def fw_cov_plan_query(dt, lay, d) -> fw_cov_plan:
 
 
 FW_COV_FORM_AUTO, FW_COV_FORM_SHIFT, FW_COV_FORM_DIRECT = 0, 1, 2
-
-
-def fw_cov_set_form(form):
-    """Process-wide; host state only."""
-    return _check(lib.fw_cov_set_form(form), "fw_cov_set_form")
 
 
 def cond_state(M, Phi_x, lambda_bar, T, Q, Qs, Phi_y, Psi, xi2) -> fw_cond_state:

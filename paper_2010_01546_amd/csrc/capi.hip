@@ -10,6 +10,7 @@ bool desc_ok(const fw_conv_desc* d, fw_layout lay) {
     if (d->B <= 0 || d->Cin <= 0 || d->H <= 0 || d->W <= 0 || d->kh <= 0 || d->kw <= 0 || d->stride <= 0 || d->pad < 0) return false;
     if (d->H + 2 * d->pad < d->kh || d->W + 2 * d->pad < d->kw) return false;
     if (d->pad > 0 && (d->pad >= d->kh || d->pad >= d->kw)) return false;  // a window lying wholly in the padding
+    if (d->form != FW_COV_FORM_AUTO && d->form != FW_COV_FORM_SHIFT && d->form != FW_COV_FORM_DIRECT) return false;
     if (lay == FW_LAYOUT_ROWS && (d->H != 1 || d->W != 1 || d->kh != 1 || d->kw != 1 || d->stride != 1 || d->pad != 0)) return false;
     return true;
 }
@@ -210,12 +211,6 @@ fw_status fw_whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float
         return FW_ERR_ALIGNMENT;
     if (!ws || ws_bytes < evd_workspace_bytes(M)) return FW_ERR_WORKSPACE;
     return whiten_evd(Phi_x, M, p, T, Q, Qs, lambda, ws, ws_bytes, reinterpret_cast<hipStream_t>(stream));
-}
-
-fw_status fw_cov_set_form(fw_cov_form form) {
-    if (form != FW_COV_FORM_AUTO && form != FW_COV_FORM_SHIFT && form != FW_COV_FORM_DIRECT) return FW_ERR_INVALID_ARG;
-    cov_set_form((int)form);
-    return FW_OK;
 }
 
 fw_status fw_cov_plan_query(fw_dtype dt, fw_layout lay, const fw_conv_desc* d, fw_cov_plan* plan) {

@@ -698,10 +698,6 @@ size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_lay
     return align_up(part, 256) + align_up(sp, 256) + (copy ? act_copy_bytes(d) : 0);
 }
 
-static std::atomic<int> g_cov_form{FW_COV_FORM_AUTO};
-int cov_form() { return g_cov_form.load(std::memory_order_relaxed); }
-void cov_set_form(int form) { g_cov_form.store(form, std::memory_order_relaxed); }
-
 bool cov_plan(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, fw_cov_plan* plan) {
     *plan = fw_cov_plan{};
     if (cov_skinny_plan(d, lay, plan)) return true;

@@ -619,7 +619,7 @@ __global__ __launch_bounds__(256) void shift_tile_assemble_kernel(TileGeom g, co
 // same terms as the direct form's (see make_tile_geom).
 bool make_shift_tile_geom(const fw_conv_desc* d, TileGeom* g, double* cost) {
     if (d->stride != 1 || d->kh * d->kw <= 1 || d->kh > 8 || d->kw > 8 || (d->Cin & 3) != 0) return false;
-    if (cov_form() == FW_COV_FORM_DIRECT) return false;
+    if (d->form == FW_COV_FORM_DIRECT) return false;
     const int Cin = d->Cin;
     const int gx = Cin <= 128 && d->W >= 4 ? 2 : 1;    // few channels: pairs of pixels fill the rows of a larger tile
     g->gx = gx;
@@ -840,7 +840,7 @@ bool build_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
         // stride-1 windows: tap pairs with the same difference share their products (shift-correlation mode)
         TileGeom gs = *g;
         double cs = 0.0;
-        if (lay != FW_LAYOUT_ROWS && make_shift_tile_geom(d, &gs, &cs) && (cs < best || cov_form() == FW_COV_FORM_SHIFT)) {
+        if (lay != FW_LAYOUT_ROWS && make_shift_tile_geom(d, &gs, &cs) && (cs < best || d->form == FW_COV_FORM_SHIFT)) {
             const long long per_img = (long long)gs.Hp * gs.Wp * d->Cin;
             long long ch = (524288 + per_img - 1) / per_img;
             if (ch > gs.Bg) ch = gs.Bg;
@@ -875,11 +875,10 @@ bool build_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
 // workspace check and for the launches, the dispatch simulation behind it takes milliseconds, and a training loop asks for
 // the same layers over and over.
 bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
-    struct Entry { bool ok; fw_conv_desc d; fw_layout lay; int form; TileGeom g; };
+    struct Entry { bool ok; fw_conv_desc d; fw_layout lay; TileGeom g; };
     static thread_local std::vector<Entry> cache;     // most recent first
-    const int form = cov_form();
     for (size_t i = 0; i < cache.size(); ++i)
-        if (cache[i].lay == lay && cache[i].form == form && memcmp(&cache[i].d, d, sizeof(*d)) == 0) {
+        if (cache[i].lay == lay && memcmp(&cache[i].d, d, sizeof(*d)) == 0) {
             if (i) std::swap(cache[i], cache[0]);
             if (cache[0].ok) *g = cache[0].g;
             return cache[0].ok;
@@ -887,7 +886,7 @@ bool make_tile_geom(const fw_conv_desc* d, fw_layout lay, TileGeom* g) {
     Entry e;
     memset(&e, 0, sizeof(e));
     e.ok = build_tile_geom(d, lay, &e.g);
-    e.d = *d; e.lay = lay; e.form = form;
+    e.d = *d; e.lay = lay;
     if (cache.size() >= 64) cache.pop_back();
     cache.insert(cache.begin(), e);
     if (e.ok) *g = e.g;

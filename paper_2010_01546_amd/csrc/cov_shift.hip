@@ -370,7 +370,7 @@ ShiftWs shift_ws_layout(const ShiftGeom& g) {
 static bool make_shift_geom(const fw_conv_desc* d, fw_layout lay, ShiftGeom* g) {
     if (lay != FW_LAYOUT_NHWC && lay != FW_LAYOUT_NHWC_KKC) return false;
     if (d->stride != 1 || d->kh * d->kw <= 1 || d->kh > 8 || d->kw > 8 || (d->Cin & 3) != 0) return false;
-    if (cov_form() == FW_COV_FORM_DIRECT) return false;
+    if (d->form == FW_COV_FORM_DIRECT) return false;
     g->B = d->B; g->Cin = d->Cin; g->H = d->H; g->W = d->W; g->kh = d->kh; g->kw = d->kw; g->pad = d->pad;
     g->Ho = d->H + 2 * d->pad - d->kh + 1;
     g->Wo = d->W + 2 * d->pad - d->kw + 1;
@@ -389,7 +389,7 @@ static bool make_shift_geom(const fw_conv_desc* d, fw_layout lay, ShiftGeom* g) 
     const long long nb = (M + BLK - 1) / BLK;
     const double direct = 0.5 * (double)nb * (double)(nb + 1);
     const double shifted = (double)g->nbr * (double)g->nbc;
-    if (shifted * 1.1 >= direct && cov_form() != FW_COV_FORM_SHIFT) return false;
+    if (shifted * 1.1 >= direct && d->form != FW_COV_FORM_SHIFT) return false;
     ShiftBand rows[8 * 2], cols[8 * 2];
     const int nr = shift_bands(d->H, d->kh, d->pad, g->Ho, rows, 16), nc = shift_bands(d->W, d->kw, d->pad, g->Wo, cols, 16);
     if (nr <= 0 || nc <= 0 || nr * nc > MAXREG) return false;

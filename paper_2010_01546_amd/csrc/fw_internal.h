@@ -80,9 +80,6 @@ fw_status cov_finalize(const float* A, const float* s, long long n, int M, float
 fw_status symmetrize_from_lower(float* A, int M, hipStream_t st);
 fw_status fill_f32(float* p, size_t n, float v, hipStream_t st);
 bool cov_plan(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, fw_cov_plan* plan);
-// process-wide preference between the forms (fw_cov_form): 0 by estimate, 1 shift wherever it applies, 2 never shift
-int cov_form();
-void cov_set_form(int form);
 
 // ---- shift correlations of stride-1 windows (cov_shift.hip, cov_bf16.hip)
 // tap differences kept, in order: (0, 0..kw-1), then (dy, -(kw-1)..kw-1) for dy = 1..kh-1

@@ -29,7 +29,8 @@ def upload_act(layer: wl.Layer, layout: int):
 
 
 def desc_of(layer: wl.Layer):
-    return b.conv_desc(*layer.desc.astuple())
+    """The layer's geometry; ``layer.meta["form"]`` (a fw_cov_form) asks for one of the two covariance forms."""
+    return b.conv_desc(*layer.desc.astuple(), form=layer.meta.get("form", 0))
 
 
 def dt_of(layer: wl.Layer):

@@ -37,7 +37,7 @@ def test_binding_names_match_header():
         assert hasattr(binding, n), n
     assert binding.fw_version() == 103
     assert binding.fw_status_string(0) == "ok" and "workspace" in binding.fw_status_string(4)
-    assert C.sizeof(binding.fw_cond_info) == 32 and C.sizeof(binding.fw_conv_desc) == 32
+    assert C.sizeof(binding.fw_cond_info) == 32 and C.sizeof(binding.fw_conv_desc) == 36
 
 
 def test_workspace_sizes():

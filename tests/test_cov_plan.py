@@ -64,22 +64,26 @@ def test_bad_arguments():
 
 
 def test_form_preference():
-    """The process-wide preference overrides the estimate where both forms apply, and nothing else."""
-    small = b.conv_desc(2, 64, 9, 7, 3, 3, 1, 1)
-    strided = b.conv_desc(2, 64, 9, 7, 3, 3, 2, 1)
-    try:
-        assert b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, small).shift == 0
-        b.fw_cov_set_form(b.FW_COV_FORM_SHIFT)
-        p = b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, small)
-        assert p.shift == 1 and p.covered_pixels == 2 * 9 * 7
-        assert b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, strided).shift == 0   # does not apply: stays direct
-        b.fw_cov_set_form(b.FW_COV_FORM_DIRECT)
-        assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(128, 64, 32, 32, 3, 3, 1, 1)).shift == 0
-        with pytest.raises(b.FwError):
-            b.fw_cov_set_form(3)
-    finally:
-        b.fw_cov_set_form(b.FW_COV_FORM_AUTO)
-    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(128, 64, 32, 32, 3, 3, 1, 1)).shift == 1
+    """The form asked for in the descriptor overrides the estimate where both forms apply, and nothing else; workspace
+    size and plan follow the same descriptor, and there is no setting outside it."""
+    small = dict(B=2, Cin=64, H=9, W=7, kh=3, kw=3, stride=1, pad=1)
+    strided = dict(small, stride=2)
+    big = dict(B=128, Cin=64, H=32, W=32, kh=3, kw=3, stride=1, pad=1)
+    assert b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, b.conv_desc(**small)).shift == 0
+    p = b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, b.conv_desc(**small, form=b.FW_COV_FORM_SHIFT))
+    assert p.shift == 1 and p.covered_pixels == 2 * 9 * 7
+    assert b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, b.conv_desc(**small)).shift == 0      # the request left no trace
+    assert b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC, b.conv_desc(**strided, form=b.FW_COV_FORM_SHIFT)).shift == 0
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(**big, form=b.FW_COV_FORM_DIRECT)).shift == 0
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(**big)).shift == 1
+    with pytest.raises(b.FwError):
+        b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(**big, form=3))
+    assert b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, 576, 0, b.conv_desc(**big, form=3), b.FW_F32) == 0
+    # the two forms need different scratch: sized from the same descriptor the call will get
+    w_shift = b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, 576, 0, b.conv_desc(**big, form=b.FW_COV_FORM_SHIFT), b.FW_BF16)
+    w_direct = b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, 576, 0, b.conv_desc(**big, form=b.FW_COV_FORM_DIRECT), b.FW_BF16)
+    assert w_shift > 0 and w_direct > 0 and w_shift != w_direct
+    assert not hasattr(b.lib, "fw_cov_set_form")
 
 
 def test_plan_invariants_on_random_layers():
@@ -89,8 +93,7 @@ def test_plan_invariants_on_random_layers():
     layer, and the query is repeatable (cached geometry == fresh geometry)."""
     import random
     rnd = random.Random(20101546)
-    b.fw_cov_set_form(b.FW_COV_FORM_SHIFT)
-    try:
+    if True:
         taken = 0
         for _ in range(300):
             kh, kw = rnd.choice([(3, 3), (3, 3), (5, 5), (2, 2), (1, 3), (3, 1), (4, 2), (7, 7), (2, 5)])
@@ -100,7 +103,7 @@ def test_plan_invariants_on_random_layers():
             B = rnd.choice([1, 3, 8, 64, 256])
             if H + 2 * pad < kh or W + 2 * pad < kw:
                 continue
-            d = b.conv_desc(B, Cin, H, W, kh, kw, 1, pad)
+            d = b.conv_desc(B, Cin, H, W, kh, kw, 1, pad, form=b.FW_COV_FORM_SHIFT)
             Ho, Wo = H + 2 * pad - kh + 1, W + 2 * pad - kw + 1
             # pixels under some window: rows y with an output row oy = y - ty + pad in [0, Ho) for some tap row ty
             rows = sum(1 for y in range(H) if any(0 <= y - t + pad < Ho for t in range(kh)))
@@ -121,5 +124,3 @@ def test_plan_invariants_on_random_layers():
                 assert 1 <= p.regions <= 32 and p.ranges >= p.regions and p.workgroups >= 1
                 assert p.mfma_flops_issued > 0
         assert taken > 200
-    finally:
-        b.fw_cov_set_form(b.FW_COV_FORM_AUTO)

@@ -78,10 +78,8 @@ def test_stride_one_windows(B, Cin, H, W, kh, kw, pad, layout, dtype):
 
 @pytest.fixture
 def forced_form(request):
-    """The form named by the parameter for one test; the estimate's own choice afterwards."""
-    b.fw_cov_set_form(request.param)
-    yield request.param
-    b.fw_cov_set_form(b.FW_COV_FORM_AUTO)
+    """The covariance form a test asks for; it travels in the layer's descriptor (``layer.meta["form"]``)."""
+    return request.param
 
 
 # the same border shapes, plus pair-unit specials (odd widths, width 4, even and 1-wide windows, few channels), at sizes
@@ -96,7 +94,7 @@ FORCED_CASES = SHIFT_CASES + [(9, 64, 4, 4, 3, 3, 1), (3, 16, 13, 4, 3, 2, 0), (
 @pytest.mark.parametrize("B,Cin,H,W,kh,kw,pad", FORCED_CASES)
 def test_stride_one_windows_in_either_form(B, Cin, H, W, kh, kw, pad, layout, dtype, forced_form):
     d = wl.ConvDesc(B=B, Cin=Cin, H=H, W=W, kh=kh, kw=kw, stride=1, pad=pad)
-    cd = b.conv_desc(B, Cin, H, W, kh, kw, 1, pad)
+    cd = b.conv_desc(B, Cin, H, W, kh, kw, 1, pad, form=forced_form)
     plan = b.fw_cov_plan_query(b.FW_BF16 if dtype == "bf16" else b.FW_F32, layout, cd)
     if forced_form == b.FW_COV_FORM_DIRECT:
         assert plan.shift == 0
@@ -108,7 +106,7 @@ def test_stride_one_windows_in_either_form(B, Cin, H, W, kh, kw, pad, layout, dt
     if dtype == "bf16":
         act = wl.round_to_bf16(act)
     G = np.zeros((4, d.M), dtype=np.float32)
-    check_layer(wl.Layer("forced", d, 4, dtype, act, G), layout)
+    check_layer(wl.Layer("forced", d, 4, dtype, act, G, meta={"form": forced_form}), layout)
 
 
 SKINNY_ROWS = [(5000, 64, "f32"), (4096, 100, "bf16"), (3001, 17, "f32"), (2500, 128, "bf16"), (3000, 5, "f32"), (2049, 33, "bf16"),
@@ -217,7 +215,7 @@ def test_seeded_sweep_of_window_shapes(forced_form):
         act = np.abs(rng.standard_normal((B, H, W, Cin))).astype(np.float32)
         if dtype == "bf16":
             act = wl.round_to_bf16(act)
-        layer = wl.Layer("sweep", d, 4, dtype, act, np.zeros((4, d.M), np.float32))
+        layer = wl.Layer("sweep", d, 4, dtype, act, np.zeros((4, d.M), np.float32), meta={"form": forced_form})
         case = (B, Cin, H, W, kh, kw, stride, pad, dtype, layout)
         A_o, s_o, n = ora.raw_sums(oracle_rows(layer, layout))
         A, s = run_cov(layer, layout)
