@@ -95,6 +95,7 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
     info = torch.zeros(8, dtype=torch.int32, device=dev)
     ws_cov = torch.empty(b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, M, 0, desc, dt), dtype=torch.uint8, device=dev)
     ws_cond = torch.empty(b.fw_workspace_bytes(b.FW_OP_COND_REDUCE_STEP, M), dtype=torch.uint8, device=dev)
+    ws_ref = torch.empty(b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, M), dtype=torch.uint8, device=dev)
     prm = b.cond_params()                          # the paper's hyper-parameters (Sec. 6)
     alpha = 0.1
     st = b.cond_state(M, Phi, lbar, T, Q, Qs, Py, Psi, xi2)   # holds the nine tensors
@@ -119,7 +120,7 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
         if ev is not None:
             ev[2].record()
         if refresh:
-            b.fw_cond_state_refresh(st)      # Psi is part of the state: no scratch needed
+            b.fw_cond_state_refresh(st, ws_ref)   # full workspace: the products run on the bfloat16 pipe with split operands
         if ev is not None:
             ev[3].record()
         b.fw_cond_reduce_step(st, prm, info, ws_cond)

@@ -209,9 +209,16 @@ fw_status fw_cond_state_init(const fw_cond_state* st, void* stream);
 /* A new block brings a new Phi_x while T, Q, Qs carry over (Sec. 2: the moments are re-estimated block by block; Sec. 4:
  * the recursion works on the covariance of the transformed input).  Recomputes, for the T at hand,
  *   Psi = T Phi_x,   Phi_y = T Phi_x T^T (written exactly symmetric),   xi2 = squared column norms of Phi_y
- * by two M x M x M float32 products on the matrix cores.  T, Q, Qs are not touched.
- *   ws   scratch of fw_workspace_bytes(FW_OP_COND_STATE_REFRESH, M, 0, NULL, FW_F32) bytes, needed only when st->Psi is NULL
+ * by two M x M x M products on the matrix cores.  T, Q, Qs are not touched.
+ *   ws   scratch of fw_workspace_bytes(FW_OP_COND_STATE_REFRESH, M, 0, NULL, FW_F32) bytes (about 16 M^2 bytes).
+ *        With it the float32 operands are split into two bfloat16 numbers each (hi + lo, 16 significant bits) and the
+ *        products run on the bfloat16 matrix cores as hi hi + hi lo + lo hi with float32 accumulation: relative
+ *        Frobenius error of Psi and Phi_y a few 1e-6, several times faster.
+ *        With ws NULL or smaller than that, or M < FW_REFRESH_SPLIT_MIN_M (where the split form would not be faster), the
+ *        products run in plain float32 (error a few 1e-7); that needs st->Psi, or at least M^2 floats (rounded up to 256
+ *        bytes) of ws to stand in for it (FW_ERR_WORKSPACE otherwise).
  */
+#define FW_REFRESH_SPLIT_MIN_M 1536
 fw_status fw_cond_state_refresh(const fw_cond_state* st, void* ws, size_t ws_bytes, void* stream);
 
 /* One step: estimate the high-power direction v of Phi_y (Sec. 4.2), lambda_e, g_e, a_e (eqs. (lambda), (ge), (xi)),
@@ -227,7 +234,7 @@ fw_status fw_cond_reduce_step(const fw_cond_state* st, const fw_cond_params* p, 
 
 /* The same step for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Identical arithmetic and kernels; the scratch is a fixed array
- * of 4 MiB in the library's device image (one copy per GPU, held until the process ends), so
+ * of 6 MiB in the library's device image (one copy per GPU, held until the process ends), so
  *   - M is limited to FW_COND_STATIC_MAX_M (FW_ERR_UNSUPPORTED beyond it, nothing enqueued),
  *   - the call allocates and frees nothing (its only set-up is one symbol-address lookup per device, on the first call
  *     made with that device current),

@@ -230,6 +230,7 @@ def fw_cond_reduce_step(st, p, info_dev, ws, stream=None):
 
 
 FW_COND_STATIC_MAX_M = 4608
+FW_REFRESH_SPLIT_MIN_M = 1536
 
 
 def fw_cond_reduce_step_static(st, p, info_dev, stream=None):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfw.so")
-SOURCES = ["capi.hip", "cov.hip", "cov_shift.hip", "cov_skinny.hip", "cov_bf16.hip", "gemm.hip", "cond.hip", "evd.hip", "extras.hip"]
+SOURCES = ["capi.hip", "cov.hip", "cov_shift.hip", "cov_skinny.hip", "cov_bf16.hip", "gemm.hip", "gemm_split.hip", "cond.hip", "evd.hip", "extras.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -161,7 +161,7 @@ fw_status fw_cond_state_refresh(const fw_cond_state* st, void* ws, size_t ws_byt
         (ws && !aligned16(ws)))
         return FW_ERR_ALIGNMENT;
     if (!st->Psi && (!ws || ws_bytes < align_up((size_t)st->M * st->M * sizeof(float), 256))) return FW_ERR_WORKSPACE;
-    return cond_state_refresh(st, reinterpret_cast<float*>(ws), reinterpret_cast<hipStream_t>(stream));
+    return cond_state_refresh(st, ws, ws_bytes, reinterpret_cast<hipStream_t>(stream));
 }
 
 // argument checks shared by the two forms of the recursive step (everything except the workspace)
@@ -236,7 +236,7 @@ size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtyp
             return grad_ws_bytes(M) + ((dt == FW_BF16 && S > 0) ? grad_wide_bytes(S, M) : 0);
         case FW_OP_COND_REDUCE_STEP: return M > 0 && M <= 16384 ? cond_workspace_bytes(M) : 0;
         case FW_OP_WHITEN_EVD: return M > 0 && M <= 16384 ? evd_workspace_bytes(M) : 0;
-        case FW_OP_COND_STATE_REFRESH: return M > 0 && M <= 16384 ? align_up((size_t)M * M * sizeof(float), 256) : 0;
+        case FW_OP_COND_STATE_REFRESH: return M > 0 && M <= 16384 ? cond_refresh_workspace_bytes(M) : 0;
         case FW_OP_GRAD_TRANSFORM_TAPS:
         case FW_OP_SGD_UPDATE: return (M > 0 && M <= 16384 && S > 0) ? grad_wide_bytes(S, M) : 0;
         case FW_OP_DIAGNOSTICS: return M > 0 && M <= 16384 ? diagnostics_workspace_bytes(M) : 0;

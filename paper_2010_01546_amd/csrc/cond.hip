@@ -3,10 +3,12 @@
 //
 //   estimate (Sec. 4.2):  m' = argmax xi   ->  c = Phi_y Phi_y e_m'  ->  coherence set, weights w  ->
 //                         v~ = Phi_y w  ->  v = v~/|v~|   [optional refinements v <- Phi_y v / |Phi_y v|]
-//   step (Sec. 4.1):      u = Phi_y v, lambda_e = v^T u, g_e, a_e;  t = T^T v;  p = Phi_x t (only if gamma < 1)
+//   step (Sec. 4.1):      u = Phi_y v, lambda_e = v^T u, g_e, a_e;  t = T^T v;  p = Phi_x t = Psi^T v (only if gamma < 1)
 //   The small reductions in between (arg-max, size of the set, |v~|) are done by every workgroup of the pass that
-//   needs them, for itself, from vectors of M entries, so that a step is seven launches:
-//   c | v~ | u and the partial products of t | t and the scalars | p | update | squared row norms.
+//   needs them, for itself, from vectors of M entries, so that a step is six launches, four of which touch M x M data:
+//   c | v~ | u and the partial products of t and p | t, p and the scalars | update | squared row norms.
+//   p = Phi_x T^T v is taken as Psi^T v (Psi = T Phi_x is part of the state): all three products of the third launch
+//   then need nothing but v, and no pass has to wait for t.
 //   update, one fused pass over pairs of mirrored 32x32 tiles:
 //       T'     = gamma (T + a v t^T) + (1-gamma) I                                               eq. (vT_rec)
 //       Q'     = gamma^2 (Q + a(a+2) t t^T) + (1-gamma)^2 I
@@ -24,7 +26,7 @@
 // Scratch of the allocation-free variant of the step (fw_cond_reduce_step_static): the workspace of one step for
 // M <= 4608, held by every GPU the library runs on until the process ends.  In host code this name is only a handle
 // for hipGetSymbolAddress; the address kernels are given comes from static_scratch() below.
-static __device__ __align__(256) unsigned char scratch[4u << 20];
+static __device__ __align__(256) unsigned char scratch[6u << 20];
 
 namespace fw {
 namespace {
@@ -38,7 +40,7 @@ constexpr int TILE = 32;
 constexpr int VM_ROWS_MIN = 16;  // fewest rows a workgroup takes in the T^T v partial products
 
 struct WsLayout {
-    size_t c, w, vt, v, u, t, p, tpart, xpart, scal, total;
+    size_t c, w, vt, v, u, t, p, tpart, ppart, xpart, scal, total;
     int Mp, nrb, vm_rows, nt;
 };
 inline WsLayout ws_layout(int M) {
@@ -57,6 +59,7 @@ inline WsLayout ws_layout(int M) {
     auto take = [&](size_t floats) { size_t at = o; o += align_up(floats * sizeof(float), 256); return at; };
     L.c = take(L.Mp); L.w = take(L.Mp); L.vt = take(L.Mp); L.v = take(L.Mp); L.u = take(L.Mp); L.t = take(L.Mp); L.p = take(L.Mp);
     L.tpart = take((size_t)L.nrb * L.Mp);
+    L.ppart = take((size_t)L.nrb * L.Mp);
     L.xpart = take((size_t)L.nt * L.Mp);
     L.scal = take(64);
     L.total = o;
@@ -142,12 +145,55 @@ __device__ __forceinline__ float row_dot(const float* __restrict__ row, const fl
     return wave_sum(acc);
 }
 
+// The first four 16-byte loads of a row, issued before a workgroup's preparation (arg-max, weights, norm) so that the
+// memory pipe is already busy while the small reductions run; row_dot_pref consumes them and continues like row_dot.
+struct RowPref { float4 a[4]; };
+__device__ __forceinline__ void row_prefetch(const float* __restrict__ row, int M, int lane, RowPref& p) {
+    if ((M & 3) != 0) return;
+    const float4* r4 = reinterpret_cast<const float4*>(row);
+    const int n4 = M >> 2;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) p.a[j] = r4[lane + 64 * j < n4 ? lane + 64 * j : 0];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(p.a[j].x), "+v"(p.a[j].y), "+v"(p.a[j].z), "+v"(p.a[j].w));   // issued here, not later
+}
+__device__ __forceinline__ float row_dot_pref(const float* __restrict__ row, const float* __restrict__ x, int M, int lane, const RowPref& p) {
+    if ((M & 3) != 0) return row_dot(row, x, M, lane);
+    const float4* r4 = reinterpret_cast<const float4*>(row);
+    const float4* x4 = reinterpret_cast<const float4*>(x);
+    const int n4 = M >> 2;
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (lane + 64 * j < n4) {
+            const float4 a = p.a[j], b = x4[lane + 64 * j];
+            acc += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+        }
+    int k = lane + 256;
+    for (; k + 192 < n4; k += 256) {
+        float4 a[4], b[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { a[j] = r4[k + 64 * j]; b[j] = x4[k + 64 * j]; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc += a[j].x * b[j].x + a[j].y * b[j].y + a[j].z * b[j].z + a[j].w * b[j].w;
+    }
+    for (; k < n4; k += 64) {
+        const float4 a = r4[k], b = x4[k];
+        acc += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+    }
+    return wave_sum(acc);
+}
+
 // c = Phi_y (Phi_y e_m') (eq. (vc)) with the arg-max of eq. (mt) found by every workgroup for itself; four rows per
 // workgroup, one wavefront each.  Workgroup 0 records m' and xi_m'.
 __global__ __launch_bounds__(256) void matvec_c_kernel(const float* __restrict__ P, const float* __restrict__ xi2, int M,
                                                        Scal* __restrict__ sc, float* __restrict__ c) {
     __shared__ float bv[4];
     __shared__ int bi[4];
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    RowPref pre;
+    row_prefetch(P + (size_t)(r < M ? r : 0) * M, M, lane, pre);
     float best; int mp;
     block_argmax(xi2, M, bv, bi, &best, &mp);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -155,20 +201,9 @@ __global__ __launch_bounds__(256) void matvec_c_kernel(const float* __restrict__
         sc->xi_mp = sqrtf(fmaxf(best, 0.f));
         sc->flags = 0;
     }
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= M) return;
-    const float acc = row_dot(P + (size_t)r * M, P + (size_t)mp * M, M, lane);
+    const float acc = row_dot_pref(P + (size_t)r * M, P + (size_t)mp * M, M, lane, pre);
     if (lane == 0) c[r] = acc;
-}
-
-// y[r] = P[r,:] . x, one wavefront per row
-__global__ __launch_bounds__(256) void matvec_kernel(const float* __restrict__ P, const float* __restrict__ x, int M, float* __restrict__ y) {
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= M) return;
-    const float acc = row_dot(P + (size_t)r * M, x, M, lane);
-    if (lane == 0) y[r] = acc;
 }
 
 // v~ = Phi_y w (first line of eq. (tve)) with the coherence set and the alignment weights w_m = 1/(|set| c_m) on the
@@ -178,6 +213,10 @@ __global__ __launch_bounds__(256) void matvec_vt_kernel(const float* __restrict_
                                                         Scal* __restrict__ sc, float* __restrict__ vt) {
     extern __shared__ __attribute__((aligned(16))) float wl[];   // M weights
     __shared__ float red[4];
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    RowPref pre;
+    row_prefetch(P + (size_t)(r < M ? r : 0) * M, M, lane, pre);
     const float xi_mp = sc->xi_mp;
     // first pass: c_m on the set and 0 elsewhere into LDS, and the size of the set
     float cnt = 0.f;
@@ -213,10 +252,8 @@ __global__ __launch_bounds__(256) void matvec_vt_kernel(const float* __restrict_
         wl[m] = cm != 0.f ? 1.f / (total * cm) : 0.f;
     }
     __syncthreads();
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= M) return;
-    const float acc = row_dot(P + (size_t)r * M, wl, M, lane);
+    const float acc = row_dot_pref(P + (size_t)r * M, wl, M, lane, pre);
     if (lane == 0) vt[r] = acc;
 }
 
@@ -255,14 +292,19 @@ __global__ __launch_bounds__(256) void matvec_refine_kernel(const float* __restr
     if (lane == 0) out[r] = acc;
 }
 
-// v = v~/|v~|, u = Phi_y v (workgroups below nmv: four rows each) and the partial products of t = T^T v over bands of
-// vm_rows rows, tpart[band][j] = sum_{i in band} T[i][j] v[i] (the other workgroups), in one launch.
+// v = v~/|v~|, u = Phi_y v (workgroups below nmv: four rows each) and the partial products of t = T^T v and, with leak,
+// p = Psi^T v over bands of vm_rows rows, tpart[band][j] = sum_{i in band} T[i][j] v[i] (the other workgroups: first
+// those of T, then those of Psi), in one launch.
 __global__ __launch_bounds__(256) void matvec_u_vecmat_kernel(const float* __restrict__ P, const float* __restrict__ T,
-                                                              const float* __restrict__ vt, int M, int Mp, int vm_rows, int nmv,
+                                                              const float* __restrict__ Psi,
+                                                              const float* __restrict__ vt, int M, int Mp, int vm_rows, int nmv, int nvm,
                                                               Scal* __restrict__ sc, float* __restrict__ v, float* __restrict__ u,
-                                                              float* __restrict__ tpart) {
+                                                              float* __restrict__ tpart, float* __restrict__ ppart) {
     __shared__ float red[4];
     float nrm;
+    RowPref pre;
+    const int ur = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if ((int)blockIdx.x < nmv) row_prefetch(P + (size_t)(ur < M ? ur : 0) * M, M, threadIdx.x & 63, pre);
     const float inv = block_inv_norm(vt, M, sc, red, &nrm);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         sc->vnorm = nrm;
@@ -270,14 +312,19 @@ __global__ __launch_bounds__(256) void matvec_u_vecmat_kernel(const float* __res
     }
     if ((int)blockIdx.x < nmv) {
         const int lane = threadIdx.x & 63;
-        const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+        const int r = ur;
         if (r >= M) return;
-        const float acc = row_dot(P + (size_t)r * M, vt, M, lane) * inv;
+        const float acc = row_dot_pref(P + (size_t)r * M, vt, M, lane, pre) * inv;
         if (lane == 0) { u[r] = acc; v[r] = vt[r] * inv; }
         return;
     }
     const int ncol = (M + 255) / 256;
-    const int b = (int)blockIdx.x - nmv;
+    int b = (int)blockIdx.x - nmv;
+    if (b >= nvm) {        // the second set of bands multiplies Psi
+        b -= nvm;
+        T = Psi;
+        tpart = ppart;
+    }
     const int j = (b % ncol) * 256 + threadIdx.x;
     const int band = b / ncol;
     const int i0 = band * vm_rows;
@@ -330,15 +377,20 @@ __global__ __launch_bounds__(256) void partial_sum_kernel(const float* __restric
     partial_sum_block(part, nparts, M, Mp, blockIdx.x, out, red);
 }
 
-// t = T^T v from its partial products (workgroups below nred), and in the last workgroup lambda_e = v^T u
-// (eq. (lambda)), g_e, a_e (eqs. (ge), (xi)), the guard and the diagnostics
-__global__ __launch_bounds__(256) void t_reduce_scalars_kernel(const float* __restrict__ tpart, int nparts, int M, int Mp, int nred,
-                                                               float* __restrict__ t, const float* __restrict__ v,
+// t = T^T v (workgroups below nred) and p = Psi^T v (the next nred, with leak) from their partial products, and in the
+// last workgroup lambda_e = v^T u (eq. (lambda)), g_e, a_e (eqs. (ge), (xi)), the guard and the diagnostics
+__global__ __launch_bounds__(256) void t_reduce_scalars_kernel(const float* __restrict__ tpart, const float* __restrict__ ppart,
+                                                               int nparts, int M, int Mp, int nred, int last,
+                                                               float* __restrict__ t, float* __restrict__ pv, const float* __restrict__ v,
                                                                const float* __restrict__ u, const float* __restrict__ lambda_bar,
                                                                fw_cond_params prm, Scal* __restrict__ sc, fw_cond_info* __restrict__ info) {
     __shared__ float red[16][16];
     if ((int)blockIdx.x < nred) {
         partial_sum_block(tpart, nparts, M, Mp, blockIdx.x, t, red);
+        return;
+    }
+    if ((int)blockIdx.x < last) {
+        partial_sum_block(ppart, nparts, M, Mp, blockIdx.x - nred, pv, red);
         return;
     }
     float dot = 0.f;
@@ -363,15 +415,24 @@ __global__ __launch_bounds__(256) void t_reduce_scalars_kernel(const float* __re
     }
 }
 
-// Fused update over the pair of mirrored tiles (I,J) and (J,I), I >= J.
+// Fused update over the pair of mirrored tiles (I,J) and (J,I), I >= J, one workgroup per pair (pairs enumerated along a
+// one-dimensional grid).  Q, Qs, Phi_y and Phi_x are symmetric and kept exactly so: only their tile (I,J) is read, the
+// mirrored position takes its old values from that tile transposed through LDS, so the pass reads 4 of the 16 M^2 words
+// of a step only half (9 M^2 words move instead of 11).  T and Psi are not symmetric: both of their tiles are read, each
+// position needs its own element and, for the terms T + T^T and Psi + Psi^T, the other tile's transposed one.
 __global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const float* __restrict__ v, const float* __restrict__ u,
                                                      const float* __restrict__ t, const float* __restrict__ p, const Scal* __restrict__ sc,
                                                      float gamma, float beta, int Mp, float* __restrict__ xpart) {
-    const int I = blockIdx.y, J = blockIdx.x;
-    if (J > I) return;
+    // pair index -> (I, J), I >= J: I (I + 1) / 2 + J
+    int I = (int)((sqrtf(8.f * (float)blockIdx.x + 1.f) - 1.f) * 0.5f);
+    while ((I + 1) * (I + 2) / 2 <= (int)blockIdx.x) ++I;
+    while (I * (I + 1) / 2 > (int)blockIdx.x) --I;
+    const int J = (int)blockIdx.x - I * (I + 1) / 2;
     const int M = s.M;
     const bool leak = gamma < 1.f;
-    __shared__ float Ta[TILE][TILE + 1], Tb[TILE][TILE + 1], Pa[TILE][TILE + 1], Pb[TILE][TILE + 1];
+    // four LDS tiles, used twice: first for the transposed elements of T and Psi, then for those of the symmetric
+    // matrices (a workgroup's LDS decides how many of them a compute unit holds, and with them the loads in flight)
+    __shared__ float L0[TILE][TILE + 1], L1[TILE][TILE + 1], L2[TILE][TILE + 1], L3[TILE][TILE + 1];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const float a = sc->a_e, lam = sc->lambda_e;
     const float g1 = 1.f - gamma, g2 = gamma * gamma, gg1 = gamma * g1, g1sq = g1 * g1, b1 = 1.f - beta;
@@ -380,7 +441,18 @@ __global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const floa
     // Everything this workgroup reads is asked for before anything is stored (the state pointers may not be told apart
     // by the compiler, so a load behind a store would wait for it: a chain of round trips that dominates small M).
     const int npos = (I == J) ? 1 : 2;
-    float Qv[2][4], Yv[2][4], Sv[2][4], Xv[2][4], Tv[2][4];
+    float Qv[4], Yv[4], Sv[4], Xv[4], Tv[2][4], Pv[2][4], Tt[2][4], Pt[2][4];
+    {
+        const int j = J * TILE + tx;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = I * TILE + ty + 8 * r;
+            const bool ok = i < M && j < M;
+            const size_t e = ok ? (size_t)i * M + j : 0;
+            Qv[r] = s.Q[e]; Yv[r] = s.Phi_y[e]; Sv[r] = s.Qs[e];
+            Xv[r] = leak ? s.Phi_x[e] : 0.f;
+        }
+    }
 #pragma unroll
     for (int pos = 0; pos < 2; ++pos) {
         const int rowblk = pos == 0 ? I : J, colblk = pos == 0 ? J : I;
@@ -390,23 +462,36 @@ __global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const floa
             const int i = rowblk * TILE + ty + 8 * r;
             const bool ok = pos < npos && i < M && j < M;
             const size_t e = ok ? (size_t)i * M + j : 0;
-            Qv[pos][r] = s.Q[e]; Yv[pos][r] = s.Phi_y[e]; Sv[pos][r] = s.Qs[e];
-            Xv[pos][r] = leak ? s.Phi_x[e] : 0.f;
-            Tv[pos][r] = leak ? 0.f : s.T[e];
+            Tv[pos][r] = s.T[e];
+            Pv[pos][r] = leak ? s.Psi[e] : 0.f;
+            Tt[pos][r] = 0.f; Pt[pos][r] = 0.f;
+            if (!ok) { Tv[pos][r] = 0.f; Pv[pos][r] = 0.f; }
         }
     }
-    // stage the old T and Psi tiles of both positions (only needed for the transposed terms)
     if (leak) {
+        // transposed elements of T and Psi: position a reads tile b transposed and the other way round (the diagonal
+        // tile reads itself)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int yy = ty + 8 * r;
-            const int ia = I * TILE + yy, ja = J * TILE + tx;   // position a
-            const int ib = J * TILE + yy, jb = I * TILE + tx;   // position b (mirrored tile)
-            const bool oka = ia < M && ja < M, okb = ib < M && jb < M;
-            Ta[yy][tx] = oka ? s.T[(size_t)ia * M + ja] : 0.f;
-            Pa[yy][tx] = oka ? s.Psi[(size_t)ia * M + ja] : 0.f;
-            Tb[yy][tx] = okb ? s.T[(size_t)ib * M + jb] : 0.f;
-            Pb[yy][tx] = okb ? s.Psi[(size_t)ib * M + jb] : 0.f;
+            L0[yy][tx] = Tv[0][r]; L1[yy][tx] = Pv[0][r];
+            if (npos == 2) { L2[yy][tx] = Tv[1][r]; L3[yy][tx] = Pv[1][r]; }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int yy = ty + 8 * r;
+            if (npos == 2) { Tt[0][r] = L2[tx][yy]; Pt[0][r] = L3[tx][yy]; Tt[1][r] = L0[tx][yy]; Pt[1][r] = L1[tx][yy]; }
+            else { Tt[0][r] = L0[tx][yy]; Pt[0][r] = L1[tx][yy]; }
+        }
+    }
+    if (npos == 2) {
+        // old values of the symmetric matrices at the mirrored position: the tile (I,J), read transposed where used
+        if (leak) __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int yy = ty + 8 * r;
+            L0[yy][tx] = Qv[r]; L1[yy][tx] = Yv[r]; L2[yy][tx] = Sv[r]; L3[yy][tx] = Xv[r];
         }
         __syncthreads();
     }
@@ -427,29 +512,21 @@ __global__ __launch_bounds__(256) void update_kernel(fw_cond_state s, const floa
                 const size_t e = (size_t)i * M + j;
                 const float vi = v[i], ui = u[i], ti = t[i];
                 const float dij = (i == j) ? 1.f : 0.f;
-                float Told, Tt = 0.f, Psiold = 0.f, Psit = 0.f, phix = 0.f, pi = 0.f;
-                if (leak) {
-                    // own element from the staged tile, transposed element from the mirrored tile
-                    Told = pos == 0 ? Ta[yy][tx] : Tb[yy][tx];
-                    Psiold = pos == 0 ? Pa[yy][tx] : Pb[yy][tx];
-                    if (I == J) { Tt = Ta[tx][yy]; Psit = Pa[tx][yy]; }
-                    else { Tt = pos == 0 ? Tb[tx][yy] : Ta[tx][yy]; Psit = pos == 0 ? Pb[tx][yy] : Pa[tx][yy]; }
-                    phix = Xv[pos][r];
-                    pi = p[i];
-                } else {
-                    Told = Tv[pos][r];
-                }
+                const float Told = Tv[pos][r];
+                const float Qold = pos == 0 ? Qv[r] : L0[tx][yy], Yold = pos == 0 ? Yv[r] : L1[tx][yy];
+                const float Sold = pos == 0 ? Sv[r] : L2[tx][yy];
                 const float Tn = gamma * (Told + a * vi * tj) + g1 * dij;
-                float Qn = g2 * (Qv[pos][r] + aa2 * (ti * tj)) + g1sq * dij;
-                float Yn = g2 * (Yv[pos][r] + a * (vi * uj + ui * vj) + a2lam * (vi * vj));
+                float Qn = g2 * (Qold + aa2 * (ti * tj)) + g1sq * dij;
+                float Yn = g2 * (Yold + a * (vi * uj + ui * vj) + a2lam * (vi * vj));
                 if (leak) {
-                    Qn += gg1 * (a * (vi * tj + ti * vj) + Told + Tt);
-                    Yn += gg1 * (Psiold + Psit + a * (vi * pj + pi * vj)) + g1sq * phix;
+                    const float Psiold = Pv[pos][r], phix = pos == 0 ? Xv[r] : L3[tx][yy], pi = p[i];
+                    Qn += gg1 * (a * (vi * tj + ti * vj) + Told + Tt[pos][r]);
+                    Yn += gg1 * (Psiold + Pt[pos][r] + a * (vi * pj + pi * vj)) + g1sq * phix;
                     s.Psi[e] = gamma * (Psiold + a * vi * pj) + g1 * phix;
                 }
                 s.T[e] = Tn;
                 s.Q[e] = Qn;
-                s.Qs[e] = beta * Sv[pos][r] + b1 * Qn;
+                s.Qs[e] = beta * Sold + b1 * Qn;
                 s.Phi_y[e] = Yn;
                 sq = Yn * Yn;
             }
@@ -499,16 +576,41 @@ fw_status cond_state_init(const fw_cond_state* s, hipStream_t st) {
     return FW_OK;
 }
 
-// New block, new Phi_x: Psi = T Phi_x and Phi_y = T Phi_x T^T = Psi T^T by two M x M x M products on the matrix cores
-// (the gradient GEMM computes G Q^T with Q read along its rows: Phi_x is symmetric, and T is exactly the factor
-// wanted), Phi_y made exactly symmetric from its lower triangle, and the squared row norms for the arg-max.
-fw_status cond_state_refresh(const fw_cond_state* s, float* psi_scratch, hipStream_t st) {
+// Workspace of the refresh: room for Psi when the state has none, then the packed hi / lo planes of T, Phi_x and Psi.
+size_t cond_refresh_workspace_bytes(int M) {
+    return align_up((size_t)M * M * sizeof(float), 256) + 3 * gemm_split_packed_bytes(M, M);
+}
+
+// New block, new Phi_x: Psi = T Phi_x and Phi_y = T Phi_x T^T = Psi T^T by two M x M x M products, Phi_y made exactly
+// symmetric from its lower triangle, and the squared row norms for the arg-max.  Both products have the form A B^T with
+// row-major operands: Phi_x is symmetric (its rows stand for its columns), and T is exactly the factor wanted.
+// With the full workspace the operands are split into bfloat16 hi + lo planes and multiplied on the bfloat16 matrix
+// cores (three products per term, float32 accumulation: see gemm_split.hip), only the lower triangle of Phi_y being
+// computed; without it (allowed when the state carries Psi) the products run in plain float32 on the matrix cores.
+fw_status cond_state_refresh(const fw_cond_state* s, void* ws, size_t ws_bytes, hipStream_t st) {
     const int M = s->M;
-    float* Psi = s->Psi ? s->Psi : psi_scratch;
-    fw_status rc = grad_gemm(s->T, FW_F32, M, M, s->Phi_x, Psi, st);
-    if (rc != FW_OK) return rc;
-    rc = grad_gemm(Psi, FW_F32, M, M, s->T, s->Phi_y, st);
-    if (rc != FW_OK) return rc;
+    const size_t psi_bytes = align_up((size_t)M * M * sizeof(float), 256);
+    char* base = reinterpret_cast<char*>(ws);
+    float* Psi = s->Psi ? s->Psi : reinterpret_cast<float*>(base);
+    fw_status rc;
+    // Below about 1500 features the float32 kernel is as fast (too few 256-wide tiles for 256 compute units, and the
+    // three packing passes cost as much as a product); FW_REFRESH_SPLIT_MIN_M is where the split form starts.
+    if (ws && ws_bytes >= cond_refresh_workspace_bytes(M) && M >= FW_REFRESH_SPLIT_MIN_M) {
+        const size_t pb = gemm_split_packed_bytes(M, M);
+        void* Tp = base + psi_bytes;
+        void* Xp = base + psi_bytes + pb;
+        void* Pp = base + psi_bytes + 2 * pb;
+        if ((rc = gemm_split_pack(s->T, M, M, Tp, st)) != FW_OK) return rc;
+        if ((rc = gemm_split_pack(s->Phi_x, M, M, Xp, st)) != FW_OK) return rc;
+        if ((rc = gemm_split_run(Tp, Xp, M, M, M, 0, Psi, st)) != FW_OK) return rc;
+        if ((rc = gemm_split_pack(Psi, M, M, Pp, st)) != FW_OK) return rc;
+        if ((rc = gemm_split_run(Pp, Tp, M, M, M, 1, s->Phi_y, st)) != FW_OK) return rc;
+    } else {
+        rc = grad_gemm(s->T, FW_F32, M, M, s->Phi_x, Psi, st);
+        if (rc != FW_OK) return rc;
+        rc = grad_gemm(Psi, FW_F32, M, M, s->T, s->Phi_y, st);
+        if (rc != FW_OK) return rc;
+    }
     rc = symmetrize_from_lower(s->Phi_y, M, st);
     if (rc != FW_OK) return rc;
     hipLaunchKernelGGL(rownorm2_kernel, dim3((M + 3) / 4), dim3(256), 0, st, s->Phi_y, M, s->xi2);
@@ -549,6 +651,7 @@ fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_c
     float* t = reinterpret_cast<float*>(base + L.t);
     float* pv = reinterpret_cast<float*>(base + L.p);
     float* tpart = reinterpret_cast<float*>(base + L.tpart);
+    float* ppart = reinterpret_cast<float*>(base + L.ppart);
     float* xpart = reinterpret_cast<float*>(base + L.xpart);
     Scal* sc = reinterpret_cast<Scal*>(base + L.scal);
     const dim3 mv_grid((M + 3) / 4), mv_blk(256);
@@ -562,13 +665,13 @@ fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_c
         hipLaunchKernelGGL(matvec_refine_kernel, mv_grid, mv_blk, 0, st, s->Phi_y, cur, M, sc, other);
         float* tmp = cur; cur = other; other = tmp;
     }
-    hipLaunchKernelGGL(matvec_u_vecmat_kernel, dim3(nmv + ncol * L.nrb), mv_blk, 0, st, s->Phi_y, s->T, cur, M, L.Mp, L.vm_rows, nmv, sc,
-                       v, u, tpart);
-    hipLaunchKernelGGL(t_reduce_scalars_kernel, dim3(nred + 1), mv_blk, 0, st, tpart, L.nrb, M, L.Mp, nred, t, v, u, s->lambda_bar, *p, sc,
-                       info);
-    if (p->gamma < 1.f)
-        hipLaunchKernelGGL(matvec_kernel, mv_grid, mv_blk, 0, st, s->Phi_x, t, M, pv);
-    hipLaunchKernelGGL(update_kernel, dim3(L.nt, L.nt), dim3(256), 0, st, *s, v, u, t, pv, sc, p->gamma, p->beta, L.Mp, xpart);
+    const bool leak = p->gamma < 1.f;
+    const int nvm = ncol * L.nrb, last = nred * (leak ? 2 : 1);
+    hipLaunchKernelGGL(matvec_u_vecmat_kernel, dim3(nmv + nvm * (leak ? 2 : 1)), mv_blk, 0, st, s->Phi_y, s->T, s->Psi, cur, M, L.Mp,
+                       L.vm_rows, nmv, nvm, sc, v, u, tpart, ppart);
+    hipLaunchKernelGGL(t_reduce_scalars_kernel, dim3(last + 1), mv_blk, 0, st, tpart, ppart, L.nrb, M, L.Mp, nred, last, t, pv, v, u,
+                       s->lambda_bar, *p, sc, info);
+    hipLaunchKernelGGL(update_kernel, dim3(L.nt * (L.nt + 1) / 2), dim3(256), 0, st, *s, v, u, t, pv, sc, p->gamma, p->beta, L.Mp, xpart);
     hipLaunchKernelGGL(partial_sum_kernel, dim3(nred), dim3(256), 0, st, xpart, L.nt, M, L.Mp, s->xi2);
     FW_LAUNCH_CHECK();
     return FW_OK;

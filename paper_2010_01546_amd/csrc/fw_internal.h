@@ -152,6 +152,11 @@ fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, vo
 fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const GemmEpilogue& e, hipStream_t st);
 fw_status grad_stage_rows(const void* G, fw_dtype dt, int S, int M, int taps, float* dst, hipStream_t st);
 
+// ---- gemm_split.hip: C = A B^T in float32-grade accuracy on the bfloat16 matrix cores (operands split in hi + lo)
+size_t gemm_split_packed_bytes(int rows, int K);
+fw_status gemm_split_pack(const float* X, int rows, int K, void* Xp, hipStream_t st);
+fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st);
+
 // ---- extras.hip
 fw_status bias_compensate(float* b, const float* W, int S, int M, int taps, const float* mu_old, const float* mu_new, float scale,
                           hipStream_t st);
@@ -164,7 +169,8 @@ fw_status cond_probe(const float* Phi_y, int M, const float* b0, int k, float* o
 size_t cond_workspace_bytes(int M);
 fw_status cond_state_init(const fw_cond_state* s, hipStream_t st);
 fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_cond_info* info, void* ws, hipStream_t st);
-fw_status cond_state_refresh(const fw_cond_state* s, float* psi_scratch, hipStream_t st);
+size_t cond_refresh_workspace_bytes(int M);
+fw_status cond_state_refresh(const fw_cond_state* s, void* ws, size_t ws_bytes, hipStream_t st);
 fw_status cond_static_scratch(void** ptr, size_t* bytes);
 
 // ---- evd.hip

@@ -88,10 +88,14 @@ def test_config1_sixteen_steps():
     assert applied >= 8
 
 
-@pytest.mark.parametrize("M,leak", [(96, True), (130, True), (64, False), (70, False), (1152, True), (2304, True)])
-def test_refresh_for_a_new_block(M, leak):
+@pytest.mark.parametrize("split", [False, True])
+@pytest.mark.parametrize("M,leak", [(96, True), (130, True), (64, False), (70, False), (147, True), (1152, True), (1536, True), (1600, False), (2304, True)])
+def test_refresh_for_a_new_block(M, leak, split):
     """A new block changes Phi_x while T carries over: Psi, Phi_y and the column norms are rebuilt for the T at hand, and
-    the next steps agree with the oracle, which forms T Phi_x T^T explicitly from the new Phi_x."""
+    the next steps agree with the oracle, which forms T Phi_x T^T explicitly from the new Phi_x.  Both forms of the two
+    products: plain float32 (no workspace beyond a stand-in for Psi) and bfloat16 hi + lo splits (full workspace), whose
+    operands carry 16 significant bits: relative residual 2^-17 per operand, about 2^-16 = 1.5e-5 per product term at
+    worst and a few 1e-6 in Frobenius norm, hence the tolerance 2e-5 there."""
     Phi1 = spd(M, 11).astype(np.float32).astype(np.float64)
     Phi2 = spd(M, 12, hi=1.5, lo=-1.0).astype(np.float32).astype(np.float64)
     kw = dict() if leak else dict(gamma=1.0, beta=0.0)
@@ -105,15 +109,27 @@ def test_refresh_for_a_new_block(M, leak):
     run.Phi_x.copy_(dev(Phi2))
     lbar2 = float(np.float32(np.trace(Phi2) / M))
     run.lbar.fill_(lbar2)
-    ws = None if leak else workspace(b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, M))
+    full = b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, M)
+    assert full >= 4 * 4 * M * M
+    if split:
+        ws = workspace(full)
+    else:
+        ws = None if leak else workspace((4 * M * M + 255) // 256 * 256)   # room for Psi only: the float32 form
     b.fw_cond_state_refresh(run.st, ws)
     torch.cuda.synchronize()
+    tol = 2e-5 if split else 1e-5
     want = ora.transformed_covariance(T, Phi2)
     Py = run.host("Phi_y")
-    assert relF(Py, want) < 1e-5 and np.array_equal(Py, Py.T)
+    e_py = relF(Py, want)
+    print(f"M={M} split={split}: rel-F(Phi_y) = {e_py:.2e}")
+    assert e_py < tol and np.array_equal(Py, Py.T)
+    if split and M >= b.FW_REFRESH_SPLIT_MIN_M:
+        assert e_py > 1e-6, "the split form was due but the error is that of plain float32"
+    else:
+        assert e_py < 1e-6, "plain float32 was due"
     if leak:
-        assert relF(run.host("Psi"), T @ Phi2) < 1e-5
-    assert relF(run.host("xi2"), np.sum(want ** 2, axis=0)) < 1e-5
+        assert relF(run.host("Psi"), T @ Phi2) < tol
+    assert relF(run.host("xi2"), np.sum(want ** 2, axis=0)) < 2 * tol
     assert np.array_equal(run.host("T"), T)
     for _ in range(3):   # teacher-forced steps on the new block
         st = ora.CondState(Phi2, run.host("T"), run.host("Q"), run.host("Qs"))
