@@ -117,17 +117,23 @@ def membership_band(M, c_rel):
 def marginal_decision_ok(info, oi, op, band_argmax=BAND, band_set=None):
     """The GPU's integer decisions differ from the oracle's: true when the difference is explained by rounding (the
     GPU's arg-max is within the band of the oracle's maximum, and the GPU's set size lies between the number of members
-    that are in beyond doubt and that number plus the members inside the band)."""
+    that are in beyond doubt and that number plus the members inside the band).  Prints what it found otherwise."""
     M = oi.xi.shape[0]
     band_set = membership_band(M, op.c_rel) if band_set is None else band_set
     if not oi.xi[info.m_prime] >= oi.xi[oi.m_prime] * (1 - band_argmax):
+        print(f"arg-max: gpu {info.m_prime} (xi {oi.xi[info.m_prime]:.9g}) oracle {oi.m_prime} (xi {oi.xi[oi.m_prime]:.9g}), band {band_argmax:g}")
         return False
     xi, c = oi.xi, ora.high_power_subspace(oi.Phi_y, op.c_rel, op.c_abs, 0, forced_m_prime=info.m_prime)[4]
     thr = np.maximum(op.c_rel * xi[info.m_prime] * xi, op.c_abs)
     sure_in = np.abs(c) >= thr * (1 + band_set)
     sure_out = np.abs(c) < thr * (1 - band_set)
     n_marg = int((~sure_in & ~sure_out).sum())
-    return bool(sure_in.sum() <= info.set_size <= sure_in.sum() + n_marg)
+    ok = bool(sure_in.sum() <= info.set_size <= sure_in.sum() + n_marg)
+    if not ok:
+        ratio = np.sort(np.abs(np.abs(c) / thr - 1.0))[:6]
+        print(f"coherence set: gpu size {info.set_size}, oracle {oi.set_size} (m' gpu {info.m_prime}, oracle {oi.m_prime}); sure members "
+              f"{int(sure_in.sum())}, inside the band {n_marg} (band {band_set:g}); smallest relative margins {ratio}")
+    return ok
 
 
 def oracle_params(gp):

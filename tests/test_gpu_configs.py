@@ -217,20 +217,32 @@ def test_free_running_condition_number_trajectory(cfg, n_steps, checkpoints):
     op = oracle_params(gp)
     st_o = ora.CondState.initial(P64)
     c0 = cond_number(np.eye(M), P64)
-    band = 5e-5
     worst, resyncs, longest, since = 0.0, 0, 0, 0
+    drift = 0.0            # rel-F distance of the two T before the step at hand
     for k in range(1, n_steps + 1):
         info = run.step(gp)
         st_o, oi = ora.cond_reduce_step(st_o, lbar32, op)
+        Tg = run.host("T")
         if info.m_prime != oi.m_prime or info.set_size != oi.set_size:
-            assert marginal_decision_ok(info, oi, op, band_argmax=band, band_set=2.0 * membership_band(M, op.c_rel)), \
+            # The estimator weighs the members of the coherence set by 1 / c_m, so weakly coherent members near the
+            # threshold carry large weights and a free run amplifies the distance of two nearby states by a factor of
+            # two to three per step (measured); the guard band of a decision therefore has to cover the distance the
+            # states had BEFORE this step: Phi_y = T Phi_x T^T moves by about twice the relative distance of T, c (a
+            # product of two of its columns) by about four times, i.e. 4 drift / c_rel relative to the threshold.
+            band_set = 2.0 * membership_band(M, op.c_rel) + 2.0 * 4.0 * drift / op.c_rel
+            band_argmax = 5e-5 + 8.0 * drift
+            print(f"{layer.name} step {k}: decisions differ (m' {info.m_prime}/{oi.m_prime}, |set| {info.set_size}/{oi.set_size}); "
+                  f"distance of the two T before the step {drift:.2e}, bands {band_argmax:.1e} / {band_set:.1e}")
+            assert marginal_decision_ok(info, oi, op, band_argmax=band_argmax, band_set=band_set), \
                 f"step {k}: arg-max or coherence set differs beyond rounding and drift"
             st_o = ora.CondState(P64, run.host("T"), run.host("Q"), run.host("Qs"))
             resyncs += 1
             since = 0
+            drift = 0.0
         else:
             since += 1
             longest = max(longest, since)
+            drift = relF(Tg, st_o.T)
         if k in checkpoints:
             cg, co = cond_number(run.host("T"), P64), cond_number(st_o.T, P64)
             dev_rel = abs(cg / co - 1.0)
