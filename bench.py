@@ -96,6 +96,7 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
     ws_cov = torch.empty(b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, M, 0, desc, dt), dtype=torch.uint8, device=dev)
     ws_cond = torch.empty(b.fw_workspace_bytes(b.FW_OP_COND_REDUCE_STEP, M), dtype=torch.uint8, device=dev)
     ws_ref = torch.empty(b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, M), dtype=torch.uint8, device=dev)
+    ws_grad = torch.empty(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S), dtype=torch.uint8, device=dev)
     prm = b.cond_params()                          # the paper's hyper-parameters (Sec. 6)
     alpha = 0.1
     st = b.cond_state(M, Phi, lbar, T, Q, Qs, Py, Psi, xi2)   # holds the nine tensors
@@ -126,7 +127,7 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
         b.fw_cond_reduce_step(st, prm, info, ws_cond)
         if ev is not None:
             ev[4].record()
-        b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout)
+        b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout, ws_grad)
         if ev is not None:
             ev[5].record()
 
@@ -243,9 +244,16 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
           "traffic": None,
           "note": None if M > 1152 else "state of this size stays in the caches: launch- and latency-bound, no HBM fraction claimed"}
     t4 = ex["cond_state_refresh"] * 1e-3
-    rf = {"bound": "mfma", "export": "fw_cond_state_refresh", "kernel": "two M x M x M products + mirror + row norms",
-          "achieved": 4.0 * M ** 3 / t4 / 1e12, "peak": PEAK["f32"] / 1e12, "unit": "TFLOP/s", "frac": 4.0 * M ** 3 / t4 / PEAK["f32"],
-          "ms": ex["cond_state_refresh"], "traffic": None}
+    rp = b.fw_cond_refresh_plan_query(M, b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, M))
+    rpeak = PEAK["bf16" if rp.split else "f32"]
+    rf = {"bound": "mfma", "export": "fw_cond_state_refresh",
+          "kernel": ("3 x split_pack + 2 x gemm_split (bf16 hi/lo operands, 3 MFMA terms per product) + mirror + row norms" if rp.split
+                     else "2 x grad_gemm_f32_strip + mirror + row norms"),
+          "achieved": rp.mfma_flops_issued / t4 / 1e12, "peak": rpeak / 1e12, "unit": "TFLOP/s",
+          "frac": rp.mfma_flops_issued / t4 / rpeak, "ms": ex["cond_state_refresh"], "mfma_flops_issued": rp.mfma_flops_issued,
+          "float32_equivalent_rate_TFLOPs": 4.0 * M ** 3 / t4 / 1e12,
+          "note": "achieved = matrix-core flops issued for both products (whole tiles; the second product only on the lower "
+                  "triangle) / time of the call, packing passes included", "traffic": None}
     t5 = ex["cov_finalize"] * 1e-3
     fin_bytes = 4.0 * (M * (M + 1) + M * M)
     fn = {"bound": "hbm", "export": "fw_cov_finalize", "kernel": "finalize_phi64 + finalize_vec", "achieved": fin_bytes / t5 / 1e9,

@@ -119,8 +119,11 @@ fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, fl
  *   Q      in   [M, M] float32, symmetric (Q or its smoothed version Q_s, eq. (vQs)); may be NULL if T is given
  *   T      in   [M, M] float32 or NULL.  Used only when Q is NULL: Q = T^T T is then built in the workspace first.
  *   G_out  out  [S, M] element type `dt`; must not overlap G
- *   ws     scratch, fw_workspace_bytes(FW_OP_GRAD_TRANSFORM, M, S, NULL, dt) bytes; required when Q is NULL,
- *               optional (but several times faster) for dt = FW_BF16 with Q given
+ *   ws     scratch, fw_workspace_bytes(FW_OP_GRAD_TRANSFORM, M, S, NULL, dt) bytes; required when Q is NULL (the first
+ *               fw_workspace_bytes(FW_OP_GRAD_TRANSFORM, M, 0, NULL, FW_F32) bytes of it suffice for that), optional
+ *               otherwise: with all of it a product with few output tiles (small S) cuts its contraction index into runs
+ *               over more workgroups and adds the runs in a fixed order (same float32 arithmetic, another summation
+ *               order); for dt = FW_BF16 with Q given it also selects the widened form below (several times faster)
  * dt = FW_F32: float32 matrix-core products.
  * dt = FW_BF16 with the workspace: G is widened to float32 in the workspace, the products are float32 on the matrix
  *   cores with Q as it is, G_out is rounded to bfloat16 (nearest even).
@@ -219,6 +222,12 @@ fw_status fw_cond_state_init(const fw_cond_state* st, void* stream);
  *        bytes) of ws to stand in for it (FW_ERR_WORKSPACE otherwise).
  */
 #define FW_REFRESH_SPLIT_MIN_M 1536
+
+/* How fw_cond_state_refresh would run for a given M and workspace size (host arithmetic only): which form the two
+ * products take and the flops the matrix cores execute for them (split form: bfloat16 flops, three terms per float32
+ * multiplication, whole tiles, lower triangle only for Phi_y; float32 form: 4 M^3). */
+typedef struct { int split; double mfma_flops_issued; } fw_refresh_plan;
+fw_status fw_cond_refresh_plan_query(int M, size_t ws_bytes, fw_refresh_plan* plan);
 fw_status fw_cond_state_refresh(const fw_cond_state* st, void* ws, size_t ws_bytes, void* stream);
 
 /* One step: estimate the high-power direction v of Phi_y (Sec. 4.2), lambda_e, g_e, a_e (eqs. (lambda), (ge), (xi)),

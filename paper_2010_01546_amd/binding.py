@@ -26,8 +26,8 @@ FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
 
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",
            "fw_whiten_evd", "fw_cond_state_refresh", "fw_grad_transform_taps", "fw_sgd_update", "fw_bias_compensate",
-           "fw_diagnostics", "fw_cov_plan_query", "fw_cond_reduce_step_static", "fw_cond_probe", "fw_workspace_bytes", "fw_status_string", "fw_version"]
-N_STATUS_EXPORTS = 14   # the leading entries of EXPORTS return fw_status
+           "fw_diagnostics", "fw_cov_plan_query", "fw_cond_reduce_step_static", "fw_cond_probe", "fw_cond_refresh_plan_query", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+N_STATUS_EXPORTS = 15   # the leading entries of EXPORTS return fw_status
 
 
 class fw_conv_desc(C.Structure):
@@ -58,6 +58,10 @@ class fw_cov_plan(C.Structure):
                 ("covered_pixels", C.c_longlong), ("mfma_flops_issued", C.c_double)]
 
 
+class fw_refresh_plan(C.Structure):
+    _fields_ = [("split", C.c_int), ("mfma_flops_issued", C.c_double)]
+
+
 class fw_evd_params(C.Structure):
     _fields_ = [("eps", C.c_float), ("g_max", C.c_float), ("beta", C.c_float), ("tol", C.c_float),
                 ("gain_mode", C.c_int), ("max_sweeps", C.c_int)]
@@ -77,6 +81,7 @@ lib.fw_sgd_update.argtypes = [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.POIN
 lib.fw_bias_compensate.argtypes = [_P, _P, C.c_int, C.c_int, C.c_int, _P, _P, C.c_float, _P]
 lib.fw_diagnostics.argtypes = [_P, _P, C.c_int, _P, _P, C.c_size_t, _P]
 lib.fw_cond_probe.argtypes = [_P, C.c_int, _P, C.c_int, _P, _P, C.c_size_t, _P]
+lib.fw_cond_refresh_plan_query.argtypes = [C.c_int, C.c_size_t, C.POINTER(fw_refresh_plan)]
 lib.fw_cov_plan_query.argtypes = [C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.POINTER(fw_cov_plan)]
 lib.fw_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.c_int]
 lib.fw_workspace_bytes.restype = C.c_size_t
@@ -184,6 +189,13 @@ FW_COND_PROBE_MAX_K = 32
 def fw_cond_probe(Phi_y, M, b0, k, out, ws, stream=None):
     wp, n = _ws(ws)
     return _check(lib.fw_cond_probe(_ptr(Phi_y), M, _ptr(b0), k, _ptr(out), wp, n, _stream(stream)), "fw_cond_probe")
+
+
+def fw_cond_refresh_plan_query(M, ws_bytes) -> fw_refresh_plan:
+    """Host arithmetic only: works without a GPU."""
+    plan = fw_refresh_plan()
+    _check(lib.fw_cond_refresh_plan_query(M, ws_bytes, C.byref(plan)), "fw_cond_refresh_plan_query")
+    return plan
 
 
 def fw_cov_plan_query(dt, lay, d) -> fw_cov_plan:

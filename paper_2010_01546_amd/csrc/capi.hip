@@ -75,6 +75,11 @@ fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const floa
         if (rc != FW_OK) return rc;
         Q = Qb;
     }
+    // workspace beyond the Q build (and the widened gradient): partial strips, so that a product with few tiles can cut
+    // its contraction index into runs over more workgroups
+    const size_t fixed = grad_ws_bytes(M) + (dt == FW_BF16 ? grad_wide_bytes(S, M) : 0);
+    float* part = (ws && ws_bytes >= fixed + grad_gemm_partial_bytes(S, M))
+                      ? reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + fixed) : nullptr;
     if (dt == FW_BF16 && ws && ws_bytes >= grad_ws_bytes(M) + grad_wide_bytes(S, M)) {
         // widened to float32 in the workspace, multiplied in float32, rounded to bfloat16 as the results are stored
         float* G32 = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + grad_ws_bytes(M));
@@ -82,9 +87,9 @@ fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const floa
         if (rc != FW_OK) return rc;
         GemmEpilogue e = {};
         e.out = G_out; e.out_bf16 = 1; e.taps = 1;
-        return grad_gemm_f32(G32, S, M, Q, e, st);
+        return grad_gemm_f32(G32, S, M, Q, e, st, part);
     }
-    return grad_gemm(G, dt, S, M, Q, G_out, st);
+    return grad_gemm(G, dt, S, M, Q, G_out, st, dt == FW_F32 ? part : nullptr);
 }
 
 fw_status fw_grad_transform_taps(const void* G, fw_dtype dt, int S, int M, int taps, const float* Q, void* G_out, void* ws,
@@ -179,6 +184,11 @@ static fw_status cond_step_check(const fw_cond_state* st, const fw_cond_params* 
     return FW_OK;
 }
 
+fw_status fw_cond_refresh_plan_query(int M, size_t ws_bytes, fw_refresh_plan* plan) {
+    if (!plan || M <= 0) return FW_ERR_INVALID_ARG;
+    return cond_refresh_plan(M, ws_bytes, plan) ? FW_OK : FW_ERR_UNSUPPORTED;
+}
+
 fw_status fw_cond_reduce_step(const fw_cond_state* st, const fw_cond_params* p, fw_cond_info* info_dev, void* ws, size_t ws_bytes,
                               void* stream) {
     const fw_status rc = cond_step_check(st, p);
@@ -233,7 +243,7 @@ size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtyp
         }
         case FW_OP_GRAD_TRANSFORM:
             if (M <= 0 || M > 16384) return 0;
-            return grad_ws_bytes(M) + ((dt == FW_BF16 && S > 0) ? grad_wide_bytes(S, M) : 0);
+            return grad_ws_bytes(M) + ((dt == FW_BF16 && S > 0) ? grad_wide_bytes(S, M) : 0) + (S > 0 ? grad_gemm_partial_bytes(S, M) : 0);
         case FW_OP_COND_REDUCE_STEP: return M > 0 && M <= 16384 ? cond_workspace_bytes(M) : 0;
         case FW_OP_WHITEN_EVD: return M > 0 && M <= 16384 ? evd_workspace_bytes(M) : 0;
         case FW_OP_COND_STATE_REFRESH: return M > 0 && M <= 16384 ? cond_refresh_workspace_bytes(M) : 0;

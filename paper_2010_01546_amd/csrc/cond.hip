@@ -581,6 +581,14 @@ size_t cond_refresh_workspace_bytes(int M) {
     return align_up((size_t)M * M * sizeof(float), 256) + 3 * gemm_split_packed_bytes(M, M);
 }
 
+bool cond_refresh_plan(int M, size_t ws_bytes, fw_refresh_plan* plan) {
+    if (M <= 0 || M > 16384) return false;
+    plan->split = (ws_bytes >= cond_refresh_workspace_bytes(M) && M >= FW_REFRESH_SPLIT_MIN_M) ? 1 : 0;
+    if (plan->split) plan->mfma_flops_issued = gemm_split_flops_issued(M, M, M, 0) + gemm_split_flops_issued(M, M, M, 1);
+    else plan->mfma_flops_issued = 4.0 * (double)M * M * M;
+    return true;
+}
+
 // New block, new Phi_x: Psi = T Phi_x and Phi_y = T Phi_x T^T = Psi T^T by two M x M x M products, Phi_y made exactly
 // symmetric from its lower triangle, and the squared row norms for the arg-max.  Both products have the form A B^T with
 // row-major operands: Phi_x is symmetric (its rows stand for its columns), and T is exactly the factor wanted.

@@ -148,13 +148,17 @@ struct GemmEpilogue {
     float* V;         // momentum buffer, or null
     float lr, momentum, wd;
 };
-fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st);
-fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const GemmEpilogue& e, hipStream_t st);
+// `part`: optional scratch of grad_gemm_partial_bytes(S, M) bytes that lets the float32 product cut its contraction index
+// into runs over more workgroups (few tiles otherwise leave compute units idle); null = never cut
+size_t grad_gemm_partial_bytes(int S, int M);
+fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st, float* part = nullptr);
+fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const GemmEpilogue& e, hipStream_t st, float* part = nullptr);
 fw_status grad_stage_rows(const void* G, fw_dtype dt, int S, int M, int taps, float* dst, hipStream_t st);
 
 // ---- gemm_split.hip: C = A B^T in float32-grade accuracy on the bfloat16 matrix cores (operands split in hi + lo)
 size_t gemm_split_packed_bytes(int rows, int K);
 fw_status gemm_split_pack(const float* X, int rows, int K, void* Xp, hipStream_t st);
+double gemm_split_flops_issued(int R, int N, int K, int lower);
 fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st);
 
 // ---- extras.hip
@@ -170,6 +174,7 @@ size_t cond_workspace_bytes(int M);
 fw_status cond_state_init(const fw_cond_state* s, hipStream_t st);
 fw_status cond_reduce_step(const fw_cond_state* s, const fw_cond_params* p, fw_cond_info* info, void* ws, hipStream_t st);
 size_t cond_refresh_workspace_bytes(int M);
+bool cond_refresh_plan(int M, size_t ws_bytes, fw_refresh_plan* plan);
 fw_status cond_state_refresh(const fw_cond_state* s, void* ws, size_t ws_bytes, hipStream_t st);
 fw_status cond_static_scratch(void** ptr, size_t* bytes);
 

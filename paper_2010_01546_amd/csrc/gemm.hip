@@ -98,9 +98,12 @@ struct StripCfg {
 
 // PLAIN: the result is a float32 [S, M] array and nothing else happens to it (the epilogue's other fields are ignored);
 // kept as an instantiation of its own so that the general epilogue costs the plain product no registers.
+// With gridDim.z > 1 the contraction index is cut into gridDim.z runs of `kchunks` whole chunks (the last run takes what
+// is left, the ragged end included); workgroup z then writes its partial strip to part[z][S][M] instead of finishing
+// the result, and strip_reduce_kernel adds the runs in a fixed order and applies the epilogue.
 template <int MF, int C, bool PLAIN>
 __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* __restrict__ G, const float* __restrict__ Q,
-                                                                  GemmEpilogue Out, int S, int M) {
+                                                                  GemmEpilogue Out, int S, int M, int kchunks, float* __restrict__ part) {
     typedef StripCfg<MF, C> K;
     typedef typename Mfma<MF>::acc_t acc_t;
     __shared__ __attribute__((aligned(16))) float sm[K::SMEM];
@@ -125,9 +128,12 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
         const int grow = p == 0 ? min(row0 + r, S - 1) : min(col0 + (p - 1) * MF + r, M - 1);
         doff[i] = grow * M + 4 * q;
     }
+    // this workgroup's run of the contraction index: [kbeg, kbeg + klen)
+    const int kbeg = (int)blockIdx.z * kchunks * K::KC;
+    const int klen = blockIdx.z + 1 == gridDim.z ? M - kbeg : kchunks * K::KC;
     auto dma_one = [&](int k0, int stage, int i) {   // i is a compile-time constant after unrolling
         const int p = i / K::U;
-        dma16((p == 0 ? G : Q) + doff[i] + k0, &sm[stage * K::STAGE + p * K::PANEL + ((i % K::U) * 4 + wave) * 256]);
+        dma16((p == 0 ? G : Q) + doff[i] + kbeg + k0, &sm[stage * K::STAGE + p * K::PANEL + ((i % K::U) * 4 + wave) * 256]);
     };
     auto issue = [&](int c, int stage) {
 #pragma unroll
@@ -159,7 +165,7 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
         for (int t = 0; t < NT; ++t) mfma_one(f, t);
     };
 
-    const int nfull = M / K::KC;
+    const int nfull = klen / K::KC;
     if (nfull > 0) {
         issue(0, 0);
         if (nfull > 1) issue(1, 1);
@@ -208,8 +214,8 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
             if (c + 1 < nfull) iteration(c + 1, fr[1], fr[0], std::false_type());
         }
     }
-    if (nfull * K::KC < M) {   // ragged last chunk through registers, zero beyond M
-        const int k0 = nfull * K::KC;
+    if (nfull * K::KC < klen) {   // ragged last chunk through registers, zero beyond the end
+        const int k0 = kbeg + nfull * K::KC;
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < K::IPW; ++i) {
@@ -249,7 +255,8 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
                     for (int w = 0; w < 4; ++w) v += (w == q) ? acc[(4 * g + q) % C][i] : red[((q * 4 + w) * K::NACC + i) * 64 + lane];
                     const int row = row0 + Mfma<MF>::row(i, lk);
                     if (row < S && col < M) {
-                        if (PLAIN) reinterpret_cast<float*>(Out.out)[(size_t)row * M + col] = v;
+                        if (gridDim.z > 1) part[((size_t)blockIdx.z * S + row) * M + col] = v;
+                        else if (PLAIN) reinterpret_cast<float*>(Out.out)[(size_t)row * M + col] = v;
                         else emit(Out, row, col, M, v);
                     }
                 }
@@ -259,12 +266,18 @@ __global__ __launch_bounds__(256) void grad_gemm_f32_strip_kernel(const float* _
     }
 }
 
-// (MF, C) with the lowest cost: rounds of 256 workgroups x MFMA time of a workgroup, contraction padded to whole chunks
-struct StripChoice { int mf, c; };
-inline StripChoice pick_strip(int S, int M, bool plain) {
+// (MF, C) with the lowest cost: rounds of 256 workgroups x MFMA time of a workgroup, contraction padded to whole chunks.
+// When that choice still leaves three quarters of the compute units without a workgroup (few rows of G), and a
+// workspace for partial strips is at hand, the contraction index is cut into up to STRIP_MAX_RUNS runs of whole chunks;
+// a run shorter than about 16 chunks is not worth it (filling the LDS ring and summing the four wavefronts' strips at
+// the end take about as long as ten chunks: measured, a 256 x 2304 x 2304 product got slower when cut in four).
+struct StripChoice { int mf, c, nks, kchunks; };
+constexpr int STRIP_MAX_RUNS = 8;
+inline StripChoice pick_strip(int S, int M, bool plain, bool can_split) {
     static const int cs[6] = {9, 6, 4, 3, 2, 1};
-    StripChoice best = {32, 1};
+    StripChoice best = {32, 1, 1, 0};
     double best_cost = 1e300;
+    long long best_wgs = 1;
     for (int mf = 32; mf >= 16; mf -= 16)
         for (int ci = 0; ci < 6; ++ci) {
             const int c = cs[ci];
@@ -277,19 +290,48 @@ inline StripChoice pick_strip(int S, int M, bool plain) {
             // a 16x16 tile is a quarter of the MFMA work of a 32x32 tile and reads twice the operands per flop;
             // a wider strip reads fewer operands per MFMA
             const double cost = rounds * c * (mf == 32 ? 1.0 : 0.25 * 1.06) * kpad * (1.0 + 0.02 / c);
-            if (cost < best_cost) { best_cost = cost; best = {mf, c}; }
+            if (cost < best_cost) { best_cost = cost; best = {mf, c, 1, 0}; best_wgs = wgs; }
         }
+    if (can_split && best_wgs <= 64) {
+        const int kc = 4 * (best.mf == 32 ? 8 : 16) * strip_u(best.mf, best.c);
+        const int nchunks = M / kc;
+        int nks = (int)(256 / best_wgs);
+        if (nks > STRIP_MAX_RUNS) nks = STRIP_MAX_RUNS;
+        while (nks > 1 && nchunks / nks < 16) --nks;
+        if (nks > 1) { best.nks = nks; best.kchunks = (nchunks + nks - 1) / nks; }
+    }
     return best;
 }
 
+// sum of the partial strips of the runs, in run order, then the epilogue
+template <bool PLAIN>
+__global__ __launch_bounds__(256) void strip_reduce_kernel(const float* __restrict__ part, int nks, GemmEpilogue Out, int S, int M) {
+    const size_t n4 = (size_t)S * M / 4;
+    const size_t stride = (size_t)S * M;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n4; e += (size_t)gridDim.x * 256) {
+        float4 v = *reinterpret_cast<const float4*>(part + 4 * e);
+        for (int z = 1; z < nks; ++z) {
+            const float4 w = *reinterpret_cast<const float4*>(part + (size_t)z * stride + 4 * e);
+            v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+        }
+        if (PLAIN) {
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(Out.out) + 4 * e) = v;
+        } else {
+            const int row = (int)((4 * e) / M), col = (int)((4 * e) - (size_t)row * M);
+            emit(Out, row, col, M, v.x); emit(Out, row, col + 1, M, v.y); emit(Out, row, col + 2, M, v.z); emit(Out, row, col + 3, M, v.w);
+        }
+    }
+}
+
 template <int MF>
-void launch_strip(int c, const float* G, const float* Q, const GemmEpilogue& Out, int S, int M, hipStream_t st) {
-    const dim3 grid(((M + MF - 1) / MF + c - 1) / c, (S + MF - 1) / MF);
+void launch_strip(const StripChoice& ch, const float* G, const float* Q, const GemmEpilogue& Out, int S, int M, float* part, hipStream_t st) {
+    const int c = ch.c;
+    const dim3 grid(((M + MF - 1) / MF + c - 1) / c, (S + MF - 1) / MF, ch.nks);
     const bool plain = Out.out && !Out.out_bf16 && Out.taps == 1 && !Out.W;
 #define FW_STRIP_LAUNCH(CC)                                                                                                \
-    if (plain) hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, CC, true>), grid, dim3(256), 0, st, G, Q, Out, S, M);   \
+    if (plain) hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, CC, true>), grid, dim3(256), 0, st, G, Q, Out, S, M, ch.kchunks, part);   \
     else if constexpr (!(MF == 32 && CC == 9))                                                                             \
-        hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, CC, false>), grid, dim3(256), 0, st, G, Q, Out, S, M)
+        hipLaunchKernelGGL((grad_gemm_f32_strip_kernel<MF, CC, false>), grid, dim3(256), 0, st, G, Q, Out, S, M, ch.kchunks, part)
     switch (c) {
         case 9: FW_STRIP_LAUNCH(9); break;
         case 6: FW_STRIP_LAUNCH(6); break;
@@ -299,6 +341,12 @@ void launch_strip(int c, const float* G, const float* Q, const GemmEpilogue& Out
         default: FW_STRIP_LAUNCH(1); break;
     }
 #undef FW_STRIP_LAUNCH
+    if (ch.nks > 1) {
+        size_t blocks = ((size_t)S * M / 4 + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        if (plain) hipLaunchKernelGGL(strip_reduce_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, part, ch.nks, Out, S, M);
+        else hipLaunchKernelGGL(strip_reduce_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, part, ch.nks, Out, S, M);
+    }
 }
 
 // M not a multiple of 4 (rows of G and Q not 16-byte aligned): a workgroup owns a 32x32 tile of G_out and its four
@@ -440,20 +488,23 @@ __global__ __launch_bounds__(256) void taps_to_rows_kernel(const void* __restric
 
 }  // namespace
 
-fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const GemmEpilogue& e, hipStream_t st) {
+size_t grad_gemm_partial_bytes(int S, int M) { return align_up((size_t)STRIP_MAX_RUNS * S * M * sizeof(float), 256); }
+
+// part: room for grad_gemm_partial_bytes(S, M) bytes, or null (then the contraction index is not cut into runs)
+fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const GemmEpilogue& e, hipStream_t st, float* part) {
     if ((M & 3) != 0)
         hipLaunchKernelGGL(grad_gemm_f32_small_kernel, dim3((M + 31) / 32, (S + 31) / 32), dim3(256), 0, st, G, Q, e, S, M);
     else {
         const bool plain = e.out && !e.out_bf16 && e.taps == 1 && !e.W;
-        const StripChoice ch = pick_strip(S, M, plain);
-        if (ch.mf == 32) launch_strip<32>(ch.c, G, Q, e, S, M, st);
-        else launch_strip<16>(ch.c, G, Q, e, S, M, st);
+        const StripChoice ch = pick_strip(S, M, plain, part != nullptr);
+        if (ch.mf == 32) launch_strip<32>(ch, G, Q, e, S, M, part, st);
+        else launch_strip<16>(ch, G, Q, e, S, M, part, st);
     }
     FW_LAUNCH_CHECK();
     return FW_OK;
 }
 
-fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st) {
+fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st, float* part) {
     if (dt == FW_BF16) {
         const dim3 grid((M + TN - 1) / TN, (S + TM - 1) / TM);
         hipLaunchKernelGGL(grad_gemm_bf16_kernel, grid, dim3(256), 0, st, reinterpret_cast<const unsigned short*>(G), Q,
@@ -463,7 +514,7 @@ fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, vo
     }
     GemmEpilogue e = {};
     e.out = G_out; e.taps = 1;
-    return grad_gemm_f32(reinterpret_cast<const float*>(G), S, M, Q, e, st);
+    return grad_gemm_f32(reinterpret_cast<const float*>(G), S, M, Q, e, st, part);
 }
 
 // bfloat16 (or per-tap) gradient -> float32 rows in scratch.  src is [S, M] (taps == 1) or [S, M, taps]; dst is

@@ -27,6 +27,7 @@ namespace {
 
 constexpr int SP_NCT = 4;          // column MFMA tile pairs: tile width 256
 constexpr int SP_TC = 64 * SP_NCT;
+constexpr int SP_SBR = 4, SP_SBC = 8;   // super-block of tiles an XCD works through together (full grids)
 
 struct SplitGeom {
     int R, N, K;          // C is [R, N], contraction length K
@@ -107,13 +108,28 @@ __global__ __launch_bounds__(256) void gemm_split_kernel(const uint4* __restrict
     const int per_xcd = (g.ntiles + 7) / 8;
     int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
     if (tile >= g.ntiles || ((int)blockIdx.x >> 3) >= per_xcd) return;
-    int I = 0;
-    for (;;) {
-        const int n = sp_cols_of_row(I, TR, g.ncb, g.lower);
-        if (tile < n) break;
-        tile -= n; ++I;
+    int I = 0, J = 0;
+    if (g.lower) {
+        for (;;) {
+            const int n = sp_cols_of_row(I, TR, g.ncb, g.lower);
+            if (tile < n) break;
+            tile -= n; ++I;
+        }
+        J = tile;
+    } else {
+        // full grid: the run of an XCD walks super-blocks of SP_SBR x SP_SBC tiles (row-major inside), so that the 32 tiles
+        // its compute units hold at a time share few row panels AND few column panels
+        for (int sI = 0; sI < g.nrb; sI += SP_SBR) {
+            const int hr = min(SP_SBR, g.nrb - sI);
+            bool found = false;
+            for (int sJ = 0; sJ < g.ncb; sJ += SP_SBC) {
+                const int wc = min(SP_SBC, g.ncb - sJ);
+                if (tile < hr * wc) { I = sI + tile / wc; J = sJ + tile % wc; found = true; break; }
+                tile -= hr * wc;
+            }
+            if (found) break;
+        }
     }
-    int J = tile;
     I = __builtin_amdgcn_readfirstlane(I); J = __builtin_amdgcn_readfirstlane(J);
 
     // slab this wavefront brings: plane = wave >> 1, parity of the 16-byte group along k = wave & 1
@@ -252,6 +268,13 @@ fw_status gemm_split_pack(const float* X, int rows, int K, void* Xp, hipStream_t
                        reinterpret_cast<uint4*>(Xp));
     FW_LAUNCH_CHECK();
     return FW_OK;
+}
+
+// flops the matrix cores execute for one product (three bfloat16 terms per float32 multiplication, whole tiles)
+double gemm_split_flops_issued(int R, int N, int K, int lower) {
+    SplitGeom g;
+    if (!make_split_geom(R, N, K, lower, &g)) return 0.0;
+    return 3.0 * 2.0 * (double)g.ntiles * g.tr * SP_TC * (8.0 * g.KB);
 }
 
 // C [R, N] = A B^T from the packed operands (A [R, K], B [N, K]); lower != 0: C is known to be symmetric (R == N) and

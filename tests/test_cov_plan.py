@@ -124,3 +124,20 @@ def test_plan_invariants_on_random_layers():
                 assert 1 <= p.regions <= 32 and p.ranges >= p.regions and p.workgroups >= 1
                 assert p.mfma_flops_issued > 0
         assert taken > 200
+
+
+def test_refresh_plan():
+    """The refresh takes the split form only with the full workspace and from FW_REFRESH_SPLIT_MIN_M features on; its
+    issued flops are three bfloat16 terms per product on whole tiles, the second product on the lower triangle only."""
+    full = b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, 4608)
+    p = b.fw_cond_refresh_plan_query(4608, full)
+    assert p.split == 1
+    dense = 2.0 * 4608 ** 3
+    assert 3 * dense * 1.5 <= p.mfma_flops_issued <= 3 * dense * 1.7        # one full product + a good half
+    assert b.fw_cond_refresh_plan_query(4608, full - 256).split == 0
+    assert b.fw_cond_refresh_plan_query(4608, 0).mfma_flops_issued == 2 * dense
+    small = b.fw_cond_refresh_plan_query(b.FW_REFRESH_SPLIT_MIN_M - 64, 1 << 40)
+    assert small.split == 0
+    assert b.fw_cond_refresh_plan_query(b.FW_REFRESH_SPLIT_MIN_M, 1 << 40).split == 1
+    with pytest.raises(b.FwError):
+        b.fw_cond_refresh_plan_query(0, 0)

@@ -29,6 +29,32 @@ def test_f32_with_Q(S, M):
     assert relF(out.cpu().numpy(), want) < 1e-5
 
 
+@pytest.mark.parametrize("S,M", [(32, 64), (64, 576), (70, 200), (256, 2304), (96, 1024), (17, 4608), (1, 2052), (33, 1156), (512, 1152)])
+def test_f32_with_Q_and_the_workspace(S, M):
+    """With the whole workspace a product with few output tiles cuts its contraction index into runs (ragged last run
+    included) and adds them in a fixed order: same result to float32 rounding, and the same bits on a second call."""
+    T32, Q64 = sym_Q(M, M + 5)
+    Q32 = Q64.astype(np.float32)
+    G = (rng.standard_normal((S, M)) * 0.1).astype(np.float32)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S))
+    out = torch.full((S, M), float("nan"), device=DEV)
+    b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, dev(Q32), out, ws)
+    torch.cuda.synchronize()
+    assert relF(out.cpu().numpy(), ora.grad_transform(G, Q32)) < 1e-5
+    out2 = torch.full((S, M), float("nan"), device=DEV)
+    ws.fill_(0xFF)                     # nothing in the workspace may matter between calls
+    b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, dev(Q32), out2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    # bfloat16 gradient through the same path (widened, product in float32, rounded on the way out)
+    Gb = wl.round_to_bf16(G)
+    wsb = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S, None, b.FW_BF16))
+    outb = torch.zeros(S, M, device=DEV, dtype=torch.bfloat16)
+    b.fw_grad_transform(dev(Gb, torch.bfloat16), b.FW_BF16, S, M, None, dev(Q32), outb, wsb)
+    torch.cuda.synchronize()
+    assert relF(outb.float().cpu().numpy(), ora.grad_transform(Gb, Q32)) < 3e-3
+
+
 @pytest.mark.parametrize("S,M", [(32, 64), (5, 7), (64, 576), (70, 200), (130, 147), (33, 260)])
 def test_bf16_with_Q(S, M):
     T32, Q64 = sym_Q(M, M + 1)
