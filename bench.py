@@ -30,13 +30,20 @@ if ROOT not in sys.path:
 PEAK = {"f32": 157.3e12, "bf16": 2.5e15}   # dense MFMA peaks of MI355X, flop/s
 HBM_PEAK = 8.0e12
 
-# HBM bytes (read + written) per fw_cov_accumulate call, all its kernels.  NOT measured by this script: copied from
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --config cN --no-extras --copy-calibration` whose summary is
-# profiles/fw_cov_accumulate_hbm_traffic_counters.txt, each counter scaled by what it reads on a 256 MiB device copy
-# (2 KiB per FETCH_SIZE count, 1 KiB per WRITE_SIZE count).  Default layout (kkc) only.
-PROFILED_TRAFFIC = {"c2": {"read": 122.5e6, "written": 58.9e6},
-                    "c3": {"read": 195.6e6, "written": 116.2e6},
-                    "c4": {"read": 499.9e6, "written": 184.1e6}}
+# HBM bytes (read, written) per call of an export, all its kernels.  NOT measured by this script: copied from rocprofv3
+# --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --config cN --no-cpu-baseline --no-extras --copy-calibration --steps 20
+# --warmup 5` whose summary is profiles/whitened_update_step_hbm_traffic_counters.txt, each counter scaled by what it reads on
+# a 256 MiB device copy appended to the same run.  Default layout (kkc) only.
+PROFILED_TRAFFIC = {
+    "c2": {"cov_accumulate": (122.5e6, 58.9e6), "cond_reduce_step": (13.1e6, 6.9e6), "cond_state_refresh": (2.7e6, 0.7e6),
+           "grad_transform": (17.5e6, 1.5e6), "cov_finalize": (1.7e6, 1.3e6)},
+    "c3": {"cov_accumulate": (195.3e6, 116.2e6), "cond_reduce_step": (196.9e6, 108.3e6), "cond_state_refresh": (454.9e6, 106.3e6),
+           "grad_transform": (40.4e6, 2.4e6), "cov_finalize": (22.0e6, 21.3e6)},
+    "c4": {"cov_accumulate": (500.0e6, 184.1e6), "cond_reduce_step": (778.6e6, 429.8e6), "cond_state_refresh": (2123.1e6, 424.8e6),
+           "grad_transform": (160.9e6, 9.4e6), "cov_finalize": (85.5e6, 85.0e6)},
+}
+TRAFFIC_SOURCE = ("profiles/whitened_update_step_hbm_traffic_counters.txt (rocprofv3 counters of an earlier run of this command, "
+                  "not measured by this run)")
 
 EXPORTS = ("cov_accumulate", "cov_finalize", "cond_state_refresh", "cond_reduce_step", "grad_transform")
 
@@ -214,7 +221,13 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
     dense = float(n_rows) * M * (M + 1)
     peak = PEAK["bf16" if bf16 else "f32"]
     t = ex["cov_accumulate"] * 1e-3
-    tr = PROFILED_TRAFFIC.get(cfg_key) if (layer.is_rows or layout_name == "kkc") else None
+    prof = PROFILED_TRAFFIC.get(cfg_key) if (layer.is_rows or layout_name == "kkc") else None
+
+    def traffic_of(export):
+        if not prof or export not in prof:
+            return {"traffic": None}
+        r_, w_ = prof[export]
+        return {"traffic": r_ + w_, "traffic_read_written": [r_, w_], "traffic_source": TRAFFIC_SOURCE}
     shifted = bool(plan.shift)
     a1 = {"bound": "mfma", "export": "fw_cov_accumulate",
           "kernel": (("pack_images + cov_bf16_tile + shift_tile_assemble + column_sums" if shifted else
@@ -226,23 +239,23 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
           "note": "achieved = flops the matrix cores issue per call (padding included) / time of the call",
           "dense_equivalent_flops": dense, "dense_equivalent_rate_TFLOPs": dense / t / 1e12,
           "speedup_vs_direct_form_flops": dense / issued,
-          "traffic": (tr["read"] + tr["written"]) if tr else None,
-          "traffic_source": "profiles/fw_cov_accumulate_hbm_traffic_counters.txt (rocprofv3 counters of an earlier run of this "
-                            "command, not measured by this run)" if tr else None,
-          "traffic_read_written": tr, "algorithmic_bytes": r["act_bytes"] + 4.0 * M * M,
+          "algorithmic_bytes": r["act_bytes"] + 4.0 * M * M,
           "plan": {"shift": plan.shift, "regions": plan.regions, "differences": plan.differences,
                    "workgroups": plan.workgroups, "ranges": plan.ranges}}
+    a1.update(traffic_of("cov_accumulate"))
     t2 = ex["grad_transform"] * 1e-3
     a2 = {"bound": "mfma", "export": "fw_grad_transform", "kernel": "grad_gemm_f32_strip", "achieved": 2.0 * S * M * M / t2 / 1e12,
-          "peak": PEAK["f32"] / 1e12, "unit": "TFLOP/s", "frac": 2.0 * S * M * M / t2 / PEAK["f32"], "ms": ex["grad_transform"],
-          "traffic": None}
+          "peak": PEAK["f32"] / 1e12, "unit": "TFLOP/s", "frac": 2.0 * S * M * M / t2 / PEAK["f32"], "ms": ex["grad_transform"]}
+    a2.update(traffic_of("grad_transform"))
     words = 16 if r["gamma"] < 1.0 else 10
     t3 = ex["cond_reduce_step"] * 1e-3
     a3 = {"bound": "hbm", "export": "fw_cond_reduce_step", "kernel": "matvec_c + matvec_vt + matvec_u_vecmat + t_reduce_scalars + "
           "matvec + update + partial_sum", "achieved": words * 4.0 * M * M / t3 / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
           "frac": words * 4.0 * M * M / t3 / HBM_PEAK, "ms": ex["cond_reduce_step"], "algorithmic_bytes": words * 4.0 * M * M,
-          "traffic": None,
-          "note": None if M > 1152 else "state of this size stays in the caches: launch- and latency-bound, no HBM fraction claimed"}
+          "note": ("achieved = the algorithmic 16 M^2 words (10 without leak) / time; the update pass reads the symmetric matrices' "
+                   "tiles once for both mirrored positions, so fewer bytes than that move") if M > 1152 else
+                  "state of this size stays in the caches: launch- and latency-bound, no HBM fraction claimed"}
+    a3.update(traffic_of("cond_reduce_step"))
     t4 = ex["cond_state_refresh"] * 1e-3
     rp = b.fw_cond_refresh_plan_query(M, b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, M))
     rpeak = PEAK["bf16" if rp.split else "f32"]
@@ -253,11 +266,13 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
           "frac": rp.mfma_flops_issued / t4 / rpeak, "ms": ex["cond_state_refresh"], "mfma_flops_issued": rp.mfma_flops_issued,
           "float32_equivalent_rate_TFLOPs": 4.0 * M ** 3 / t4 / 1e12,
           "note": "achieved = matrix-core flops issued for both products (whole tiles; the second product only on the lower "
-                  "triangle) / time of the call, packing passes included", "traffic": None}
+                  "triangle) / time of the call, packing passes included"}
+    rf.update(traffic_of("cond_state_refresh"))
     t5 = ex["cov_finalize"] * 1e-3
     fin_bytes = 4.0 * (M * (M + 1) + M * M)
     fn = {"bound": "hbm", "export": "fw_cov_finalize", "kernel": "finalize_phi64 + finalize_vec", "achieved": fin_bytes / t5 / 1e9,
-          "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": fin_bytes / t5 / HBM_PEAK, "ms": ex["cov_finalize"], "traffic": None}
+          "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": fin_bytes / t5 / HBM_PEAK, "ms": ex["cov_finalize"]}
+    fn.update(traffic_of("cov_finalize"))
     return {"a1_cov_accumulate": a1, "a1_cov_finalize": fn, "a2_grad_transform": a2, "a3_cond_reduce_step": a3,
             "a3_cond_state_refresh": rf}
 
