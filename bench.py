@@ -219,7 +219,8 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
     plan = b.fw_cov_plan_query(b.FW_BF16 if bf16 else b.FW_F32, r["lay"], b.conv_desc(*d.astuple()))
     issued = plan.mfma_flops_issued
     dense = float(n_rows) * M * (M + 1)
-    peak = PEAK["bf16" if bf16 else "f32"]
+    split = bool(plan.split_bf16)         # float32 input as hi + lo bfloat16 planes on the bfloat16 kernels
+    peak = PEAK["bf16" if (bf16 or split) else "f32"]
     t = ex["cov_accumulate"] * 1e-3
     prof = PROFILED_TRAFFIC.get(cfg_key) if (layer.is_rows or layout_name == "kkc") else None
 
@@ -230,18 +231,19 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
         return {"traffic": r_ + w_, "traffic_read_written": [r_, w_], "traffic_source": TRAFFIC_SOURCE}
     shifted = bool(plan.shift)
     a1 = {"bound": "mfma", "export": "fw_cov_accumulate",
-          "kernel": (("pack_images + cov_bf16_tile + shift_tile_assemble + column_sums" if shifted else
-                      "pack_images + cov_bf16_tile (+ tile_reduce) + column_sums") if bf16 else
+          "kernel": ((("pack_images + cov_bf16_tile + shift_tile_assemble + column_sums" if shifted else
+                       "pack_images + cov_bf16_tile (+ tile_reduce) + column_sums") + (" + split_fold" if split else "")) if (bf16 or split) else
                      ("shift_partial_f32 + shift_region_reduce + shift_assemble" if shifted else
                       "cov_partial_f32v4 + cov_reduce")) + " = one fw_cov_accumulate",
           "achieved": issued / t / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s", "frac": issued / t / peak,
-          "ms": ex["cov_accumulate"], "mfma_flops_issued": issued,
+          "ms": ex["cov_accumulate"], "mfma_flops_issued": issued, "arithmetic": "bf16 hi+lo split of f32 input, f32 accumulate" if split else
+          ("bf16 x bf16, f32 accumulate" if bf16 else "f32"),
           "note": "achieved = flops the matrix cores issue per call (padding included) / time of the call",
           "dense_equivalent_flops": dense, "dense_equivalent_rate_TFLOPs": dense / t / 1e12,
           "speedup_vs_direct_form_flops": dense / issued,
           "algorithmic_bytes": r["act_bytes"] + 4.0 * M * M,
           "plan": {"shift": plan.shift, "regions": plan.regions, "differences": plan.differences,
-                   "workgroups": plan.workgroups, "ranges": plan.ranges}}
+                   "workgroups": plan.workgroups, "ranges": plan.ranges, "split_bf16": plan.split_bf16}}
     a1.update(traffic_of("cov_accumulate"))
     t2 = ex["grad_transform"] * 1e-3
     a2 = {"bound": "mfma", "export": "fw_grad_transform", "kernel": "grad_gemm_f32_strip", "achieved": 2.0 * S * M * M / t2 / 1e12,

@@ -62,7 +62,16 @@ typedef enum {
  * (stride-1 windows: tap pairs with the same offset share one product) apply.  Both compute the same sums of Sec. 2;
  * AUTO picks by an estimate of the run time.  SHIFT and DIRECT are meant for tuning and for tests that must reach one
  * form at sizes where the estimate prefers the other; where the shift form does not apply the field changes nothing. */
-typedef enum { FW_COV_FORM_AUTO = 0, FW_COV_FORM_SHIFT = 1, FW_COV_FORM_DIRECT = 2 } fw_cov_form;
+typedef enum {
+    FW_COV_FORM_AUTO = 0,     /* by estimate: for float32 input this includes FW_COV_FORM_SPLIT when the layer has at least 4096
+                                 rows and 128 features */
+    FW_COV_FORM_SHIFT = 1,    /* shift form wherever it applies (products in the input's own precision) */
+    FW_COV_FORM_DIRECT = 2,   /* never the shift form (products in the input's own precision) */
+    FW_COV_FORM_SPLIT = 3     /* float32 input only (ignored for bfloat16): every value is split into two bfloat16 numbers
+                                 hi + lo (16 significant bits, residual <= 2^-17 |x| of either sign) and the sums are taken on
+                                 the bfloat16 matrix cores as (hi+lo)(hi+lo) with float32 accumulation: several times faster; the
+                                 residuals are zero-mean rounding errors whose sum over N rows grows like sqrt(N) */
+} fw_cov_form;
 
 /* Geometry of a layer input.  FW_LAYOUT_ROWS: B = N_rows, Cin = M, H = W = kh = kw = stride = 1, pad = 0.
  * `form` (a fw_cov_form) travels with the geometry, so that fw_workspace_bytes, fw_cov_plan_query and fw_cov_accumulate
@@ -86,7 +95,8 @@ typedef enum {
  *   A      i/o  [M, M] float32, accumulated in place (zero it before the first batch of a block)
  *   s      i/o  [M] float32, accumulated in place
  *   ws     scratch, fw_workspace_bytes(FW_OP_COV_ACCUMULATE, M, 0, d, dt) bytes
- * Products are accumulated in float32 on the matrix cores (bf16 inputs: bf16 x bf16 -> float32).  When the rows are
+ * Products are accumulated in float32 on the matrix cores (bf16 inputs: bf16 x bf16 -> float32; float32 inputs: float32
+ * products, or hi + lo bfloat16 pairs in the split form, see fw_cov_form).  When the rows are
  * split into ranges, the partial sums of the ranges are combined in float64 before they are added to A; a tile
  * covered by a single range is added to A directly in float32.  The result is deterministic run to run.
  * Limits: M <= 16384; activation below 2^31 elements.
@@ -320,6 +330,8 @@ typedef struct {
     int shift, regions, differences, workgroups, ranges;
     long long covered_pixels;
     double mfma_flops_issued;
+    int split_bf16;           /* 1: float32 input taken in the split form (the other fields then describe the bfloat16 run on
+                                 twice the channels, mfma_flops_issued counts bfloat16 flops) */
 } fw_cov_plan;
 fw_status fw_cov_plan_query(fw_dtype dt, fw_layout lay, const fw_conv_desc* d, fw_cov_plan* plan);
 

@@ -55,7 +55,7 @@ class fw_sgd_params(C.Structure):
 
 class fw_cov_plan(C.Structure):
     _fields_ = [("shift", C.c_int), ("regions", C.c_int), ("differences", C.c_int), ("workgroups", C.c_int), ("ranges", C.c_int),
-                ("covered_pixels", C.c_longlong), ("mfma_flops_issued", C.c_double)]
+                ("covered_pixels", C.c_longlong), ("mfma_flops_issued", C.c_double), ("split_bf16", C.c_int)]
 
 
 class fw_refresh_plan(C.Structure):
@@ -205,7 +205,7 @@ def fw_cov_plan_query(dt, lay, d) -> fw_cov_plan:
     return plan
 
 
-FW_COV_FORM_AUTO, FW_COV_FORM_SHIFT, FW_COV_FORM_DIRECT = 0, 1, 2
+FW_COV_FORM_AUTO, FW_COV_FORM_SHIFT, FW_COV_FORM_DIRECT, FW_COV_FORM_SPLIT = 0, 1, 2, 3
 
 
 def cond_state(M, Phi_x, lambda_bar, T, Q, Qs, Phi_y, Psi, xi2) -> fw_cond_state:

@@ -10,7 +10,7 @@ bool desc_ok(const fw_conv_desc* d, fw_layout lay) {
     if (d->B <= 0 || d->Cin <= 0 || d->H <= 0 || d->W <= 0 || d->kh <= 0 || d->kw <= 0 || d->stride <= 0 || d->pad < 0) return false;
     if (d->H + 2 * d->pad < d->kh || d->W + 2 * d->pad < d->kw) return false;
     if (d->pad > 0 && (d->pad >= d->kh || d->pad >= d->kw)) return false;  // a window lying wholly in the padding
-    if (d->form != FW_COV_FORM_AUTO && d->form != FW_COV_FORM_SHIFT && d->form != FW_COV_FORM_DIRECT) return false;
+    if (d->form < FW_COV_FORM_AUTO || d->form > FW_COV_FORM_SPLIT) return false;
     if (lay == FW_LAYOUT_ROWS && (d->H != 1 || d->W != 1 || d->kh != 1 || d->kw != 1 || d->stride != 1 || d->pad != 0)) return false;
     return true;
 }
@@ -19,7 +19,7 @@ bool dtype_ok(fw_dtype dt) { return dt == FW_F32 || dt == FW_BF16; }
 bool layout_ok(fw_layout l) { return l == FW_LAYOUT_ROWS || l == FW_LAYOUT_NCHW || l == FW_LAYOUT_NHWC || l == FW_LAYOUT_NHWC_KKC; }
 
 size_t grad_ws_bytes(int M) {
-    fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0};
+    fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0, FW_COV_FORM_DIRECT};   // products in float32, never the split form
     return align_up((size_t)M * M * sizeof(float), 256) + align_up((size_t)M * sizeof(float), 256) +
            cov_workspace_bytes(M, &d, FW_F32, FW_LAYOUT_ROWS);
 }
@@ -63,7 +63,7 @@ fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const floa
         const size_t qbytes = align_up((size_t)M * M * sizeof(float), 256);
         float* sdummy = reinterpret_cast<float*>(base + qbytes);
         const size_t sbytes = align_up((size_t)M * sizeof(float), 256);
-        const fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0};
+        const fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0, FW_COV_FORM_DIRECT};   // products in float32, never the split form
         fw_status rc = fill_f32(Qb, (size_t)M * M, 0.f, st);
         if (rc != FW_OK) return rc;
         rc = fill_f32(sdummy, (size_t)M, 0.f, st);

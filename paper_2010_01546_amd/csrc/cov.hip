@@ -666,6 +666,49 @@ __global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ p, si
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256) p[e] = v;
 }
 
+// ---- float32 activations on the bfloat16 matrix cores (split form).
+// Every value x is written as two bfloat16 numbers, hi = bf16(x) and lo = bf16(x - hi) (hi + lo carries 16 significant
+// bits of x, residual at most 2^-17 |x| and of either sign with equal likelihood), taken as a tensor with twice the
+// channels, [pixel][hi 0..C-1 | lo 0..C-1] (formed by the packing pre-pass of the bfloat16 kernels as it reads the float32
+// tensor: no copy of its own).  The bfloat16 kernels then accumulate the moments of that tensor, and
+//     sum x_i x_j  ~  sum (hi_i + lo_i)(hi_j + lo_j)  =  the four blocks (hi,hi) + (hi,lo) + (lo,hi) + (lo,lo)
+// of its second moments, which split_fold_kernel adds up: four bfloat16 products per float32 product on a pipe sixteen
+// times faster.  The residuals are rounding errors of zero mean, so over N rows their sum grows like sqrt(N) against N
+// for the moment itself.
+// A[i][j] += the four blocks of A2 (moments of the doubled tensor, features ordered (tap, plane, channel), lower triangle
+// valid) that belong to the pair of features (i, j), j <= i, in the caller's order: ckk = 1: m = c * kk + t, else m = t * C + c.
+// The last row of workgroups does the same for the column sums.
+__global__ __launch_bounds__(256) void split_fold_kernel(const float* __restrict__ A2, const float* __restrict__ s2, int M, int C, int kk,
+                                                         int ckk, float* __restrict__ A, float* __restrict__ s) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    auto split_index = [&](int m, int* t, int* c) {
+        if (ckk) { *c = m / kk; *t = m - *c * kk; }
+        else { *t = m / C; *c = m - *t * C; }
+    };
+    const int M2 = 2 * M;
+    if ((int)blockIdx.y == M) {
+        if (j >= M) return;
+        int t, c;
+        split_index(j, &t, &c);
+        s[j] = (float)((double)s[j] + (double)s2[t * 2 * C + c] + (double)s2[t * 2 * C + C + c]);
+        return;
+    }
+    const int i = blockIdx.y;
+    if (j > i) return;
+    int t1, c1, t2, c2;
+    split_index(i, &t1, &c1);
+    split_index(j, &t2, &c2);
+    double v = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        int p = t1 * 2 * C + (k & 1 ? C : 0) + c1, q = t2 * 2 * C + (k & 2 ? C : 0) + c2;
+        if (p < q) { const int x = p; p = q; q = x; }      // A2 holds its lower triangle
+        v += (double)A2[(size_t)p * M2 + q];
+    }
+    float* dst = A + (size_t)i * M + j;
+    *dst = (float)((double)*dst + v);
+}
+
 }  // namespace
 
 fw_status fill_f32(float* p, size_t n, float v, hipStream_t st) {
@@ -684,11 +727,45 @@ static bool nchw_through_copy(const fw_conv_desc* d, fw_dtype dt, fw_layout lay)
 }
 static size_t act_copy_bytes(const fw_conv_desc* d) { return align_up((size_t)d->B * d->Cin * d->H * d->W * sizeof(float), 256); }
 
+// The split form (float32 activations as hi + lo bfloat16 planes on the bfloat16 kernels): taken when asked for, or by
+// the estimate for layers that are large enough for the matrix cores to matter (the float32 MFMA peak is a sixteenth of
+// the bfloat16 one, the split form issues four times the products) and whose rows are many enough for the split
+// residuals to average out.  `lay` is the layout after the NCHW copy, if any.
+struct SplitPlan { fw_conv_desc d2; fw_layout lay2; size_t a2, s2, inner, total; int ckk; };
+static bool split_plan(const fw_conv_desc* d, fw_layout lay, SplitPlan* sp) {
+    if (d->form != FW_COV_FORM_AUTO && d->form != FW_COV_FORM_SPLIT) return false;
+    if (lay == FW_LAYOUT_NCHW) return false;
+    const long long M = (long long)d->Cin * d->kh * d->kw;
+    const long long Ho = (d->H + 2 * d->pad - d->kh) / d->stride + 1, Wo = (d->W + 2 * d->pad - d->kw) / d->stride + 1;
+    const long long n_rows = (long long)d->B * Ho * Wo;
+    if (2 * M > 16384 || (long long)d->B * d->H * d->W * 2 * d->Cin >= (1ll << 31)) return false;
+    if (d->form == FW_COV_FORM_AUTO && (n_rows < 4096 || M < 128)) return false;
+    sp->d2 = *d;
+    sp->d2.Cin = 2 * d->Cin;
+    sp->d2.form = FW_COV_FORM_AUTO;                       // the bfloat16 kernels choose between their own two forms
+    sp->lay2 = lay == FW_LAYOUT_ROWS ? FW_LAYOUT_ROWS : FW_LAYOUT_NHWC_KKC;
+    sp->ckk = (lay == FW_LAYOUT_NHWC) ? 1 : 0;             // caller's feature order (c, ky, kx) against the kernels' (ky, kx, c)
+    sp->inner = cov_bf16_workspace_bytes(&sp->d2, sp->lay2);
+    if (sp->inner == 0) return false;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { const size_t at = o; o += align_up(bytes, 256); return at; };
+    sp->a2 = take((size_t)4 * M * M * sizeof(float));
+    sp->s2 = take((size_t)2 * M * sizeof(float));
+    const size_t in = take(sp->inner);
+    sp->inner = in;                                        // from here on: offset of the bfloat16 kernels' own workspace
+    sp->total = o;
+    return true;
+}
+
 size_t cov_workspace_bytes(int /*M*/, const fw_conv_desc* d, fw_dtype dt, fw_layout lay) {
     if (d && cov_skinny_applies(d, lay)) return cov_skinny_workspace_bytes(d, lay);
     if (dt == FW_BF16) return cov_bf16_workspace_bytes(d, lay);
     if (!d) return 0;
     const bool copy = nchw_through_copy(d, dt, lay);
+    {
+        SplitPlan sp;
+        if (split_plan(d, copy ? FW_LAYOUT_NHWC : lay, &sp)) return sp.total + (copy ? act_copy_bytes(d) : 0);
+    }
     if (cov_shift_applies(d, copy ? FW_LAYOUT_NHWC : lay))
         return cov_shift_workspace_bytes(d, copy ? FW_LAYOUT_NHWC : lay) + (copy ? act_copy_bytes(d) : 0);
     CovGeom g;
@@ -703,6 +780,14 @@ bool cov_plan(const fw_conv_desc* d, fw_dtype dt, fw_layout lay, fw_cov_plan* pl
     if (cov_skinny_plan(d, lay, plan)) return true;
     if (dt == FW_BF16) return cov_bf16_plan(d, lay, plan);
     if (nchw_through_copy(d, dt, lay)) lay = FW_LAYOUT_NHWC;
+    {
+        SplitPlan sp;
+        if (split_plan(d, lay, &sp)) {
+            if (!cov_bf16_plan(&sp.d2, sp.lay2, plan)) return false;
+            plan->split_bf16 = 1;
+            return true;
+        }
+    }
     if (cov_shift_plan(d, lay, plan)) return true;
     CovGeom g;
     if (!make_geom(d, dt, lay, &g)) return false;
@@ -719,6 +804,33 @@ fw_status cov_accumulate(const void* X, fw_dtype dt, fw_layout lay, const fw_con
     if (dt == FW_BF16) return cov_bf16_accumulate(X, lay, d, A, s, ws, ws_bytes, st);
     const bool copy = nchw_through_copy(d, dt, lay);
     if (copy) lay = FW_LAYOUT_NHWC;
+    {
+        SplitPlan sp;
+        if (split_plan(d, lay, &sp)) {
+            const size_t need = sp.total + (copy ? act_copy_bytes(d) : 0);
+            if (!ws || ws_bytes < need) return FW_ERR_WORKSPACE;
+            char* base = reinterpret_cast<char*>(ws);
+            if (copy) {
+                float* Xc = reinterpret_cast<float*>(base + sp.total);
+                const int HW = d->H * d->W;
+                hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3((HW + 31) / 32, (d->Cin + 31) / 32, d->B), dim3(256), 0, st,
+                                   reinterpret_cast<const float*>(X), Xc, d->Cin, HW);
+                FW_LAUNCH_CHECK();
+                X = Xc;
+            }
+            float* A2 = reinterpret_cast<float*>(base + sp.a2);
+            float* s2 = reinterpret_cast<float*>(base + sp.s2);
+            const int M = d->Cin * d->kh * d->kw;
+            // A2 and s2 lie next to each other (a2 then s2): one fill
+            fw_status rc = fill_f32(A2, (sp.s2 - sp.a2) / sizeof(float) + 2 * (size_t)M, 0.f, st);
+            if (rc != FW_OK) return rc;
+            rc = cov_bf16_accumulate(X, sp.lay2, &sp.d2, A2, s2, base + sp.inner, sp.total - sp.inner, st, true);
+            if (rc != FW_OK) return rc;
+            hipLaunchKernelGGL(split_fold_kernel, dim3((M + 255) / 256, M + 1), dim3(256), 0, st, A2, s2, M, d->Cin, d->kh * d->kw, sp.ckk, A, s);
+            FW_LAUNCH_CHECK();
+            return FW_OK;
+        }
+    }
     if (cov_shift_applies(d, lay)) {
         // stride-1 window: tap pairs with the same offset share their products (cov_shift.hip)
         const size_t need = cov_shift_workspace_bytes(d, lay) + (copy ? act_copy_bytes(d) : 0);

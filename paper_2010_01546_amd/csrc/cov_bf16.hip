@@ -106,10 +106,14 @@ typedef unsigned short u16;
 // S8[chunk][yp][xp][c] has a fixed order of additions.
 // The first row of workgroups also writes the unit table: offset (in 16-byte elements) of the top-left tap of every
 // unit, -1 for the padding up to a whole number of chunks.
-template <bool SHIFT>
-__global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict__ X, std::conditional_t<SHIFT, TileGeom, TileCore> g,
+// SPLIT: the source is a float32 tensor with g.Cin / 2 channels; packed channel c < Cin / 2 takes hi = bf16(x) of source
+// channel c, packed channel Cin / 2 + c takes lo = bf16(x - hi) (the split form of float32 moments, see cov.hip).
+template <bool SHIFT, bool SPLIT>
+__global__ __launch_bounds__(256) void pack_images_kernel(const void* __restrict__ Xv, std::conditional_t<SHIFT, TileGeom, TileCore> g,
                                                           uint4* __restrict__ P,
                                                           float* __restrict__ S8, int* __restrict__ utab) {
+    const u16* __restrict__ X = reinterpret_cast<const u16*>(Xv);
+    const float* __restrict__ Xf = reinterpret_cast<const float*>(Xv);
     const int per_img = g.Hp * g.Wp * g.Cin;
     const int e = blockIdx.x * 256 + threadIdx.x;
     const int chunk = blockIdx.y;
@@ -161,8 +165,11 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
     }
     const int y = yp - g.py, x = xp - g.px;
     const bool inside = (unsigned)y < (unsigned)g.H && (unsigned)x < (unsigned)g.W;
-    const long long img_stride = (long long)g.Cin * g.H * g.W;
-    const long long src0 = g.layout == FW_LAYOUT_NCHW ? ((long long)c * g.H + y) * g.W + x : ((long long)y * g.W + x) * g.Cin + c;
+    const int Csrc = SPLIT ? g.Cin >> 1 : g.Cin;            // channels of the source tensor
+    const int csrc = SPLIT ? (c >= Csrc ? c - Csrc : c) : c;
+    const bool lo_plane = SPLIT && c >= Csrc;
+    const long long img_stride = (long long)Csrc * g.H * g.W;
+    const long long src0 = g.layout == FW_LAYOUT_NCHW ? ((long long)csrc * g.H + y) * g.W + x : ((long long)y * g.W + x) * Csrc + csrc;
     const int dst0 = (yp * g.Wp + xp) * g.Cin + c;
     const int bg0 = chunk * g.bg_per_chunk, bg1 = min(g.Bg, bg0 + g.bg_per_chunk);
     float acc = 0.f;
@@ -174,12 +181,18 @@ __global__ __launch_bounds__(256) void pack_images_kernel(const u16* __restrict_
         for (int i = 0; i < 8; ++i) {
             const int b = bg * 8 + i;
             const long long idx = (inside && b < g.B) ? (long long)b * img_stride + src0 : 0;
-            v[i] = X[idx];
+            if constexpr (SPLIT) v[i] = __float_as_uint(Xf[idx]);
+            else v[i] = X[idx];
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             asm volatile("" : "+v"(v[i]));
             if (!(inside && bg * 8 + i < g.B)) v[i] = 0u;
+            if constexpr (SPLIT) {
+                const float xf = __uint_as_float(v[i]);
+                const unsigned short h = f32_to_bf16_rne(xf);
+                v[i] = lo_plane ? (unsigned)f32_to_bf16_rne(xf - bf16_to_f32(h)) : (unsigned)h;   // the difference is exact
+            }
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc += __uint_as_float(v[i] << 16);
@@ -935,8 +948,9 @@ size_t cov_bf16_workspace_bytes(const fw_conv_desc* d, fw_layout lay) {
     return ws_layout(g).total;
 }
 
+// split_f32: X is a float32 tensor with d->Cin / 2 channels, taken as hi + lo bfloat16 planes (d describes the doubled tensor)
 fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws, size_t ws_bytes,
-                              hipStream_t st) {
+                              hipStream_t st, bool split_f32) {
     TileGeom g;
     if (!make_tile_geom(d, lay, &g)) return FW_ERR_UNSUPPORTED;
     const Bf16Ws L = ws_layout(g);
@@ -949,12 +963,11 @@ fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* 
     double* cpart = reinterpret_cast<double*>(base + L.cpart);
     const int per_img = g.Hp * g.Wp * g.Cin;
     const TileCore& core = g;   // the direct form's kernels take the geometry without the regions
-    if (g.shift)
-        hipLaunchKernelGGL(pack_images_kernel<true>, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st,
-                           reinterpret_cast<const u16*>(X), g, P, S8, utab);
-    else
-        hipLaunchKernelGGL(pack_images_kernel<false>, dim3((per_img + 255) / 256, g.bg_chunks), dim3(256), 0, st,
-                           reinterpret_cast<const u16*>(X), core, P, S8, utab);
+    const dim3 pgrid((per_img + 255) / 256, g.bg_chunks);
+    if (g.shift && split_f32) hipLaunchKernelGGL((pack_images_kernel<true, true>), pgrid, dim3(256), 0, st, X, g, P, S8, utab);
+    else if (g.shift) hipLaunchKernelGGL((pack_images_kernel<true, false>), pgrid, dim3(256), 0, st, X, g, P, S8, utab);
+    else if (split_f32) hipLaunchKernelGGL((pack_images_kernel<false, true>), pgrid, dim3(256), 0, st, X, core, P, S8, utab);
+    else hipLaunchKernelGGL((pack_images_kernel<false, false>), pgrid, dim3(256), 0, st, X, core, P, S8, utab);
     FW_LAUNCH_CHECK();
     const dim3 grid(g.shift && !g.spread ? 8 * g.ntiles * ((g.nsplit + 7) / 8) : (g.ntiles * g.nsplit + 7) / 8 * 8);
 #define FW_TILE_LAUNCH(R, C, S, G) hipLaunchKernelGGL((cov_bf16_tile_kernel<R, C, S>), grid, dim3(256), 0, st, P, utab, G, part, A)

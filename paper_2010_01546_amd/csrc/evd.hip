@@ -25,7 +25,7 @@ struct EvdWs {
     int nblk, nblk_even, npairs, nslices;
 };
 inline size_t cov_ws_for(int M) {
-    fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0};
+    fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0, FW_COV_FORM_DIRECT};   // products in float32, never the split form
     return cov_workspace_bytes(M, &d, FW_F32, FW_LAYOUT_ROWS);
 }
 inline EvdWs evd_layout(int M) {
@@ -410,7 +410,7 @@ fw_status whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float* T
     hipLaunchKernelGGL(gains_kernel, dim3(1), dim3(1024), 0, st, lam, M, p->eps, p->g_max, p->gain_mode, lambda, gq, gh);
     FW_LAUNCH_CHECK();
 
-    const fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0};
+    const fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0, FW_COV_FORM_DIRECT};   // products in float32, never the split form
     for (int which = 0; which < 2; ++which) {
         float* out = which == 0 ? T : Q;
         hipLaunchKernelGGL(scale_rows_kernel, dim3(grid_for(n)), dim3(256), 0, st, V, which == 0 ? gq : gh, M, X);

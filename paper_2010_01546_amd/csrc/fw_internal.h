@@ -136,7 +136,7 @@ fw_status cov_skinny_accumulate(const void* X, fw_dtype dt, fw_layout lay, const
 bool cov_bf16_plan(const fw_conv_desc* d, fw_layout lay, fw_cov_plan* plan);
 size_t cov_bf16_workspace_bytes(const fw_conv_desc* d, fw_layout lay);
 fw_status cov_bf16_accumulate(const void* X, fw_layout lay, const fw_conv_desc* d, float* A, float* s, void* ws,
-                              size_t ws_bytes, hipStream_t st);
+                              size_t ws_bytes, hipStream_t st, bool split_f32 = false);
 
 // ---- gemm.hip
 // what the float32 product does with its result (see emit() in gemm.hip)

@@ -16,9 +16,12 @@ SHAPES = [  # B, Cin, H, W, kh, kw, stride, pad
 @pytest.mark.parametrize("shape", SHAPES)
 def test_stride_one_windows_take_the_shift_form(shape, dt):
     B, Cin, H, W, kh, kw, stride, pad = shape
-    d = b.conv_desc(*shape)
+    # float32: the shift form in the input's own precision is asked for (left to itself the estimate would hand the large
+    # layers to the split form, whose plan is that of a bfloat16 layer with twice the channels)
+    d = b.conv_desc(*shape, form=b.FW_COV_FORM_SHIFT if dt == b.FW_F32 else b.FW_COV_FORM_AUTO)
     for lay in (b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NHWC_KKC, b.FW_LAYOUT_NCHW):
         p = b.fw_cov_plan_query(dt, lay, d)
+        assert p.split_bf16 == 0
         if dt == b.FW_BF16 and B < 128 and p.shift == 0:
             continue   # tiny bfloat16 layers: the cost estimate may keep the direct form
         assert p.shift == 1, (shape, lay)
@@ -50,10 +53,15 @@ def test_other_shapes_keep_the_direct_form(shape, lay, dt):
 
 def test_headline_workload_numbers():
     """Config 2: 9 regions, 13 differences, 64 x 832 x 131072 products."""
-    p = b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(128, 64, 32, 32, 3, 3, 1, 1))
+    p = b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(128, 64, 32, 32, 3, 3, 1, 1, form=b.FW_COV_FORM_SHIFT))
     assert (p.shift, p.regions, p.differences) == (1, 9, 13)
     assert p.mfma_flops_issued == 2.0 * 64 * 832 * 131072
     assert p.workgroups <= 256
+    # left to the estimate, the same layer goes to the bfloat16 matrix cores as 128 channels of hi + lo planes (pairs of
+    # pixels as units: 8 differences), and issues bfloat16 flops
+    q = b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(128, 64, 32, 32, 3, 3, 1, 1))
+    bf = b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(128, 128, 32, 32, 3, 3, 1, 1))
+    assert q.split_bf16 == 1 and (q.shift, q.regions, q.differences, q.mfma_flops_issued) == (bf.shift, bf.regions, bf.differences, bf.mfma_flops_issued)
 
 
 def test_bad_arguments():
@@ -77,8 +85,8 @@ def test_form_preference():
     assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(**big, form=b.FW_COV_FORM_DIRECT)).shift == 0
     assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(**big)).shift == 1
     with pytest.raises(b.FwError):
-        b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(**big, form=3))
-    assert b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, 576, 0, b.conv_desc(**big, form=3), b.FW_F32) == 0
+        b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(**big, form=4))
+    assert b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, 576, 0, b.conv_desc(**big, form=4), b.FW_F32) == 0
     # the two forms need different scratch: sized from the same descriptor the call will get
     w_shift = b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, 576, 0, b.conv_desc(**big, form=b.FW_COV_FORM_SHIFT), b.FW_BF16)
     w_direct = b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, 576, 0, b.conv_desc(**big, form=b.FW_COV_FORM_DIRECT), b.FW_BF16)

@@ -24,7 +24,10 @@ def check_layer(layer, layout):
     mu, Phi, phi, lbar = run_finalize(A, s, n, M, 0.0, 1)
     mu_o, Phi_o, phi_o, lbar_o = ora.block_moments(X, 0.0, True)
     assert relF(Phi.cpu().numpy(), Phi_o) < TOL[layer.dtype]
-    assert relF(mu.cpu().numpy(), mu_o) < 1e-6 and relF(phi.cpu().numpy(), phi_o) < 1e-5
+    # the split form keeps 16 significant bits of every value (residual <= 2^-17 |x|): the column sums of a few hundred rows
+    # with means near zero then agree to 1e-5 rather than to float32's 1e-6
+    mu_tol = 1e-5 if layer.meta.get("form") == b.FW_COV_FORM_SPLIT else 1e-6
+    assert relF(mu.cpu().numpy(), mu_o) < mu_tol and relF(phi.cpu().numpy(), phi_o) < 1e-5
     assert abs(float(lbar[0]) - lbar_o) <= 1e-5 * abs(lbar_o)
     Ph = Phi.cpu().numpy()
     assert np.array_equal(Ph, Ph.T)
@@ -224,3 +227,40 @@ def test_seeded_sweep_of_window_shapes(forced_form):
         assert relF(s.cpu().numpy(), s_o) < RAW_TOL[dtype], case
         assert np.array_equal(np.triu(A_h, 1), np.zeros_like(A_h)), case
         done += 1
+
+
+SPLIT_CASES = [  # B, Cin, H, W, kh, kw, stride, pad
+    (9, 64, 8, 8, 3, 3, 1, 1), (5, 24, 9, 7, 3, 3, 1, 1), (4, 16, 11, 10, 5, 5, 2, 2), (6, 6, 7, 9, 3, 3, 1, 0), (3, 32, 6, 6, 1, 1, 1, 0),
+    (17, 12, 5, 6, 2, 3, 1, 1), (2, 132, 6, 5, 3, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("layout", [b.FW_LAYOUT_NHWC, b.FW_LAYOUT_NCHW, b.FW_LAYOUT_NHWC_KKC])
+@pytest.mark.parametrize("B,Cin,H,W,kh,kw,stride,pad", SPLIT_CASES)
+def test_float32_input_in_the_split_form(B, Cin, H, W, kh, kw, stride, pad, layout):
+    """float32 activations taken as hi + lo bfloat16 pairs on the bfloat16 kernels (asked for through the descriptor): the
+    same sums to the accuracy of a 16-bit split, every layout and feature order, windows with and without stride."""
+    d = wl.ConvDesc(B=B, Cin=Cin, H=H, W=W, kh=kh, kw=kw, stride=stride, pad=pad)
+    cd = b.conv_desc(B, Cin, H, W, kh, kw, stride, pad, form=b.FW_COV_FORM_SPLIT)
+    plan = b.fw_cov_plan_query(b.FW_F32, layout, cd)
+    if layout == b.FW_LAYOUT_NCHW and Cin % 4 != 0:
+        assert plan.split_bf16 == 0        # raw NCHW with odd channel counts stays on the float32 kernels
+    else:
+        assert plan.split_bf16 == 1
+    rng = np.random.default_rng(B * 131 + Cin)
+    act = np.abs(rng.standard_normal((B, H, W, Cin)) @ (np.eye(Cin) + 0.3 * rng.standard_normal((Cin, Cin)) / np.sqrt(Cin))).astype(np.float32)
+    check_layer(wl.Layer("split", d, 4, "f32", act, np.zeros((4, d.M), np.float32), meta={"form": b.FW_COV_FORM_SPLIT}), layout)
+
+
+def test_split_form_on_plain_rows_and_by_estimate():
+    # plain rows, asked for
+    layer = wl.small_rows(31, 700, 200, 4, dtype="f32")
+    layer.meta["form"] = b.FW_COV_FORM_SPLIT
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_ROWS, b.conv_desc(*layer.desc.astuple(), form=b.FW_COV_FORM_SPLIT)).split_bf16 == 1
+    check_layer(layer, b.FW_LAYOUT_ROWS)
+    # the estimate takes it for large layers only, and never for bfloat16 input or when a float32 form is asked for
+    big = dict(B=128, Cin=64, H=32, W=32, kh=3, kw=3, stride=1, pad=1)
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(**big)).split_bf16 == 1
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(**big, form=b.FW_COV_FORM_SHIFT)).split_bf16 == 0
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(**big, form=b.FW_COV_FORM_DIRECT)).split_bf16 == 0
+    assert b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(**big, form=b.FW_COV_FORM_SPLIT)).split_bf16 == 0
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(4, 64, 8, 8, 3, 3, 1, 1)).split_bf16 == 0
