@@ -133,7 +133,10 @@ fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, fl
  *               fw_workspace_bytes(FW_OP_GRAD_TRANSFORM, M, 0, NULL, FW_F32) bytes of it suffice for that), optional
  *               otherwise: with all of it a product with few output tiles (small S) cuts its contraction index into runs
  *               over more workgroups and adds the runs in a fixed order (same float32 arithmetic, another summation
- *               order); for dt = FW_BF16 with Q given it also selects the widened form below (several times faster)
+ *               order); for dt = FW_BF16 with Q given it also selects the widened form below (several times faster); for
+ *               dt = FW_F32 with M >= 3072 and S >= 128 it selects the split form: G and Q are split into bfloat16 hi + lo
+ *               planes (16 significant bits each) and multiplied on the bfloat16 matrix cores as hi hi + hi lo + lo hi with
+ *               float32 accumulation (relative Frobenius error a few 1e-6 instead of a few 1e-7; about twice as fast)
  * dt = FW_F32: float32 matrix-core products.
  * dt = FW_BF16 with the workspace: G is widened to float32 in the workspace, the products are float32 on the matrix
  *   cores with Q as it is, G_out is rounded to bfloat16 (nearest even).

@@ -27,6 +27,13 @@ size_t grad_ws_bytes(int M) {
 // bfloat16 (or per-tap) gradients: a float32 copy of the gradient as [rows, M]
 size_t grad_wide_bytes(long long rows, int M) { return align_up((size_t)rows * M * sizeof(float), 256); }
 
+// float32 gradients of layers with many features: the product on the bfloat16 matrix cores with hi + lo split operands
+// (gemm_split.hip) needs the packed planes of Q and of G and room for partial results
+bool grad_split_applies(int S, int M) { return M >= 3072 && S >= 128; }
+size_t grad_split_bytes(int S, int M) {
+    return grad_split_applies(S, M) ? gemm_split_packed_bytes(M, M) + gemm_split_packed_bytes(S, M) + gemm_split_partial_bytes(S, M) : 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -88,6 +95,18 @@ fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const floa
         GemmEpilogue e = {};
         e.out = G_out; e.out_bf16 = 1; e.taps = 1;
         return grad_gemm_f32(G32, S, M, Q, e, st, part);
+    }
+    if (dt == FW_F32 && grad_split_applies(S, M) && ws &&
+        ws_bytes >= fixed + grad_gemm_partial_bytes(S, M) + grad_split_bytes(S, M)) {
+        char* base = reinterpret_cast<char*>(ws) + fixed + grad_gemm_partial_bytes(S, M);
+        void* Qp = base;
+        void* Gp = base + gemm_split_packed_bytes(M, M);
+        float* sp = reinterpret_cast<float*>(base + gemm_split_packed_bytes(M, M) + gemm_split_packed_bytes(S, M));
+        fw_status rc = gemm_split_pack(Q, M, M, Qp, st);          // Q is symmetric: its rows stand for its columns
+        if (rc != FW_OK) return rc;
+        rc = gemm_split_pack(reinterpret_cast<const float*>(G), S, M, Gp, st);
+        if (rc != FW_OK) return rc;
+        return gemm_split_run(Gp, Qp, S, M, M, 0, reinterpret_cast<float*>(G_out), st, sp);
     }
     return grad_gemm(G, dt, S, M, Q, G_out, st, dt == FW_F32 ? part : nullptr);
 }
@@ -243,7 +262,8 @@ size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtyp
         }
         case FW_OP_GRAD_TRANSFORM:
             if (M <= 0 || M > 16384) return 0;
-            return grad_ws_bytes(M) + ((dt == FW_BF16 && S > 0) ? grad_wide_bytes(S, M) : 0) + (S > 0 ? grad_gemm_partial_bytes(S, M) : 0);
+            return grad_ws_bytes(M) + ((dt == FW_BF16 && S > 0) ? grad_wide_bytes(S, M) : 0) + (S > 0 ? grad_gemm_partial_bytes(S, M) : 0) +
+                   ((dt == FW_F32 && S > 0) ? grad_split_bytes(S, M) : 0);
         case FW_OP_COND_REDUCE_STEP: return M > 0 && M <= 16384 ? cond_workspace_bytes(M) : 0;
         case FW_OP_WHITEN_EVD: return M > 0 && M <= 16384 ? evd_workspace_bytes(M) : 0;
         case FW_OP_COND_STATE_REFRESH: return M > 0 && M <= 16384 ? cond_refresh_workspace_bytes(M) : 0;

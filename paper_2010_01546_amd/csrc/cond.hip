@@ -551,6 +551,76 @@ __global__ __launch_bounds__(256) void state_init_kernel(fw_cond_state s) {
     }
 }
 
+// Lower triangle -> full symmetric matrix, and the squared row norms of the result, in one pass over pairs of 64 x 64 tiles
+// (I, J), I >= J (M a multiple of 4): the tile (I,J) is read once with 16-byte loads, written transposed as (J,I) through
+// LDS, and leaves two sets of partial sums of squares: over its columns for the rows of block I, over its rows for the
+// rows of block J (the mirrored tile's rows).  xpart[colblock][row], summed by partial_sum_kernel.
+__global__ __launch_bounds__(256) void mirror_rownorm_kernel(float* __restrict__ P, int M, int Mp, float* __restrict__ xpart) {
+    __shared__ float t[64][65];
+    int I = (int)((sqrtf(8.f * (float)blockIdx.x + 1.f) - 1.f) * 0.5f);
+    while ((I + 1) * (I + 2) / 2 <= (int)blockIdx.x) ++I;
+    while (I * (I + 1) / 2 > (int)blockIdx.x) --I;
+    const int J = (int)blockIdx.x - I * (I + 1) / 2;
+    const int q = threadIdx.x & 15, r0 = threadIdx.x >> 4;     // 16 threads along a row (4 floats each), 16 rows per pass
+    const int j = J * 64 + 4 * q;
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int rr = r0 + 16 * pass, i = I * 64 + rr;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < M && j < M) {
+            v = *reinterpret_cast<const float4*>(P + (size_t)i * M + j);
+            if (I == J) {            // diagonal tile: what lies above the diagonal is taken from below it, after the barrier
+                if (j > i) v.x = 0.f;
+                if (j + 1 > i) v.y = 0.f;
+                if (j + 2 > i) v.z = 0.f;
+                if (j + 3 > i) v.w = 0.f;
+            }
+        }
+        t[rr][4 * q] = v.x; t[rr][4 * q + 1] = v.y; t[rr][4 * q + 2] = v.z; t[rr][4 * q + 3] = v.w;
+    }
+    __syncthreads();
+    if (I == J) {
+        // complete the tile in LDS (upper = lower transposed), write it back whole, one set of row sums
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int rr = r0 + 16 * pass, i = I * 64 + rr;
+            float x[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { const int cc = 4 * q + k; x[k] = cc > rr ? t[cc][rr] : t[rr][cc]; }
+            float sq = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+            if (i < M && j < M) *reinterpret_cast<float4*>(P + (size_t)i * M + j) = make_float4(x[0], x[1], x[2], x[3]);
+            else sq = 0.f;
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+            if (q == 0 && i < M) xpart[(size_t)J * Mp + i] = sq;
+        }
+        return;
+    }
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int rr = r0 + 16 * pass;
+        // row sums of the tile as read (rows of block I, column block J)
+        const int i = I * 64 + rr;
+        float sq = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { const float x = t[rr][4 * q + k]; sq += x * x; }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+        if (q == 0 && i < M) xpart[(size_t)J * Mp + i] = sq;
+        // the mirrored tile: row rr of (J, I) is column rr of (I, J)
+        const int im = J * 64 + rr, jm = I * 64 + 4 * q;
+        float x[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x[k] = t[4 * q + k][rr];
+        float sm = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+        if (im < M && jm < M) *reinterpret_cast<float4*>(P + (size_t)im * M + jm) = make_float4(x[0], x[1], x[2], x[3]);
+        else sm = 0.f;
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) sm += __shfl_xor(sm, o, 64);
+        if (q == 0 && im < M) xpart[(size_t)I * Mp + im] = sm;
+    }
+}
+
 __global__ __launch_bounds__(256) void rownorm2_kernel(const float* __restrict__ P, int M, float* __restrict__ out) {
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -577,8 +647,12 @@ fw_status cond_state_init(const fw_cond_state* s, hipStream_t st) {
 }
 
 // Workspace of the refresh: room for Psi when the state has none, then the packed hi / lo planes of T, Phi_x and Psi.
+static size_t refresh_xpart_bytes(int M) {
+    const size_t nt = (size_t)(M + 63) / 64, Mp = (size_t)(M + 63) / 64 * 64;
+    return align_up(nt * Mp * sizeof(float), 256);
+}
 size_t cond_refresh_workspace_bytes(int M) {
-    return align_up((size_t)M * M * sizeof(float), 256) + 3 * gemm_split_packed_bytes(M, M);
+    return align_up((size_t)M * M * sizeof(float), 256) + 3 * gemm_split_packed_bytes(M, M) + refresh_xpart_bytes(M);
 }
 
 bool cond_refresh_plan(int M, size_t ws_bytes, fw_refresh_plan* plan) {
@@ -613,6 +687,15 @@ fw_status cond_state_refresh(const fw_cond_state* s, void* ws, size_t ws_bytes, 
         if ((rc = gemm_split_run(Tp, Xp, M, M, M, 0, Psi, st)) != FW_OK) return rc;
         if ((rc = gemm_split_pack(Psi, M, M, Pp, st)) != FW_OK) return rc;
         if ((rc = gemm_split_run(Pp, Tp, M, M, M, 1, s->Phi_y, st)) != FW_OK) return rc;
+        if ((M & 3) == 0) {
+            // mirror and squared row norms in one pass
+            float* xpart = reinterpret_cast<float*>(base + psi_bytes + 3 * pb);
+            const int nt = (M + 63) / 64, Mp = nt * 64;
+            hipLaunchKernelGGL(mirror_rownorm_kernel, dim3(nt * (nt + 1) / 2), dim3(256), 0, st, s->Phi_y, M, Mp, xpart);
+            hipLaunchKernelGGL(partial_sum_kernel, dim3((M + 15) / 16), dim3(256), 0, st, xpart, nt, M, Mp, s->xi2);
+            FW_LAUNCH_CHECK();
+            return FW_OK;
+        }
     } else {
         rc = grad_gemm(s->T, FW_F32, M, M, s->Phi_x, Psi, st);
         if (rc != FW_OK) return rc;

@@ -159,7 +159,9 @@ fw_status grad_stage_rows(const void* G, fw_dtype dt, int S, int M, int taps, fl
 size_t gemm_split_packed_bytes(int rows, int K);
 fw_status gemm_split_pack(const float* X, int rows, int K, void* Xp, hipStream_t st);
 double gemm_split_flops_issued(int R, int N, int K, int lower);
-fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st);
+size_t gemm_split_partial_bytes(int R, int N);
+fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st,
+                         float* part = nullptr);
 
 // ---- extras.hip
 fw_status bias_compensate(float* b, const float* W, int S, int M, int taps, const float* mu_old, const float* mu_new, float scale,

@@ -27,6 +27,7 @@ namespace {
 
 constexpr int SP_NCT = 4;          // column MFMA tile pairs: tile width 256
 constexpr int SP_TC = 64 * SP_NCT;
+constexpr int GEMM_SPLIT_MAX_RUNS = 8;
 constexpr int SP_SBR = 4, SP_SBC = 8;   // super-block of tiles an XCD works through together (full grids)
 
 struct SplitGeom {
@@ -35,6 +36,7 @@ struct SplitGeom {
     int nrt, tr, nrb, ncb, ntiles;
     int lower;            // 1: only tiles that touch the lower triangle (C symmetric), entries above the diagonal not written
     int zero_a, zero_b;   // a 16-byte element of each packed operand that is always zero
+    int nks, spk;         // runs the contraction index is cut into (few tiles: more workgroups), stages per run
 };
 
 __host__ __device__ inline int sp_cols_of_row(int I, int tr, int ncb, int lower) {
@@ -89,9 +91,11 @@ __global__ __launch_bounds__(256) void split_pack_kernel(const float* __restrict
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 16) Xp[(size_t)2 * KB * Rp + threadIdx.x] = make_uint4(0, 0, 0, 0);
 }
 
+// With g.nks > 1 workgroup (tile, run) multiplies only the stages of its run and writes the tile to part[run][R][N];
+// split_reduce_kernel adds the runs in a fixed order.
 template <int NRT>
 __global__ __launch_bounds__(256) void gemm_split_kernel(const uint4* __restrict__ Ap, const uint4* __restrict__ Bp, SplitGeom g,
-                                                         float* __restrict__ C) {
+                                                         float* __restrict__ C, float* __restrict__ part) {
     constexpr int NCT = SP_NCT;
     constexpr int TR = 64 * NRT, TC = 64 * NCT;
     constexpr int NF = NRT + NCT;       // groups of 64 rows per slab: NRT of the A panel, NCT of the B panel
@@ -105,9 +109,12 @@ __global__ __launch_bounds__(256) void gemm_split_kernel(const uint4* __restrict
     const int half = lane >> 5, l32 = lane & 31;
     // workgroups go to the 8 XCDs round-robin by linear index: give each XCD a contiguous run of tiles (row-major:
     // neighbours share the A panel and walk through B), so that its L2 serves the panels to several compute units
-    const int per_xcd = (g.ntiles + 7) / 8;
+    const int total = g.ntiles * g.nks;
+    const int per_xcd = (total + 7) / 8;
     int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-    if (tile >= g.ntiles || ((int)blockIdx.x >> 3) >= per_xcd) return;
+    if (tile >= total || ((int)blockIdx.x >> 3) >= per_xcd) return;
+    const int run = __builtin_amdgcn_readfirstlane(tile / g.ntiles);   // run-major: neighbours share the contraction range
+    tile -= run * g.ntiles;
     int I = 0, J = 0;
     if (g.lower) {
         for (;;) {
@@ -143,10 +150,12 @@ __global__ __launch_bounds__(256) void gemm_split_kernel(const uint4* __restrict
         off[k] = ok ? r : 0;
         okmask |= (ok ? 1u : 0u) << k;
     }
-    const int nch = g.KB >> 1;           // stages of 16 contraction entries
+    // stages of 16 contraction entries: this workgroup's run is [c0, c0 + nch)
+    const int c0 = run * g.spk;
+    const int nch = min(g.spk, (g.KB >> 1) - c0);
     auto dma_one = [&](int stage, int c, int k) {   // k is a compile-time constant after unrolling
         const bool live = c < nch && ((okmask >> k) & 1u);
-        const int kb = plane * g.KB + 2 * c + kbl;
+        const int kb = plane * g.KB + 2 * (c0 + c) + kbl;
         const uint4* src = k < NRT ? Ap + (live ? (size_t)kb * g.Rp + off[k] : (size_t)g.zero_a)
                                    : Bp + (live ? (size_t)kb * g.Np + off[k] : (size_t)g.zero_b);
         dma16(src, &pan[stage][wave][64 * k]);
@@ -216,7 +225,8 @@ __global__ __launch_bounds__(256) void gemm_split_kernel(const uint4* __restrict
     FW_WAIT_VM(0);
     FW_WAIT_LGKM0();
 
-    // ---- write-out: 32 lanes along a row of C
+    // ---- write-out: 32 lanes along a row of C (or of this run's partial result)
+    if (g.nks > 1) C = part + (size_t)run * g.R * g.N;
 #pragma unroll
     for (int ta = 0; ta < NRT; ++ta)
 #pragma unroll
@@ -232,26 +242,63 @@ __global__ __launch_bounds__(256) void gemm_split_kernel(const uint4* __restrict
 
 struct SplitWs { size_t a, b, total; };
 
-inline bool make_split_geom(int R, int N, int K, int lower, SplitGeom* g) {
+inline bool make_split_geom(int R, int N, int K, int lower, SplitGeom* g, int max_runs = 1) {
     if (R <= 0 || N <= 0 || K <= 0 || R > 16384 || N > 16384 || K > 16384) return false;
     g->R = R; g->N = N; g->K = K; g->lower = lower;
     g->Rp = (R + 63) / 64 * 64; g->Np = (N + 63) / 64 * 64;
     g->KB = (K + 15) / 16 * 2;
     g->zero_a = 2 * g->KB * g->Rp;
     g->zero_b = 2 * g->KB * g->Np;
-    // tile height (64 nrt): fewest rounds of 256 workgroups times the work of a tile
+    // Tile height (64 nrt) and, when partial results may be used (max_runs > 1) and the tiles are few, the number of runs
+    // the contraction index is cut into: least estimated time = rounds of 256 workgroups x (stages of a run + ring fill) x
+    // time of a stage (its MFMAs, or its loads into LDS at about 23 bytes per cycle and compute unit), plus the pass that
+    // adds runs + 1 copies of the result.  A run keeps at least 32 stages.
+    const int nst = (g->KB) >> 1;
     double best = 1e300;
     for (int nrt = 4; nrt >= 2; --nrt) {
         const int tr = 64 * nrt, nrb = (R + tr - 1) / tr, ncb = (N + SP_TC - 1) / SP_TC;
         long long nt = 0;
         for (int I = 0; I < nrb; ++I) nt += sp_cols_of_row(I, tr, ncb, lower);
-        const double rounds = (double)((nt + 255) / 256);
-        // time of a stage: its MFMAs, or its loads into LDS at about 23 bytes per cycle and compute unit
         const double t_mfma = 3.0 * nrt * SP_NCT * 32.0 + 100.0, t_load = (double)(tr + SP_TC) * 64.0 / 23.0;
-        const double cost = rounds * (t_mfma > t_load ? t_mfma : t_load);
-        if (cost < best * 0.999) { best = cost; g->nrt = nrt; g->tr = tr; g->nrb = nrb; g->ncb = ncb; g->ntiles = (int)nt; }
+        const double t_stage = t_mfma > t_load ? t_mfma : t_load;
+        int kmax = 1;
+        if (max_runs > 1 && nt <= 128) {
+            kmax = (int)(256 / nt);
+            if (kmax > max_runs) kmax = max_runs;
+            while (kmax > 1 && nst / kmax < 32) --kmax;
+        }
+        for (int nks = 1; nks <= kmax; ++nks) {
+            const int spk = (nst + nks - 1) / nks;
+            const int runs = (nst + spk - 1) / spk;
+            const double rounds = (double)((nt * runs + 255) / 256);
+            double cost = rounds * (spk + 5.0) * t_stage;
+            if (runs > 1) cost += (runs + 1.0) * R * (double)N * 4.0 / 4.0e12 * 2.0e9 + 4000.0;
+            if (cost < best * 0.999) {
+                best = cost;
+                g->nrt = nrt; g->tr = tr; g->nrb = nrb; g->ncb = ncb; g->ntiles = (int)nt; g->nks = runs; g->spk = spk;
+            }
+        }
     }
     return true;
+}
+
+// C = sum of the runs' partial results, in run order
+__global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restrict__ part, int nks, size_t n, float* __restrict__ C) {
+    const size_t n4 = n / 4;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n4; e += (size_t)gridDim.x * 256) {
+        float4 v = *reinterpret_cast<const float4*>(part + 4 * e);
+        for (int z = 1; z < nks; ++z) {
+            const float4 w = *reinterpret_cast<const float4*>(part + (size_t)z * n + 4 * e);
+            v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+        }
+        *reinterpret_cast<float4*>(C + 4 * e) = v;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        for (size_t e = 4 * n4; e < n; ++e) {
+            float v = part[e];
+            for (int z = 1; z < nks; ++z) v += part[(size_t)z * n + e];
+            C[e] = v;
+        }
 }
 
 }  // namespace
@@ -271,6 +318,8 @@ fw_status gemm_split_pack(const float* X, int rows, int K, void* Xp, hipStream_t
 }
 
 // flops the matrix cores execute for one product (three bfloat16 terms per float32 multiplication, whole tiles)
+size_t gemm_split_partial_bytes(int R, int N) { return align_up((size_t)GEMM_SPLIT_MAX_RUNS * R * N * sizeof(float), 256); }
+
 double gemm_split_flops_issued(int R, int N, int K, int lower) {
     SplitGeom g;
     if (!make_split_geom(R, N, K, lower, &g)) return 0.0;
@@ -279,18 +328,27 @@ double gemm_split_flops_issued(int R, int N, int K, int lower) {
 
 // C [R, N] = A B^T from the packed operands (A [R, K], B [N, K]); lower != 0: C is known to be symmetric (R == N) and
 // only its lower triangle is written.
-fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st) {
+// part: room for gemm_split_partial_bytes(R, N) bytes, or null (then the contraction index is never cut into runs)
+fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st, float* part) {
     SplitGeom g;
-    if (!make_split_geom(R, N, K, lower, &g)) return FW_ERR_UNSUPPORTED;
-    const dim3 grid((g.ntiles + 7) / 8 * 8);
+    if (!make_split_geom(R, N, K, lower, &g, (part && !lower) ? GEMM_SPLIT_MAX_RUNS : 1)) return FW_ERR_UNSUPPORTED;
+    const dim3 grid((g.ntiles * g.nks + 7) / 8 * 8);
     const uint4* a = reinterpret_cast<const uint4*>(Ap);
     const uint4* b = reinterpret_cast<const uint4*>(Bp);
     switch (g.nrt) {
-        case 4: hipLaunchKernelGGL(gemm_split_kernel<4>, grid, dim3(256), 0, st, a, b, g, C); break;
-        case 3: hipLaunchKernelGGL(gemm_split_kernel<3>, grid, dim3(256), 0, st, a, b, g, C); break;
-        default: hipLaunchKernelGGL(gemm_split_kernel<2>, grid, dim3(256), 0, st, a, b, g, C); break;
+        case 4: hipLaunchKernelGGL(gemm_split_kernel<4>, grid, dim3(256), 0, st, a, b, g, C, part); break;
+        case 3: hipLaunchKernelGGL(gemm_split_kernel<3>, grid, dim3(256), 0, st, a, b, g, C, part); break;
+        default: hipLaunchKernelGGL(gemm_split_kernel<2>, grid, dim3(256), 0, st, a, b, g, C, part); break;
     }
     FW_LAUNCH_CHECK();
+    if (g.nks > 1) {
+        const size_t n = (size_t)R * N;
+        size_t blocks = (n / 4 + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        if (blocks == 0) blocks = 1;
+        hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, g.nks, n, C);
+        FW_LAUNCH_CHECK();
+    }
     return FW_OK;
 }
 

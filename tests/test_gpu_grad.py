@@ -55,6 +55,34 @@ def test_f32_with_Q_and_the_workspace(S, M):
     assert relF(outb.float().cpu().numpy(), ora.grad_transform(Gb, Q32)) < 3e-3
 
 
+@pytest.mark.parametrize("S,M", [(512, 4608), (130, 3076), (256, 3072), (1000, 3200)])
+def test_f32_split_form_for_many_features(S, M):
+    """float32 gradients with M >= 3072 and S >= 128 and the whole workspace: G and Q as bfloat16 hi + lo planes on the
+    bfloat16 matrix cores (three products per term, float32 accumulation), the contraction index cut into runs when S
+    gives few tiles.  Operands carry 16 significant bits: tolerance 2e-5 (float32 form: 1e-5); reproducible bit for bit."""
+    T32, Q64 = sym_Q(M, M + 9)
+    Q32 = Q64.astype(np.float32)
+    G = (rng.standard_normal((S, M)) * 0.1).astype(np.float32)
+    want = ora.grad_transform(G, Q32)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S))
+    out = torch.full((S, M), float("nan"), device=DEV)
+    b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, dev(Q32), out, ws)
+    torch.cuda.synchronize()
+    e = relF(out.cpu().numpy(), want)
+    print(f"S={S} M={M}: rel-F = {e:.2e}")
+    assert 1e-6 < e < 2e-5            # the split form ran (float32 would be below 1e-6) and is inside its tolerance
+    ws.fill_(0xFF)
+    out2 = torch.full((S, M), float("nan"), device=DEV)
+    b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, dev(Q32), out2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    # without the workspace: plain float32
+    out3 = torch.full((S, M), float("nan"), device=DEV)
+    b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, dev(Q32), out3)
+    torch.cuda.synchronize()
+    assert relF(out3.cpu().numpy(), want) < 1e-6
+
+
 @pytest.mark.parametrize("S,M", [(32, 64), (5, 7), (64, 576), (70, 200), (130, 147), (33, 260)])
 def test_bf16_with_Q(S, M):
     T32, Q64 = sym_Q(M, M + 1)
