@@ -158,42 +158,85 @@ __global__ __launch_bounds__(256) void probe_matvec_kernel(const float* __restri
 
 // Step j of the recurrence, one workgroup: alpha_j = q_j . w, w made orthogonal to q_0 .. q_j (twice, all coefficients of
 // a pass taken from the same w), beta_j = |w|, q_(j+1) = w / beta_j -- or the breakdown flag when nothing is left of w.
-__global__ __launch_bounds__(1024) void probe_orth_kernel(int j, int M, size_t ld, double* __restrict__ Qb, double* __restrict__ w,
+// Thread t keeps the entries t, t + 1024, ... of w in registers (PER of them: M <= 1024 PER), so a pass reads the basis
+// twice and nothing else; basis vectors are taken NB at a time so that the loads of a batch are in flight together; the
+// j + 1 coefficients of a pass are summed over the wavefronts in a fixed order.
+template <int PER, int NB>
+__global__ __launch_bounds__(1024) void probe_orth_kernel(int j, int M, size_t ld, double* __restrict__ Qb, const double* __restrict__ w,
                                                           double* __restrict__ alpha, double* __restrict__ beta, double breakdown,
                                                           ProbeState* __restrict__ st) {
     __shared__ double red[16];
-    __shared__ double coef[PROBE_MAX_K + 1];
+    __shared__ double part[16][PROBE_MAX_K + 1];
+    __shared__ double coef[PROBE_MAX_K + 1 + 4];
     if (st->done) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double wl[PER];
     double s0 = 0.0;
-    for (int m = threadIdx.x; m < M; m += 1024) s0 += w[m] * w[m];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int m = threadIdx.x + 1024 * k;
+        wl[k] = m < M ? w[m] : 0.0;
+        s0 += wl[k] * wl[k];
+    }
     const double n0 = sqrt(block_sum_1024(s0, red));
+    // entries beyond M (and basis vectors beyond j) read entry 0 of vector 0 and count with weight zero
+    auto load_batch = [&](int i0, double (&qv)[NB][PER]) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const int m = threadIdx.x + 1024 * k;
+                const bool ok = i0 + b <= j && m < M;
+                qv[b][k] = Qb[ok ? (size_t)(i0 + b) * ld + m : 0];
+                if (!ok) qv[b][k] = 0.0;
+            }
+    };
     for (int pass = 0; pass < 2; ++pass) {
-        // wavefront v takes the basis vectors v, v + 16, ...
-        for (int i = wave; i <= j; i += 16) {
-            const double* qi = Qb + (size_t)i * ld;
-            double d = 0.0;
-            for (int m = lane; m < M; m += 64) d += qi[m] * w[m];
-            d = wave_sum(d);
-            if (lane == 0) coef[i] = d;
+        for (int i0 = 0; i0 <= j; i0 += NB) {
+            double qv[NB][PER];
+            load_batch(i0, qv);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                double d = 0.0;
+#pragma unroll
+                for (int k = 0; k < PER; ++k) d += qv[b][k] * wl[k];
+                d = wave_sum(d);
+                if (lane == 0 && i0 + b <= j) part[wave][i0 + b] = d;
+            }
         }
         __syncthreads();
-        if (pass == 0 && threadIdx.x == 0) alpha[j] = coef[j];
-        for (int m = threadIdx.x; m < M; m += 1024) {
-            double x = w[m];
-            for (int i = 0; i <= j; ++i) x -= coef[i] * Qb[(size_t)i * ld + m];
-            w[m] = x;
-        }
+        if ((int)threadIdx.x <= j) {
+            double c = 0.0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) c += part[v][threadIdx.x];
+            coef[threadIdx.x] = c;
+            if (pass == 0 && (int)threadIdx.x == j) alpha[j] = c;
+        } else if ((int)threadIdx.x <= j + NB) coef[threadIdx.x] = 0.0;
         __syncthreads();
+        for (int i0 = 0; i0 <= j; i0 += NB) {
+            double qv[NB][PER];
+            load_batch(i0, qv);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const double c = coef[i0 + b];
+#pragma unroll
+                for (int k = 0; k < PER; ++k) wl[k] -= c * qv[b][k];
+            }
+        }
     }
     double s1 = 0.0;
-    for (int m = threadIdx.x; m < M; m += 1024) s1 += w[m] * w[m];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) s1 += wl[k] * wl[k];
     const double nw = sqrt(block_sum_1024(s1, red));
     const bool stop = !(nw > breakdown * n0);
     if (!stop) {
         const double inv = 1.0 / nw;
         double* qn = Qb + (size_t)(j + 1) * ld;
-        for (int m = threadIdx.x; m < M; m += 1024) qn[m] = w[m] * inv;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int m = threadIdx.x + 1024 * k;
+            if (m < M) qn[m] = wl[k] * inv;
+        }
     }
     if (threadIdx.x == 0) {
         beta[j] = nw;
@@ -216,29 +259,44 @@ __device__ int tridiag_count_below(const double* a, const double* b, int n, doub
     return cnt;
 }
 
-__global__ void probe_final_kernel(const double* __restrict__ alpha, const double* __restrict__ beta, const ProbeState* __restrict__ st,
-                                   float* __restrict__ out) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+// One wavefront; every round cuts the bracket of each of the two eigenvalues into 65 parts, one trial point per lane.
+__global__ __launch_bounds__(64) void probe_final_kernel(const double* __restrict__ alpha, const double* __restrict__ beta,
+                                                         const ProbeState* __restrict__ st, float* __restrict__ out) {
+    if (blockIdx.x != 0) return;
     const int n = st->steps;
-    if (n <= 0) { out[0] = 0.f; out[1] = 0.f; out[2] = 0.f; out[3] = 0.f; return; }
+    const int lane = threadIdx.x;
+    if (n <= 0) { if (lane < 4) out[lane] = 0.f; return; }
     double lo = alpha[0], hi = alpha[0];
     for (int i = 0; i < n; ++i) {
         const double r = (i > 0 ? fabs(beta[i - 1]) : 0.0) + (i + 1 < n ? fabs(beta[i]) : 0.0);
         lo = fmin(lo, alpha[i] - r);
         hi = fmax(hi, alpha[i] + r);
     }
-    // largest: the smallest x with count_below(x) = n;  smallest: the smallest x with count_below(x) >= 1
-    double a0 = lo, b0 = hi, a1 = lo, b1 = hi;
-    for (int it = 0; it < 64; ++it) {   // the bracket shrinks below float64 resolution
-        const double m0 = 0.5 * (a0 + b0), m1 = 0.5 * (a1 + b1);
-        if (tridiag_count_below(alpha, beta, n, m0) >= n) b0 = m0; else a0 = m0;
-        if (tridiag_count_below(alpha, beta, n, m1) >= 1) b1 = m1; else a1 = m1;
+    // largest: the smallest x with count_below(x) = n;  smallest: the smallest x with count_below(x) >= 1.
+    // count_below grows with x, so the lanes that reach the count form a suffix: the bracket becomes the part between
+    // the last lane that does not and the first that does.
+    double res[2];
+    for (int which = 0; which < 2; ++which) {
+        const int need = which == 0 ? n : 1;
+        double a = lo, b = hi;
+        for (int it = 0; it < 12; ++it) {   // 65^12 > 2^72: the bracket shrinks below float64 resolution
+            const double h = (b - a) / 65.0;
+            const double x = a + h * (double)(lane + 1);
+            const bool ok = tridiag_count_below(alpha, beta, n, x) >= need;
+            const unsigned long long mask = __ballot(ok);
+            const int first = mask ? __ffsll((long long)mask) - 1 : 64;   // trial points first .. 63 reach the count
+            const double na = a + h * (double)first, nb = first < 64 ? a + h * (double)(first + 1) : b;
+            a = na; b = nb;
+        }
+        res[which] = 0.5 * (a + b);
     }
-    const double lmax = 0.5 * (a0 + b0), lmin = 0.5 * (a1 + b1);
-    out[0] = (float)lmax;
-    out[1] = (float)lmin;
-    out[2] = lmin > 0.0 ? (float)(lmax / lmin) : __builtin_inff();
-    out[3] = (float)n;
+    if (lane == 0) {
+        const double lmax = res[0], lmin = res[1];
+        out[0] = (float)lmax;
+        out[1] = (float)lmin;
+        out[2] = lmin > 0.0 ? (float)(lmax / lmin) : __builtin_inff();
+        out[3] = (float)n;
+    }
 }
 
 }  // namespace
@@ -273,7 +331,9 @@ fw_status cond_probe(const float* Phi_y, int M, const float* b0, int k, float* o
     hipLaunchKernelGGL(probe_init_kernel, dim3(1), dim3(1024), 0, st, b0, M, Qb, ps);
     for (int j = 0; j < k; ++j) {
         hipLaunchKernelGGL(probe_matvec_kernel, dim3((M + 3) / 4), dim3(256), 0, st, Phi_y, Qb + (size_t)j * L.ld, M, w, ps);
-        hipLaunchKernelGGL(probe_orth_kernel, dim3(1), dim3(1024), 0, st, j, M, L.ld, Qb, w, alpha, beta, 1e-7, ps);
+        if (M <= 4096) hipLaunchKernelGGL((probe_orth_kernel<4, 4>), dim3(1), dim3(1024), 0, st, j, M, L.ld, Qb, w, alpha, beta, 1e-7, ps);
+        else if (M <= 8192) hipLaunchKernelGGL((probe_orth_kernel<8, 2>), dim3(1), dim3(1024), 0, st, j, M, L.ld, Qb, w, alpha, beta, 1e-7, ps);
+        else hipLaunchKernelGGL((probe_orth_kernel<16, 1>), dim3(1), dim3(1024), 0, st, j, M, L.ld, Qb, w, alpha, beta, 1e-7, ps);
     }
     hipLaunchKernelGGL(probe_final_kernel, dim3(1), dim3(64), 0, st, alpha, beta, ps, out);
     FW_LAUNCH_CHECK();
