@@ -161,6 +161,45 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
         out["ms_per_step_stationary"], st_ms = timed(False)
         out["export_ms_stationary"] = st_ms
 
+        # The same steps on two streams.  fw_cov_accumulate of batch k + 1 depends on that batch only, so a training loop
+        # issues it (at forward time) while batch k's refresh, recursion and gradient product still run: here it goes to
+        # a second stream and waits only for fw_cov_finalize of batch k to have read the sums.  Every export still runs
+        # once per step; the first accumulation and the last step's tail have nothing to overlap with and are timed too.
+        def timed_two_streams():
+            main = torch.cuda.current_stream()
+            side = torch.cuda.Stream()                 # default priority
+            sums_read = torch.cuda.Event()
+            sums_ready = torch.cuda.Event()
+
+            def accumulate(k):
+                with torch.cuda.stream(side):
+                    side.wait_event(sums_read)
+                    As.zero_()
+                    b.fw_cov_accumulate(Xs[k & 1], dt, lay, desc, A, s, ws_cov)
+                    sums_ready.record(side)
+
+            def run(n):
+                sums_read.record(main)
+                accumulate(0)
+                for k in range(n):
+                    main.wait_event(sums_ready)
+                    b.fw_cov_finalize(A, s, n_rows, M, alpha, 0, mu, Phi, phi, lbar)
+                    sums_read.record(main)
+                    if k + 1 < n:
+                        accumulate(k + 1)
+                    b.fw_cond_state_refresh(st, ws_ref)
+                    b.fw_cond_reduce_step(st, prm, info, ws_cond)
+                    b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout, ws_grad)
+                main.wait_stream(side)
+
+            run(warmup)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run(steps)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / steps
+        out["ms_per_step_two_streams"] = timed_two_streams()
+
         def time_call(fn, reps=20):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             fn(); torch.cuda.synchronize()
@@ -349,6 +388,9 @@ def config_record(cfg_key, args, torch, b, wl, np):
     if "ms_per_step_stationary" in r:
         rec["ms_per_step_stationary_phi_x"] = r["ms_per_step_stationary"]
         rec["updates_per_s_stationary_phi_x"] = 1e3 / r["ms_per_step_stationary"]
+    if "ms_per_step_two_streams" in r:
+        rec["ms_per_step_two_streams"] = r["ms_per_step_two_streams"]
+        rec["updates_per_s_two_streams"] = 1e3 / r["ms_per_step_two_streams"]
         rec["breakdown_ms_stationary_phi_x"] = r["export_ms_stationary"]
     if r["extra_ms"]:
         rec["companion_exports_ms"] = r["extra_ms"]
