@@ -35,12 +35,12 @@ HBM_PEAK = 8.0e12
 # --warmup 5` whose summary is profiles/whitened_update_step_hbm_traffic_counters.txt, each counter scaled by what it reads on
 # a 256 MiB device copy appended to the same run.  Default layout (kkc) only.
 PROFILED_TRAFFIC = {
-    "c2": {"cov_accumulate": (122.5e6, 58.9e6), "cond_reduce_step": (13.1e6, 6.9e6), "cond_state_refresh": (2.7e6, 0.7e6),
-           "grad_transform": (17.5e6, 1.5e6), "cov_finalize": (1.7e6, 1.3e6)},
-    "c3": {"cov_accumulate": (195.3e6, 116.2e6), "cond_reduce_step": (196.9e6, 108.3e6), "cond_state_refresh": (454.9e6, 106.3e6),
-           "grad_transform": (40.4e6, 2.4e6), "cov_finalize": (22.0e6, 21.3e6)},
-    "c4": {"cov_accumulate": (500.0e6, 184.1e6), "cond_reduce_step": (778.6e6, 429.8e6), "cond_state_refresh": (2123.1e6, 424.8e6),
-           "grad_transform": (160.9e6, 9.4e6), "cov_finalize": (85.5e6, 85.0e6)},
+    "c2": {"cov_accumulate": (156.7e6, 121.9e6), "cond_reduce_step": (12.6e6, 6.6e6), "cond_state_refresh": (28.6e6, 3.2e6),
+           "grad_transform": (3.8e6, 0.1e6), "cov_finalize": (1.7e6, 1.3e6)},
+    "c3": {"cov_accumulate": (195.3e6, 116.2e6), "cond_reduce_step": (189.3e6, 104.1e6), "cond_state_refresh": (408.7e6, 102.7e6),
+           "grad_transform": (38.9e6, 2.3e6), "cov_finalize": (22.0e6, 21.3e6)},
+    "c4": {"cov_accumulate": (499.7e6, 184.1e6), "cond_reduce_step": (748.7e6, 413.2e6), "cond_state_refresh": (1925.4e6, 410.3e6),
+           "grad_transform": (272.0e6, 163.3e6), "cov_finalize": (85.5e6, 85.0e6)},
 }
 TRAFFIC_SOURCE = ("profiles/whitened_update_step_hbm_traffic_counters.txt (rocprofv3 counters of an earlier run of this command, "
                   "not measured by this run)")
@@ -285,8 +285,15 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
                    "workgroups": plan.workgroups, "ranges": plan.ranges, "split_bf16": plan.split_bf16}}
     a1.update(traffic_of("cov_accumulate"))
     t2 = ex["grad_transform"] * 1e-3
-    a2 = {"bound": "mfma", "export": "fw_grad_transform", "kernel": "grad_gemm_f32_strip", "achieved": 2.0 * S * M * M / t2 / 1e12,
-          "peak": PEAK["f32"] / 1e12, "unit": "TFLOP/s", "frac": 2.0 * S * M * M / t2 / PEAK["f32"], "ms": ex["grad_transform"]}
+    gp = b.fw_grad_plan_query(b.FW_F32, S, M, b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S))
+    gpeak = PEAK["bf16" if gp.split else "f32"]
+    a2 = {"bound": "mfma", "export": "fw_grad_transform",
+          "kernel": ("2 x split_pack + gemm_split (bf16 hi/lo operands, 3 MFMA terms, contraction cut into runs) + split_reduce" if gp.split
+                     else "grad_gemm_f32_strip"),
+          "achieved": gp.mfma_flops_issued / t2 / 1e12, "peak": gpeak / 1e12, "unit": "TFLOP/s",
+          "frac": gp.mfma_flops_issued / t2 / gpeak, "ms": ex["grad_transform"], "mfma_flops_issued": gp.mfma_flops_issued,
+          "float32_equivalent_rate_TFLOPs": 2.0 * S * M * M / t2 / 1e12,
+          "note": "achieved = matrix-core flops issued (whole tiles) / time of the call, packing and run-sum passes included"}
     a2.update(traffic_of("grad_transform"))
     words = 16 if r["gamma"] < 1.0 else 10
     t3 = ex["cond_reduce_step"] * 1e-3

@@ -146,6 +146,12 @@ fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, fl
 fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const float* T, const float* Q,
                             void* G_out, void* ws, size_t ws_bytes, void* stream);
 
+/* How fw_grad_transform would run the product G Q for a given shape, element type and workspace size (host arithmetic
+ * only): whether it takes the split form, and the flops the matrix cores execute for it (split form: bfloat16 flops,
+ * three terms per float32 multiplication, whole tiles; otherwise 2 S M^2 float32 flops). */
+typedef struct { int split; double mfma_flops_issued; } fw_grad_plan;
+fw_status fw_grad_plan_query(fw_dtype dt, int S, int M, size_t ws_bytes, fw_grad_plan* plan);
+
 /* Per-tap form of eq. (mod_weight_grad): a layer of eq. (vzrp3) has one S x M weight matrix per spatial offset n, and
  * each of their gradients is multiplied by the same Q.  For a convolution whitened per input channel (M = Cin, the
  * whitening placed in front of the convolution, Sec. 6) the offsets are the kernel taps:

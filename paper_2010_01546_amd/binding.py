@@ -26,8 +26,9 @@ FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
 
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",
            "fw_whiten_evd", "fw_cond_state_refresh", "fw_grad_transform_taps", "fw_sgd_update", "fw_bias_compensate",
-           "fw_diagnostics", "fw_cov_plan_query", "fw_cond_reduce_step_static", "fw_cond_probe", "fw_cond_refresh_plan_query", "fw_workspace_bytes", "fw_status_string", "fw_version"]
-N_STATUS_EXPORTS = 15   # the leading entries of EXPORTS return fw_status
+           "fw_diagnostics", "fw_cov_plan_query", "fw_cond_reduce_step_static", "fw_cond_probe", "fw_cond_refresh_plan_query",
+           "fw_grad_plan_query", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+N_STATUS_EXPORTS = 16   # the leading entries of EXPORTS return fw_status
 
 
 class fw_conv_desc(C.Structure):
@@ -62,6 +63,10 @@ class fw_refresh_plan(C.Structure):
     _fields_ = [("split", C.c_int), ("mfma_flops_issued", C.c_double)]
 
 
+class fw_grad_plan(C.Structure):
+    _fields_ = [("split", C.c_int), ("mfma_flops_issued", C.c_double)]
+
+
 class fw_evd_params(C.Structure):
     _fields_ = [("eps", C.c_float), ("g_max", C.c_float), ("beta", C.c_float), ("tol", C.c_float),
                 ("gain_mode", C.c_int), ("max_sweeps", C.c_int)]
@@ -83,6 +88,7 @@ lib.fw_diagnostics.argtypes = [_P, _P, C.c_int, _P, _P, C.c_size_t, _P]
 lib.fw_cond_probe.argtypes = [_P, C.c_int, _P, C.c_int, _P, _P, C.c_size_t, _P]
 lib.fw_cond_refresh_plan_query.argtypes = [C.c_int, C.c_size_t, C.POINTER(fw_refresh_plan)]
 lib.fw_cov_plan_query.argtypes = [C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.POINTER(fw_cov_plan)]
+lib.fw_grad_plan_query.argtypes = [C.c_int, C.c_int, C.c_int, C.c_size_t, C.POINTER(fw_grad_plan)]
 lib.fw_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.c_int]
 lib.fw_workspace_bytes.restype = C.c_size_t
 lib.fw_status_string.argtypes = [C.c_int]
@@ -195,6 +201,13 @@ def fw_cond_refresh_plan_query(M, ws_bytes) -> fw_refresh_plan:
     """Host arithmetic only: works without a GPU."""
     plan = fw_refresh_plan()
     _check(lib.fw_cond_refresh_plan_query(M, ws_bytes, C.byref(plan)), "fw_cond_refresh_plan_query")
+    return plan
+
+
+def fw_grad_plan_query(dt, S, M, ws_bytes) -> fw_grad_plan:
+    """Host arithmetic only: works without a GPU."""
+    plan = fw_grad_plan()
+    _check(lib.fw_grad_plan_query(dt, S, M, ws_bytes, C.byref(plan)), "fw_grad_plan_query")
     return plan
 
 

@@ -203,6 +203,16 @@ static fw_status cond_step_check(const fw_cond_state* st, const fw_cond_params* 
     return FW_OK;
 }
 
+fw_status fw_grad_plan_query(fw_dtype dt, int S, int M, size_t ws_bytes, fw_grad_plan* plan) {
+    if (!plan || S <= 0 || M <= 0 || (dt != FW_F32 && dt != FW_BF16)) return FW_ERR_INVALID_ARG;
+    if (M > 16384) return FW_ERR_UNSUPPORTED;
+    const size_t fixed = grad_ws_bytes(M) + (dt == FW_BF16 ? grad_wide_bytes(S, M) : 0);
+    plan->split = dt == FW_F32 && grad_split_applies(S, M) &&
+                  ws_bytes >= fixed + grad_gemm_partial_bytes(S, M) + grad_split_bytes(S, M);
+    plan->mfma_flops_issued = plan->split ? gemm_split_flops_issued(S, M, M, 0, true) : 2.0 * (double)S * M * M;
+    return FW_OK;
+}
+
 fw_status fw_cond_refresh_plan_query(int M, size_t ws_bytes, fw_refresh_plan* plan) {
     if (!plan || M <= 0) return FW_ERR_INVALID_ARG;
     return cond_refresh_plan(M, ws_bytes, plan) ? FW_OK : FW_ERR_UNSUPPORTED;

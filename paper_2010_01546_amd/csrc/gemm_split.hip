@@ -320,9 +320,10 @@ fw_status gemm_split_pack(const float* X, int rows, int K, void* Xp, hipStream_t
 // flops the matrix cores execute for one product (three bfloat16 terms per float32 multiplication, whole tiles)
 size_t gemm_split_partial_bytes(int R, int N) { return align_up((size_t)GEMM_SPLIT_MAX_RUNS * R * N * sizeof(float), 256); }
 
-double gemm_split_flops_issued(int R, int N, int K, int lower) {
+// with_runs: as gemm_split_run chooses the tiles when it is given room for partial results
+double gemm_split_flops_issued(int R, int N, int K, int lower, bool with_runs) {
     SplitGeom g;
-    if (!make_split_geom(R, N, K, lower, &g)) return 0.0;
+    if (!make_split_geom(R, N, K, lower, &g, (with_runs && !lower) ? GEMM_SPLIT_MAX_RUNS : 1)) return 0.0;
     return 3.0 * 2.0 * (double)g.ntiles * g.tr * SP_TC * (8.0 * g.KB);
 }
 

@@ -149,3 +149,21 @@ def test_refresh_plan():
     assert b.fw_cond_refresh_plan_query(b.FW_REFRESH_SPLIT_MIN_M, 1 << 40).split == 1
     with pytest.raises(b.FwError):
         b.fw_cond_refresh_plan_query(0, 0)
+
+
+def test_grad_plan():
+    """The gradient product takes the split form for float32 gradients of many features (M >= 3072, S >= 128) when the
+    call has its whole workspace; its issued flops are then three bfloat16 terms on whole tiles."""
+    S, M = 512, 4608
+    full = b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S)
+    p = b.fw_grad_plan_query(b.FW_F32, S, M, full)
+    dense = 2.0 * S * M * M
+    assert p.split == 1 and 3 * dense <= p.mfma_flops_issued <= 3 * dense * 1.2
+    q = b.fw_grad_plan_query(b.FW_F32, S, M, full - 256)
+    assert q.split == 0 and q.mfma_flops_issued == dense
+    assert b.fw_grad_plan_query(b.FW_F32, 256, 2304, 1 << 40).split == 0      # too few features
+    assert b.fw_grad_plan_query(b.FW_F32, 64, 4608, 1 << 40).split == 0       # too few rows
+    assert b.fw_grad_plan_query(b.FW_BF16, S, M, 1 << 40).split == 0          # bfloat16 gradients take the widened form
+    with pytest.raises(b.FwError):
+        b.fw_grad_plan_query(b.FW_F32, 0, M, 0)
+
