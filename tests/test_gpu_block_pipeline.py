@@ -157,3 +157,69 @@ def test_blocks_on_the_evd_leg_with_rank_limited_gains(dtype, layout):
         assert relF(host(Gout), ora.grad_transform(G.astype(np.float64), host(Qs))) < 1e-4
     assert 1 <= min(ranks) and max(ranks) < M          # the rank limit was active
     assert relF(host(Qs), np.eye(M)) > 1e-3            # and the smoothing has moved Qs away from its start
+
+
+@pytest.mark.parametrize("dtype,Cin,H", [("f32", 64, 20), ("bf16", 128, 14)])
+def test_next_batch_accumulated_on_a_second_stream(dtype, Cin, H):
+    """The sums of batch k+1 are accumulated on a second stream while batch k's refresh, recursion and gradient product
+    run, ordered by two events (the sums are free once finalize has read them; finalize waits for the sums).  The calls
+    share nothing but their arguments, so every matrix must come out bit for bit as on one stream."""
+    B, S, steps = 16, 48, 5
+    lays = [wl.small_conv(900 + i, B=B, Cin=Cin, H=H, W=H, k=3, stride=1, pad=1, S=S, dtype=dtype) for i in range(2)]
+    d = desc_of(lays[0])
+    dt = dt_of(lays[0])
+    M, n_rows = lays[0].desc.M, lays[0].desc.n_rows
+    up = [upload_act(l, 2) for l in lays]
+    lay = up[0][1]
+    Xs = [u[0] for u in up]
+    G = torch.as_tensor(lays[0].G).to(DEV)
+    gp = b.cond_params()
+
+    def run(two_streams):
+        A = torch.zeros(M, M, device=DEV); s = torch.zeros(M, device=DEV)
+        mu = torch.zeros(M, device=DEV); Phi = torch.zeros(M, M, device=DEV); phi = torch.zeros(M, device=DEV)
+        lbar = torch.zeros(4, device=DEV)
+        T, Q, Qs, Py, Psi = (torch.empty(M, M, device=DEV) for _ in range(5))
+        xi2 = torch.empty(M, device=DEV)
+        info = torch.zeros(8, dtype=torch.int32, device=DEV)
+        Gout = torch.empty_like(G)
+        st = b.cond_state(M, Phi, lbar, T, Q, Qs, Py, Psi, xi2)
+        ws_cov = workspace(b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, M, 0, d, dt))
+        ws_cond = workspace(b.fw_workspace_bytes(b.FW_OP_COND_REDUCE_STEP, M))
+        ws_ref = workspace(b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, M))
+        ws_grad = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S))
+        b.fw_cov_accumulate(Xs[0], dt, lay, d, A, s, ws_cov)
+        b.fw_cov_finalize(A, s, n_rows, M, 0.3, 1, mu, Phi, phi, lbar)
+        b.fw_cond_state_init(st)
+        torch.cuda.synchronize()
+        main = torch.cuda.current_stream()
+        side = torch.cuda.Stream() if two_streams else main
+        sums_read, sums_ready = torch.cuda.Event(), torch.cuda.Event()
+
+        def accumulate(k):
+            with torch.cuda.stream(side):
+                side.wait_event(sums_read)
+                A.zero_(); s.zero_()
+                b.fw_cov_accumulate(Xs[k & 1], dt, lay, d, A, s, ws_cov)
+                sums_ready.record(side)
+
+        sums_read.record(main)
+        accumulate(1)
+        for k in range(1, steps + 1):
+            main.wait_event(sums_ready)
+            b.fw_cov_finalize(A, s, n_rows, M, 0.3, 0, mu, Phi, phi, lbar)
+            sums_read.record(main)
+            if k < steps:
+                accumulate(k + 1)
+            b.fw_cond_state_refresh(st, ws_ref)
+            b.fw_cond_reduce_step(st, gp, info, ws_cond)
+            b.fw_grad_transform(G, b.FW_F32, S, M, None, Qs, Gout, ws_grad)
+        main.wait_stream(side)
+        torch.cuda.synchronize()
+        return [t.clone() for t in (Phi, mu, T, Q, Qs, Py, Psi, xi2, Gout)]
+
+    one = run(False)
+    two = run(True)
+    for x, y in zip(one, two):
+        assert torch.isfinite(x).all()
+        assert torch.equal(x, y)
