@@ -216,6 +216,8 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
         xm = out["extra_ms"]
         xm["sgd_update_fused"] = time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt))
         xm["diagnostics_whiteness"] = time_call(lambda: b.fw_diagnostics(Py, None, M, diag_out, ws_diag))
+        # the transform handed a raw T instead of Q: Q = T^T T is built in the workspace first (M^2 (M+1) flops)
+        xm["grad_transform_from_raw_T"] = time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, T, None, Gout, ws_grad), reps=5)
         ws_probe = torch.empty(b.fw_workspace_bytes(b.FW_OP_COND_PROBE, M, 16), dtype=torch.uint8, device=dev)
         xm["cond_probe_16_steps"] = time_call(lambda: b.fw_cond_probe(Py, M, None, 16, diag_out, ws_probe), reps=5)
         if not layer.is_rows and d.kh * d.kw > 1:
@@ -233,7 +235,7 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
             xm["per_channel_variant_cov_accumulate"] = time_call(lambda: b.fw_cov_accumulate(X0, dt, lay, desc1, A1, s1, ws1))
             xm["per_channel_variant_grad_transform_taps"] = time_call(
                 lambda: b.fw_grad_transform_taps(G4, b.FW_F32, S, d.Cin, taps, Q1, G4o, ws4))
-    if evd:   # the EVD / ZCA reference construction replaces the recursive step; timed once, outside the headline
+    if evd or extras:   # the EVD / ZCA reference construction replaces the recursive step; timed once, outside the headline
         ws_evd = torch.empty(b.fw_workspace_bytes(b.FW_OP_WHITEN_EVD, M), dtype=torch.uint8, device=dev)
         lam = torch.empty(M, device=dev)
         Te, Qe = torch.empty(M, M, device=dev), torch.empty(M, M, device=dev)
@@ -247,10 +249,10 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
 def rooflines_of(r, layer, b, cfg_key, layout_name):
     """One roofline entry per export of the step, from the event times of the timed region.
 
-    a1: issued matrix-core flops / time against the MFMA peak of the input type (the shift-correlation form issues fewer
-    flops than the dense lower triangle N_rows M (M+1); that dense-equivalent rate is reported beside it, it is a speed-up
-    over the direct form, not a utilisation).  a2, refresh: 2 S M^2 and 4 M^3 float32 flops against the float32 MFMA
-    peak.  a3: 16 M^2 (10 M^2 without leak) float32 words against the HBM peak; finalize: lower triangle of A and of the
+    a1: issued matrix-core flops / time against the MFMA peak of the type the product runs in (the shift-correlation form
+    issues fewer flops than the dense lower triangle N_rows M (M+1); that dense-equivalent rate is reported beside it, it is a
+    speed-up over the direct form, not a utilisation).  a2, refresh: issued flops of the form the call takes (float32, or
+    three bfloat16 terms per multiplication on whole tiles) against the peak of that form.  a3: 16 M^2 (10 M^2 without leak) float32 words against the HBM peak; finalize: lower triangle of A and of the
     old Phi_x read, Phi_x written."""
     M, S, n_rows, bf16 = r["M"], r["S"], r["n_rows"], r["bf16"]
     d = layer.desc
@@ -361,7 +363,13 @@ def cpu_baseline_of(layer, np):
         spent += tc4 - tc0
     secs = {k: v / reps for k, v in secs.items()}
     t_update = (secs["unfold"] + secs["moments"]) * scale + secs["cond_step"] + secs["grad_transform"]
-    return {"value": 1.0 / t_update, "unit": "updates/s", "cores": int(cores), "kind": "oracle",
+    cpu_model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "unknown")
+    except OSError:
+        pass
+    return {"value": 1.0 / t_update, "unit": "updates/s", "cores": int(cores), "cpu_model": cpu_model, "kind": "oracle",
             "sample": f"{reps} update(s) on {Bs} of {d.B} images (moment terms scaled by {scale:g}), "
                       f"float64 numpy, {spent:.1f} s of CPU work",
             "seconds_per_update": secs}
@@ -417,12 +425,25 @@ def run_c5(args, torch, b, wl):
         flops = float(r["n_rows"]) * r["M"] * (r["M"] + 1)
         plan = b.fw_cov_plan_query(b.FW_BF16, r["lay"], b.conv_desc(*layer.desc.astuple()))
         ex = r["export_ms"]
+        rpl = b.fw_cond_refresh_plan_query(r["M"], b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, r["M"]))
+        gpl = b.fw_grad_plan_query(b.FW_F32, r["S"], r["M"], b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, r["M"], r["S"]))
         rows.append({"layer": layer.name, "M": r["M"], "S": r["S"], "n_rows": r["n_rows"], "ms_per_step": round(r["ms_per_step"], 4),
                      "cov_ms": round(ex["cov_accumulate"], 4), "fin_ms": round(ex["cov_finalize"], 4),
                      "refresh_ms": round(ex["cond_state_refresh"], 4), "cond_ms": round(ex["cond_reduce_step"], 4),
                      "grad_ms": round(ex["grad_transform"], 4), "shift_form": int(plan.shift),
                      "cov_issued_frac_of_bf16_peak": round(plan.mfma_flops_issued / (ex["cov_accumulate"] * 1e-3) / PEAK["bf16"], 4),
                      "cov_dense_equivalent_TFLOPs": round(flops / (ex["cov_accumulate"] * 1e-3) / 1e12, 1),
+                     # the other exports against their roofs: refresh and gradient product by the flops of the form taken
+                     # over that form's MFMA peak; the recursive step by its 16 M^2 words over the HBM peak (only where
+                     # the state does not sit in the caches)
+                     "refresh_frac_of_mfma_peak": round(rpl.mfma_flops_issued / (ex["cond_state_refresh"] * 1e-3) /
+                                                        PEAK["bf16" if rpl.split else "f32"], 4),
+                     "refresh_form": "bf16 split" if rpl.split else "f32",
+                     "grad_frac_of_mfma_peak": round(gpl.mfma_flops_issued / (ex["grad_transform"] * 1e-3) /
+                                                     PEAK["bf16" if gpl.split else "f32"], 4),
+                     "grad_form": "bf16 split" if gpl.split else "f32",
+                     "cond_frac_of_hbm_peak": (round(64.0 * r["M"] ** 2 / (ex["cond_reduce_step"] * 1e-3) / HBM_PEAK, 4)
+                                               if r["M"] > 1152 else None),
                      "issued": plan.mfma_flops_issued, "dense": flops})
         print(f"[c5] {layer.name}: {r['ms_per_step']:.3f} ms", file=sys.stderr, flush=True)
         del layer

@@ -127,7 +127,10 @@ fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, fl
  *
  *   G      in   [S, M] element type `dt`
  *   Q      in   [M, M] float32, symmetric (Q or its smoothed version Q_s, eq. (vQs)); may be NULL if T is given
- *   T      in   [M, M] float32 or NULL.  Used only when Q is NULL: Q = T^T T is then built in the workspace first.
+ *   T      in   [M, M] float32 or NULL.  Used only when Q is NULL: Q = T^T T is then built in the workspace first (in
+ *               float32 below FW_REFRESH_SPLIT_MIN_M features; from there on with the columns of T split into bfloat16
+ *               hi + lo planes on the bfloat16 matrix cores, relative Frobenius error of Q a few 1e-6, about 15 times
+ *               faster at M = 4608).
  *   G_out  out  [S, M] element type `dt`; must not overlap G
  *   ws     scratch, fw_workspace_bytes(FW_OP_GRAD_TRANSFORM, M, S, NULL, dt) bytes; required when Q is NULL (the first
  *               fw_workspace_bytes(FW_OP_GRAD_TRANSFORM, M, 0, NULL, FW_F32) bytes of it suffice for that), optional

@@ -18,10 +18,14 @@ bool desc_ok(const fw_conv_desc* d, fw_layout lay) {
 bool dtype_ok(fw_dtype dt) { return dt == FW_F32 || dt == FW_BF16; }
 bool layout_ok(fw_layout l) { return l == FW_LAYOUT_ROWS || l == FW_LAYOUT_NCHW || l == FW_LAYOUT_NHWC || l == FW_LAYOUT_NHWC_KKC; }
 
+// Q = T^T T built in the workspace: Q itself, a dummy vector of column sums, and the larger of the covariance kernel's
+// scratch (float32 form) and the packed planes of T^T (split form, from FW_REFRESH_SPLIT_MIN_M features on)
+bool q_build_split(int M) { return M >= FW_REFRESH_SPLIT_MIN_M; }
 size_t grad_ws_bytes(int M) {
     fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0, FW_COV_FORM_DIRECT};   // products in float32, never the split form
-    return align_up((size_t)M * M * sizeof(float), 256) + align_up((size_t)M * sizeof(float), 256) +
-           cov_workspace_bytes(M, &d, FW_F32, FW_LAYOUT_ROWS);
+    const size_t cov = cov_workspace_bytes(M, &d, FW_F32, FW_LAYOUT_ROWS);
+    const size_t packed = q_build_split(M) ? gemm_split_packed_bytes(M, M) : 0;
+    return align_up((size_t)M * M * sizeof(float), 256) + align_up((size_t)M * sizeof(float), 256) + (cov > packed ? cov : packed);
 }
 
 // bfloat16 (or per-tap) gradients: a float32 copy of the gradient as [rows, M]
@@ -70,14 +74,25 @@ fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const floa
         const size_t qbytes = align_up((size_t)M * M * sizeof(float), 256);
         float* sdummy = reinterpret_cast<float*>(base + qbytes);
         const size_t sbytes = align_up((size_t)M * sizeof(float), 256);
-        const fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0, FW_COV_FORM_DIRECT};   // products in float32, never the split form
-        fw_status rc = fill_f32(Qb, (size_t)M * M, 0.f, st);
-        if (rc != FW_OK) return rc;
-        rc = fill_f32(sdummy, (size_t)M, 0.f, st);
-        if (rc != FW_OK) return rc;
-        // Q = T^T T: the rows of T are the "samples" of a symmetric rank-M update (eq. (vQ))
-        rc = cov_accumulate(T, FW_F32, FW_LAYOUT_ROWS, &d, Qb, sdummy, base + qbytes + sbytes, ws_bytes - qbytes - sbytes, st);
-        if (rc != FW_OK) return rc;
+        fw_status rc;
+        if (q_build_split(M)) {
+            // Q = T^T T = (T^T)(T^T)^T on the bfloat16 matrix cores: the columns of T, packed as hi + lo planes, are both
+            // operands; only the tiles that touch the lower triangle are multiplied (eq. (vQ))
+            void* Tp = base + qbytes + sbytes;
+            rc = gemm_split_pack_transposed(T, M, M, Tp, st);
+            if (rc != FW_OK) return rc;
+            rc = gemm_split_run(Tp, Tp, M, M, M, 1, Qb, st);
+            if (rc != FW_OK) return rc;
+        } else {
+            const fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0, FW_COV_FORM_DIRECT};   // products in float32, never the split form
+            rc = fill_f32(Qb, (size_t)M * M, 0.f, st);
+            if (rc != FW_OK) return rc;
+            rc = fill_f32(sdummy, (size_t)M, 0.f, st);
+            if (rc != FW_OK) return rc;
+            // Q = T^T T: the rows of T are the "samples" of a symmetric rank-M update (eq. (vQ))
+            rc = cov_accumulate(T, FW_F32, FW_LAYOUT_ROWS, &d, Qb, sdummy, base + qbytes + sbytes, ws_bytes - qbytes - sbytes, st);
+            if (rc != FW_OK) return rc;
+        }
         rc = symmetrize_from_lower(Qb, M, st);
         if (rc != FW_OK) return rc;
         Q = Qb;

@@ -158,6 +158,7 @@ fw_status grad_stage_rows(const void* G, fw_dtype dt, int S, int M, int taps, fl
 // ---- gemm_split.hip: C = A B^T in float32-grade accuracy on the bfloat16 matrix cores (operands split in hi + lo)
 size_t gemm_split_packed_bytes(int rows, int K);
 fw_status gemm_split_pack(const float* X, int rows, int K, void* Xp, hipStream_t st);
+fw_status gemm_split_pack_transposed(const float* X, int K, int rows, void* Xp, hipStream_t st);
 double gemm_split_flops_issued(int R, int N, int K, int lower, bool with_runs = false);
 size_t gemm_split_partial_bytes(int R, int N);
 fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st,

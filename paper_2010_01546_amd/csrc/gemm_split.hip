@@ -91,6 +91,34 @@ __global__ __launch_bounds__(256) void split_pack_kernel(const float* __restrict
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 16) Xp[(size_t)2 * KB * Rp + threadIdx.x] = make_uint4(0, 0, 0, 0);
 }
 
+// The same packed planes for the TRANSPOSE of X: X is [K, R] row-major (contraction index along its rows), the packed
+// operand has R rows.  Thread (kb, r) reads the eight entries X[8 kb .. 8 kb + 7][r]; consecutive threads read and write
+// consecutive addresses, so no staging is needed.
+__global__ __launch_bounds__(256) void split_pack_transposed_kernel(const float* __restrict__ X, int K, int R, int Rp, int KB,
+                                                                    uint4* __restrict__ Xp) {
+    const int r = blockIdx.x * 256 + threadIdx.x, kb = blockIdx.y;
+    if (blockIdx.x == 0 && kb == 0 && threadIdx.x < 16) Xp[(size_t)2 * KB * Rp + threadIdx.x] = make_uint4(0, 0, 0, 0);
+    if (r >= Rp) return;
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int k = 8 * kb + i;
+        x[i] = (r < R && k < K) ? X[(size_t)k * R + r] : 0.f;
+    }
+    unsigned hi[8], lo[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const unsigned short h = f32_to_bf16_rne(x[i]);
+        hi[i] = h;
+        lo[i] = f32_to_bf16_rne(x[i] - bf16_to_f32(h));      // the difference is exact in float32
+    }
+    uint4 oh, ol;
+    oh.x = hi[0] | (hi[1] << 16); oh.y = hi[2] | (hi[3] << 16); oh.z = hi[4] | (hi[5] << 16); oh.w = hi[6] | (hi[7] << 16);
+    ol.x = lo[0] | (lo[1] << 16); ol.y = lo[2] | (lo[3] << 16); ol.z = lo[4] | (lo[5] << 16); ol.w = lo[6] | (lo[7] << 16);
+    Xp[(size_t)kb * Rp + r] = oh;
+    Xp[((size_t)KB + kb) * Rp + r] = ol;
+}
+
 // With g.nks > 1 workgroup (tile, run) multiplies only the stages of its run and writes the tile to part[run][R][N];
 // split_reduce_kernel adds the runs in a fixed order.
 template <int NRT>
@@ -312,6 +340,15 @@ size_t gemm_split_packed_bytes(int rows, int K) {
 fw_status gemm_split_pack(const float* X, int rows, int K, void* Xp, hipStream_t st) {
     const int Rp = (rows + 63) / 64 * 64, KB = (K + 15) / 16 * 2;
     hipLaunchKernelGGL(split_pack_kernel, dim3((8 * KB + 63) / 64, Rp / 64), dim3(256), 0, st, X, rows, K, Rp, KB,
+                       reinterpret_cast<uint4*>(Xp));
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
+// Xp = packed hi / lo planes of X^T for X [K, rows] (the operand has `rows` rows and contraction length K)
+fw_status gemm_split_pack_transposed(const float* X, int K, int rows, void* Xp, hipStream_t st) {
+    const int Rp = (rows + 63) / 64 * 64, KB = (K + 15) / 16 * 2;
+    hipLaunchKernelGGL(split_pack_transposed_kernel, dim3((Rp + 255) / 256, KB), dim3(256), 0, st, X, K, rows, Rp, KB,
                        reinterpret_cast<uint4*>(Xp));
     FW_LAUNCH_CHECK();
     return FW_OK;

@@ -122,6 +122,25 @@ def test_f32_from_nonsymmetric_T(S, M):
     assert relF(out.cpu().numpy(), wrong) > 1e-3
 
 
+@pytest.mark.parametrize("S,M", [(40, 1536), (24, 1670), (160, 3072)])
+def test_f32_from_nonsymmetric_T_split_build(S, M):
+    """From FW_REFRESH_SPLIT_MIN_M features on Q = T^T T (eq. (vQ)) is built on the bfloat16 matrix cores from the hi + lo
+    planes of T's columns (and for M >= 3072, S >= 128 the product G Q takes the split form as well): float32-grade results,
+    and still T^T T, not T T^T."""
+    T32, Q64 = sym_Q(M, 5 * M)
+    G = (rng.standard_normal((S, M)) * 0.1).astype(np.float32)
+    out = torch.zeros(S, M, device=DEV)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S))
+    b.fw_grad_transform(dev(G), b.FW_F32, S, M, dev(T32), None, out, ws)
+    torch.cuda.synchronize()
+    want = ora.grad_transform(G, ora.Q_from_T(T32))
+    err = relF(out.cpu().numpy(), want)
+    print(f"raw T, split build: S={S} M={M} rel-F {err:.2e}")
+    assert err < 2e-5
+    wrong = ora.grad_transform(G, T32.astype(np.float64) @ T32.astype(np.float64).T)
+    assert relF(out.cpu().numpy(), wrong) > 1e-3
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_large_feature_count(dtype):
     """M = 9216: Q = I + u u^T keeps the float64 reference cheap."""
