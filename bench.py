@@ -214,7 +214,8 @@ def time_layer(layer, layout_name, steps, warmup, torch, b, wl, evd=False, extra
         diag_out = torch.zeros(4, device=dev)
         ws_diag = torch.empty(b.fw_workspace_bytes(b.FW_OP_DIAGNOSTICS, M), dtype=torch.uint8, device=dev)
         xm = out["extra_ms"]
-        xm["sgd_update_fused"] = time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt))
+        ws_sgd = torch.empty(b.fw_workspace_bytes(b.FW_OP_SGD_UPDATE, M, S), dtype=torch.uint8, device=dev)
+        xm["sgd_update_fused"] = time_call(lambda: b.fw_sgd_update(G, b.FW_F32, S, M, 1, Qs, sgd, Wt, Vt, ws_sgd))
         xm["diagnostics_whiteness"] = time_call(lambda: b.fw_diagnostics(Py, None, M, diag_out, ws_diag))
         # the transform handed a raw T instead of Q: Q = T^T T is built in the workspace first (M^2 (M+1) flops)
         xm["grad_transform_from_raw_T"] = time_call(lambda: b.fw_grad_transform(G, b.FW_F32, S, M, T, None, Gout, ws_grad), reps=5)

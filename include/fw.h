@@ -164,6 +164,8 @@ fw_status fw_grad_plan_query(fw_dtype dt, int S, int M, size_t ws_bytes, fw_grad
  *   Q          [M, M] float32, symmetric
  *   ws         scratch, fw_workspace_bytes(FW_OP_GRAD_TRANSFORM_TAPS, M, S * taps, NULL, dt) bytes (the gradient as rows)
  * Products are float32 on the matrix cores for both element types; bfloat16 results are rounded to nearest even.
+ * With M >= 3072 (a multiple of 4) and S * taps >= 128 the product takes the split form of fw_grad_transform (bfloat16
+ * hi + lo planes, relative error a few 1e-6).
  */
 fw_status fw_grad_transform_taps(const void* G, fw_dtype dt, int S, int M, int taps, const float* Q, void* G_out,
                                  void* ws, size_t ws_bytes, void* stream);
@@ -174,8 +176,11 @@ fw_status fw_grad_transform_taps(const void* G, fw_dtype dt, int S, int M, int t
  *   G      in      [S, M] (taps = 1) or [S, M, taps], element type `dt`; not overlapping W or V
  *   W      in/out  stored weights W~, float32, same shape as G
  *   V      in/out  momentum buffer, float32, same shape, zero before the first update; may be NULL when momentum = 0
- *   ws     scratch, fw_workspace_bytes(FW_OP_SGD_UPDATE, M, S * taps, NULL, dt) bytes; not needed for FW_F32 with taps = 1
- * The transformed gradient itself is not written anywhere.
+ *   ws     scratch, fw_workspace_bytes(FW_OP_SGD_UPDATE, M, S * taps, NULL, dt) bytes; not needed for FW_F32 with taps = 1.
+ *          With it, M >= 3072 (a multiple of 4) and S * taps >= 128 the product takes the split form of fw_grad_transform
+ *          (about 1.6 times faster at S = 512, M = 4608); its runs of the contraction index are then kept in the workspace
+ *          and added by the pass that updates W and V.
+ * Without the split form the transformed gradient is not written anywhere.
  */
 typedef struct { float lr, momentum, weight_decay; } fw_sgd_params;
 fw_status fw_sgd_update(const void* G, fw_dtype dt, int S, int M, int taps, const float* Q, const fw_sgd_params* p,

@@ -38,6 +38,23 @@ size_t grad_split_bytes(int S, int M) {
     return grad_split_applies(S, M) ? gemm_split_packed_bytes(M, M) + gemm_split_packed_bytes(S, M) + gemm_split_partial_bytes(S, M) : 0;
 }
 
+// rows [n, M] float32 times Q on the bfloat16 matrix cores (split form), the runs of the contraction index added by the
+// epilogue `e`; tail: grad_split_bytes(n, M) bytes
+fw_status split_rows_apply(const float* rows, int n, int M, const float* Q, const GemmEpilogue& e, void* tail, hipStream_t st) {
+    char* base = reinterpret_cast<char*>(tail);
+    void* Qp = base;
+    void* Gp = base + gemm_split_packed_bytes(M, M);
+    float* sp = reinterpret_cast<float*>(base + gemm_split_packed_bytes(M, M) + gemm_split_packed_bytes(n, M));
+    fw_status rc = gemm_split_pack(Q, M, M, Qp, st);              // Q is symmetric: its rows stand for its columns
+    if (rc != FW_OK) return rc;
+    rc = gemm_split_pack(rows, n, M, Gp, st);
+    if (rc != FW_OK) return rc;
+    int runs = 1;
+    rc = gemm_split_run(Gp, Qp, n, M, M, 0, sp, st, sp, &runs);
+    if (rc != FW_OK) return rc;
+    return grad_epilogue_from_runs(sp, runs, e, n, M, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -138,6 +155,9 @@ fw_status fw_grad_transform_taps(const void* G, fw_dtype dt, int S, int M, int t
     if (rc != FW_OK) return rc;
     GemmEpilogue e = {};
     e.out = G_out; e.out_bf16 = dt == FW_BF16 ? 1 : 0; e.taps = taps;
+    const size_t wide = grad_wide_bytes((long long)S * taps, M);
+    if (grad_split_applies(S * taps, M) && (M & 3) == 0 && ws_bytes >= wide + grad_split_bytes(S * taps, M))
+        return split_rows_apply(rows, S * taps, M, Q, e, reinterpret_cast<char*>(ws) + wide, st);
     return grad_gemm_f32(rows, S * taps, M, Q, e, st);
 }
 
@@ -160,6 +180,9 @@ fw_status fw_sgd_update(const void* G, fw_dtype dt, int S, int M, int taps, cons
     GemmEpilogue e = {};
     e.taps = taps; e.W = W; e.V = p->momentum > 0.f ? V : nullptr;
     e.lr = p->lr; e.momentum = p->momentum; e.wd = p->weight_decay;
+    const size_t wide = grad_wide_bytes((long long)S * taps, M);
+    if (grad_split_applies(S * taps, M) && (M & 3) == 0 && ws && ws_bytes >= wide + grad_split_bytes(S * taps, M))
+        return split_rows_apply(rows, S * taps, M, Q, e, reinterpret_cast<char*>(ws) + wide, st);
     return grad_gemm_f32(rows, S * taps, M, Q, e, st);
 }
 
@@ -293,7 +316,7 @@ size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtyp
         case FW_OP_WHITEN_EVD: return M > 0 && M <= 16384 ? evd_workspace_bytes(M) : 0;
         case FW_OP_COND_STATE_REFRESH: return M > 0 && M <= 16384 ? cond_refresh_workspace_bytes(M) : 0;
         case FW_OP_GRAD_TRANSFORM_TAPS:
-        case FW_OP_SGD_UPDATE: return (M > 0 && M <= 16384 && S > 0) ? grad_wide_bytes(S, M) : 0;
+        case FW_OP_SGD_UPDATE: return (M > 0 && M <= 16384 && S > 0) ? grad_wide_bytes(S, M) + grad_split_bytes(S, M) : 0;
         case FW_OP_DIAGNOSTICS: return M > 0 && M <= 16384 ? diagnostics_workspace_bytes(M) : 0;
         case FW_OP_COND_PROBE: return M > 0 && M <= 16384 ? cond_probe_workspace_bytes(M, S > 0 ? S : FW_COND_PROBE_MAX_K) : 0;
     }

@@ -154,6 +154,7 @@ size_t grad_gemm_partial_bytes(int S, int M);
 fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st, float* part = nullptr);
 fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const GemmEpilogue& e, hipStream_t st, float* part = nullptr);
 fw_status grad_stage_rows(const void* G, fw_dtype dt, int S, int M, int taps, float* dst, hipStream_t st);
+fw_status grad_epilogue_from_runs(const float* part, int nks, const GemmEpilogue& e, int S, int M, hipStream_t st);
 
 // ---- gemm_split.hip: C = A B^T in float32-grade accuracy on the bfloat16 matrix cores (operands split in hi + lo)
 size_t gemm_split_packed_bytes(int rows, int K);
@@ -162,7 +163,7 @@ fw_status gemm_split_pack_transposed(const float* X, int K, int rows, void* Xp, 
 double gemm_split_flops_issued(int R, int N, int K, int lower, bool with_runs = false);
 size_t gemm_split_partial_bytes(int R, int N);
 fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st,
-                         float* part = nullptr);
+                         float* part = nullptr, int* runs_out = nullptr);
 
 // ---- extras.hip
 fw_status bias_compensate(float* b, const float* W, int S, int M, int taps, const float* mu_old, const float* mu_new, float scale,

@@ -504,6 +504,18 @@ fw_status grad_gemm_f32(const float* G, int S, int M, const float* Q, const Gemm
     return FW_OK;
 }
 
+// Epilogue applied to a product that sits in the workspace as `nks` partial results [nks][S][M] (M a multiple of 4): the
+// runs are added in order and every element goes where `e` says (store, per-tap position, rounding, weight update)
+fw_status grad_epilogue_from_runs(const float* part, int nks, const GemmEpilogue& e, int S, int M, hipStream_t st) {
+    if ((M & 3) != 0 || nks < 1) return FW_ERR_UNSUPPORTED;
+    size_t blocks = ((size_t)S * M / 4 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(strip_reduce_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, part, nks, e, S, M);
+    FW_LAUNCH_CHECK();
+    return FW_OK;
+}
+
 fw_status grad_gemm(const void* G, fw_dtype dt, int S, int M, const float* Q, void* G_out, hipStream_t st, float* part) {
     if (dt == FW_BF16) {
         const dim3 grid((M + TN - 1) / TN, (S + TM - 1) / TM);

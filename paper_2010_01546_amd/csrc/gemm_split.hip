@@ -367,7 +367,11 @@ double gemm_split_flops_issued(int R, int N, int K, int lower, bool with_runs) {
 // C [R, N] = A B^T from the packed operands (A [R, K], B [N, K]); lower != 0: C is known to be symmetric (R == N) and
 // only its lower triangle is written.
 // part: room for gemm_split_partial_bytes(R, N) bytes, or null (then the contraction index is never cut into runs)
-fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st, float* part) {
+// runs_out: when given (with part, and C == part), the runs are left unsummed in part[run][R][N] (a single run: part[0]) and
+//   their number is returned, for a caller that adds them in an epilogue of its own
+fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st, float* part,
+                         int* runs_out) {
+    if (runs_out && (!part || C != part || lower)) return FW_ERR_INVALID_ARG;
     SplitGeom g;
     if (!make_split_geom(R, N, K, lower, &g, (part && !lower) ? GEMM_SPLIT_MAX_RUNS : 1)) return FW_ERR_UNSUPPORTED;
     const dim3 grid((g.ntiles * g.nks + 7) / 8 * 8);
@@ -379,6 +383,7 @@ fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, in
         default: hipLaunchKernelGGL(gemm_split_kernel<2>, grid, dim3(256), 0, st, a, b, g, C, part); break;
     }
     FW_LAUNCH_CHECK();
+    if (runs_out) { *runs_out = g.nks; return FW_OK; }
     if (g.nks > 1) {
         const size_t n = (size_t)R * N;
         size_t blocks = (n / 4 + 255) / 256;
