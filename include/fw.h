@@ -63,8 +63,8 @@ typedef enum {
  * AUTO picks by an estimate of the run time.  SHIFT and DIRECT are meant for tuning and for tests that must reach one
  * form at sizes where the estimate prefers the other; where the shift form does not apply the field changes nothing. */
 typedef enum {
-    FW_COV_FORM_AUTO = 0,     /* by estimate: for float32 input this includes FW_COV_FORM_SPLIT when the layer has at least 4096
-                                 rows and 128 features */
+    FW_COV_FORM_AUTO = 0,     /* by estimate: for float32 input this includes FW_COV_FORM_SPLIT from the measured break-even
+                                 on: at least 32768 rows for 512 <= M < 1024, 8192 for M < 2048, 1024 for M < 4096, 256 beyond */
     FW_COV_FORM_SHIFT = 1,    /* shift form wherever it applies (products in the input's own precision) */
     FW_COV_FORM_DIRECT = 2,   /* never the shift form (products in the input's own precision) */
     FW_COV_FORM_SPLIT = 3     /* float32 input only (ignored for bfloat16): every value is split into two bfloat16 numbers

@@ -729,8 +729,7 @@ static size_t act_copy_bytes(const fw_conv_desc* d) { return align_up((size_t)d-
 
 // The split form (float32 activations as hi + lo bfloat16 planes on the bfloat16 kernels): taken when asked for, or by
 // the estimate for layers that are large enough for the matrix cores to matter (the float32 MFMA peak is a sixteenth of
-// the bfloat16 one, the split form issues four times the products) and whose rows are many enough for the split
-// residuals to average out.  `lay` is the layout after the NCHW copy, if any.
+// the bfloat16 one, the split form issues four times the products).  `lay` is the layout after the NCHW copy, if any.
 struct SplitPlan { fw_conv_desc d2; fw_layout lay2; size_t a2, s2, inner, total; int ckk; };
 static bool split_plan(const fw_conv_desc* d, fw_layout lay, SplitPlan* sp) {
     if (d->form != FW_COV_FORM_AUTO && d->form != FW_COV_FORM_SPLIT) return false;
@@ -739,7 +738,13 @@ static bool split_plan(const fw_conv_desc* d, fw_layout lay, SplitPlan* sp) {
     const long long Ho = (d->H + 2 * d->pad - d->kh) / d->stride + 1, Wo = (d->W + 2 * d->pad - d->kw) / d->stride + 1;
     const long long n_rows = (long long)d->B * Ho * Wo;
     if (2 * M > 16384 || (long long)d->B * d->H * d->W * 2 * d->Cin >= (1ll << 31)) return false;
-    if (d->form == FW_COV_FORM_AUTO && (n_rows < 4096 || M < 128)) return false;
+    if (d->form == FW_COV_FORM_AUTO) {
+        // Measured break-even against the float32 kernels (rows and 3 x 3 windows alike): the split form pays a fixed
+        // price in M^2 (A2 is four times A: filled, accumulated and folded), the float32 kernels lose ground as M grows
+        // (64 x 64 blocks re-read their panels per block: 15 TFLOP/s at M = 4608 against 70 at M = 576).
+        const long long least_rows = M >= 4096 ? 256 : M >= 2048 ? 1024 : M >= 1024 ? 8192 : M >= 512 ? 32768 : -1;
+        if (least_rows < 0 || n_rows < least_rows) return false;
+    }
     sp->d2 = *d;
     sp->d2.Cin = 2 * d->Cin;
     sp->d2.form = FW_COV_FORM_AUTO;                       // the bfloat16 kernels choose between their own two forms

@@ -264,3 +264,17 @@ def test_split_form_on_plain_rows_and_by_estimate():
     assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(**big, form=b.FW_COV_FORM_DIRECT)).split_bf16 == 0
     assert b.fw_cov_plan_query(b.FW_BF16, b.FW_LAYOUT_NHWC_KKC, b.conv_desc(**big, form=b.FW_COV_FORM_SPLIT)).split_bf16 == 0
     assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_NHWC, b.conv_desc(4, 64, 8, 8, 3, 3, 1, 1)).split_bf16 == 0
+
+
+@pytest.mark.parametrize("n_rows,M", [(1100, 2304), (300, 4100), (9000, 1028)])
+def test_many_features_go_to_the_split_form_by_estimate(n_rows, M):
+    """float32 rows with many features: past the measured break-even the estimate itself hands the layer to the split form
+    (the float32 kernel's 64 x 64 blocks re-read their panels per block); same parity bar."""
+    layer = wl.small_rows(n_rows + M, n_rows, M, 4, dtype="f32")
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_ROWS, b.conv_desc(*layer.desc.astuple())).split_bf16 == 1
+    layer.meta["form"] = b.FW_COV_FORM_SPLIT      # the mean's bound of the split form (the plan is the same)
+    check_layer(layer, b.FW_LAYOUT_ROWS)
+    # just below the break-even the float32 kernel stays
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_ROWS, b.conv_desc(1000, 2304, 1, 1, 1, 1, 1, 0)).split_bf16 == 0
+    assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_ROWS, b.conv_desc(100000, 500, 1, 1, 1, 1, 1, 0)).split_bf16 == 0
+
