@@ -137,15 +137,19 @@ fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, fl
  *               otherwise: with all of it a product with few output tiles (small S) cuts its contraction index into runs
  *               over more workgroups and adds the runs in a fixed order (same float32 arithmetic, another summation
  *               order); for dt = FW_BF16 with Q given it also selects the widened form below (several times faster); for
- *               dt = FW_F32 with M >= 3072 and S >= 128 it selects the split form: G and Q are split into bfloat16 hi + lo
- *               planes (16 significant bits each) and multiplied on the bfloat16 matrix cores as hi hi + hi lo + lo hi with
- *               float32 accumulation (relative Frobenius error a few 1e-6 instead of a few 1e-7; about twice as fast)
+ *               dt = FW_F32 and a large enough product (M >= 1024, S >= 128, S M >= FW_GRAD_SPLIT_MIN_SM, or
+ *               FW_GRAD_SPLIT_MIN_SM_WIDE from M = 2048 on: the measured break-even) it selects the split form: G and Q
+ *               are split into bfloat16 hi + lo planes (16 significant bits each) and multiplied on the bfloat16 matrix
+ *               cores as hi hi + hi lo + lo hi with float32 accumulation (relative Frobenius error a few 1e-6 instead of
+ *               a few 1e-7; 1.5 to 2.6 times as fast)
  * dt = FW_F32: float32 matrix-core products.
  * dt = FW_BF16 with the workspace: G is widened to float32 in the workspace, the products are float32 on the matrix
  *   cores with Q as it is, G_out is rounded to bfloat16 (nearest even).
  * dt = FW_BF16 without it: Q is rounded to bfloat16 on the fly, products are bf16 x bf16 accumulated in float32,
  *   G_out is rounded to bfloat16.  Q must be symmetric in every mode (its rows are read as its columns).
  */
+#define FW_GRAD_SPLIT_MIN_SM 1500000
+#define FW_GRAD_SPLIT_MIN_SM_WIDE 1100000
 fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const float* T, const float* Q,
                             void* G_out, void* ws, size_t ws_bytes, void* stream);
 
@@ -164,8 +168,8 @@ fw_status fw_grad_plan_query(fw_dtype dt, int S, int M, size_t ws_bytes, fw_grad
  *   Q          [M, M] float32, symmetric
  *   ws         scratch, fw_workspace_bytes(FW_OP_GRAD_TRANSFORM_TAPS, M, S * taps, NULL, dt) bytes (the gradient as rows)
  * Products are float32 on the matrix cores for both element types; bfloat16 results are rounded to nearest even.
- * With M >= 3072 (a multiple of 4) and S * taps >= 128 the product takes the split form of fw_grad_transform (bfloat16
- * hi + lo planes, relative error a few 1e-6).
+ * When M is a multiple of 4 and the S * taps rows meet fw_grad_transform's size rule for the split form, the product takes
+ * that form (bfloat16 hi + lo planes, relative error a few 1e-6).
  */
 fw_status fw_grad_transform_taps(const void* G, fw_dtype dt, int S, int M, int taps, const float* Q, void* G_out,
                                  void* ws, size_t ws_bytes, void* stream);
@@ -177,9 +181,9 @@ fw_status fw_grad_transform_taps(const void* G, fw_dtype dt, int S, int M, int t
  *   W      in/out  stored weights W~, float32, same shape as G
  *   V      in/out  momentum buffer, float32, same shape, zero before the first update; may be NULL when momentum = 0
  *   ws     scratch, fw_workspace_bytes(FW_OP_SGD_UPDATE, M, S * taps, NULL, dt) bytes; not needed for FW_F32 with taps = 1.
- *          With it, M >= 3072 (a multiple of 4) and S * taps >= 128 the product takes the split form of fw_grad_transform
- *          (about 1.6 times faster at S = 512, M = 4608); its runs of the contraction index are then kept in the workspace
- *          and added by the pass that updates W and V.
+ *          With it, M a multiple of 4 and S * taps rows that meet fw_grad_transform's size rule for the split form, the
+ *          product takes that form (about 1.7 times faster at S = 512, M = 4608); its runs of the contraction index are
+ *          then kept in the workspace and added by the pass that updates W and V.
  * Without the split form the transformed gradient is not written anywhere.
  */
 typedef struct { float lr, momentum, weight_decay; } fw_sgd_params;

@@ -256,6 +256,7 @@ def fw_cond_reduce_step(st, p, info_dev, ws, stream=None):
 
 FW_COND_STATIC_MAX_M = 4608
 FW_REFRESH_SPLIT_MIN_M = 1536
+FW_GRAD_SPLIT_MIN_SM, FW_GRAD_SPLIT_MIN_SM_WIDE = 1500000, 1100000
 
 
 def fw_cond_reduce_step_static(st, p, info_dev, stream=None):

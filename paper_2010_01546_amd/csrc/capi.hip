@@ -31,9 +31,12 @@ size_t grad_ws_bytes(int M) {
 // bfloat16 (or per-tap) gradients: a float32 copy of the gradient as [rows, M]
 size_t grad_wide_bytes(long long rows, int M) { return align_up((size_t)rows * M * sizeof(float), 256); }
 
-// float32 gradients of layers with many features: the product on the bfloat16 matrix cores with hi + lo split operands
+// float32 gradients of large layers: the product on the bfloat16 matrix cores with hi + lo split operands
 // (gemm_split.hip) needs the packed planes of Q and of G and room for partial results
-bool grad_split_applies(int S, int M) { return M >= 3072 && S >= 128; }
+// measured break-even against the float32 strip kernel: the packing of Q costs M^2, the product gains with S M
+bool grad_split_applies(int S, int M) {
+    return M >= 1024 && S >= 128 && (long long)S * M >= (M >= 2048 ? FW_GRAD_SPLIT_MIN_SM_WIDE : FW_GRAD_SPLIT_MIN_SM);
+}
 size_t grad_split_bytes(int S, int M) {
     return grad_split_applies(S, M) ? gemm_split_packed_bytes(M, M) + gemm_split_packed_bytes(S, M) + gemm_split_partial_bytes(S, M) : 0;
 }

@@ -152,7 +152,7 @@ def test_refresh_plan():
 
 
 def test_grad_plan():
-    """The gradient product takes the split form for float32 gradients of many features (M >= 3072, S >= 128) when the
+    """The gradient product takes the split form for float32 gradients of large products (size rule of the header) when the
     call has its whole workspace; its issued flops are then three bfloat16 terms on whole tiles."""
     S, M = 512, 4608
     full = b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S)
@@ -161,7 +161,11 @@ def test_grad_plan():
     assert p.split == 1 and 3 * dense <= p.mfma_flops_issued <= 3 * dense * 1.2
     q = b.fw_grad_plan_query(b.FW_F32, S, M, full - 256)
     assert q.split == 0 and q.mfma_flops_issued == dense
-    assert b.fw_grad_plan_query(b.FW_F32, 256, 2304, 1 << 40).split == 0      # too few features
+    assert b.fw_grad_plan_query(b.FW_F32, 256, 2304, 1 << 40).split == 0      # product too small (config 3)
+    assert b.fw_grad_plan_query(b.FW_F32, 512, 2304, 1 << 40).split == 1
+    assert b.fw_grad_plan_query(b.FW_F32, 1024, 1152, 1 << 40).split == 0
+    assert b.fw_grad_plan_query(b.FW_F32, 2048, 1152, 1 << 40).split == 1
+    assert b.fw_grad_plan_query(b.FW_F32, 4096, 1000, 1 << 40).split == 0     # too few features
     assert b.fw_grad_plan_query(b.FW_F32, 64, 4608, 1 << 40).split == 0       # too few rows
     assert b.fw_grad_plan_query(b.FW_BF16, S, M, 1 << 40).split == 0          # bfloat16 gradients take the widened form
     with pytest.raises(b.FwError):

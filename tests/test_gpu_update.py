@@ -22,7 +22,7 @@ def host(t):
 
 @pytest.mark.parametrize("S,M,taps,dtype", [(5, 8, 9, "f32"), (33, 64, 9, "f32"), (64, 130, 9, "bf16"), (17, 67, 4, "f32"),
                                             (40, 256, 9, "bf16"), (3, 5, 1, "f32"), (128, 512, 9, "f32"), (12, 96, 49, "bf16"),
-                                            (16, 3072, 9, "f32"), (15, 3076, 9, "bf16")])   # many features: split form
+                                            (44, 3072, 9, "f32"), (41, 3076, 9, "bf16")])   # large products: split form
 def test_per_tap_transform(S, M, taps, dtype):
     rng = np.random.default_rng(S * 1000 + M)
     G = (0.03 * rng.standard_normal((S, M, taps))).astype(np.float32)
@@ -48,9 +48,9 @@ def test_per_tap_transform(S, M, taps, dtype):
 @pytest.mark.parametrize("S,M,taps,dtype,mom,wd", [(32, 64, 1, "f32", 0.0, 0.0), (64, 576, 1, "f32", 0.9, 5e-4), (19, 67, 1, "f32", 0.9, 1e-4),
                                                    (48, 128, 9, "f32", 0.9, 5e-4), (40, 256, 1, "bf16", 0.9, 5e-4),
                                                    (33, 96, 9, "bf16", 0.5, 0.0), (512, 2304, 1, "f32", 0.9, 1e-4),
-                                                   # many features with the workspace: the product takes the split form
-                                                   (256, 3072, 1, "f32", 0.9, 5e-4), (130, 3076, 1, "bf16", 0.9, 5e-4),
-                                                   (16, 3072, 9, "f32", 0.5, 1e-4)])
+                                                   # large products with the workspace: the product takes the split form
+                                                   (400, 3072, 1, "f32", 0.9, 5e-4), (370, 3076, 1, "bf16", 0.9, 5e-4),
+                                                   (48, 3072, 9, "f32", 0.5, 1e-4), (1100, 1536, 1, "f32", 0.9, 5e-4)])
 def test_fused_weight_update(S, M, taps, dtype, mom, wd):
     rng = np.random.default_rng(S + 7 * M + taps)
     shape = (S, M) if taps == 1 else (S, M, taps)
@@ -66,7 +66,7 @@ def test_fused_weight_update(S, M, taps, dtype, mom, wd):
         G = (0.05 * rng.standard_normal(shape)).astype(np.float32)
         if dtype == "bf16":
             G = wl.round_to_bf16(G)
-        b.fw_sgd_update(dev(G, tdt), dt, S, M, taps, dev(Q), prm, Wd, Vd, ws if (dtype == "bf16" or taps > 1 or M >= 3072) else None)
+        b.fw_sgd_update(dev(G, tdt), dt, S, M, taps, dev(Q), prm, Wd, Vd, ws if (dtype == "bf16" or taps > 1 or M >= 1536) else None)
         torch.cuda.synchronize()
         # teacher-forced: the oracle starts every update from the GPU's previous float32 state
         W_prev = W_o
