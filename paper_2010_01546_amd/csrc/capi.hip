@@ -38,7 +38,7 @@ bool grad_split_applies(int S, int M) {
     return M >= 1024 && S >= 128 && (long long)S * M >= (M >= 2048 ? FW_GRAD_SPLIT_MIN_SM_WIDE : FW_GRAD_SPLIT_MIN_SM);
 }
 size_t grad_split_bytes(int S, int M) {
-    return grad_split_applies(S, M) ? gemm_split_packed_bytes(M, M) + gemm_split_packed_bytes(S, M) + gemm_split_partial_bytes(S, M) : 0;
+    return grad_split_applies(S, M) ? gemm_split_packed_bytes(M, M) + gemm_split_packed_bytes(S, M) + gemm_split_partial_bytes(S, M, M) : 0;
 }
 
 // rows [n, M] float32 times Q on the bfloat16 matrix cores (split form), the runs of the contraction index added by the

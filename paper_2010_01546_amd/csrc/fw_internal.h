@@ -161,7 +161,8 @@ size_t gemm_split_packed_bytes(int rows, int K);
 fw_status gemm_split_pack(const float* X, int rows, int K, void* Xp, hipStream_t st);
 fw_status gemm_split_pack_transposed(const float* X, int K, int rows, void* Xp, hipStream_t st);
 double gemm_split_flops_issued(int R, int N, int K, int lower, bool with_runs = false);
-size_t gemm_split_partial_bytes(int R, int N);
+int gemm_split_runs(int R, int N, int K);
+size_t gemm_split_partial_bytes(int R, int N, int K);
 fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st,
                          float* part = nullptr, int* runs_out = nullptr);
 

@@ -355,7 +355,16 @@ fw_status gemm_split_pack_transposed(const float* X, int K, int rows, void* Xp, 
 }
 
 // flops the matrix cores execute for one product (three bfloat16 terms per float32 multiplication, whole tiles)
-size_t gemm_split_partial_bytes(int R, int N) { return align_up((size_t)GEMM_SPLIT_MAX_RUNS * R * N * sizeof(float), 256); }
+// runs gemm_split_run cuts the contraction index of a full product into when it is given room for partial results
+int gemm_split_runs(int R, int N, int K) {
+    SplitGeom g;
+    if (!make_split_geom(R, N, K, 0, &g, GEMM_SPLIT_MAX_RUNS)) return 1;
+    return g.nks;
+}
+// room for those runs (for one result at least: a caller that sums the runs itself gets a single run there too)
+size_t gemm_split_partial_bytes(int R, int N, int K) {
+    return align_up((size_t)gemm_split_runs(R, N, K) * R * N * sizeof(float), 256);
+}
 
 // with_runs: as gemm_split_run chooses the tiles when it is given room for partial results
 double gemm_split_flops_issued(int R, int N, int K, int lower, bool with_runs) {
@@ -366,7 +375,7 @@ double gemm_split_flops_issued(int R, int N, int K, int lower, bool with_runs) {
 
 // C [R, N] = A B^T from the packed operands (A [R, K], B [N, K]); lower != 0: C is known to be symmetric (R == N) and
 // only its lower triangle is written.
-// part: room for gemm_split_partial_bytes(R, N) bytes, or null (then the contraction index is never cut into runs)
+// part: room for gemm_split_partial_bytes(R, N, K) bytes, or null (then the contraction index is never cut into runs)
 // runs_out: when given (with part, and C == part), the runs are left unsummed in part[run][R][N] (a single run: part[0]) and
 //   their number is returned, for a caller that adds them in an epilogue of its own
 fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, int lower, float* C, hipStream_t st, float* part,
