@@ -144,7 +144,8 @@ fw_status fw_cov_finalize(const float* A, const float* s, long long n, int M, fl
  *               a few 1e-7; 1.5 to 2.6 times as fast)
  * dt = FW_F32: float32 matrix-core products.
  * dt = FW_BF16 with the workspace: G is widened to float32 in the workspace, the products are float32 on the matrix
- *   cores with Q as it is, G_out is rounded to bfloat16 (nearest even).
+ *   cores with Q as it is (past the size rule above, with M a multiple of 4: the split form), G_out is rounded to
+ *   bfloat16 (nearest even).
  * dt = FW_BF16 without it: Q is rounded to bfloat16 on the fly, products are bf16 x bf16 accumulated in float32,
  *   G_out is rounded to bfloat16.  Q must be symmetric in every mode (its rows are read as its columns).
  */

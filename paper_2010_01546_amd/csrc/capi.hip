@@ -129,6 +129,9 @@ fw_status fw_grad_transform(const void* G, fw_dtype dt, int S, int M, const floa
         if (rc != FW_OK) return rc;
         GemmEpilogue e = {};
         e.out = G_out; e.out_bf16 = 1; e.taps = 1;
+        // a large product takes the split form from the widened copy, its runs summed and rounded by the epilogue pass
+        if (grad_split_applies(S, M) && (M & 3) == 0 && ws_bytes >= fixed + grad_gemm_partial_bytes(S, M) + grad_split_bytes(S, M))
+            return split_rows_apply(G32, S, M, Q, e, reinterpret_cast<char*>(ws) + fixed + grad_gemm_partial_bytes(S, M), st);
         return grad_gemm_f32(G32, S, M, Q, e, st, part);
     }
     if (dt == FW_F32 && grad_split_applies(S, M) && ws &&
@@ -314,7 +317,7 @@ size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtyp
         case FW_OP_GRAD_TRANSFORM:
             if (M <= 0 || M > 16384) return 0;
             return grad_ws_bytes(M) + ((dt == FW_BF16 && S > 0) ? grad_wide_bytes(S, M) : 0) + (S > 0 ? grad_gemm_partial_bytes(S, M) : 0) +
-                   ((dt == FW_F32 && S > 0) ? grad_split_bytes(S, M) : 0);
+                   (S > 0 ? grad_split_bytes(S, M) : 0);
         case FW_OP_COND_REDUCE_STEP: return M > 0 && M <= 16384 ? cond_workspace_bytes(M) : 0;
         case FW_OP_WHITEN_EVD: return M > 0 && M <= 16384 ? evd_workspace_bytes(M) : 0;
         case FW_OP_COND_STATE_REFRESH: return M > 0 && M <= 16384 ? cond_refresh_workspace_bytes(M) : 0;

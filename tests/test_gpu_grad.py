@@ -81,6 +81,16 @@ def test_f32_split_form_for_many_features(S, M):
     b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, dev(Q32), out3)
     torch.cuda.synchronize()
     assert relF(out3.cpu().numpy(), want) < 1e-6
+    # bfloat16 gradients of the same size: widened, split form, one rounding at the end
+    if M % 4 == 0:
+        Gb = wl.round_to_bf16(G)
+        wsb = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S, None, b.FW_BF16))
+        outb = torch.zeros(S, M, device=DEV, dtype=torch.bfloat16)
+        b.fw_grad_transform(dev(Gb, torch.bfloat16), b.FW_BF16, S, M, None, dev(Q32), outb, wsb)
+        torch.cuda.synchronize()
+        wantb = ora.grad_transform(Gb, Q32)
+        assert relF(outb.float().cpu().numpy(), wantb) < 3e-3
+        assert np.all(np.abs(outb.float().cpu().numpy() - wantb) <= np.abs(wantb) * 2.0 ** -8 + 1e-5 * np.abs(wantb).max())
 
 
 @pytest.mark.parametrize("S,M", [(32, 64), (5, 7), (64, 576), (70, 200), (130, 147), (33, 260)])
