@@ -56,7 +56,8 @@ def parse(argv=None):
     ap.add_argument("--config", default="all", choices=["all", "c1", "c2", "c3", "c4", "c5"],
                     help="all (default): C2, C3 and C4 in one process, C4 on top; c5 sweeps the 21 ResNet-18 layers and "
                          "reports the aggregate")
-    ap.add_argument("--evd", action="store_true", help="also time one fw_whiten_evd call (outside the headline)")
+    ap.add_argument("--evd", action="store_true",
+                    help="time one fw_whiten_evd call (outside the headline) even with --no-extras; the default run times it anyway")
     ap.add_argument("--layout", default="kkc", choices=["kkc", "nhwc", "nchw"],
                     help="kkc: NHWC tensor with channels-last feature order (ky,kx,c); nhwc/nchw: feature order (c,ky,kx)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
