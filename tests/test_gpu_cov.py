@@ -278,3 +278,30 @@ def test_many_features_go_to_the_split_form_by_estimate(n_rows, M):
     assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_ROWS, b.conv_desc(1000, 2304, 1, 1, 1, 1, 1, 0)).split_bf16 == 0
     assert b.fw_cov_plan_query(b.FW_F32, b.FW_LAYOUT_ROWS, b.conv_desc(100000, 500, 1, 1, 1, 1, 1, 0)).split_bf16 == 0
 
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_largest_feature_count(dtype):
+    """M = 16384, the library's limit (A is 1 GiB): a handful of rows keeps the float64 reference cheap; compared row
+    block by row block on the device-side copy; one more feature is refused."""
+    n_rows, M = 6, 16384
+    rng = np.random.default_rng(5)
+    X = (rng.standard_normal((n_rows, M)) + 0.25).astype(np.float32)
+    if dtype == "bf16":
+        X = wl.round_to_bf16(X)
+    layer = wl.Layer("max-M", wl.ConvDesc(B=n_rows, Cin=M, H=1, W=1), 4, dtype, X, np.zeros((4, M), np.float32), is_rows=True)
+    A, s = run_cov(layer, b.FW_LAYOUT_ROWS)
+    X64 = X.astype(np.float64)
+    assert relF(s.cpu().numpy(), X64.sum(axis=0)) < 1e-5
+    num = den = 0.0
+    for r0 in range(0, M, 2048):
+        want = X64[:, r0:r0 + 2048].T @ X64                       # rows r0 .. of X^T X
+        got = A[r0:r0 + 2048].cpu().numpy().astype(np.float64)
+        mask = np.arange(M)[None, :] <= (r0 + np.arange(want.shape[0]))[:, None]
+        assert not got[~mask].any(), "entries above the diagonal must stay untouched"
+        num += float(((got - want)[mask] ** 2).sum())
+        den += float((want[mask] ** 2).sum())
+    assert (num / den) ** 0.5 < 1e-5
+    del A
+    d = b.conv_desc(n_rows, M + 1, 1, 1, 1, 1, 1, 0)
+    assert b.fw_workspace_bytes(b.FW_OP_COV_ACCUMULATE, M + 1, 0, d, b.FW_F32) == 0

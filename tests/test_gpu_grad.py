@@ -181,3 +181,29 @@ def test_config1_gradient_with_identity_is_copy():
     b.fw_grad_transform(dev(L.G), b.FW_F32, S, M, None, torch.eye(M, device=DEV), out)
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), L.G)
+
+
+def test_largest_feature_count():
+    """M = 16384, the library's limit (Q is 1 GiB): Q = I + u u^T + v v^T keeps the float64 reference a few dot products."""
+    S, M = 40, 16384
+    r = np.random.default_rng(12)
+    u = (r.standard_normal(M) / np.sqrt(M)).astype(np.float32)
+    v = (r.standard_normal(M) / np.sqrt(M)).astype(np.float32)
+    Q = torch.eye(M, device=DEV)
+    ud, vd = dev(u), dev(v)
+    Q += torch.outer(ud, ud) + torch.outer(vd, vd)
+    Q = torch.maximum(Q, Q.T).contiguous()                       # exactly symmetric
+    G = (r.standard_normal((S, M)) * 0.1).astype(np.float32)
+    out = torch.full((S, M), float("nan"), device=DEV)
+    b.fw_grad_transform(dev(G), b.FW_F32, S, M, None, Q, out)
+    torch.cuda.synchronize()
+    # the reference from the same float32 Q, block of columns by block of columns
+    G64 = G.astype(np.float64)
+    num = den = 0.0
+    for c0 in range(0, M, 2048):
+        want = G64 @ Q[:, c0:c0 + 2048].cpu().numpy().astype(np.float64)
+        got = out[:, c0:c0 + 2048].cpu().numpy().astype(np.float64)
+        num += float(((got - want) ** 2).sum()); den += float((want ** 2).sum())
+    assert (num / den) ** 0.5 < 1e-5
+    with pytest.raises(b.FwError):
+        b.fw_grad_transform(dev(G[:, :64]), b.FW_F32, S, M + 4, None, Q, out)
