@@ -140,6 +140,15 @@ def grad_checks(layer, Qs_dev, label):
     e = relF(out.cpu().numpy(), ora.grad_transform(layer.G, Qh))
     print(f"{label}: rel-F(G Q) = {e:.3e}")
     assert e < 1e-5
+    # as the benchmark calls it: with the whole workspace (large products then take the split form: 16-bit operands)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S))
+    out2 = torch.empty_like(Gd)
+    b.fw_grad_transform(Gd, b.FW_F32, S, M, None, Qs_dev, out2, ws)
+    torch.cuda.synchronize()
+    e2 = relF(out2.cpu().numpy(), ora.grad_transform(layer.G, Qh))
+    split = b.fw_grad_plan_query(b.FW_F32, S, M, b.fw_workspace_bytes(b.FW_OP_GRAD_TRANSFORM, M, S)).split
+    print(f"{label}: with the workspace ({'split' if split else 'float32'} form) rel-F(G Q) = {e2:.3e}")
+    assert e2 < (2e-5 if split else 1e-5)
     Gb = wl.round_to_bf16(layer.G)
     want = ora.grad_transform(Gb, Qh)
     outb = torch.empty(S, M, device=DEV, dtype=torch.bfloat16)
