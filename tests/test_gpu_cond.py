@@ -140,3 +140,31 @@ def test_refresh_for_a_new_block(M, leak, split):
         assert max(relF(run.host("T"), new.T), relF(run.host("Q"), new.Q), relF(run.host("Qs"), new.Qs)) < 1e-4
     Tn = run.host("T")
     assert relF(run.host("Phi_y"), Tn @ Phi2 @ Tn.T) < 1e-4
+
+
+@pytest.mark.timeout(600)
+def test_refresh_at_the_largest_config_size():
+    """M = 4608, as the benchmark calls it (whole workspace: both products in the split form on 192 x 256 tiles, the second
+    on the lower triangle only): Psi, Phi_y and the column norms against explicit float64 products."""
+    M = 4608
+    Phi1 = spd(M, 21).astype(np.float32).astype(np.float64)
+    Phi2 = spd(M, 22, hi=1.5, lo=-1.0).astype(np.float32).astype(np.float64)
+    gp = b.cond_params()
+    run = CondRunner(Phi1, np.trace(Phi1) / M, gamma_lt_one=True)
+    for _ in range(8):
+        run.step(gp)
+    T = run.host("T")
+    assert not np.allclose(T, np.eye(M))
+    run.Phi_x.copy_(dev(Phi2))
+    run.lbar.fill_(float(np.float32(np.trace(Phi2) / M)))
+    full = b.fw_workspace_bytes(b.FW_OP_COND_STATE_REFRESH, M)
+    assert b.fw_cond_refresh_plan_query(M, full).split == 1
+    b.fw_cond_state_refresh(run.st, workspace(full))
+    torch.cuda.synchronize()
+    Psi_o = T @ Phi2
+    want = Psi_o @ T.T
+    Py = run.host("Phi_y")
+    e_psi, e_py = relF(run.host("Psi"), Psi_o), relF(Py, want)
+    print(f"M={M}: rel-F(Psi) = {e_psi:.2e}, rel-F(Phi_y) = {e_py:.2e}")
+    assert e_psi < 2e-5 and e_py < 2e-5 and np.array_equal(Py, Py.T)
+    assert relF(run.host("xi2"), np.sum(want ** 2, axis=0)) < 4e-5
