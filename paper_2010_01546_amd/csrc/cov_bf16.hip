@@ -609,6 +609,15 @@ __global__ __launch_bounds__(256) void shift_tile_assemble_kernel(TileGeom g, co
         if (!active) return;
         const double v[4] = {v0, v1, v2, v3};
         const bool kkc = g.layout == FW_LAYOUT_NHWC_KKC;
+        if (kkc && (t1 != t2 || c2 + 3 <= c1)) {
+            // channels-last order: the four columns are contiguous in A (16-byte aligned: Cin and c2 are multiples of 4)
+            float4* dst = reinterpret_cast<float4*>(A + (size_t)(t1 * g.Cin + c1) * g.M + (size_t)t2 * g.Cin + c2);
+            float4 o = *dst;
+            o.x = (float)((double)o.x + v0); o.y = (float)((double)o.y + v1);
+            o.z = (float)((double)o.z + v2); o.w = (float)((double)o.w + v3);
+            *dst = o;
+            return;
+        }
         // the four old values are read before the first new one is written (a read behind a write would wait for it)
         float* dst[4];
         float old[4];
