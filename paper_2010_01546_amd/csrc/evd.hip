@@ -9,8 +9,9 @@
 // that makes the 64 rows orthogonal to each other, and the application of that rotation to the rows of W and V.
 // A round therefore streams W and V once for 64 rows per pair instead of once per single row pair.  All of it runs
 // in float64 inside the workspace so that small eigenvalues, which carry the largest gains, keep their relative
-// accuracy.  T = V^T diag(sqrt g) V and Q = V^T diag(g) V are then symmetric rank-M updates of row-scaled copies of V
-// and reuse the float32 matrix-core covariance kernel.
+// accuracy.  T = V^T diag(sqrt g) V and Q = V^T diag(g) V are then symmetric rank-M updates of row-scaled copies of V:
+// through the float32 matrix-core covariance kernel, or for many features as split products on the bfloat16 matrix
+// cores (gemm_split.hip).
 #include "fw_internal.h"
 
 namespace fw {
@@ -24,7 +25,12 @@ struct EvdWs {
     size_t W, V, lam, gq, gh, cnt, X, dummy_s, cov, gpart, rot, flags, total;
     int nblk, nblk_even, npairs, nslices;
 };
+// T and Q from the scaled eigenvectors: from FW_REFRESH_SPLIT_MIN_M features on as split products on the bfloat16 matrix
+// cores (the packed planes of X^T live where the covariance kernel's scratch would), below that through the float32
+// covariance kernel
+inline bool evd_products_split(int M) { return M >= FW_REFRESH_SPLIT_MIN_M; }
 inline size_t cov_ws_for(int M) {
+    if (evd_products_split(M)) return gemm_split_packed_bytes(M, M);
     fw_conv_desc d = {M, M, 1, 1, 1, 1, 1, 0, FW_COV_FORM_DIRECT};   // products in float32, never the split form
     return cov_workspace_bytes(M, &d, FW_F32, FW_LAYOUT_ROWS);
 }
@@ -414,11 +420,21 @@ fw_status whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float* T
     for (int which = 0; which < 2; ++which) {
         float* out = which == 0 ? T : Q;
         hipLaunchKernelGGL(scale_rows_kernel, dim3(grid_for(n)), dim3(256), 0, st, V, which == 0 ? gq : gh, M, X);
-        hipLaunchKernelGGL(fill_kernel, dim3(grid_for(n)), dim3(256), 0, st, out, n, 0.f);
-        hipLaunchKernelGGL(fill_kernel, dim3(grid_for(M)), dim3(256), 0, st, dummy_s, (size_t)M, 0.f);
         FW_LAUNCH_CHECK();
-        fw_status rc = cov_accumulate(X, FW_F32, FW_LAYOUT_ROWS, &d, out, dummy_s, cov_ws, cov_ws_bytes, st);
-        if (rc != FW_OK) return rc;
+        fw_status rc;
+        if (evd_products_split(M)) {
+            // X^T X = (X^T)(X^T)^T: the columns of X as hi + lo planes are both operands; lower triangle only
+            rc = gemm_split_pack_transposed(X, M, M, cov_ws, st);
+            if (rc != FW_OK) return rc;
+            rc = gemm_split_run(cov_ws, cov_ws, M, M, M, 1, out, st);
+            if (rc != FW_OK) return rc;
+        } else {
+            hipLaunchKernelGGL(fill_kernel, dim3(grid_for(n)), dim3(256), 0, st, out, n, 0.f);
+            hipLaunchKernelGGL(fill_kernel, dim3(grid_for(M)), dim3(256), 0, st, dummy_s, (size_t)M, 0.f);
+            FW_LAUNCH_CHECK();
+            rc = cov_accumulate(X, FW_F32, FW_LAYOUT_ROWS, &d, out, dummy_s, cov_ws, cov_ws_bytes, st);
+            if (rc != FW_OK) return rc;
+        }
         rc = symmetrize_from_lower(out, M, st);
         if (rc != FW_OK) return rc;
     }
