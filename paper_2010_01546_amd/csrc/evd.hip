@@ -159,17 +159,17 @@ __global__ __launch_bounds__(256) void gram_kernel(const double* __restrict__ W,
     }
 }
 
-// Diagonalisation of the 64x64 Gram matrix of a pair: cyclic Jacobi with 32 disjoint index pairs per step (8 threads
-// per index pair).  The accumulated rotation R (new rows = R old rows, R G R^T diagonal) goes to Rot[pair];
+// Diagonalisation of the 64x64 Gram matrix of a pair: cyclic Jacobi with 32 disjoint index pairs per step (32 threads
+// per index pair: half a wavefront).  The accumulated rotation R (new rows = R old rows, R G R^T diagonal) goes to Rot[pair];
 // flags[pair] = 1 if any rotation was applied, and the counter gets the number applied in the first inner sweep.
-__global__ __launch_bounds__(256) void pair_evd_kernel(const double* __restrict__ Gpart, int nslices, double tol, int inner_sweeps,
+__global__ __launch_bounds__(1024) void pair_evd_kernel(const double* __restrict__ Gpart, int nslices, double tol, int inner_sweeps,
                                                        double* __restrict__ Rot,
                                                        int* __restrict__ flags, int* __restrict__ counter) {
     __shared__ double Gs[JP][JP + 1], Rs[JP][JP + 1];
     __shared__ int n_rot, n_first;
     const int tid = threadIdx.x;
-    const int kk = tid >> 3, sub = tid & 7;
-    for (int e = tid; e < JP * JP; e += 256) {
+    const int kk = tid >> 5, sub = tid & 31;
+    for (int e = tid; e < JP * JP; e += 1024) {
         const double* src = Gpart + (size_t)blockIdx.x * nslices * (JP * JP) + e;
         double g = 0.0;
         for (int sl = 0; sl < nslices; ++sl) g += src[(size_t)sl * (JP * JP)];
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void pair_evd_kernel(const double* __restrict_
             int i, j;
             rr_pair(JP, step, kk, &i, &j);
             if (i > j) { const int t = i; i = j; j = t; }
-            // every thread of the index pair works out the rotation for itself: the eight of them sit in one wavefront,
+            // every thread of the index pair works out the rotation for itself: the 32 of them sit in one wavefront,
             // so all of them have read the three entries before any of them rewrites rows i and j
             const double al = Gs[i][i], be = Gs[j][j], ga = Gs[i][j];
             double c = 1.0, s = 0.0;
@@ -197,8 +197,8 @@ __global__ __launch_bounds__(256) void pair_evd_kernel(const double* __restrict_
             }
             if (s != 0.0) {   // rows i, j of G and of R
 #pragma unroll
-                for (int m = 0; m < 8; ++m) {
-                    const int col = sub + 8 * m;
+                for (int m = 0; m < 2; ++m) {
+                    const int col = sub + 32 * m;
                     const double x = Gs[i][col], y = Gs[j][col];
                     Gs[i][col] = c * x - s * y; Gs[j][col] = s * x + c * y;
                     const double e = Rs[i][col], f = Rs[j][col];
@@ -208,8 +208,8 @@ __global__ __launch_bounds__(256) void pair_evd_kernel(const double* __restrict_
             __syncthreads();
             if (s != 0.0) {   // columns i, j of G
 #pragma unroll
-                for (int m = 0; m < 8; ++m) {
-                    const int row = sub + 8 * m;
+                for (int m = 0; m < 2; ++m) {
+                    const int row = sub + 32 * m;
                     const double x = Gs[row][i], y = Gs[row][j];
                     Gs[row][i] = c * x - s * y; Gs[row][j] = s * x + c * y;
                 }
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256) void pair_evd_kernel(const double* __restrict_
         if (r == 0) break;
     }
     if (total > 0)
-        for (int e = tid; e < JP * JP; e += 256) Rot[(size_t)blockIdx.x * (JP * JP) + e] = Rs[e >> 6][e & 63];
+        for (int e = tid; e < JP * JP; e += 1024) Rot[(size_t)blockIdx.x * (JP * JP) + e] = Rs[e >> 6][e & 63];
     if (tid == 0) {
         flags[blockIdx.x] = total > 0 ? 1 : 0;
         if (n_first > 0) atomicAdd(counter, n_first);
@@ -402,7 +402,7 @@ fw_status whiten_evd(const float* Phi_x, int M, const fw_evd_params* p, float* T
         hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, cnt);
         for (int r = 0; r < L.nblk_even - 1; ++r) {
             hipLaunchKernelGGL(gram_kernel, dim3(L.nslices, L.npairs), dim3(256), 0, st, W, M, L.nblk, L.nblk_even, r, L.nslices, Gpart);
-            hipLaunchKernelGGL(pair_evd_kernel, dim3(L.npairs), dim3(256), 0, st, Gpart, L.nslices, tol, inner, Rot, flags, cnt);
+            hipLaunchKernelGGL(pair_evd_kernel, dim3(L.npairs), dim3(1024), 0, st, Gpart, L.nslices, tol, inner, Rot, flags, cnt);
             hipLaunchKernelGGL(rotate_rows_kernel, dim3(ncolblk, L.npairs, 2), dim3(256), 0, st, W, V, M, L.nblk, L.nblk_even, r, Rot,
                                flags);
         }
