@@ -45,6 +45,12 @@ PROFILED_TRAFFIC = {
 TRAFFIC_SOURCE = ("profiles/whitened_update_step_hbm_traffic_counters.txt (rocprofv3 counters of an earlier run of this command, "
                   "not measured by this run)")
 
+# What a kernel of nothing but dense bfloat16 MFMAs on random operands sustains on this chip (all 256 compute units busy:
+# the matrix cores then run at about 1.45 GHz under the chip's power limit, not at the 2.4 GHz of the published peak).
+# NOT measured by this script: from ablations of the split product kernel (its loads, LDS reads and barriers removed).
+SUSTAINED_BF16_MFMA = 1.45e15
+SUSTAINED_SOURCE = "ablation of gemm_split_kernel (MFMAs alone, M = 4096 and 4608), not measured by this run"
+
 EXPORTS = ("cov_accumulate", "cov_finalize", "cond_state_refresh", "cond_reduce_step", "grad_transform")
 
 
@@ -325,6 +331,11 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
     fn = {"bound": "hbm", "export": "fw_cov_finalize", "kernel": "finalize_phi64 + finalize_vec", "achieved": fin_bytes / t5 / 1e9,
           "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": fin_bytes / t5 / HBM_PEAK, "ms": ex["cov_finalize"]}
     fn.update(traffic_of("cov_finalize"))
+    for e in (a1, a2, rf):   # bfloat16 products: the fraction of what the matrix cores sustain under the power limit, for context
+        if e["peak"] == PEAK["bf16"] / 1e12:
+            e["frac_of_sustained_mfma_rate"] = e["achieved"] * 1e12 / SUSTAINED_BF16_MFMA
+            e["sustained_mfma_rate_TFLOPs"] = SUSTAINED_BF16_MFMA / 1e12
+            e["sustained_mfma_rate_source"] = SUSTAINED_SOURCE
     return {"a1_cov_accumulate": a1, "a1_cov_finalize": fn, "a2_grad_transform": a2, "a3_cond_reduce_step": a3,
             "a3_cond_state_refresh": rf}
 
