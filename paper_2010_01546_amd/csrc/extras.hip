@@ -109,6 +109,7 @@ __global__ __launch_bounds__(1024) void diagnostics_final_kernel(const double* _
 // image already lies in the space built so far) is recorded in `st` on the device and the remaining launches return at once.
 struct ProbeState { int steps, done; double prev_beta; };
 constexpr int PROBE_MAX_K = 32;
+constexpr int PROBE_SPREAD_MIN_M = 2048;   // above this the orthogonalisation of a step runs on many workgroups
 
 // q_0 = b0 / |b0| (b0 = all ones when absent)
 __global__ __launch_bounds__(1024) void probe_init_kernel(const float* __restrict__ b0, int M, double* __restrict__ q0, ProbeState* __restrict__ st) {
@@ -245,6 +246,94 @@ __global__ __launch_bounds__(1024) void probe_orth_kernel(int j, int M, size_t l
     }
 }
 
+// The same step for many features, spread over ceil(M / 256) workgroups (thread t of workgroup b owns entry 256 b + t of
+// w) in four launches, because every reduction over all of w needs the workgroups to meet:
+//   phase 1  partial coefficients q_i . w of the first pass and the partial |w|^2
+//   phase 2  coefficients summed over the workgroups in a fixed order, w made orthogonal once, partial coefficients of the
+//            second pass (alpha_j = the first pass's coefficient of q_j)
+//   phase 3  second pass applied, partial |w|^2
+//   phase 4  beta_j = |w|, q_(j+1) = w / beta_j, or the breakdown flag
+// part: [2][nb][PROBE_MAX_K + 1] coefficients, then [2][nb] squared norms.
+constexpr int PROBE_WG = 256;
+__device__ __forceinline__ double block_sum_256(double v, double* red4) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red4[0] + red4[1] + red4[2] + red4[3];
+}
+template <int PHASE>
+__global__ __launch_bounds__(PROBE_WG) void probe_orth_phase_kernel(int j, int M, size_t ld, double* __restrict__ Qb, double* __restrict__ w,
+                                                                    double* __restrict__ part, double* __restrict__ alpha,
+                                                                    double* __restrict__ beta, double breakdown, ProbeState* __restrict__ st) {
+    constexpr int KP = PROBE_MAX_K + 1;
+    __shared__ double red4[4];
+    __shared__ double wpart[4][KP];
+    __shared__ double coef[KP];
+    if (st->done) return;
+    const int nb = gridDim.x, blk = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = blk * PROBE_WG + threadIdx.x;
+    const bool ok = m < M;
+    double* cpart = part;                              // [2][nb][KP]
+    double* npart = part + (size_t)2 * nb * KP;        // [2][nb]
+    double wm = ok ? w[m] : 0.0;
+    if (PHASE == 2 || PHASE == 3) {
+        // coefficients of the pass before: every workgroup adds the partial results in the same order
+        // (lane i of wavefront g takes the workgroups g, g + 4, ... of coefficient i; the four sums are added in order)
+        const double* src = cpart + (size_t)(PHASE - 2) * nb * KP;
+        {
+            double c = 0.0;
+            if (lane <= j) {
+#pragma unroll 4
+                for (int b = wave; b < nb; b += 4) c += src[(size_t)b * KP + lane];
+            }
+            if (lane < KP) wpart[wave][lane] = c;
+        }
+        __syncthreads();
+        if ((int)threadIdx.x <= j) {
+            const double c = wpart[0][threadIdx.x] + wpart[1][threadIdx.x] + wpart[2][threadIdx.x] + wpart[3][threadIdx.x];
+            coef[threadIdx.x] = c;
+            if (PHASE == 2 && blk == 0 && (int)threadIdx.x == j) alpha[j] = c;
+        }
+        __syncthreads();
+        for (int i = 0; i <= j; ++i) wm -= coef[i] * (ok ? Qb[(size_t)i * ld + m] : 0.0);
+        if (ok) w[m] = wm;
+    }
+    if (PHASE == 1 || PHASE == 2) {
+        double* dst = cpart + ((size_t)(PHASE - 1) * nb + blk) * KP;
+        for (int i = 0; i <= j; ++i) {
+            double d = ok ? Qb[(size_t)i * ld + m] * wm : 0.0;
+            d = wave_sum(d);
+            if (lane == 0) wpart[wave][i] = d;
+        }
+        __syncthreads();
+        if ((int)threadIdx.x <= j) dst[threadIdx.x] = wpart[0][threadIdx.x] + wpart[1][threadIdx.x] + wpart[2][threadIdx.x] + wpart[3][threadIdx.x];
+    }
+    if (PHASE == 1 || PHASE == 3) {
+        const double s = block_sum_256(wm * wm, red4);
+        if (threadIdx.x == 0) npart[(size_t)(PHASE == 1 ? 0 : 1) * nb + blk] = s;
+    }
+    if (PHASE == 4) {
+        // at most 64 workgroups (M <= 16384): one partial norm per lane of the first wavefront, butterfly sum (fixed order)
+        double s0 = ((int)threadIdx.x < nb) ? npart[threadIdx.x] : 0.0;
+        double s1 = ((int)threadIdx.x < nb) ? npart[(size_t)nb + threadIdx.x] : 0.0;
+        s0 = wave_sum(s0); s1 = wave_sum(s1);
+        if (threadIdx.x == 0) { red4[0] = s0; red4[1] = s1; }
+        __syncthreads();
+        const double n0 = sqrt(red4[0]), nw = sqrt(red4[1]);
+        const bool stop = !(nw > breakdown * n0);
+        if (!stop && ok) Qb[(size_t)(j + 1) * ld + m] = wm / nw;
+        // beta and the state are written by one thread of this last launch of the step.  A workgroup of this launch that
+        // starts after the flag was raised returns at once; it would have written nothing (no q_(j+1) after a breakdown).
+        if (blk == nb - 1 && threadIdx.x == 0) {
+            beta[j] = nw;
+            st->steps = j + 1;
+            if (stop) st->done = 1;
+        }
+    }
+}
+
 // extreme eigenvalues of the symmetric tridiagonal matrix (alpha_0..alpha_(n-1); beta_0..beta_(n-2)) by bisection on the
 // number of eigenvalues below x (sign changes of the pivots of T - x I)
 __device__ int tridiag_count_below(const double* a, const double* b, int n, double x) {
@@ -302,7 +391,7 @@ __global__ __launch_bounds__(64) void probe_final_kernel(const double* __restric
 }  // namespace
 
 namespace {
-struct ProbeWs { size_t Q, w, alpha, beta, st, total, ld; };
+struct ProbeWs { size_t Q, w, alpha, beta, st, part, total, ld; };
 ProbeWs probe_layout(int M, int k) {
     ProbeWs L;
     L.ld = align_up((size_t)M, 32);
@@ -313,6 +402,8 @@ ProbeWs probe_layout(int M, int k) {
     L.alpha = take(PROBE_MAX_K * sizeof(double));
     L.beta = take(PROBE_MAX_K * sizeof(double));
     L.st = take(sizeof(ProbeState));
+    const size_t nb = ((size_t)M + PROBE_WG - 1) / PROBE_WG;
+    L.part = take((2 * nb * (PROBE_MAX_K + 1) + 2 * nb) * sizeof(double));
     L.total = o;
     return L;
 }
@@ -328,10 +419,19 @@ fw_status cond_probe(const float* Phi_y, int M, const float* b0, int k, float* o
     double* alpha = reinterpret_cast<double*>(base + L.alpha);
     double* beta = reinterpret_cast<double*>(base + L.beta);
     ProbeState* ps = reinterpret_cast<ProbeState*>(base + L.st);
+    double* part = reinterpret_cast<double*>(base + L.part);
     hipLaunchKernelGGL(probe_init_kernel, dim3(1), dim3(1024), 0, st, b0, M, Qb, ps);
     for (int j = 0; j < k; ++j) {
         hipLaunchKernelGGL(probe_matvec_kernel, dim3((M + 3) / 4), dim3(256), 0, st, Phi_y, Qb + (size_t)j * L.ld, M, w, ps);
-        if (M <= 4096) hipLaunchKernelGGL((probe_orth_kernel<4, 4>), dim3(1), dim3(1024), 0, st, j, M, L.ld, Qb, w, alpha, beta, 1e-7, ps);
+        if (M > PROBE_SPREAD_MIN_M) {
+            // many features: the step spread over ceil(M / 256) workgroups, four launches
+            const dim3 g((M + PROBE_WG - 1) / PROBE_WG), blk(PROBE_WG);
+            hipLaunchKernelGGL(probe_orth_phase_kernel<1>, g, blk, 0, st, j, M, L.ld, Qb, w, part, alpha, beta, 1e-7, ps);
+            hipLaunchKernelGGL(probe_orth_phase_kernel<2>, g, blk, 0, st, j, M, L.ld, Qb, w, part, alpha, beta, 1e-7, ps);
+            hipLaunchKernelGGL(probe_orth_phase_kernel<3>, g, blk, 0, st, j, M, L.ld, Qb, w, part, alpha, beta, 1e-7, ps);
+            hipLaunchKernelGGL(probe_orth_phase_kernel<4>, g, blk, 0, st, j, M, L.ld, Qb, w, part, alpha, beta, 1e-7, ps);
+        }
+        else if (M <= 4096) hipLaunchKernelGGL((probe_orth_kernel<4, 4>), dim3(1), dim3(1024), 0, st, j, M, L.ld, Qb, w, alpha, beta, 1e-7, ps);
         else if (M <= 8192) hipLaunchKernelGGL((probe_orth_kernel<8, 2>), dim3(1), dim3(1024), 0, st, j, M, L.ld, Qb, w, alpha, beta, 1e-7, ps);
         else hipLaunchKernelGGL((probe_orth_kernel<16, 1>), dim3(1), dim3(1024), 0, st, j, M, L.ld, Qb, w, alpha, beta, 1e-7, ps);
     }

@@ -145,7 +145,7 @@ def test_diagnostics(M):
     assert float(out[0]) == pytest.approx(1.0 / M, rel=1e-4)
 
 
-@pytest.mark.parametrize("M,k", [(8, 8), (33, 6), (200, 16), (577, 16), (2304, 12), (64, 32)])
+@pytest.mark.parametrize("M,k", [(8, 8), (33, 6), (200, 16), (577, 16), (2304, 12), (64, 32), (2500, 10), (4608, 16)])
 def test_condition_probe_against_the_oracle(M, k):
     """Extreme Ritz values of a symmetric positive definite matrix on a k-dimensional Krylov space: the GPU's Lanczos
     recurrence against the oracle's projection form, same start vector.  Both work in float64 on the float32 matrix, so
@@ -207,3 +207,20 @@ def test_condition_probe_follows_the_recursion():
     w = np.linalg.eigvalsh(run.host("Phi_y"))
     assert after < before / 3 and after <= w[-1] / w[0] * (1 + 1e-5)
     assert float(out[0]) == pytest.approx(w[-1], rel=1e-3)
+
+
+def test_condition_probe_breakdown_with_many_features():
+    """The form for many features (the step spread over several workgroups): an invariant subspace of dimension 3 stops the
+    recurrence there, on the device, and the later launches of the call do nothing."""
+    M = 3000
+    d = np.full(M, 0.25, dtype=np.float32)
+    d[7], d[1234], d[2999] = 9.0, 4.0, 1.0
+    b0 = np.zeros(M, dtype=np.float32)
+    b0[7] = b0[1234] = b0[2999] = 1.0
+    out = torch.full((4,), float("nan"), device=DEV)
+    ws = workspace(b.fw_workspace_bytes(b.FW_OP_COND_PROBE, M, 12))
+    b.fw_cond_probe(torch.diag(dev(d)).contiguous(), M, dev(b0), 12, out, ws)
+    torch.cuda.synchronize()
+    assert [float(v) for v in out] == pytest.approx([9.0, 1.0, 9.0, 3.0], rel=1e-6)
+    assert ora.condition_probe(np.diag(d.astype(np.float64)), b0.astype(np.float64), 12)[3] == 3
+
