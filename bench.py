@@ -45,11 +45,29 @@ PROFILED_TRAFFIC = {
 TRAFFIC_SOURCE = ("profiles/whitened_update_step_hbm_traffic_counters.txt (rocprofv3 counters of an earlier run of this command, "
                   "not measured by this run)")
 
-# What a kernel of nothing but dense bfloat16 MFMAs on random operands sustains on this chip (all 256 compute units busy:
-# the matrix cores then run at about 1.45 GHz under the chip's power limit, not at the 2.4 GHz of the published peak).
-# NOT measured by this script: from ablations of the split product kernel (its loads, LDS reads and barriers removed).
-SUSTAINED_BF16_MFMA = 1.45e15
-SUSTAINED_SOURCE = "ablation of gemm_split_kernel (MFMAs alone, M = 4096 and 4608), not measured by this run"
+# What a kernel of nothing but dense bfloat16 MFMAs on pseudo-random operands sustains on this chip (all 256 compute units
+# busy: the matrix cores then run well below the 2.4 GHz of the published peak, under the chip's power limit).  Measured
+# by every run with fw_mfma_rate_probe (measure_mfma_ceiling); the fallback is the figure of earlier runs.
+SUSTAINED_BF16_MFMA = {"rate": 1.45e15, "source": "earlier runs of fw_mfma_rate_probe, not measured by this run"}
+
+
+def measure_mfma_ceiling(torch, b):
+    """Sustained bfloat16 matrix-core rate of this GPU: ten back-to-back launches of the library's measurement kernel
+    (dense MFMAs on register operands, every compute unit busy) timed by events, for pseudo-random and for zero operands."""
+    sink = torch.zeros(4, device="cuda:0")
+    out = {}
+    for name, zero in (("random_operands", 0), ("zero_operands", 1)):
+        b.fw_mfma_rate_probe(zero, 400, sink); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = sum(b.fw_mfma_rate_probe(zero, 400, sink) for _ in range(10))
+        e1.record(); torch.cuda.synchronize()
+        out[name + "_TFLOPs"] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    out["kernel"] = "mfma_rate_kernel: 4096 wavefronts x 400 rounds x 16 v_mfma_f32_32x32x16_bf16, 10 launches"
+    out["published_peak_TFLOPs"] = PEAK["bf16"] / 1e12
+    SUSTAINED_BF16_MFMA["rate"] = out["random_operands_TFLOPs"] * 1e12
+    SUSTAINED_BF16_MFMA["source"] = "fw_mfma_rate_probe with pseudo-random operands, measured by this run before the timed loops"
+    return out
 
 EXPORTS = ("cov_accumulate", "cov_finalize", "cond_state_refresh", "cond_reduce_step", "grad_transform")
 
@@ -333,9 +351,9 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
     fn.update(traffic_of("cov_finalize"))
     for e in (a1, a2, rf):   # bfloat16 products: the fraction of what the matrix cores sustain under the power limit, for context
         if e["peak"] == PEAK["bf16"] / 1e12:
-            e["frac_of_sustained_mfma_rate"] = e["achieved"] * 1e12 / SUSTAINED_BF16_MFMA
-            e["sustained_mfma_rate_TFLOPs"] = SUSTAINED_BF16_MFMA / 1e12
-            e["sustained_mfma_rate_source"] = SUSTAINED_SOURCE
+            e["frac_of_sustained_mfma_rate"] = e["achieved"] * 1e12 / SUSTAINED_BF16_MFMA["rate"]
+            e["sustained_mfma_rate_TFLOPs"] = SUSTAINED_BF16_MFMA["rate"] / 1e12
+            e["sustained_mfma_rate_source"] = SUSTAINED_BF16_MFMA["source"]
     return {"a1_cov_accumulate": a1, "a1_cov_finalize": fn, "a2_grad_transform": a2, "a3_cond_reduce_step": a3,
             "a3_cond_state_refresh": rf}
 
@@ -508,8 +526,12 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
+    # (left out with --no-extras, so that a profile of such a run holds the kernels of the step only)
+    ceiling = None if args.no_extras else measure_mfma_ceiling(torch, b)
     if args.config == "c5":
-        print(json.dumps(run_c5(args, torch, b, wl)))
+        rec = run_c5(args, torch, b, wl)
+        rec["mfma_ceiling"] = ceiling
+        print(json.dumps(rec))
         return
     if args.config == "all":
         recs = {}
@@ -521,6 +543,7 @@ def main():
     else:
         out = config_record(args.config, args, torch, b, wl, np)
 
+    out["mfma_ceiling"] = ceiling
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, device="cuda:0")      # 256 MiB read + 256 MiB written per copy
         dst = torch.empty_like(src)

@@ -357,6 +357,16 @@ typedef struct {
 } fw_cov_plan;
 fw_status fw_cov_plan_query(fw_dtype dt, fw_layout lay, const fw_conv_desc* d, fw_cov_plan* plan);
 
+/* Measurement helper (not a step of the method): every compute unit runs nothing but dense bfloat16 matrix instructions
+ * (v_mfma_f32_32x32x16_bf16 on register operands: pseudo-random values, or zeros when zero_operands != 0) for `iters` rounds
+ * of 16 products per wavefront, 4096 wavefronts.  Timed by the caller, *flops_host / time is what the matrix cores
+ * sustain under the chip's power limit: the ceiling against which the rates of the product kernels are read
+ * (the published peak assumes a clock the chip does not hold under this load).
+ *   sink        out  one float on the device (never actually written: it keeps the products alive)
+ *   flops_host  out  HOST double: flops the launch executes; may be NULL
+ */
+fw_status fw_mfma_rate_probe(int zero_operands, int iters, float* sink, double* flops_host, void* stream);
+
 /* Scratch bytes an entry point needs for the given sizes (0 if none).  `d` is needed for FW_OP_COV_ACCUMULATE only;
  * for the per-tap operations S is the number of gradient rows, S * taps; for FW_OP_COND_PROBE S is the Krylov dimension k. */
 size_t fw_workspace_bytes(fw_op op, int M, int S, const fw_conv_desc* d, fw_dtype dt);

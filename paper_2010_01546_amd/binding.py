@@ -27,8 +27,8 @@ FW_LAYOUT_ROWS, FW_LAYOUT_NCHW, FW_LAYOUT_NHWC, FW_LAYOUT_NHWC_KKC = 0, 1, 2, 3
 EXPORTS = ["fw_cov_accumulate", "fw_cov_finalize", "fw_grad_transform", "fw_cond_state_init", "fw_cond_reduce_step",
            "fw_whiten_evd", "fw_cond_state_refresh", "fw_grad_transform_taps", "fw_sgd_update", "fw_bias_compensate",
            "fw_diagnostics", "fw_cov_plan_query", "fw_cond_reduce_step_static", "fw_cond_probe", "fw_cond_refresh_plan_query",
-           "fw_grad_plan_query", "fw_workspace_bytes", "fw_status_string", "fw_version"]
-N_STATUS_EXPORTS = 16   # the leading entries of EXPORTS return fw_status
+           "fw_grad_plan_query", "fw_mfma_rate_probe", "fw_workspace_bytes", "fw_status_string", "fw_version"]
+N_STATUS_EXPORTS = 17   # the leading entries of EXPORTS return fw_status
 
 
 class fw_conv_desc(C.Structure):
@@ -89,6 +89,7 @@ lib.fw_cond_probe.argtypes = [_P, C.c_int, _P, C.c_int, _P, _P, C.c_size_t, _P]
 lib.fw_cond_refresh_plan_query.argtypes = [C.c_int, C.c_size_t, C.POINTER(fw_refresh_plan)]
 lib.fw_cov_plan_query.argtypes = [C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.POINTER(fw_cov_plan)]
 lib.fw_grad_plan_query.argtypes = [C.c_int, C.c_int, C.c_int, C.c_size_t, C.POINTER(fw_grad_plan)]
+lib.fw_mfma_rate_probe.argtypes = [C.c_int, C.c_int, _P, C.POINTER(C.c_double), _P]
 lib.fw_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(fw_conv_desc), C.c_int]
 lib.fw_workspace_bytes.restype = C.c_size_t
 lib.fw_status_string.argtypes = [C.c_int]
@@ -209,6 +210,13 @@ def fw_grad_plan_query(dt, S, M, ws_bytes) -> fw_grad_plan:
     plan = fw_grad_plan()
     _check(lib.fw_grad_plan_query(dt, S, M, ws_bytes, C.byref(plan)), "fw_grad_plan_query")
     return plan
+
+
+def fw_mfma_rate_probe(zero_operands, iters, sink, stream=None) -> float:
+    """Launches the measurement kernel; returns the flops it executes (time it with events)."""
+    flops = C.c_double(0.0)
+    _check(lib.fw_mfma_rate_probe(int(bool(zero_operands)), int(iters), _ptr(sink), C.byref(flops), _stream(stream)), "fw_mfma_rate_probe")
+    return flops.value
 
 
 def fw_cov_plan_query(dt, lay, d) -> fw_cov_plan:

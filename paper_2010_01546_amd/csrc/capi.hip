@@ -214,6 +214,11 @@ fw_status fw_cond_probe(const float* Phi_y, int M, const float* b0, int k, float
     return cond_probe(Phi_y, M, b0, k, out, ws, reinterpret_cast<hipStream_t>(stream));
 }
 
+fw_status fw_mfma_rate_probe(int zero_operands, int iters, float* sink, double* flops_host, void* stream) {
+    if (!sink || iters <= 0 || iters > (1 << 24)) return FW_ERR_INVALID_ARG;
+    return mfma_rate_probe(zero_operands ? 1 : 0, iters, sink, flops_host, reinterpret_cast<hipStream_t>(stream));
+}
+
 fw_status fw_cond_state_init(const fw_cond_state* st, void* stream) {
     if (!st || st->M <= 0 || !st->Phi_x || !st->T || !st->Q || !st->Qs || !st->Phi_y || !st->xi2) return FW_ERR_INVALID_ARG;
     if (!aligned16(st->Phi_x) || !aligned16(st->T) || !aligned16(st->Q) || !aligned16(st->Qs) || !aligned16(st->Phi_y) ||

@@ -440,6 +440,55 @@ fw_status cond_probe(const float* Phi_y, int M, const float* b0, int k, float* o
     return FW_OK;
 }
 
+// ---- measurement helper: what the bfloat16 matrix cores sustain when every compute unit does nothing but dense
+// v_mfma_f32_32x32x16_bf16 (the ceiling under the chip's power limit, against which the product kernels are read).
+// A wavefront holds four A and four B fragments in registers (pseudo-random bfloat16 values in [-2, 2), or zeros) and
+// runs `iters` rounds of the 16 products a_i b_j on 16 independent accumulators; the accumulators are added into `sink`
+// at the end so that nothing is optimised away.
+namespace {
+constexpr int RATE_WGS = 1024;
+__global__ __launch_bounds__(256) void mfma_rate_kernel(int zero_operands, int iters, float* __restrict__ sink) {
+    bf16x8 a[4], b[4];
+    unsigned h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+    for (int f = 0; f < 8; ++f) {
+        unsigned short v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+            // sign, exponent 126..128 (values in [0.5, 4)), 7 mantissa bits
+            v[i] = zero_operands ? (unsigned short)0 : (unsigned short)(((h >> 3) & 0x8000u) | ((126u + (h >> 20) % 3u) << 7) | (h & 0x7Fu));
+        }
+        union { unsigned short u[8]; bf16x8 x; } cv;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) cv.u[i] = v[i];
+        if (f < 4) a[f] = cv.x; else b[f - 4] = cv.x;
+    }
+    floatx16 acc[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 16; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t >> 2], b[t & 3], acc[t], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum += acc[t][i];
+    if (sum == 123.456f) sink[0] = sum;     // never true for these operands: keeps the products alive without a store per lane
+}
+}  // namespace
+
+fw_status mfma_rate_probe(int zero_operands, int iters, float* sink, double* flops, hipStream_t st) {
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(RATE_WGS), dim3(256), 0, st, zero_operands, iters, sink);
+    FW_LAUNCH_CHECK();
+    if (flops) *flops = (double)RATE_WGS * 4.0 * (double)iters * 16.0 * 2.0 * 32.0 * 32.0 * 16.0;
+    return FW_OK;
+}
+
 fw_status bias_compensate(float* b, const float* W, int S, int M, int taps, const float* mu_old, const float* mu_new, float scale,
                           hipStream_t st) {
     hipLaunchKernelGGL(bias_compensate_kernel, dim3((S + 3) / 4), dim3(256), 0, st, b, W, S, M, taps, mu_old, mu_new, scale);

@@ -167,6 +167,7 @@ fw_status gemm_split_run(const void* Ap, const void* Bp, int R, int N, int K, in
                          float* part = nullptr, int* runs_out = nullptr);
 
 // ---- extras.hip
+fw_status mfma_rate_probe(int zero_operands, int iters, float* sink, double* flops, hipStream_t st);
 fw_status bias_compensate(float* b, const float* W, int S, int M, int taps, const float* mu_old, const float* mu_new, float scale,
                           hipStream_t st);
 size_t diagnostics_workspace_bytes(int M);

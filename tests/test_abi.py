@@ -72,6 +72,9 @@ def test_argument_validation_without_a_device():
     assert L.fw_cov_accumulate(fake + 4, 0, 2, C.byref(d), fake, fake, fake, 1 << 30, None) == b.FW_ERR_ALIGNMENT
     assert L.fw_cov_accumulate(fake, 0, 2, C.byref(d), fake, fake, None, 0, None) == b.FW_ERR_WORKSPACE
     assert L.fw_cov_accumulate(fake, 0, 2, C.byref(d), fake, fake, fake, 16, None) == b.FW_ERR_WORKSPACE
+    # measurement helper
+    assert L.fw_mfma_rate_probe(0, 100, None, None, None) == b.FW_ERR_INVALID_ARG
+    assert L.fw_mfma_rate_probe(0, 0, fake, None, None) == b.FW_ERR_INVALID_ARG
     # finalize
     assert L.fw_cov_finalize(fake, fake, 0, 8, 0.5, 0, fake, fake, fake, fake, None) == b.FW_ERR_INVALID_ARG
     assert L.fw_cov_finalize(fake, fake, 10, 8, 1.5, 0, fake, fake, fake, fake, None) == b.FW_ERR_INVALID_ARG

@@ -224,3 +224,20 @@ def test_condition_probe_breakdown_with_many_features():
     assert [float(v) for v in out] == pytest.approx([9.0, 1.0, 9.0, 3.0], rel=1e-6)
     assert ora.condition_probe(np.diag(d.astype(np.float64)), b0.astype(np.float64), 12)[3] == 3
 
+
+def test_matrix_core_rate_probe():
+    """The measurement kernel behind the bench's ceiling: runs, reports its flops, and multiplying zeros is not slower than
+    multiplying pseudo-random values (the chip is power-limited under dense matrix instructions)."""
+    sink = torch.zeros(4, device=DEV)
+    rates = {}
+    for zero in (0, 1):
+        b.fw_mfma_rate_probe(zero, 200, sink); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = sum(b.fw_mfma_rate_probe(zero, 200, sink) for _ in range(5))
+        e1.record(); torch.cuda.synchronize()
+        assert flops == 5 * 4096 * 200 * 16 * 2 * 32 * 32 * 16
+        rates[zero] = flops / (e0.elapsed_time(e1) * 1e-3)
+    assert float(sink.abs().sum()) == 0.0                      # the sink is never written
+    assert 0.3e15 < rates[0] < 2.6e15 and rates[1] > 0.9 * rates[0]
+
