@@ -69,6 +69,33 @@ def measure_mfma_ceiling(torch, b):
     SUSTAINED_BF16_MFMA["source"] = "fw_mfma_rate_probe with pseudo-random operands, measured by this run before the timed loops"
     return out
 
+# What plain streaming kernels reach on this chip's HBM (published: 8 TB/s); measured by every run (measure_hbm_ceiling).
+SUSTAINED_HBM = {"rate": 5.9e12, "source": "earlier runs (torch add over 1 GiB tensors), not measured by this run"}
+
+
+def measure_hbm_ceiling(torch):
+    """HBM rate of two plain streaming kernels of PyTorch over 1 GiB float32 tensors (far beyond the caches): a copy (one
+    read, one write) and an addition (two reads, one write), ten launches each."""
+    n = 256 * 1024 * 1024
+    a, c = torch.ones(n, device="cuda:0"), torch.empty(n, device="cuda:0")
+    bb = torch.ones(n, device="cuda:0")
+    out = {}
+    for name, fn, nbytes in (("copy", lambda: c.copy_(a), 8.0 * n), ("add", lambda: torch.add(a, bb, out=c), 12.0 * n)):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        out[name + "_GBs"] = 10 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    out["published_peak_GBs"] = HBM_PEAK / 1e9
+    SUSTAINED_HBM["rate"] = max(out["copy_GBs"], out["add_GBs"]) * 1e9
+    SUSTAINED_HBM["source"] = "the faster of a copy and an addition over 1 GiB tensors, measured by this run before the timed loops"
+    del a, bb, c
+    torch.cuda.empty_cache()
+    return out
+
+
 EXPORTS = ("cov_accumulate", "cov_finalize", "cond_state_refresh", "cond_reduce_step", "grad_transform")
 
 
@@ -349,6 +376,10 @@ def rooflines_of(r, layer, b, cfg_key, layout_name):
     fn = {"bound": "hbm", "export": "fw_cov_finalize", "kernel": "finalize_phi64 + finalize_vec", "achieved": fin_bytes / t5 / 1e9,
           "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": fin_bytes / t5 / HBM_PEAK, "ms": ex["cov_finalize"]}
     fn.update(traffic_of("cov_finalize"))
+    for e in (a3, fn):       # HBM-bound exports: the fraction of what plain streaming kernels reach, for context
+        e["frac_of_sustained_hbm_rate"] = e["achieved"] * 1e9 / SUSTAINED_HBM["rate"]
+        e["sustained_hbm_rate_GBs"] = SUSTAINED_HBM["rate"] / 1e9
+        e["sustained_hbm_rate_source"] = SUSTAINED_HBM["source"]
     for e in (a1, a2, rf):   # bfloat16 products: the fraction of what the matrix cores sustain under the power limit, for context
         if e["peak"] == PEAK["bf16"] / 1e12:
             e["frac_of_sustained_mfma_rate"] = e["achieved"] * 1e12 / SUSTAINED_BF16_MFMA["rate"]
@@ -528,9 +559,11 @@ def main():
 
     # (left out with --no-extras, so that a profile of such a run holds the kernels of the step only)
     ceiling = None if args.no_extras else measure_mfma_ceiling(torch, b)
+    hbm_ceiling = None if args.no_extras else measure_hbm_ceiling(torch)
     if args.config == "c5":
         rec = run_c5(args, torch, b, wl)
         rec["mfma_ceiling"] = ceiling
+        rec["hbm_ceiling"] = hbm_ceiling
         print(json.dumps(rec))
         return
     if args.config == "all":
@@ -544,6 +577,7 @@ def main():
         out = config_record(args.config, args, torch, b, wl, np)
 
     out["mfma_ceiling"] = ceiling
+    out["hbm_ceiling"] = hbm_ceiling
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, device="cuda:0")      # 256 MiB read + 256 MiB written per copy
         dst = torch.empty_like(src)
